@@ -1,0 +1,224 @@
+"""ctypes front end of the C oracle (oracle/torq_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Imported by tests/, by the smoke check and by the
+benchmark's CPU-baseline leg; never by the product package.  All arrays are
+numpy, C-contiguous, on the host.  This module does argument marshalling only:
+every number comes out of the C functions.
+"""
+import ctypes as C
+import os
+
+import numpy as np
+
+from . import build as _build
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build()
+        L = C.CDLL(path)
+        i64, i32, f32, f64, vp = C.c_int64, C.c_int, C.c_float, C.c_double, C.c_void_p
+        L.torq_o_bf16_to_f32.restype = f32
+        L.torq_o_bf16_to_f32.argtypes = [C.c_uint16]
+        L.torq_o_f32_to_bf16.restype = C.c_uint16
+        L.torq_o_f32_to_bf16.argtypes = [f32]
+        L.torq_o_rotate_inter.restype = None
+        L.torq_o_rotate_inter.argtypes = [vp, i64, i32, i32, vp, vp]
+        L.torq_o_rotate_intra.restype = None
+        L.torq_o_rotate_intra.argtypes = [vp, i64, i32, vp, vp]
+        L.torq_o_rotate.restype = None
+        L.torq_o_rotate.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
+        L.torq_o_rotate_inverse.restype = None
+        L.torq_o_rotate_inverse.argtypes = [vp, i64, i32, i32, vp, vp, vp]
+        L.torq_o_e8m0_from_amax.restype = C.c_uint8
+        L.torq_o_e8m0_from_amax.argtypes = [f32]
+        L.torq_o_e2m1_from_f32.restype = C.c_uint8
+        L.torq_o_e2m1_from_f32.argtypes = [f32]
+        L.torq_o_e2m1_value.restype = f32
+        L.torq_o_e2m1_value.argtypes = [C.c_uint8]
+        L.torq_o_quantize.restype = None
+        L.torq_o_quantize.argtypes = [vp, i64, i32, vp, vp]
+        L.torq_o_dequantize.restype = None
+        L.torq_o_dequantize.argtypes = [vp, vp, i64, i32, vp]
+        L.torq_o_rotate_quantize.restype = None
+        L.torq_o_rotate_quantize.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
+        L.torq_o_gemm.restype = None
+        L.torq_o_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp]
+        L.torq_o_gemm_sampled.restype = None
+        L.torq_o_gemm_sampled.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, vp]
+        L.torq_o_equalize.restype = i32
+        L.torq_o_equalize.argtypes = [vp, i32, f64, vp]
+        L.torq_o_threads.restype = i32
+        L.torq_o_threads.argtypes = []
+        _lib = L
+    return _lib
+
+
+def _p(a):
+    return a.ctypes.data_as(C.c_void_p) if a is not None else None
+
+
+def _arr(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a
+
+
+def bf16_to_f32(h):
+    """h: uint16 array of bf16 patterns -> float32 array."""
+    h = _arr(h, np.uint16)
+    out = np.empty(h.shape, np.float32)
+    L = lib()
+    flat, o = h.reshape(-1), out.reshape(-1)
+    for i in range(flat.size):
+        o[i] = L.torq_o_bf16_to_f32(int(flat[i]))
+    return out
+
+
+def f32_to_bf16(f):
+    f = _arr(f, np.float32)
+    out = np.empty(f.shape, np.uint16)
+    L = lib()
+    flat, o = f.reshape(-1), out.reshape(-1)
+    for i in range(flat.size):
+        o[i] = L.torq_o_f32_to_bf16(float(flat[i]))
+    return out
+
+
+def e8m0_from_amax(amax: float) -> int:
+    return int(lib().torq_o_e8m0_from_amax(np.float32(amax)))
+
+
+def e2m1_from_f32(a: float) -> int:
+    return int(lib().torq_o_e2m1_from_f32(np.float32(a)))
+
+
+def e2m1_value(code: int) -> float:
+    return float(lib().torq_o_e2m1_value(int(code)))
+
+
+def _check_rot(d, G, R_inter, R_intra):
+    assert d % 32 == 0 and (d // 32) % G == 0
+    R_inter = _arr(R_inter, np.float32)
+    R_intra = _arr(R_intra, np.float32)
+    assert R_inter.shape == (G, G) and R_intra.shape == (32, 32)
+    return R_inter, R_intra
+
+
+def rotate_inter(x, G, R_inter):
+    x = _arr(x, np.float64)
+    M, d = x.shape
+    R_inter = _arr(R_inter, np.float32)
+    assert R_inter.shape == (G, G) and (d // 32) % G == 0
+    y = np.empty_like(x)
+    lib().torq_o_rotate_inter(_p(x), M, d, G, _p(R_inter), _p(y))
+    return y
+
+
+def rotate_intra(y, R_intra):
+    y = _arr(y, np.float64)
+    M, d = y.shape
+    R_intra = _arr(R_intra, np.float32)
+    assert R_intra.shape == (32, 32)
+    z = np.empty_like(y)
+    lib().torq_o_rotate_intra(_p(y), M, d, _p(R_intra), _p(z))
+    return z
+
+
+def rotate(x_bf16, G, R_inter, R_intra, want_f64=False):
+    """x_bf16: uint16 [M, d].  Returns z fp32 [M, d] (and z fp64 if asked)."""
+    x = _arr(x_bf16, np.uint16)
+    M, d = x.shape
+    R_inter, R_intra = _check_rot(d, G, R_inter, R_intra)
+    z32 = np.empty((M, d), np.float32)
+    z64 = np.empty((M, d), np.float64) if want_f64 else None
+    lib().torq_o_rotate(_p(x), M, d, G, _p(R_inter), _p(R_intra), _p(z32), _p(z64))
+    return (z32, z64) if want_f64 else z32
+
+
+def rotate_inverse(z, G, R_inter, R_intra):
+    z = _arr(z, np.float64)
+    M, d = z.shape
+    R_inter, R_intra = _check_rot(d, G, R_inter, R_intra)
+    x = np.empty_like(z)
+    lib().torq_o_rotate_inverse(_p(z), M, d, G, _p(R_inter), _p(R_intra), _p(x))
+    return x
+
+
+def quantize(z):
+    """z fp32 [M, d] -> (codes uint8 [M, d/2], scales uint8 [M, d/32])."""
+    z = _arr(z, np.float32)
+    M, d = z.shape
+    assert d % 32 == 0
+    codes = np.empty((M, d // 2), np.uint8)
+    scales = np.empty((M, d // 32), np.uint8)
+    lib().torq_o_quantize(_p(z), M, d, _p(codes), _p(scales))
+    return codes, scales
+
+
+def dequantize(codes, scales):
+    codes = _arr(codes, np.uint8)
+    scales = _arr(scales, np.uint8)
+    M, half = codes.shape
+    d = half * 2
+    assert scales.shape == (M, d // 32)
+    out = np.empty((M, d), np.float32)
+    lib().torq_o_dequantize(_p(codes), _p(scales), M, d, _p(out))
+    return out
+
+
+def rotate_quantize(x_bf16, G, R_inter, R_intra):
+    x = _arr(x_bf16, np.uint16)
+    M, d = x.shape
+    R_inter, R_intra = _check_rot(d, G, R_inter, R_intra)
+    codes = np.empty((M, d // 2), np.uint8)
+    scales = np.empty((M, d // 32), np.uint8)
+    lib().torq_o_rotate_quantize(_p(x), M, d, G, _p(R_inter), _p(R_intra), _p(codes), _p(scales))
+    return codes, scales
+
+
+def gemm(A_q, A_s, W_q, W_s, want_f64=False):
+    """Returns bf16 patterns uint16 [M, N] (and the unrounded fp64 if asked)."""
+    A_q, A_s = _arr(A_q, np.uint8), _arr(A_s, np.uint8)
+    W_q, W_s = _arr(W_q, np.uint8), _arr(W_s, np.uint8)
+    M, half = A_q.shape
+    N = W_q.shape[0]
+    d = half * 2
+    assert W_q.shape == (N, half) and A_s.shape == (M, d // 32) and W_s.shape == (N, d // 32)
+    out = np.empty((M, N), np.uint16)
+    o64 = np.empty((M, N), np.float64) if want_f64 else None
+    lib().torq_o_gemm(_p(A_q), _p(A_s), _p(W_q), _p(W_s), M, N, d, _p(out), _p(o64))
+    return (out, o64) if want_f64 else out
+
+
+def gemm_sampled(A_q, A_s, W_q, W_s, ms, ns, want_f64=False):
+    A_q, A_s = _arr(A_q, np.uint8), _arr(A_s, np.uint8)
+    W_q, W_s = _arr(W_q, np.uint8), _arr(W_s, np.uint8)
+    d = A_q.shape[1] * 2
+    ms, ns = _arr(ms, np.int64), _arr(ns, np.int64)
+    assert ms.shape == ns.shape and ms.ndim == 1
+    assert ms.size == 0 or (ms.min() >= 0 and ms.max() < A_q.shape[0])
+    assert ns.size == 0 or (ns.min() >= 0 and ns.max() < W_q.shape[0])
+    out = np.empty(ms.shape, np.uint16)
+    o64 = np.empty(ms.shape, np.float64) if want_f64 else None
+    lib().torq_o_gemm_sampled(_p(A_q), _p(A_s), _p(W_q), _p(W_s), d, ms.size,
+                              _p(ms), _p(ns), _p(out), _p(o64))
+    return (out, o64) if want_f64 else out
+
+
+def equalize(Sigma, eps=0.0):
+    """Corrected Algorithm 1.  Returns (R, Sigma_after, steps)."""
+    S = np.array(Sigma, dtype=np.float64, order="C", copy=True)
+    B = S.shape[0]
+    assert S.shape == (B, B)
+    R = np.empty((B, B), np.float64)
+    steps = lib().torq_o_equalize(_p(S), B, float(eps), _p(R))
+    return R, S, steps
+
+
+def threads() -> int:
+    return int(lib().torq_o_threads())
