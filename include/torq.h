@@ -1,0 +1,134 @@
+/*
+ * libtorq -- MI355X (gfx950) kernels for the online path of TORQ:
+ * two-level orthogonal rotation of bf16 activations, MXFP4 quantisation of the
+ * result, and the W4A4 MXFP4 GEMM that consumes it.
+ *
+ * Plain C ABI.  Unless a parameter is named *_host, every pointer is a DEVICE
+ * pointer owned by the caller (allocated by whatever the caller likes, e.g.
+ * torch); the library never frees or keeps it.  `stream` is a hipStream_t
+ * passed as void* (NULL = the default stream).  Every compute call only
+ * enqueues work on that stream and returns; it allocates nothing.  Calls on
+ * different streams may overlap; a rotation handle is immutable after creation
+ * and may be shared by any number of concurrent calls.
+ *
+ * Notation (paper, Section 4 "Notations"): a token row x has d features and is
+ * viewed as X[b][k] = x[32 b + k]: B = d/32 microscaling blocks of 32 elements.
+ *
+ * Return value: TORQ_OK (0) or a negative error code; on error nothing has been
+ * launched and no output has been touched.  M = 0 (or N = 0) is TORQ_OK and a
+ * no-op.  Inputs are assumed finite; a block that holds Inf/NaN gets scale
+ * byte 0xFF or 0xFD.. and unspecified codes.
+ */
+#ifndef TORQ_H
+#define TORQ_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    TORQ_OK          =  0,
+    TORQ_EINVAL      = -1,  /* null pointer, negative size, d % 32 != 0, G does not divide d/32,
+                               G not a multiple of 16 or above TORQ_MAX_G, N or d beyond the limits below */
+    TORQ_EALIGN      = -2,  /* a device pointer is not 16-byte aligned */
+    TORQ_EWORKSPACE  = -3,  /* workspace smaller than torq_linear_workspace_bytes() */
+    TORQ_EHIP        = -4,  /* the HIP runtime reported an error (allocation, copy or launch) */
+    TORQ_ENODEVICE   = -5   /* no gfx950 device is current */
+};
+
+#define TORQ_BLOCK 32       /* elements per microscaling block (the paper's K) */
+#define TORQ_MAX_G 256      /* largest supported inter-block rotation */
+
+/* Text for a status code (static storage, never NULL). */
+const char *torq_status_string(int status);
+
+/* ------------------------------------------------------------------------ */
+/* Rotation handle: the offline parameters R_inter and R_intra of Algorithm 3
+ * (Appendix A.3, "Offline parameters"), uploaded once and laid out for the
+ * matrix cores.
+ *
+ *   d             feature dimension, multiple of 32
+ *   G             size of R_inter.  R_inter acts on each run of G consecutive
+ *                 blocks of a row (block-diagonal over the row, Appendix A.7
+ *                 "decomposed into block-diagonal"); G = d/32 is Algorithm 3
+ *                 as printed.  G must be a multiple of 16, at most TORQ_MAX_G,
+ *                 and divide d/32.
+ *   R_inter_host  HOST pointer, G*G floats, row-major: Y = R_inter X
+ *                 (Algorithm 3, step 2: Y[b][k] = sum_b' R_inter[b][b'] X[b'][k])
+ *   R_intra_host  HOST pointer, 32*32 floats, row-major: Z = Y R_intra
+ *                 (Algorithm 3, step 3: Z[b][k] = sum_k' Y[b][k'] R_intra[k'][k])
+ *
+ * The handle owns a few hundred KiB of device memory on the device that is
+ * current at creation; it must be used on that device.  Creation synchronises
+ * with the device (not a hot call).  Orthogonality is not checked. */
+typedef struct torq_rotation torq_rotation_t;
+
+int  torq_rotation_create(torq_rotation_t **out, int d, int G,
+                          const float *R_inter_host, const float *R_intra_host);
+void torq_rotation_destroy(torq_rotation_t *r);   /* NULL is allowed */
+int  torq_rotation_d(const torq_rotation_t *r);
+int  torq_rotation_G(const torq_rotation_t *r);
+
+/* ------------------------------------------------------------------------ */
+/* Algorithm 3 steps 1-4 (Appendix A.3): reshape, inter-block rotation,
+ * intra-block rotation, MXFP4 quantisation (Section 4, Eq. 1).
+ *
+ *   x_bf16  [M][d] bf16, row-major
+ *   codes   [M][d/2] bytes: e2m1 codes (bit 3 sign, bits 2..0 index into
+ *           {0, .5, 1, 1.5, 2, 3, 4, 6}), element 2j in the low nibble of byte j
+ *   scales  [M][d/32] bytes: E8M0 shared exponent of each block, value
+ *           2^(byte-127) = 2^(floor(log2 amax) - 2), clamped to [0, 254]
+ *
+ * The rotation is computed on the matrix cores in split bf16 with fp32
+ * accumulation; the rotated values differ from exact arithmetic by far less
+ * than 1e-3 of the row RMS, so a code or scale can differ from an exact
+ * computation only where a rotated value sits on a rounding boundary. */
+int torq_rotate_quantize(const torq_rotation_t *r, const void *x_bf16, int64_t M,
+                         uint8_t *codes, uint8_t *scales, void *stream);
+
+/* Algorithm 3 steps 1-3 only: the rotated values Z as fp32 [M][d].  Test hook
+ * for the accuracy of the rotation; same arithmetic as torq_rotate_quantize. */
+int torq_rotate(const torq_rotation_t *r, const void *x_bf16, int64_t M,
+                float *z_f32, void *stream);
+
+/* Algorithm 3 step 4 only (Section 4, Eq. 1) on fp32 input z [M][d]: per block
+ * amax -> E8M0 scale -> round to nearest e2m1 (ties to the even code, values
+ * above 6 saturate, sign bit copied) -> packed codes.  Same quantiser code as
+ * inside torq_rotate_quantize; bit-exact by specification. */
+int torq_quantize_f32(const float *z_f32, int64_t M, int d,
+                      uint8_t *codes, uint8_t *scales, void *stream);
+
+/* The linear layer that consumes the quantised activations with the inverse
+ * rotation folded into its weights (Section 5; Algorithm 3 "Return"):
+ *
+ *   out[m][n] = sum_kb 2^(A_s[m][kb] + W_s[n][kb] - 254)
+ *                 * sum_{k<32} val(A[m][32 kb + k]) * val(W[n][32 kb + k])
+ *
+ * on the block-scaled fp4 matrix cores, fp32 accumulation, one rounding to
+ * bf16 (nearest even).  A_q [M][d/2], A_s [M][d/32], W_q [N][d/2],
+ * W_s [N][d/32] in the layout torq_rotate_quantize writes; out [M][N] bf16
+ * row-major.  d must be a multiple of 128.  Weights are prepared offline by
+ * running torq_rotate_quantize over the rows of W (the map x -> z is
+ * orthogonal, so rotating W's rows is the weight fusion W' of Section 5). */
+int mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s,
+               const uint8_t *W_q, const uint8_t *W_s,
+               void *out_bf16, int64_t M, int64_t N, int d, void *stream);
+
+/* Algorithm 3 end to end ("output of the linear layer"): torq_rotate_quantize
+ * into `workspace`, then mxfp4_gemm, on one stream.  workspace is device
+ * memory of at least torq_linear_workspace_bytes(M, d) bytes, 256-byte aligned
+ * sizes; its contents afterwards are the packed activations (codes, then
+ * scales at offset M*d/2 rounded up to 256). */
+size_t torq_linear_workspace_bytes(int64_t M, int d);
+int torq_linear(const torq_rotation_t *r, const void *x_bf16,
+                const uint8_t *W_q, const uint8_t *W_s, void *out_bf16,
+                int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
+                void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* TORQ_H */

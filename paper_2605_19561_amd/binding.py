@@ -1,0 +1,175 @@
+"""Thin ctypes binding of libtorq.so: same names as the C ABI (include/torq.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP
+stream, every step of the path runs in the library's kernels.  There is no CPU
+fallback: a missing library or a failing call raises.
+"""
+import ctypes as C
+import os
+
+import torch  # loads the HIP runtime that libtorq.so binds to
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtorq.so")
+
+EXPORTS = [
+    "torq_status_string", "torq_rotation_create", "torq_rotation_destroy", "torq_rotation_d",
+    "torq_rotation_G", "torq_rotate_quantize", "torq_rotate", "torq_quantize_f32", "mxfp4_gemm",
+    "torq_linear_workspace_bytes", "torq_linear",
+]
+
+TORQ_OK, TORQ_EINVAL, TORQ_EALIGN, TORQ_EWORKSPACE, TORQ_EHIP, TORQ_ENODEVICE = 0, -1, -2, -3, -4, -5
+
+_lib = None
+
+
+class TorqError(RuntimeError):
+    def __init__(self, status, what):
+        self.status = status
+        super().__init__(f"{what}: {status_string(status)} ({status})")
+
+
+def lib():
+    """Load libtorq.so (built by paper_2605_19561_amd.build); raise if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2605_19561_amd.build` "
+                "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        vp, i64, i32, sz = C.c_void_p, C.c_int64, C.c_int, C.c_size_t
+        L.torq_status_string.restype = C.c_char_p
+        L.torq_status_string.argtypes = [i32]
+        L.torq_rotation_create.restype = i32
+        L.torq_rotation_create.argtypes = [C.POINTER(vp), i32, i32, vp, vp]
+        L.torq_rotation_destroy.restype = None
+        L.torq_rotation_destroy.argtypes = [vp]
+        L.torq_rotation_d.restype = i32
+        L.torq_rotation_d.argtypes = [vp]
+        L.torq_rotation_G.restype = i32
+        L.torq_rotation_G.argtypes = [vp]
+        L.torq_rotate_quantize.restype = i32
+        L.torq_rotate_quantize.argtypes = [vp, vp, i64, vp, vp, vp]
+        L.torq_rotate.restype = i32
+        L.torq_rotate.argtypes = [vp, vp, i64, vp, vp]
+        L.torq_quantize_f32.restype = i32
+        L.torq_quantize_f32.argtypes = [vp, i64, i32, vp, vp, vp]
+        L.mxfp4_gemm.restype = i32
+        L.mxfp4_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp]
+        L.torq_linear_workspace_bytes.restype = sz
+        L.torq_linear_workspace_bytes.argtypes = [i64, i32]
+        L.torq_linear.restype = i32
+        L.torq_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, sz, vp]
+        _lib = L
+    return _lib
+
+
+def status_string(status: int) -> str:
+    return lib().torq_status_string(int(status)).decode()
+
+
+def _check(status, what):
+    if status != TORQ_OK:
+        raise TorqError(status, what)
+
+
+def _stream(stream=None):
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return C.c_void_p(stream.cuda_stream)
+
+
+def _dev(t: torch.Tensor, dtype, what):
+    if not (t.is_cuda and t.is_contiguous() and t.dtype == dtype):
+        raise ValueError(f"{what}: expected a contiguous {dtype} device tensor")
+    return C.c_void_p(t.data_ptr())
+
+
+class Rotation:
+    """Owner of a torq_rotation_t handle (R_inter [G, G], R_intra [32, 32], fp32 host arrays)."""
+
+    def __init__(self, d: int, G: int, R_inter, R_intra):
+        import numpy as np
+        Ri = np.ascontiguousarray(R_inter, dtype=np.float32)
+        Ra = np.ascontiguousarray(R_intra, dtype=np.float32)
+        if Ri.shape != (G, G) or Ra.shape != (32, 32):
+            raise ValueError("R_inter must be [G, G] and R_intra [32, 32]")
+        h = C.c_void_p()
+        _check(lib().torq_rotation_create(C.byref(h), d, G, Ri.ctypes.data_as(C.c_void_p),
+                                          Ra.ctypes.data_as(C.c_void_p)), "torq_rotation_create")
+        self.handle, self.d, self.G = h, d, G
+
+    def close(self):
+        if getattr(self, "handle", None):
+            lib().torq_rotation_destroy(self.handle)
+            self.handle = None
+
+    __del__ = close
+
+
+def torq_rotate_quantize(rot: Rotation, x_bf16: torch.Tensor, codes=None, scales=None, stream=None):
+    M, d = x_bf16.shape
+    assert d == rot.d
+    if codes is None:
+        codes = torch.empty((M, d // 2), dtype=torch.uint8, device=x_bf16.device)
+    if scales is None:
+        scales = torch.empty((M, d // 32), dtype=torch.uint8, device=x_bf16.device)
+    _check(lib().torq_rotate_quantize(rot.handle, _dev(x_bf16, torch.bfloat16, "x"), M,
+                                      _dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"),
+                                      _stream(stream)), "torq_rotate_quantize")
+    return codes, scales
+
+
+def torq_rotate(rot: Rotation, x_bf16: torch.Tensor, z=None, stream=None):
+    M, d = x_bf16.shape
+    assert d == rot.d
+    if z is None:
+        z = torch.empty((M, d), dtype=torch.float32, device=x_bf16.device)
+    _check(lib().torq_rotate(rot.handle, _dev(x_bf16, torch.bfloat16, "x"), M, _dev(z, torch.float32, "z"),
+                             _stream(stream)), "torq_rotate")
+    return z
+
+
+def torq_quantize_f32(z: torch.Tensor, codes=None, scales=None, stream=None):
+    M, d = z.shape
+    if codes is None:
+        codes = torch.empty((M, d // 2), dtype=torch.uint8, device=z.device)
+    if scales is None:
+        scales = torch.empty((M, d // 32), dtype=torch.uint8, device=z.device)
+    _check(lib().torq_quantize_f32(_dev(z, torch.float32, "z"), M, d, _dev(codes, torch.uint8, "codes"),
+                                   _dev(scales, torch.uint8, "scales"), _stream(stream)), "torq_quantize_f32")
+    return codes, scales
+
+
+def mxfp4_gemm(A_q, A_s, W_q, W_s, out=None, stream=None):
+    M, half = A_q.shape
+    N = W_q.shape[0]
+    d = half * 2
+    assert W_q.shape == (N, half) and A_s.shape == (M, d // 32) and W_s.shape == (N, d // 32)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=A_q.device)
+    _check(lib().mxfp4_gemm(_dev(A_q, torch.uint8, "A_q"), _dev(A_s, torch.uint8, "A_s"),
+                            _dev(W_q, torch.uint8, "W_q"), _dev(W_s, torch.uint8, "W_s"),
+                            _dev(out, torch.bfloat16, "out"), M, N, d, _stream(stream)), "mxfp4_gemm")
+    return out
+
+
+def torq_linear_workspace_bytes(M: int, d: int) -> int:
+    return int(lib().torq_linear_workspace_bytes(M, d))
+
+
+def torq_linear(rot: Rotation, x_bf16, W_q, W_s, out=None, workspace=None, stream=None):
+    M, d = x_bf16.shape
+    N = W_q.shape[0]
+    assert d == rot.d and W_q.shape == (N, d // 2) and W_s.shape == (N, d // 32)
+    need = torq_linear_workspace_bytes(M, d)
+    if workspace is None:
+        workspace = torch.empty((max(need, 1),), dtype=torch.uint8, device=x_bf16.device)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=x_bf16.device)
+    _check(lib().torq_linear(rot.handle, _dev(x_bf16, torch.bfloat16, "x"), _dev(W_q, torch.uint8, "W_q"),
+                             _dev(W_s, torch.uint8, "W_s"), _dev(out, torch.bfloat16, "out"), M, N,
+                             _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)),
+           "torq_linear")
+    return out

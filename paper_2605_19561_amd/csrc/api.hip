@@ -1,0 +1,205 @@
+// C-ABI entry points of libtorq: argument validation, the rotation handle, and
+// dispatch to the kernel launchers.  No compute happens on the host.
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "torq_internal.h"
+
+namespace {
+
+inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
+
+// fp32 -> bf16 pattern, round to nearest even (host side, for the operand tables)
+inline uint16_t to_bf16(float f) {
+  uint32_t u;
+  std::memcpy(&u, &f, 4);
+  if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+inline float from_bf16(uint16_t h) {
+  uint32_t u = (uint32_t)h << 16;
+  float f;
+  std::memcpy(&f, &u, 4);
+  return f;
+}
+// v = hi + lo + O(2^-17 |v|) with hi, lo both bf16
+inline void split_bf16(float v, uint16_t *hi, uint16_t *lo) {
+  *hi = to_bf16(v);
+  *lo = to_bf16(v - from_bf16(*hi));
+}
+
+template <class T>
+hipError_t upload(T **dst, const std::vector<T> &src) {
+  hipError_t e = hipMalloc(reinterpret_cast<void **>(dst), src.size() * sizeof(T));
+  if (e != hipSuccess) return e;
+  return hipMemcpy(*dst, src.data(), src.size() * sizeof(T), hipMemcpyHostToDevice);
+}
+
+thread_local char g_hip_msg[256] = "";
+
+int hip_fail(hipError_t e) {
+  std::snprintf(g_hip_msg, sizeof g_hip_msg, "HIP runtime error: %s", hipGetErrorString(e));
+  return TORQ_EHIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *torq_status_string(int status) {
+  switch (status) {
+    case TORQ_OK: return "ok";
+    case TORQ_EINVAL: return "invalid argument (null pointer, negative size, or a dimension the library does not support)";
+    case TORQ_EALIGN: return "device pointer not 16-byte aligned";
+    case TORQ_EWORKSPACE: return "workspace too small";
+    case TORQ_EHIP: return g_hip_msg[0] ? g_hip_msg : "HIP runtime error";
+    case TORQ_ENODEVICE: return "no gfx950 device is current";
+    default: return "unknown status";
+  }
+}
+
+int torq_rotation_create(torq_rotation_t **out, int d, int G, const float *R_inter_host,
+                         const float *R_intra_host) {
+  if (!out) return TORQ_EINVAL;
+  *out = nullptr;
+  if (!R_inter_host || !R_intra_host) return TORQ_EINVAL;
+  if (d <= 0 || d % TORQ_BLOCK != 0) return TORQ_EINVAL;
+  if (G <= 0 || G % 16 != 0 || G > TORQ_MAX_G) return TORQ_EINVAL;
+  if ((d / TORQ_BLOCK) % G != 0) return TORQ_EINVAL;
+
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return TORQ_ENODEVICE;
+  hipDeviceProp_t prop;
+  e = hipGetDeviceProperties(&prop, dev);
+  if (e != hipSuccess) return TORQ_ENODEVICE;
+  if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return TORQ_ENODEVICE;
+
+  torq_rotation *r = new (std::nothrow) torq_rotation();
+  if (!r) return TORQ_EHIP;
+  r->d = d;
+  r->G = G;
+  r->KS = (G + 31) / 32;
+  r->device = dev;
+  r->inter_hi = r->inter_lo = r->intra_hi = r->intra_lo = nullptr;
+
+  // R_inter, bf16 hi/lo, [G][KS*32] with zero padding: row b is the B operand
+  // "column" b of R_inter^T (Algorithm 3 step 2: Y[b] = sum_b' R_inter[b][b'] X[b']).
+  const int ld = r->KS * 32;
+  std::vector<uint16_t> ih((size_t)G * ld, 0), il((size_t)G * ld, 0);
+  for (int b = 0; b < G; ++b)
+    for (int bp = 0; bp < G; ++bp)
+      split_bf16(R_inter_host[(size_t)b * G + bp], &ih[(size_t)b * ld + bp], &il[(size_t)b * ld + bp]);
+
+  // R_intra^T as the A operand of v_mfma_f32_16x16x32_bf16 for the two output
+  // tiles t: lane (m = l%16, q = l/16), slot j<4 holds R_intra[4q+j][kout] and
+  // slot 4+j holds R_intra[16+4q+j][kout] (the k' order in which step 2 leaves Y
+  // in its accumulators), with kout = 8*(m/4) + 4t + m%4 so that after step 3 a
+  // lane holds eight consecutive output positions.
+  std::vector<uint16_t> ah(2 * 64 * 8), al(2 * 64 * 8);
+  for (int t = 0; t < 2; ++t)
+    for (int l = 0; l < 64; ++l) {
+      const int m = l % 16, q = l / 16;
+      const int kout = 8 * (m / 4) + 4 * t + (m % 4);
+      for (int j = 0; j < 8; ++j) {
+        const int kin = (j < 4) ? (4 * q + j) : (16 + 4 * q + (j - 4));
+        split_bf16(R_intra_host[kin * 32 + kout], &ah[(t * 64 + l) * 8 + j], &al[(t * 64 + l) * 8 + j]);
+      }
+    }
+
+  e = upload(&r->inter_hi, ih);
+  if (e == hipSuccess) e = upload(&r->inter_lo, il);
+  if (e == hipSuccess) e = upload(&r->intra_hi, ah);
+  if (e == hipSuccess) e = upload(&r->intra_lo, al);
+  if (e == hipSuccess) e = hipDeviceSynchronize();
+  if (e != hipSuccess) {
+    torq_rotation_destroy(r);
+    return hip_fail(e);
+  }
+  *out = r;
+  return TORQ_OK;
+}
+
+void torq_rotation_destroy(torq_rotation_t *r) {
+  if (!r) return;
+  if (r->inter_hi) (void)hipFree(r->inter_hi);
+  if (r->inter_lo) (void)hipFree(r->inter_lo);
+  if (r->intra_hi) (void)hipFree(r->intra_hi);
+  if (r->intra_lo) (void)hipFree(r->intra_lo);
+  delete r;
+}
+
+int torq_rotation_d(const torq_rotation_t *r) { return r ? r->d : TORQ_EINVAL; }
+int torq_rotation_G(const torq_rotation_t *r) { return r ? r->G : TORQ_EINVAL; }
+
+int torq_rotate_quantize(const torq_rotation_t *r, const void *x_bf16, int64_t M, uint8_t *codes,
+                         uint8_t *scales, void *stream) {
+  if (!r || M < 0) return TORQ_EINVAL;
+  if (M == 0) return TORQ_OK;
+  if (!x_bf16 || !codes || !scales) return TORQ_EINVAL;
+  if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return TORQ_EALIGN;
+  hipError_t e = torq::launch_rotate(r, x_bf16, M, codes, scales, nullptr, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+int torq_rotate(const torq_rotation_t *r, const void *x_bf16, int64_t M, float *z_f32, void *stream) {
+  if (!r || M < 0) return TORQ_EINVAL;
+  if (M == 0) return TORQ_OK;
+  if (!x_bf16 || !z_f32) return TORQ_EINVAL;
+  if (misaligned(x_bf16) || misaligned(z_f32)) return TORQ_EALIGN;
+  hipError_t e = torq::launch_rotate(r, x_bf16, M, nullptr, nullptr, z_f32, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+int torq_quantize_f32(const float *z_f32, int64_t M, int d, uint8_t *codes, uint8_t *scales,
+                      void *stream) {
+  if (M < 0 || d <= 0 || d % TORQ_BLOCK != 0) return TORQ_EINVAL;
+  if (M == 0) return TORQ_OK;
+  if (!z_f32 || !codes || !scales) return TORQ_EINVAL;
+  if (misaligned(z_f32) || misaligned(codes) || misaligned(scales)) return TORQ_EALIGN;
+  hipError_t e = torq::launch_quantize_f32(z_f32, M * (int64_t)(d / TORQ_BLOCK), codes, scales,
+                                           (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+int mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+               void *out_bf16, int64_t M, int64_t N, int d, void *stream) {
+  if (M < 0 || N < 0 || d <= 0 || d % 128 != 0) return TORQ_EINVAL;
+  if (M == 0 || N == 0) return TORQ_OK;
+  if (!A_q || !A_s || !W_q || !W_s || !out_bf16) return TORQ_EINVAL;
+  if (misaligned(A_q) || misaligned(W_q) || misaligned(out_bf16)) return TORQ_EALIGN;
+  if ((reinterpret_cast<uintptr_t>(A_s) & 3u) || (reinterpret_cast<uintptr_t>(W_s) & 3u)) return TORQ_EALIGN;
+  hipError_t e = torq::launch_mxfp4_gemm(A_q, A_s, W_q, W_s, out_bf16, M, N, d, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+size_t torq_linear_workspace_bytes(int64_t M, int d) {
+  if (M <= 0 || d <= 0 || d % TORQ_BLOCK != 0) return 0;
+  const size_t codes = ((size_t)M * (size_t)(d / 2) + 255) & ~(size_t)255;
+  const size_t scales = ((size_t)M * (size_t)(d / TORQ_BLOCK) + 255) & ~(size_t)255;
+  return codes + scales;
+}
+
+int torq_linear(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q, const uint8_t *W_s,
+                void *out_bf16, int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
+                void *stream) {
+  if (!r || M < 0 || N < 0) return TORQ_EINVAL;
+  if (r->d % 128 != 0) return TORQ_EINVAL;
+  if (M == 0 || N == 0) return TORQ_OK;
+  if (!x_bf16 || !W_q || !W_s || !out_bf16 || !workspace) return TORQ_EINVAL;
+  if (misaligned(x_bf16) || misaligned(W_q) || misaligned(out_bf16) || misaligned(workspace)) return TORQ_EALIGN;
+  if (reinterpret_cast<uintptr_t>(W_s) & 3u) return TORQ_EALIGN;
+  if (workspace_bytes < torq_linear_workspace_bytes(M, r->d)) return TORQ_EWORKSPACE;
+  uint8_t *codes = static_cast<uint8_t *>(workspace);
+  uint8_t *scales = codes + (((size_t)M * (size_t)(r->d / 2) + 255) & ~(size_t)255);
+  hipError_t e = torq::launch_rotate(r, x_bf16, M, codes, scales, nullptr, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = torq::launch_mxfp4_gemm(codes, scales, W_q, W_s, out_bf16, M, N, r->d, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+}  // extern "C"

@@ -1,0 +1,48 @@
+// torq_quantize_f32: MXFP4 quantisation of fp32 rows (Section 4, Eq. 1;
+// Algorithm 3, step 4).  HBM-bound: 4 B read + 17/32 B written per element.
+//
+// Four adjacent lanes share one 32-element block: each lane loads 8 consecutive
+// floats (two 16-byte loads), the block amax is an in-lane max followed by two
+// quad-permute DPP steps, and each lane stores its 8 nibbles as one dword.
+#include "torq_device.h"
+#include "torq_internal.h"
+
+namespace torq {
+
+__device__ __forceinline__ float quad_max(float v) {
+  // max over the 4 lanes of a quad: xor 1 (quad_perm [1,0,3,2]) then xor 2 ([2,3,0,1])
+  float o = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0xB1, 0xF, 0xF, true));
+  v = fmaxf(v, o);
+  o = __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), 0x4E, 0xF, 0xF, true));
+  return fmaxf(v, o);
+}
+
+__global__ void __launch_bounds__(256) quantize_f32_kernel(const float4 *__restrict__ z, int64_t n8,
+                                                           uint32_t *__restrict__ codes,
+                                                           uint8_t *__restrict__ scales) {
+  // n8 = number of 8-element pieces = 4 * (number of blocks); a multiple of 4, so a quad is
+  // never split by the bound and the DPP steps always see four live lanes.
+  const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+  for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < n8; i += stride) {
+    float4 a = z[2 * i], b = z[2 * i + 1];
+    float v[8] = {a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w};
+    float amax = quad_max(amax8(v));
+    uint32_t byte = e8m0_from_amax(amax);
+    codes[i] = pack8_e2m1(v, e8m0_to_f32(byte));
+    if ((threadIdx.x & 3) == 0) scales[i >> 2] = (uint8_t)byte;
+  }
+}
+
+hipError_t launch_quantize_f32(const float *z, int64_t nblk, uint8_t *codes, uint8_t *scales,
+                               hipStream_t stream) {
+  if (nblk == 0) return hipSuccess;
+  const int64_t n8 = nblk * 4;
+  int64_t blocks = (n8 + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  hipLaunchKernelGGL(quantize_f32_kernel, dim3((unsigned)blocks), dim3(256), 0, stream,
+                     reinterpret_cast<const float4 *>(z), n8, reinterpret_cast<uint32_t *>(codes),
+                     scales);
+  return hipGetLastError();
+}
+
+}  // namespace torq

@@ -1,0 +1,58 @@
+// Device-side helpers shared by the gfx950 kernels of libtorq.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace torq {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4;
+typedef __attribute__((__vector_size__(2 * sizeof(__bf16)))) __bf16 bf16x2;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef __attribute__((__vector_size__(8 * sizeof(int)))) int i32x8;
+typedef __attribute__((__vector_size__(4 * sizeof(int)))) int i32x4;
+typedef __attribute__((__vector_size__(4 * sizeof(short)))) short i16x4;
+
+// ---------------------------------------------------------------------------
+// MXFP4 quantiser for one microscaling block (Section 4, Eq. 1; Algorithm 3,
+// step 4).  The shared scale is the E8M0 byte with 2^(byte-127) =
+// 2^(floor(log2 amax) - 2): for a normal fp32 amax that is the exponent field
+// minus 2, clamped at 0 (amax is finite, so the field is at most 254).
+
+__device__ __forceinline__ uint32_t e8m0_from_amax(float amax) {
+  int field = (int)((__float_as_uint(amax) >> 23) & 0xFFu);
+  int b = field - 2;
+  return (uint32_t)(b < 0 ? 0 : b);
+}
+
+// 2^(byte-127) as an fp32 value; byte 0 is the subnormal 2^-127.
+__device__ __forceinline__ float e8m0_to_f32(uint32_t byte) {
+  return __uint_as_float(byte ? (byte << 23) : 0x00400000u);
+}
+
+// Eight consecutive elements of a block -> eight e2m1 nibbles in one dword,
+// element 0 in the lowest nibble.  v_cvt_scalef32_pk_fp4_f32 divides its two
+// inputs by `scale`, rounds to the nearest e2m1 value with ties to the even
+// code, saturates at 6, keeps the sign bit, and writes one byte of the result.
+__device__ __forceinline__ uint32_t pack8_e2m1(const float z[8], float scale) {
+  uint32_t r = 0;
+  r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, z[0], z[1], scale, 0);
+  r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, z[2], z[3], scale, 1);
+  r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, z[4], z[5], scale, 2);
+  r = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(r, z[6], z[7], scale, 3);
+  return r;
+}
+
+__device__ __forceinline__ float amax8(const float z[8]) {
+  float a = fmaxf(fmaxf(fabsf(z[0]), fabsf(z[1])), fabsf(z[2]));
+  a = fmaxf(fmaxf(a, fabsf(z[3])), fabsf(z[4]));
+  a = fmaxf(fmaxf(a, fabsf(z[5])), fabsf(z[6]));
+  return fmaxf(a, fabsf(z[7]));
+}
+
+// bf16 <-> fp32 bit moves
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
+
+}  // namespace torq

@@ -1,0 +1,35 @@
+// Host-side declarations shared by the translation units of libtorq.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/torq.h"
+
+struct torq_rotation {
+  int d;
+  int G;
+  int KS;            // ceil(G / 32): k-steps of the inter-block contraction
+  int device;        // device the tables live on
+  // R_inter as bf16 hi and lo parts, [G][KS*32] row-major, zero-padded columns
+  uint16_t *inter_hi, *inter_lo;
+  // R_intra^T rows permuted for the accumulator layout, bf16 hi and lo, [32][32]
+  uint16_t *intra_hi, *intra_lo;
+};
+
+namespace torq {
+
+// fp32 rows -> MXFP4.  nblk = number of 32-element blocks (M * d / 32).
+hipError_t launch_quantize_f32(const float *z, int64_t nblk, uint8_t *codes, uint8_t *scales,
+                               hipStream_t stream);
+
+// Two-level rotation (+ quantisation).  Exactly one of (codes, scales) / z_out is used:
+// z_out != nullptr writes the rotated fp32 values instead of quantising.
+hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M,
+                         uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream);
+
+hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
+                             const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, int d,
+                             hipStream_t stream);
+
+}  // namespace torq

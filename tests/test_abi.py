@@ -1,0 +1,91 @@
+"""Host-only checks of the C ABI: the library loads, exports what include/torq.h
+declares, and rejects bad arguments before touching a device."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+from paper_2605_19561_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "torq.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([A-Za-z_0-9]+)\s*\(", text)
+    return sorted({n for n in names if n.startswith("torq_") or n.startswith("mxfp4_")})
+
+
+def test_header_and_library_agree():
+    L = binding.lib()
+    declared = _declared()
+    assert declared == sorted(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings():
+    for s in (0, -1, -2, -3, -4, -5, -99):
+        assert isinstance(binding.status_string(s), str) and binding.status_string(s)
+
+
+def test_rotation_create_rejects_bad_arguments():
+    L = binding.lib()
+    h = C.c_void_p()
+    Ri = np.eye(128, dtype=np.float32)
+    Ra = np.eye(32, dtype=np.float32)
+    pi, pa = Ri.ctypes.data_as(C.c_void_p), Ra.ctypes.data_as(C.c_void_p)
+    assert L.torq_rotation_create(None, 4096, 128, pi, pa) == binding.TORQ_EINVAL
+    assert L.torq_rotation_create(C.byref(h), 4096, 128, None, pa) == binding.TORQ_EINVAL
+    assert L.torq_rotation_create(C.byref(h), 4096, 128, pi, None) == binding.TORQ_EINVAL
+    assert L.torq_rotation_create(C.byref(h), 4100, 128, pi, pa) == binding.TORQ_EINVAL    # d % 32
+    assert L.torq_rotation_create(C.byref(h), 4096, 24, pi, pa) == binding.TORQ_EINVAL     # G % 16
+    assert L.torq_rotation_create(C.byref(h), 4096, 48, pi, pa) == binding.TORQ_EINVAL     # G does not divide 128
+    assert L.torq_rotation_create(C.byref(h), 32 * 512, 512, pi, pa) == binding.TORQ_EINVAL  # G too large
+    assert L.torq_rotation_create(C.byref(h), 0, 128, pi, pa) == binding.TORQ_EINVAL
+    assert not h.value
+    L.torq_rotation_destroy(None)
+
+
+def test_compute_calls_reject_bad_arguments_without_launching():
+    L = binding.lib()
+    good = C.c_void_p(0x1000)       # never dereferenced: every call below fails validation first
+    odd = C.c_void_p(0x1004)
+    assert L.torq_quantize_f32(good, -1, 4096, good, good, None) == binding.TORQ_EINVAL
+    assert L.torq_quantize_f32(good, 4, 100, good, good, None) == binding.TORQ_EINVAL
+    assert L.torq_quantize_f32(None, 4, 4096, good, good, None) == binding.TORQ_EINVAL
+    assert L.torq_quantize_f32(odd, 4, 4096, good, good, None) == binding.TORQ_EALIGN
+    assert L.torq_quantize_f32(good, 0, 4096, None, None, None) == binding.TORQ_OK            # empty
+    assert L.mxfp4_gemm(good, good, good, good, good, 4, 4, 96, None) == binding.TORQ_EINVAL  # d % 128
+    assert L.mxfp4_gemm(good, good, good, good, good, -4, 4, 128, None) == binding.TORQ_EINVAL
+    assert L.mxfp4_gemm(None, good, good, good, good, 4, 4, 128, None) == binding.TORQ_EINVAL
+    assert L.mxfp4_gemm(odd, good, good, good, good, 4, 4, 128, None) == binding.TORQ_EALIGN
+    assert L.mxfp4_gemm(good, good, good, good, good, 0, 4, 128, None) == binding.TORQ_OK
+    assert L.mxfp4_gemm(good, good, good, good, good, 4, 0, 128, None) == binding.TORQ_OK
+    assert L.torq_rotate_quantize(None, good, 4, good, good, None) == binding.TORQ_EINVAL
+    assert L.torq_rotate(None, good, 4, good, None) == binding.TORQ_EINVAL
+    assert L.torq_linear(None, good, good, good, good, 4, 4, good, 1 << 20, None) == binding.TORQ_EINVAL
+    assert L.torq_rotation_d(None) == binding.TORQ_EINVAL
+
+
+def test_workspace_size():
+    L = binding.lib()
+    assert L.torq_linear_workspace_bytes(0, 4096) == 0
+    assert L.torq_linear_workspace_bytes(4, 100) == 0
+    # codes M*d/2 and scales M*d/32, each rounded up to 256 bytes
+    assert L.torq_linear_workspace_bytes(64, 4096) == 64 * 2048 + 64 * 128
+    assert L.torq_linear_workspace_bytes(1, 4096) == 2048 + 256
+    assert L.torq_linear_workspace_bytes(3, 32) == 256 + 256
+
+
+@pytest.mark.skipif(os.path.exists("/dev/kfd"), reason="a GPU is present")
+def test_rotation_create_without_device_reports_it():
+    L = binding.lib()
+    h = C.c_void_p()
+    Ri = np.eye(16, dtype=np.float32)
+    Ra = np.eye(32, dtype=np.float32)
+    st = L.torq_rotation_create(C.byref(h), 512, 16, Ri.ctypes.data_as(C.c_void_p), Ra.ctypes.data_as(C.c_void_p))
+    assert st == binding.TORQ_ENODEVICE and not h.value

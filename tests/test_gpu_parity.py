@@ -1,0 +1,276 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on
+the same seeded inputs.
+
+Bars (stated by the benchmark spec):
+  * codes and scales bit-exact when both sides get the same fp32 input;
+  * rotated values within 1e-3 x (row RMS) max-abs;
+  * GEMM outputs within 1e-3 relative Frobenius error of the oracle (bf16 vs bf16).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_19561_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def tq():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2605_19561_amd import binding
+    binding.lib()
+    return binding
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+# ------------------------------------------------------------ quantise -------
+
+def _quant_inputs():
+    rng = np.random.default_rng(123)
+    cases = {}
+    # several tiles and a ragged tail of rows; wide dynamic range across rows
+    z = rng.standard_t(3, size=(257, 4096)) * np.exp(rng.normal(size=(257, 1)) * 4)
+    cases["heavy_tailed"] = z.astype(np.float32)
+    cases["tiny_shape"] = rng.standard_normal((1, 32)).astype(np.float32)
+    cases["ragged"] = (rng.standard_normal((3, 96)) * 1e-3).astype(np.float32)
+    # every rounding boundary of the codebook, at several block scales, both signs
+    grid = np.arange(0, 8 * 64 + 1) / 64.0
+    g = np.concatenate([grid, -grid])
+    g = np.pad(g, (0, (-len(g)) % 32))
+    rows = []
+    for e in (-130, -126, -60, -3, 0, 1, 17, 100, 120):
+        blk = g.reshape(-1, 32).copy()
+        blk[:, 31] = 6.0                      # pins every block's scale to 2^e
+        rows.append(np.ldexp(blk, e).reshape(-1))
+    cases["boundaries"] = np.stack(rows).astype(np.float32)
+    # zero blocks, negative zero, subnormals, one huge element
+    z = np.zeros((4, 128), np.float32)
+    z[0, 5] = -0.0
+    z[1, :32] = 1e-41
+    z[1, 3] = -3e-42
+    z[2, 40] = 3.0e38
+    z[2, 41:64] = -1.0e38
+    z[3, 64:96] = np.ldexp(np.float32(1.5), -127)
+    cases["degenerate"] = z
+    return cases
+
+
+def test_quantize_f32_bit_exact(tq, oracle):
+    for name, z in _quant_inputs().items():
+        want_c, want_s = oracle.quantize(z)
+        got_c, got_s = tq.torq_quantize_f32(torch.from_numpy(z).to(DEV))
+        torch.cuda.synchronize()
+        assert np.array_equal(_np(got_s), want_s), name
+        assert np.array_equal(_np(got_c), want_c), name
+
+
+def test_quantize_f32_empty(tq):
+    z = torch.empty((0, 4096), dtype=torch.float32, device=DEV)
+    c, s = tq.torq_quantize_f32(z)
+    assert c.shape == (0, 2048) and s.shape == (0, 128)
+
+
+# -------------------------------------------------------------- rotate -------
+
+ROT_CASES = [
+    # (M, d, G, nu, outliers, scale)
+    (64, 4096, 128, 3.0, 8, 50.0),       # the tiny configuration
+    (5, 512, 16, 3.0, 2, 50.0),
+    (33, 1024, 32, 3.0, 4, 50.0),
+    (7, 3072, 48, 3.0, 4, 50.0),
+    (19, 2048, 64, 3.0, 4, 50.0),
+    (9, 5120, 80, 3.0, 26, 50.0),        # Qwen3-32B hidden size
+    (6, 3072, 96, 3.0, 8, 50.0),
+    (6, 14336, 112, 3.0, 72, 50.0),      # LLaMA3-8B MLP down input
+    (10, 8192, 128, 2.5, 82, 100.0),     # LLaMA3-70B hidden size, two groups per row
+    (3, 4608, 144, 3.0, 8, 50.0),
+    (5, 5120, 160, 3.0, 26, 50.0),
+    (4, 6656, 208, 3.0, 8, 50.0),
+    (6, 8192, 256, 2.5, 82, 100.0),      # G = B for d = 8192
+]
+
+
+@pytest.mark.parametrize("M,d,G,nu,outl,oscale", ROT_CASES)
+def test_rotate_within_1e3_of_row_rms(tq, oracle, M, d, G, nu, outl, oscale):
+    x = synth.activations(M, d, nu=nu, outliers=outl, outlier_scale=oscale, seed=1000 + G + M)
+    Ri, Ra = synth.rotations(G, seed=77 + G)
+    want = oracle.rotate(synth.bf16_bits(x), G, Ri, Ra).astype(np.float64)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    got = _np(tq.torq_rotate(rot, x.to(DEV))).astype(np.float64)
+    torch.cuda.synchronize()
+    rms = np.sqrt((want ** 2).mean(axis=1, keepdims=True))
+    err = np.abs(got - want) / rms
+    assert err.max() <= 1e-3, (err.max(), np.unravel_index(err.argmax(), err.shape))
+    rot.close()
+
+
+def _boundary_slack(z, scales, tol):
+    """For oracle values z (fp32 [M, d]) and their scale bytes: distance of each normalised
+    magnitude to the nearest rounding boundary of the e2m1 codebook, in normalised units."""
+    s = np.repeat(np.ldexp(1.0, scales.astype(np.int64) - 127), 32, axis=1)
+    a = np.abs(z.astype(np.float64)) / s
+    bounds = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
+    return np.abs(a[..., None] - bounds).min(axis=-1), s
+
+
+@pytest.mark.parametrize("M,d,G,nu,outl,oscale", ROT_CASES[:1] + ROT_CASES[5:6] + ROT_CASES[8:9] + ROT_CASES[12:])
+def test_rotate_quantize_against_oracle(tq, oracle, M, d, G, nu, outl, oscale):
+    x = synth.activations(M, d, nu=nu, outliers=outl, outlier_scale=oscale, seed=2000 + G + M)
+    Ri, Ra = synth.rotations(G, seed=78 + G)
+    xb = synth.bf16_bits(x)
+    z = oracle.rotate(xb, G, Ri, Ra)
+    want_c, want_s = oracle.quantize(z)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    xd = x.to(DEV)
+    got_c, got_s = tq.torq_rotate_quantize(rot, xd)
+    # (1) the fused kernel is its own two halves: same bits as quantising the GPU's rotated values
+    c2, s2 = tq.torq_quantize_f32(tq.torq_rotate(rot, xd))
+    torch.cuda.synchronize()
+    assert torch.equal(got_c, c2) and torch.equal(got_s, s2)
+    got_c, got_s = _np(got_c), _np(got_s)
+    # (2) against the oracle: the GPU's rotated values are within tol of the oracle's, so a scale
+    # may differ only where the oracle's block amax is within tol of a power of two, and a code
+    # only where the oracle's value is within tol of a rounding boundary (or its block's scale moved)
+    rms = np.sqrt((z.astype(np.float64) ** 2).mean(axis=1, keepdims=True))
+    tol = 1e-3 * rms                                            # absolute, per row
+    amax = np.abs(z).reshape(M, d // 32, 32).max(axis=2).astype(np.float64)
+    e = np.floor(np.log2(amax))
+    pow2_dist = np.minimum(np.abs(amax - 2.0 ** e), np.abs(amax - 2.0 ** (e + 1)))
+    sdiff = got_s != want_s
+    assert np.all(pow2_dist[sdiff] <= tol.repeat(d // 32, axis=1)[sdiff])
+    assert sdiff.mean() <= 0.002
+    unpack = lambda c: np.stack([c & 15, c >> 4], axis=-1).reshape(M, d)
+    gc, wc = unpack(got_c), unpack(want_c)
+    cdiff = gc != wc
+    same_scale = ~np.repeat(sdiff, 32, axis=1)
+    slack, s = _boundary_slack(z, want_s, tol)
+    near = slack * s <= np.broadcast_to(tol, slack.shape)
+    tiny = np.abs(z) <= np.broadcast_to(tol, z.shape)          # sign of a value that rounds to +-0
+    assert np.all(near[cdiff & same_scale] | tiny[cdiff & same_scale])
+    assert (cdiff & same_scale).mean() <= 0.005
+    # a flipped code is the neighbouring codeword (or the other zero)
+    step = np.abs((gc & 7).astype(int) - (wc & 7).astype(int))
+    assert np.all(step[cdiff & same_scale] <= 1)
+    rot.close()
+
+
+def test_rotate_quantize_identity_rotation_is_plain_mxfp4(tq, oracle):
+    # R = I: the split-bf16 rotation is exact, so codes and scales must equal the oracle's
+    # quantisation of x itself, bit for bit
+    M, d, G = 37, 4096, 128
+    x = synth.activations(M, d, seed=31)
+    rot = tq.Rotation(d, G, np.eye(G, dtype=np.float32), np.eye(32, dtype=np.float32))
+    got_c, got_s = tq.torq_rotate_quantize(rot, x.to(DEV))
+    torch.cuda.synchronize()
+    want_c, want_s = oracle.quantize(x.to(torch.float32).numpy())
+    assert np.array_equal(_np(got_s), want_s) and np.array_equal(_np(got_c), want_c)
+    rot.close()
+
+
+def test_rotate_quantize_empty_and_single_row(tq, oracle):
+    d, G = 4096, 128
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    c, s = tq.torq_rotate_quantize(rot, torch.empty((0, d), dtype=torch.bfloat16, device=DEV))
+    assert c.numel() == 0 and s.numel() == 0
+    x = synth.activations(1, d, seed=5)
+    z = _np(tq.torq_rotate(rot, x.to(DEV)))
+    want = oracle.rotate(synth.bf16_bits(x), G, Ri, Ra)
+    assert np.abs(z - want).max() <= 1e-3 * np.sqrt((want.astype(np.float64) ** 2).mean())
+    rot.close()
+
+
+# ---------------------------------------------------------------- GEMM -------
+
+def _rel_fro(got_bits, want_bits):
+    g = (got_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    w = (want_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    return np.linalg.norm(g - w) / np.linalg.norm(w)
+
+
+def _bits(t):
+    return _np(t.view(torch.int16)).view(np.uint16)
+
+
+GEMM_RANDOM = [(1, 128, 128), (16, 256, 384), (100, 200, 512), (64, 1024, 4096), (300, 520, 1280), (257, 129, 256)]
+
+
+@pytest.mark.parametrize("M,N,d", GEMM_RANDOM)
+def test_gemm_random_codes(tq, oracle, M, N, d):
+    rng = np.random.default_rng(M * 7 + N)
+    A_q = rng.integers(0, 256, size=(M, d // 2), dtype=np.uint8)
+    W_q = rng.integers(0, 256, size=(N, d // 2), dtype=np.uint8)
+    A_s = rng.integers(118, 136, size=(M, d // 32), dtype=np.uint8)
+    W_s = rng.integers(110, 126, size=(N, d // 32), dtype=np.uint8)
+    want = oracle.gemm(A_q, A_s, W_q, W_s)
+    got = tq.mxfp4_gemm(*(torch.from_numpy(a).to(DEV) for a in (A_q, A_s, W_q, W_s)))
+    torch.cuda.synchronize()
+    assert _rel_fro(_bits(got), want) <= 1e-3
+
+
+def test_gemm_tiny_config_from_oracle_quantised_operands(tq, oracle):
+    # configuration 1: X [64, 4096] heavy-tailed, W [1024, 4096], both rotated + quantised by the oracle
+    x = synth.workload_activations("tiny")
+    w = synth.workload_weights("tiny")
+    Ri, Ra = synth.rotations(128)
+    A_q, A_s = oracle.rotate_quantize(synth.bf16_bits(x), 128, Ri, Ra)
+    W_q, W_s = oracle.rotate_quantize(synth.bf16_bits(w), 128, Ri, Ra)
+    want = oracle.gemm(A_q, A_s, W_q, W_s)
+    got = tq.mxfp4_gemm(*(torch.from_numpy(a).to(DEV) for a in (A_q, A_s, W_q, W_s)))
+    torch.cuda.synchronize()
+    assert _rel_fro(_bits(got), want) <= 1e-3
+
+
+def test_gemm_integer_case_is_exact(tq):
+    # scale bytes 127, codes in {0, +-1, +-2, +-4}: an integer matrix product with |sum| < 2^8:
+    # every output is an integer that bf16 holds exactly
+    rng = np.random.default_rng(4)
+    M, N, d = 70, 130, 128
+    table = {0: 0, 2: 1, 4: 2, 10: -1, 12: -2}
+    keys = np.array(list(table.keys()), np.uint8)
+    ca = rng.choice(keys, size=(M, d)) * (rng.random((M, d)) < 0.05)
+    cw = rng.choice(keys, size=(N, d))
+    A_q = (ca[:, 0::2] | (ca[:, 1::2] << 4)).astype(np.uint8)
+    W_q = (cw[:, 0::2] | (cw[:, 1::2] << 4)).astype(np.uint8)
+    ones = lambda r: np.full((r, d // 32), 127, np.uint8)
+    got = tq.mxfp4_gemm(*(torch.from_numpy(a).to(DEV) for a in (A_q, ones(M), W_q, ones(N))))
+    want = np.vectorize(table.get)(ca).astype(np.int64) @ np.vectorize(table.get)(cw).astype(np.int64).T
+    assert np.abs(want).max() < 256
+    assert np.array_equal(_np(got.to(torch.float64)), want.astype(np.float64))
+
+
+# ---------------------------------------------------------- torq_linear ------
+
+def test_linear_is_rotate_quantize_then_gemm(tq, oracle):
+    x = synth.workload_activations("tiny")
+    w = synth.workload_weights("tiny")
+    G, d = 128, 4096
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    xd, wd = x.to(DEV), w.to(DEV)
+    W_q, W_s = tq.torq_rotate_quantize(rot, wd)               # offline weight preparation
+    out = tq.torq_linear(rot, xd, W_q, W_s)
+    A_q, A_s = tq.torq_rotate_quantize(rot, xd)
+    out2 = tq.mxfp4_gemm(A_q, A_s, W_q, W_s)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    # against the oracle's whole chain.  The two sides may round a few values sitting on a
+    # rounding boundary differently (see test_rotate_quantize_against_oracle); each such flip
+    # perturbs one of 4096 terms by at most its own quantisation error, so the layer output moves
+    # by a few 1e-3 relative at most.  5e-3 is the derived bound, the 1e-3 bar applies to the
+    # GEMM on identical operands (tests above).
+    oA = oracle.rotate_quantize(synth.bf16_bits(x), G, Ri, Ra)
+    oW = oracle.rotate_quantize(synth.bf16_bits(w), G, Ri, Ra)
+    want = oracle.gemm(oA[0], oA[1], oW[0], oW[1])
+    assert _rel_fro(_bits(out), want) <= 5e-3
+    # and the quantised layer approximates the unquantised one (Table 2's direction, no value to hit)
+    plain = (x.to(torch.float64) @ w.to(torch.float64).T).numpy()
+    o = _np(out.to(torch.float64))
+    assert np.linalg.norm(o - plain) / np.linalg.norm(plain) < 0.25
+    rot.close()
