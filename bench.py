@@ -1,0 +1,202 @@
+#!/usr/bin/env python3
+"""Benchmark of the TORQ hot path on one MI355X.
+
+One "step" is one pass of the whole online path over one batch of synthetic
+activations: torq_linear = two-level rotation + MXFP4 quantisation of X
+(Algorithm 3 steps 1-4) followed by the W4A4 MXFP4 GEMM against weights that
+were rotated and quantised offline (Algorithm 3 "Return").  Inputs are resident
+in HBM before the timed region starts.
+
+Prints ONE JSON line.  `value` is the whole step's throughput in TFLOP/s
+(2 M N d per step); `roofline` describes the dominant kernel (the GEMM, against
+the dense fp4 MFMA peak); `roofline_rotate_quant` describes the rotate+quantise
+kernel against the HBM peak (2.53125 algorithmic bytes per element);
+`cpu_baseline` is the CPU oracle timed on a bounded sample in the same run.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+FP4_PEAK_TFLOPS = 10100.0      # MI355X dense fp4 MFMA, published
+BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
+RQ_BYTES_PER_ELEMENT = 2.0 + 0.5 + 1.0 / 32.0   # bf16 in, packed nibble + 1/32 scale byte out
+
+# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a plain
+# copy kernel of known size; see the profiles/ summaries named below.  None until measured.
+MEASURED_TRAFFIC = {
+    "mxfp4_gemm/llama3_70b_up": None,
+    "torq_rotate_quantize/llama3_70b_up": None,
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="llama3_70b_up")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--sweep", action="store_true",
+                    help="also print one line per rotate+quantise bandwidth-sweep shape ([16384, d])")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "re-run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_2605_19561_amd import binding as tq, synth
+
+    assert torch.cuda.is_available(), "bench.py needs the MI355X"
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = synth.WORKLOADS[args.workload]
+    M, d, N = wl["M"], wl["d"], wl["N"]
+    G = synth.default_G(d)
+
+    # ---- synthetic inputs, generated on the device, resident before timing ----
+    x = synth.workload_activations(args.workload, device=dev)
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    w = synth.workload_weights(args.workload, device=dev)
+    W_q, W_s = tq.torq_rotate_quantize(rot, w)          # offline weight preparation
+    del w
+    out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    ws_bytes = tq.torq_linear_workspace_bytes(M, d)
+    workspace = torch.empty((ws_bytes,), dtype=torch.uint8, device=dev)
+    codes = torch.empty((M, d // 2), dtype=torch.uint8, device=dev)
+    scales = torch.empty((M, d // 32), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+
+    def step():
+        tq.torq_linear(rot, x, W_q, W_s, out=out, workspace=workspace)
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+    flops = 2.0 * M * N * d
+    value = flops / (ms_per_step * 1e-3) / 1e12
+
+    # ---- per-kernel durations: HIP events on the stream the kernels run on ----
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    for i in range(args.steps):
+        ev[i][0].record()
+        tq.torq_rotate_quantize(rot, x, codes=codes, scales=scales)
+        ev[i][1].record()
+        tq.mxfp4_gemm(codes, scales, W_q, W_s, out=out)
+        ev[i][2].record()
+    torch.cuda.synchronize()
+    rq_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
+    gemm_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+
+    gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
+    rq_bytes = M * d * RQ_BYTES_PER_ELEMENT
+    rq_gbs = rq_bytes / (rq_ms * 1e-3) / 1e9
+    # split-bf16 contraction actually executed: 2 passes over R_inter (2G flop each), 3 over R_intra (64)
+    rq_mfma_tflops = M * d * (2 * 2 * G + 3 * 64) / (rq_ms * 1e-3) / 1e12
+
+    result = {
+        "metric": "TORQ W4A4 MXFP4 linear layer (rotate + MXFP4 quantise + fp4 GEMM), whole step",
+        "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "fp4 (e2m1 x E8M0) with fp32 accumulation; rotation in split bf16",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: X bf16 [{M}, {d}] Student-t(nu={wl['nu']}) with "
+                               f"{wl['outliers']} outlier channels x{wl['outlier_scale']:g}, G={G}, "
+                               f"W [{N}, {d}] ~ N(0, {wl['wstd']}^2) rotated+quantised offline, out bf16 [{M}, {N}]",
+                   "M": M, "N": N, "d": d, "G": G},
+        "roofline": {"kernel": "mxfp4_gemm", "bound": "mfma", "achieved": round(gemm_tflops, 1),
+                     "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / FP4_PEAK_TFLOPS, 4),
+                     "traffic": MEASURED_TRAFFIC.get(f"mxfp4_gemm/{args.workload}"),
+                     "avg_kernel_ms": round(gemm_ms, 4)},
+        "roofline_rotate_quant": {"kernel": "torq_rotate_quantize", "bound": "hbm", "achieved": round(rq_gbs, 1),
+                                  "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(rq_gbs / HBM_PEAK_GBS, 4),
+                                  "traffic": MEASURED_TRAFFIC.get(f"torq_rotate_quantize/{args.workload}"),
+                                  "avg_kernel_ms": round(rq_ms, 4),
+                                  "mfma_bf16_tflops": round(rq_mfma_tflops, 1),
+                                  "mfma_bf16_frac": round(rq_mfma_tflops / BF16_PEAK_TFLOPS, 4)},
+    }
+
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d)
+
+    print(json.dumps(result), flush=True)
+
+    if args.sweep:
+        for dd in (4096, 8192, 14336, 28672):
+            print(json.dumps(sweep_line(tq, synth, dd, args.steps, args.warmup)), flush=True)
+    rot.close()
+
+
+def cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d):
+    """The CPU oracle, as it stands, on a bounded sample of the same workload: rotate+quantise of the
+    first rows of X, and the reference GEMM on an output corner, each extrapolated to the full step."""
+    import numpy as np
+    import oracle
+    from paper_2605_19561_amd import synth
+
+    rows = min(M, 8192)
+    gm, gn = min(M, 256), min(N, 2048)
+    xb = synth.bf16_bits(x[:rows])
+    t0 = time.perf_counter()
+    A_q, A_s = oracle.rotate_quantize(xb, G, Ri, Ra)
+    t_rq = time.perf_counter() - t0
+    Wq_h = W_q[:gn].cpu().numpy()
+    Ws_h = W_s[:gn].cpu().numpy()
+    t0 = time.perf_counter()
+    oracle.gemm(A_q[:gm], A_s[:gm], Wq_h, Ws_h)
+    t_gemm = time.perf_counter() - t0
+    step_s = t_rq * (M / rows) + t_gemm * (M * N / (gm * gn))
+    return {"value": round(2.0 * M * N * d / step_s / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.threads(),
+            "kind": "oracle",
+            "sample": f"oracle rotate_quantize on the first {rows} rows ({t_rq:.2f} s) + oracle GEMM on a "
+                      f"{gm}x{gn} output corner ({t_gemm:.2f} s), each extrapolated linearly to the full "
+                      f"[{M}, {N}, {d}] step",
+            "rotate_quantize_GBps": round(rows * d * RQ_BYTES_PER_ELEMENT / t_rq / 1e9, 4),
+            "gemm_GFLOPps": round(2.0 * gm * gn * d / t_gemm / 1e9, 3)}
+
+
+def sweep_line(tq, synth, d, steps, warmup):
+    """rotate+quantise alone on X [16384, d] (the memory-bound sweep)."""
+    import torch
+    dev = "cuda:0"
+    M = 16384
+    G = synth.default_G(d)
+    x = synth.activations(M, d, nu=3.0, outliers=round(0.005 * d), outlier_scale=50.0, seed=synth.SEED_BASE + 5,
+                          device=dev)
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    codes = torch.empty((M, d // 2), dtype=torch.uint8, device=dev)
+    scales = torch.empty((M, d // 32), dtype=torch.uint8, device=dev)
+    for _ in range(warmup):
+        tq.torq_rotate_quantize(rot, x, codes=codes, scales=scales)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        tq.torq_rotate_quantize(rot, x, codes=codes, scales=scales)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    gbs = M * d * RQ_BYTES_PER_ELEMENT / (ms * 1e-3) / 1e9
+    rot.close()
+    return {"metric": "torq_rotate_quantize bandwidth", "value": round(gbs, 1), "unit": "GB/s",
+            "config": {"workload": f"sweep: X bf16 [{M}, {d}], G={G}"}, "ms": round(ms, 4),
+            "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+if __name__ == "__main__":
+    main()

@@ -6,40 +6,59 @@
 // on v_mfma_scale_f32_32x32x64_f8f6f4 with both operands in e2m1: one lane holds
 // the 32 codes (16 bytes) of one microscaling block of one row, and one E8M0
 // byte per lane scales exactly that block -- the MX format maps onto the
-// instruction without any repacking of the row-major code and scale arrays.
+// instruction without any repacking of the row-major code arrays.
 //
 // The product is formed transposed (first operand = weight rows n, second =
 // activation rows m), so that an accumulator lane holds runs of four
 // consecutive n for one m and the bf16 epilogue stores 8 bytes per lane.
 //
-// Workgroup = 4 waves (2 x 2); each wave owns a (32*WM) x (32*WN) piece of the
-// output tile.  The k loop advances 128 elements (64 bytes of codes, 4 scale
-// bytes per row) per iteration: global -> registers -> LDS, double-buffered,
-// one barrier per iteration.  LDS rows are padded from 64 to 80 bytes so that
-// the 16-byte operand reads of 8 consecutive rows fall into distinct banks.
+// Workgroup = 4 waves (2 x 2), one per SIMD; each wave owns a (32 WM) x (32 WN)
+// piece of the (64 WM) x (64 WN) output tile and keeps it in accumulator
+// registers.  The k loop advances 256 elements per iteration (128 bytes of
+// codes per row = one full cache line, 8 scale bytes per row):
+//   * codes: buffer loads (tile-relative 32-bit offsets, hardware bounds check
+//     returns zero for rows past M or N) -> registers -> LDS, double-buffered in
+//     LDS; the loads of iteration kt+2 are issued right after the LDS stores of
+//     iteration kt+1;
+//   * scales: staged through LDS in pieces of 16 bytes per row (two iterations)
+//     so that their global loads are not 8-byte gathers;
+//   * operand fragments are read from LDS one k-step (64 elements) ahead of the
+//     MFMAs that use them.
+// LDS rows are 128 bytes; the 16-byte chunk index is XOR-swizzled with
+// (row >> 1) & 7, which makes both the row-wise stores and the column-wise
+// 16-byte fragment reads bank-conflict free.
 #include "torq_device.h"
 #include "torq_internal.h"
 
 namespace torq {
 
-constexpr int GEMM_BK_BYTES = 64;     // 128 e2m1 codes per row per iteration
-constexpr int GEMM_PITCH = 80;        // padded LDS row pitch in bytes
 constexpr int GEMM_GROUP_M = 8;       // tile rows per scheduling group
 
-template <int WM, int WN>
+typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
+
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint32_t bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
+}
+
+template <int WM, int WN, bool FULLK>
 __global__ void __launch_bounds__(256)
 mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A_s,
                   const uint8_t *__restrict__ W_q, const uint8_t *__restrict__ W_s,
                   uint16_t *__restrict__ out, int64_t M, int64_t N, int d,
                   int tiles_m, int tiles_n) {
   constexpr int BM = 64 * WM, BN = 64 * WN;
-  constexpr int A_CHUNKS = BM * 4 / 256, W_CHUNKS = BN * 4 / 256;   // 16-byte chunks per thread
-  constexpr int A_TILE = BM * GEMM_PITCH, W_TILE = BN * GEMM_PITCH;
-  constexpr int STAGE = A_TILE + W_TILE;
+  constexpr int A_CH = BM / 32, W_CH = BN / 32;          // 16-byte code chunks per thread per iteration
+  constexpr int ROWS = BM + BN;
+  static_assert(ROWS % 256 == 0, "every thread stages the same number of scale rows");
+  constexpr int S_CH = ROWS / 256;                       // 16-byte scale chunks per thread per 2 iterations
+  // LDS map: [A stage 0 | A stage 1 | W stage 0 | W stage 1 | scales buffer 0 | scales buffer 1]
+  constexpr int A_STAGE = BM * 128, W_STAGE = BN * 128;
+  constexpr int W_BASE = 2 * A_STAGE;
+  constexpr int S_BASE = W_BASE + 2 * W_STAGE;
+  constexpr int SSTAGE = ROWS * 16;
   extern __shared__ __attribute__((aligned(16))) char lds[];
 
-  // ---- which output tile: spread contiguous runs of tiles over the 8 XCDs, and
-  // walk groups of GEMM_GROUP_M tile rows so that co-resident tiles share operands in L2
+  // ---- which output tile: contiguous runs of tiles per XCD, groups of GEMM_GROUP_M tile rows
   const int total = tiles_m * tiles_n;
   int lid = blockIdx.x;
   if (total % 8 == 0) lid = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
@@ -50,46 +69,72 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
   const int tm = first_m + (lid % width) % gsz;
   const int tn = (lid % width) / gsz;
   const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
+  const int rows_a = (M - m0 < BM) ? (int)(M - m0) : BM;
+  const int rows_w = (N - n0 < BN) ? (int)(N - n0) : BN;
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wy = wave >> 1, wx = wave & 1;
   const int lrow = lane & 31, g = lane >> 5;
-  const int row_bytes = d / 2, srow = d / 32;
+  const int row_bytes = d / 2, srow_bytes = d / 32;
+  const int KT = (d + 255) / 256;
 
-  // ---- global -> LDS staging: thread handles chunk c = tid + i*256; row = c/4, piece = c%4
-  const uint8_t *a_src[A_CHUNKS];
-  const uint8_t *w_src[W_CHUNKS];
-  int a_dst[A_CHUNKS], w_dst[W_CHUNKS];
-#pragma unroll
-  for (int i = 0; i < A_CHUNKS; ++i) {
-    const int c = tid + i * 256, r = c >> 2, p = c & 3;
-    int64_t gr = m0 + r;
-    if (gr >= M) gr = M - 1;                       // clamp: rows past the edge are never stored
-    a_src[i] = A_q + gr * row_bytes + p * 16;
-    a_dst[i] = r * GEMM_PITCH + p * 16;
+  // ---- global side: buffer resources over this tile's rows; reads past them return 0
+  const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(A_q + m0 * row_bytes, (uint32_t)rows_a * row_bytes);
+  const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(W_q + n0 * row_bytes, (uint32_t)rows_w * row_bytes);
+  const __amdgpu_buffer_rsrc_t as_rsrc = make_rsrc(A_s + m0 * srow_bytes, (uint32_t)rows_a * srow_bytes);
+  const __amdgpu_buffer_rsrc_t ws_rsrc = make_rsrc(W_s + n0 * srow_bytes, (uint32_t)rows_w * srow_bytes);
+  // code chunk id = tid + 256 i: row = tid/8 + 32 i, chunk = tid%8
+  const int c_chunk = tid & 7, c_row = tid >> 3;
+  const int c_voff = c_row * row_bytes + c_chunk * 16;   // + 32 i rows + 128 kt via the scalar offset
+  const int c_lds = c_row * 128 + ((c_chunk ^ ((c_row >> 1) & 7)) * 16);   // + 32 i * 128 (same swizzle)
+
+  u32x4 a_regs[A_CH], w_regs[W_CH], s_regs[S_CH];
+
+#define G_LOAD(KT_)                                                                               \
+  {                                                                                               \
+    const int kt_ = (KT_);                                                                        \
+    const bool ok_ = FULLK || (kt_ * 128 + c_chunk * 16 < row_bytes);                             \
+    _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                            \
+      a_regs[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, c_voff, i * 32 * row_bytes + kt_ * 128, 0); \
+      if (!FULLK && !ok_) a_regs[i] = u32x4{0, 0, 0, 0};                                          \
+    }                                                                                             \
+    _Pragma("unroll") for (int i = 0; i < W_CH; ++i) {                                            \
+      w_regs[i] = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, c_voff, i * 32 * row_bytes + kt_ * 128, 0); \
+      if (!FULLK && !ok_) w_regs[i] = u32x4{0, 0, 0, 0};                                          \
+    }                                                                                             \
   }
-#pragma unroll
-  for (int i = 0; i < W_CHUNKS; ++i) {
-    const int c = tid + i * 256, r = c >> 2, p = c & 3;
-    int64_t gr = n0 + r;
-    if (gr >= N) gr = N - 1;
-    w_src[i] = W_q + gr * row_bytes + p * 16;
-    w_dst[i] = A_TILE + r * GEMM_PITCH + p * 16;
+#define L_STORE(P_)                                                                               \
+  {                                                                                               \
+    _Pragma("unroll") for (int i = 0; i < A_CH; ++i)                                              \
+        *reinterpret_cast<u32x4 *>(lds + c_lds + (P_) * A_STAGE + i * 32 * 128) = a_regs[i];      \
+    _Pragma("unroll") for (int i = 0; i < W_CH; ++i)                                              \
+        *reinterpret_cast<u32x4 *>(lds + c_lds + W_BASE + (P_) * W_STAGE + i * 32 * 128) = w_regs[i]; \
   }
-  // ---- scale rows of this lane's operand fragments (read straight from global)
-  const uint8_t *as_src[WM];
-  const uint8_t *ws_src[WN];
-#pragma unroll
-  for (int i = 0; i < WM; ++i) {
-    int64_t gr = m0 + (wy * WM + i) * 32 + lrow;
-    if (gr >= M) gr = M - 1;
-    as_src[i] = A_s + gr * srow;
+  // scales of iterations 2 SC_ and 2 SC_ + 1: 16 bytes per row; staged row id = tid + 256 i
+  // (A rows first, then W rows)
+#define S_LOAD(SC_)                                                                               \
+  {                                                                                               \
+    const int sc_ = (SC_);                                                                        \
+    _Pragma("unroll") for (int i = 0; i < S_CH; ++i) {                                            \
+      const int r_ = tid + 256 * i;                                                               \
+      /* 64 divides BM, so a wave stages either A rows or W rows: a scalar choice */              \
+      const bool is_a_ = __builtin_amdgcn_readfirstlane(r_) < BM;                                 \
+      const int vo_ = (is_a_ ? r_ : r_ - BM) * srow_bytes;                                        \
+      const __amdgpu_buffer_rsrc_t rs_ = is_a_ ? as_rsrc : ws_rsrc;                               \
+      if (FULLK) {                                                                                \
+        s_regs[i] = __builtin_amdgcn_raw_buffer_load_b128(rs_, vo_, sc_ * 16, 0);                 \
+      } else {                                                                                    \
+        _Pragma("unroll") for (int e = 0; e < 4; ++e) {                                           \
+          const uint32_t v_ = __builtin_amdgcn_raw_buffer_load_b32(rs_, vo_, sc_ * 16 + e * 4, 0); \
+          s_regs[i][e] = (sc_ * 16 + e * 4 < srow_bytes) ? v_ : 0x7F7F7F7Fu;                      \
+        }                                                                                         \
+      }                                                                                           \
+    }                                                                                             \
   }
-#pragma unroll
-  for (int i = 0; i < WN; ++i) {
-    int64_t gr = n0 + (wx * WN + i) * 32 + lrow;
-    if (gr >= N) gr = N - 1;
-    ws_src[i] = W_s + gr * srow;
+#define S_STORE(B_)                                                                               \
+  {                                                                                               \
+    _Pragma("unroll") for (int i = 0; i < S_CH; ++i)                                              \
+        *reinterpret_cast<u32x4 *>(lds + S_BASE + (B_) * SSTAGE + (tid + 256 * i) * 16) = s_regs[i]; \
   }
 
   f32x16 acc[WN][WM];
@@ -100,79 +145,127 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
-  uint4 a_regs[A_CHUNKS], w_regs[W_CHUNKS];
-  uint32_t as_regs[WM], ws_regs[WN], as_next[WM], ws_next[WN];
-  auto g_load = [&](int kt) {
+  // ---- fragment addressing.  Lane (lrow, g) reads chunk 2 ks + g of rows lrow + 32 i of its
+  // wave's strip; (row >> 1) & 7 is the same for all those rows, so one swizzled offset per ks
+  // serves every fragment and the row strips become immediate offsets.
+  const int f_sw = (lrow >> 1) & 7;
+  int fa_off[4], fw_off[4];
 #pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) a_regs[i] = *reinterpret_cast<const uint4 *>(a_src[i] + kt * GEMM_BK_BYTES);
-#pragma unroll
-    for (int i = 0; i < W_CHUNKS; ++i) w_regs[i] = *reinterpret_cast<const uint4 *>(w_src[i] + kt * GEMM_BK_BYTES);
-#pragma unroll
-    for (int i = 0; i < WM; ++i) as_next[i] = *reinterpret_cast<const uint32_t *>(as_src[i] + kt * 4);
-#pragma unroll
-    for (int i = 0; i < WN; ++i) ws_next[i] = *reinterpret_cast<const uint32_t *>(ws_src[i] + kt * 4);
-  };
-  auto l_store = [&](int buf) {
-    char *base = lds + buf * STAGE;
-#pragma unroll
-    for (int i = 0; i < A_CHUNKS; ++i) *reinterpret_cast<uint4 *>(base + a_dst[i]) = a_regs[i];
-#pragma unroll
-    for (int i = 0; i < W_CHUNKS; ++i) *reinterpret_cast<uint4 *>(base + w_dst[i]) = w_regs[i];
-  };
-
-  const int KT = d / 128;
-  g_load(0);
-  l_store(0);
-#pragma unroll
-  for (int i = 0; i < WM; ++i) as_regs[i] = as_next[i] >> (8 * g);
-#pragma unroll
-  for (int i = 0; i < WN; ++i) ws_regs[i] = ws_next[i] >> (8 * g);
-  __syncthreads();
-
-  for (int kt = 0; kt < KT; ++kt) {
-    const int buf = kt & 1;
-    const bool have_next = kt + 1 < KT;
-    if (have_next) g_load(kt + 1);
-
-    const char *sa = lds + buf * STAGE + (wy * WM * 32 + lrow) * GEMM_PITCH + g * 16;
-    const char *sw = lds + buf * STAGE + A_TILE + (wx * WN * 32 + lrow) * GEMM_PITCH + g * 16;
-#pragma unroll
-    for (int ks = 0; ks < 2; ++ks) {
-      i32x8 af[WM], wf[WN];
-#pragma unroll
-      for (int i = 0; i < WM; ++i) {
-        const i32x4 v = *reinterpret_cast<const i32x4 *>(sa + i * 32 * GEMM_PITCH + ks * 32);
-        af[i] = i32x8{v[0], v[1], v[2], v[3], 0, 0, 0, 0};
-      }
-#pragma unroll
-      for (int j = 0; j < WN; ++j) {
-        const i32x4 v = *reinterpret_cast<const i32x4 *>(sw + j * 32 * GEMM_PITCH + ks * 32);
-        wf[j] = i32x8{v[0], v[1], v[2], v[3], 0, 0, 0, 0};
-      }
-#pragma unroll
-      for (int j = 0; j < WN; ++j)
-#pragma unroll
-        for (int i = 0; i < WM; ++i) {
-          // lane (row, g) of a fragment carries block 2*ks + g of this iteration; its scale
-          // byte sits in byte 2*ks of the lane-shifted scale dword
-          if (ks == 0)
-            acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf[j], af[i], acc[j][i], 4, 4, 0,
-                                                                        ws_regs[j], 0, as_regs[i]);
-          else
-            acc[j][i] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wf[j], af[i], acc[j][i], 4, 4, 2,
-                                                                        ws_regs[j], 2, as_regs[i]);
-        }
-    }
-
-    if (have_next) {
-      l_store(buf ^ 1);
-#pragma unroll
-      for (int i = 0; i < WM; ++i) as_regs[i] = as_next[i] >> (8 * g);
-#pragma unroll
-      for (int i = 0; i < WN; ++i) ws_regs[i] = ws_next[i] >> (8 * g);
-    }
-    __syncthreads();
+  for (int ks = 0; ks < 4; ++ks) {
+    const int ch = ((2 * ks + g) ^ f_sw) * 16;
+    fa_off[ks] = (wy * WM * 32 + lrow) * 128 + ch;
+    fw_off[ks] = W_BASE + (wx * WN * 32 + lrow) * 128 + ch;
   }
+  const int sa_off = S_BASE + (wy * WM * 32 + lrow) * 16;
+  const int sw_off = S_BASE + (BM + wx * WN * 32 + lrow) * 16;
+
+  i32x4 fa[2][WM], fw[2][WN];
+  uint32_t sa[WM][2], sw[WN][2];                   // [frag][lo/hi dword], already shifted by 8 g
+
+#define F_LOAD(SET_, P_, KS_)                                                                     \
+  {                                                                                               \
+    _Pragma("unroll") for (int i = 0; i < WM; ++i)                                                \
+        fa[SET_][i] = *reinterpret_cast<const i32x4 *>(lds + fa_off[KS_] + (P_) * A_STAGE + i * 32 * 128); \
+    _Pragma("unroll") for (int j = 0; j < WN; ++j)                                                \
+        fw[SET_][j] = *reinterpret_cast<const i32x4 *>(lds + fw_off[KS_] + (P_) * W_STAGE + j * 32 * 128); \
+  }
+  // the 8 scale bytes of a row for iteration KT_: dword H_ = 0 (blocks 0-3) or 1 (blocks 4-7)
+#define SC_LOAD(H_, KT_)                                                                          \
+  {                                                                                               \
+    const int o_ = (((KT_) >> 1) & 1) * SSTAGE + ((KT_) & 1) * 8 + (H_) * 4;                      \
+    _Pragma("unroll") for (int i = 0; i < WM; ++i)                                                \
+        sa[i][H_] = *reinterpret_cast<const uint32_t *>(lds + sa_off + o_ + i * 32 * 16) >> (8 * g); \
+    _Pragma("unroll") for (int j = 0; j < WN; ++j)                                                \
+        sw[j][H_] = *reinterpret_cast<const uint32_t *>(lds + sw_off + o_ + j * 32 * 16) >> (8 * g); \
+  }
+  // lane (row, g) of a fragment carries block 2 ks + g of the iteration: byte (2 ks) & 3 of the
+  // shifted dword ks >> 1
+#define MFMA_ONE(SET_, KS_, J_, I_)                                                               \
+  acc[J_][I_] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(                                  \
+      i32x8{fw[SET_][J_][0], fw[SET_][J_][1], fw[SET_][J_][2], fw[SET_][J_][3], 0, 0, 0, 0},      \
+      i32x8{fa[SET_][I_][0], fa[SET_][I_][1], fa[SET_][I_][2], fa[SET_][I_][3], 0, 0, 0, 0},      \
+      acc[J_][I_], 4, 4, ((KS_) & 1) * 2, sw[J_][(KS_) >> 1], ((KS_) & 1) * 2, sa[I_][(KS_) >> 1]);
+#define MFMA_HALF(SET_, KS_, J0_, J1_)                                                            \
+  _Pragma("unroll") for (int j = (J0_); j < (J1_); ++j)                                           \
+      _Pragma("unroll") for (int i = 0; i < WM; ++i) { MFMA_ONE(SET_, KS_, j, i) }
+
+  // ---- prologue
+  G_LOAD(0);
+  S_LOAD(0);
+  L_STORE(0);
+  S_STORE(0);
+  if (KT > 1) G_LOAD(1);
+  __syncthreads();
+  SC_LOAD(0, 0);
+  F_LOAD(0, 0, 0);
+
+  // One k iteration is two scheduling regions, split by the workgroup barrier.  Each region ends
+  // with a sched_group_barrier pipeline that tells the machine scheduler how to interleave MFMAs
+  // with LDS and buffer traffic (left alone it hoists every load of the iteration to the top and
+  // runs out of registers).  P = kt & 1 is a literal so that the LDS stage and the scale staging
+  // phase are compile-time; H1 / H2 say whether iterations kt+1 and kt+2 exist.
+#define SGB(MASK_, N_) __builtin_amdgcn_sched_group_barrier(MASK_, N_, 0);
+#define SG_MFMA 0x008
+#define SG_VMEM_RD 0x020
+#define SG_DS_RD 0x100
+#define SG_DS_WR 0x200
+#define ITER(P, KT_, H1, H2)                                                                      \
+  {                                                                                               \
+    const int kt_i = (KT_);                                                                       \
+    SC_LOAD(1, kt_i);                       /* hi scale dword; the lo one came in after the barrier */ \
+    F_LOAD(1, P, 1);                                                                              \
+    MFMA_HALF(0, 0, 0, WN);                                                                       \
+    F_LOAD(0, P, 2);                                                                              \
+    MFMA_HALF(1, 1, 0, WN);                                                                       \
+    F_LOAD(1, P, 3);                                                                              \
+    MFMA_HALF(0, 2, 0, WN);                                                                       \
+    if (H1) {                                                                                     \
+      L_STORE((P) ^ 1);                                                                           \
+      if ((P) == 1) S_STORE(((kt_i + 1) >> 1) & 1);                                               \
+    }                                                                                             \
+    MFMA_HALF(1, 3, 0, WN / 2);                                                                   \
+    /* k-step 0: its MFMAs hide the hi-scale reads and the fragment reads of k-step 1 */          \
+    _Pragma("unroll") for (int n_ = 0; n_ < WM + WN + 4; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 1) } \
+    SGB(SG_MFMA, WM * WN - (WM + WN + 4) > 0 ? WM * WN - (WM + WN + 4) : 0)                       \
+    /* k-steps 1 and 2: two MFMAs per fragment read of the following k-step */                    \
+    _Pragma("unroll") for (int n_ = 0; n_ < 2 * (WM + WN); ++n_) { SGB(SG_MFMA, WM * WN / (WM + WN)) SGB(SG_DS_RD, 1) } \
+    /* first half of k-step 3: LDS stores of the next stage */                                    \
+    _Pragma("unroll") for (int n_ = 0; n_ < WM * WN / 2; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_WR, 3) } \
+    __syncthreads();                                                                              \
+    if (H1) {                                                                                     \
+      SC_LOAD(0, kt_i + 1);                                                                       \
+      F_LOAD(0, (P) ^ 1, 0);                                                                      \
+    }                                                                                             \
+    if (H2) {                                                                                     \
+      G_LOAD(kt_i + 2);                                                                           \
+      if ((P) == 0) S_LOAD((kt_i + 2) >> 1);                                                      \
+    }                                                                                             \
+    MFMA_HALF(1, 3, WN / 2, WN);                                                                  \
+    /* second half of k-step 3: fragment and lo-scale reads of the next iteration first, then   \
+       the buffer loads of the iteration after it */                                              \
+    _Pragma("unroll") for (int n_ = 0; n_ < WM * WN / 2; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 2) SGB(SG_VMEM_RD, 3) } \
+    __builtin_amdgcn_sched_barrier(0);                                                            \
+  }
+  // steady state: both the next LDS stage and the global loads two iterations ahead exist
+  int kt = 0;
+  for (; kt + 3 < KT; kt += 2) {
+    ITER(0, kt, true, true);
+    ITER(1, kt + 1, true, true);
+  }
+  // tail: 1, 2 or 3 iterations left, kt even
+  const int left = KT - kt;
+  if (left == 1) {
+    ITER(0, kt, false, false);
+  } else if (left == 2) {
+    ITER(0, kt, true, false);
+    ITER(1, kt + 1, false, false);
+  } else {
+    ITER(0, kt, true, true);
+    ITER(1, kt + 1, true, false);
+    ITER(0, kt + 2, false, false);
+  }
+#undef ITER
+#undef SGB
 
   // ---- epilogue: acc[j][i][r] = out[m = .. + lane%32][n = .. + 8*(r/4) + 4*(lane/32) + r%4]
 #pragma unroll
@@ -200,17 +293,25 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
       }
     }
   }
+#undef G_LOAD
+#undef L_STORE
+#undef S_LOAD
+#undef S_STORE
+#undef F_LOAD
+#undef SC_LOAD
+#undef MFMA_ONE
+#undef MFMA_HALF
 }
 
-template <int WM, int WN>
+template <int WM, int WN, bool FULLK>
 static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                               const uint8_t *W_s, void *out, int64_t M, int64_t N, int d,
                               hipStream_t stream) {
   constexpr int BM = 64 * WM, BN = 64 * WN;
   const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   if (tiles_m * tiles_n > 0x7FFFFFFF) return hipErrorInvalidValue;
-  const size_t lds_bytes = 2 * (size_t)(BM + BN) * GEMM_PITCH;
-  auto kern = mxfp4_gemm_kernel<WM, WN>;
+  const size_t lds_bytes = 2 * (size_t)(BM + BN) * (128 + 16);
+  auto kern = mxfp4_gemm_kernel<WM, WN, FULLK>;
   if (lds_bytes > 64 * 1024) {
     hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
                                        hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
@@ -224,10 +325,19 @@ static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint
 hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                              const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, int d,
                              hipStream_t stream) {
-  // large tile when it still gives every CU work; small tile otherwise
+  // a tile's rows must be addressable with 32-bit offsets: 256 rows of d/2 bytes
+  if ((int64_t)d * 128 >= 0x7FFFFFFF) return hipErrorInvalidValue;
+  // large tile when it still gives every CU work; small tile otherwise.  The fast k loop needs
+  // whole 512-element pieces per row and 16-byte aligned scale rows.
+  const bool fullk = (d % 512 == 0) && ((reinterpret_cast<uintptr_t>(A_s) & 15u) == 0) &&
+                     ((reinterpret_cast<uintptr_t>(W_s) & 15u) == 0);
   const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-  if (big_tiles >= 256) return launch_tile<4, 4>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
-  return launch_tile<2, 2>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
+  if (big_tiles >= 256) {
+    return fullk ? launch_tile<4, 4, true>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream)
+                 : launch_tile<4, 4, false>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
+  }
+  return fullk ? launch_tile<2, 2, true>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream)
+               : launch_tile<2, 2, false>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
 }
 
 }  // namespace torq
