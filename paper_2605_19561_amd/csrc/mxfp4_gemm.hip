@@ -77,6 +77,11 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
   const int lrow = lane & 31, g = lane >> 5;
   const int row_bytes = d / 2, srow_bytes = d / 32;
   const int KT = (d + 255) / 256;
+  // Every workgroup walks k from its own (even) starting iteration and wraps around: rows of a
+  // tile are d/2 bytes apart, a power of two for the usual d, so workgroups that sit at the same k
+  // would send all their loads to the same few L2 channels.
+  const int kt0 = FULLK ? 2 * (lid % (KT / 2)) : 0;
+#define PHYS_KT(KT_) (FULLK ? (((KT_) + kt0) % KT) : (KT_))
 
   // ---- global side: buffer resources over this tile's rows; reads past them return 0
   const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(A_q + m0 * row_bytes, (uint32_t)rows_a * row_bytes);
@@ -92,7 +97,7 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
 
 #define G_LOAD(KT_)                                                                               \
   {                                                                                               \
-    const int kt_ = (KT_);                                                                        \
+    const int kt_ = PHYS_KT(KT_);                                                                 \
     const bool ok_ = FULLK || (kt_ * 128 + c_chunk * 16 < row_bytes);                             \
     _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                            \
       a_regs[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, c_voff, i * 32 * row_bytes + kt_ * 128, 0); \
@@ -103,11 +108,11 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
       if (!FULLK && !ok_) w_regs[i] = u32x4{0, 0, 0, 0};                                          \
     }                                                                                             \
   }
-#define L_STORE(P_)                                                                               \
+#define L_STORE(P_, Q_)                         /* quarter Q_ (0..3) of the stage's chunks */    \
   {                                                                                               \
-    _Pragma("unroll") for (int i = 0; i < A_CH; ++i)                                              \
+    _Pragma("unroll") for (int i = (Q_) * A_CH / 4; i < ((Q_) + 1) * A_CH / 4; ++i)               \
         *reinterpret_cast<u32x4 *>(lds + c_lds + (P_) * A_STAGE + i * 32 * 128) = a_regs[i];      \
-    _Pragma("unroll") for (int i = 0; i < W_CH; ++i)                                              \
+    _Pragma("unroll") for (int i = (Q_) * W_CH / 4; i < ((Q_) + 1) * W_CH / 4; ++i)               \
         *reinterpret_cast<u32x4 *>(lds + c_lds + W_BASE + (P_) * W_STAGE + i * 32 * 128) = w_regs[i]; \
   }
   // scales of iterations 2 SC_ and 2 SC_ + 1: 16 bytes per row; staged row id = tid + 256 i
@@ -191,10 +196,13 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
 
   // ---- prologue
   G_LOAD(0);
-  S_LOAD(0);
-  L_STORE(0);
+  S_LOAD(PHYS_KT(0) >> 1);
+  L_STORE(0, 0);
+  L_STORE(0, 1);
+  L_STORE(0, 2);
+  L_STORE(0, 3);
   S_STORE(0);
-  if (KT > 1) G_LOAD(1);
+  G_LOAD(1);
   __syncthreads();
   SC_LOAD(0, 0);
   F_LOAD(0, 0, 0);
@@ -203,97 +211,109 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
   // with a sched_group_barrier pipeline that tells the machine scheduler how to interleave MFMAs
   // with LDS and buffer traffic (left alone it hoists every load of the iteration to the top and
   // runs out of registers).  P = kt & 1 is a literal so that the LDS stage and the scale staging
-  // phase are compile-time; H1 / H2 say whether iterations kt+1 and kt+2 exist.
+  // phase are compile-time.  Every iteration runs the same code: the last two also load and stage
+  // data that nobody will read (wrapped around to a valid k), which is cheaper than separate tail
+  // code.  The LDS stores of the next stage are spread over k-steps 1, 2 and 3 so that they do
+  // not arrive at the LDS in one burst in front of the barrier.
 #define SGB(MASK_, N_) __builtin_amdgcn_sched_group_barrier(MASK_, N_, 0);
 #define SG_MFMA 0x008
 #define SG_VMEM_RD 0x020
 #define SG_DS_RD 0x100
 #define SG_DS_WR 0x200
-#define ITER(P, KT_, H1, H2)                                                                      \
+#define ITER(P, KT_)                                                                              \
   {                                                                                               \
     const int kt_i = (KT_);                                                                       \
     SC_LOAD(1, kt_i);                       /* hi scale dword; the lo one came in after the barrier */ \
     F_LOAD(1, P, 1);                                                                              \
     MFMA_HALF(0, 0, 0, WN);                                                                       \
     F_LOAD(0, P, 2);                                                                              \
+    L_STORE((P) ^ 1, 0);                                                                          \
     MFMA_HALF(1, 1, 0, WN);                                                                       \
     F_LOAD(1, P, 3);                                                                              \
+    L_STORE((P) ^ 1, 1);                                                                          \
     MFMA_HALF(0, 2, 0, WN);                                                                       \
-    if (H1) {                                                                                     \
-      L_STORE((P) ^ 1);                                                                           \
-      if ((P) == 1) S_STORE(((kt_i + 1) >> 1) & 1);                                               \
-    }                                                                                             \
+    L_STORE((P) ^ 1, 2);                                                                          \
+    L_STORE((P) ^ 1, 3);                                                                          \
+    if ((P) == 1) S_STORE(((kt_i + 1) >> 1) & 1);                                                 \
     MFMA_HALF(1, 3, 0, WN / 2);                                                                   \
     /* k-step 0: its MFMAs hide the hi-scale reads and the fragment reads of k-step 1 */          \
     _Pragma("unroll") for (int n_ = 0; n_ < WM + WN + 4; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 1) } \
     SGB(SG_MFMA, WM * WN - (WM + WN + 4) > 0 ? WM * WN - (WM + WN + 4) : 0)                       \
-    /* k-steps 1 and 2: two MFMAs per fragment read of the following k-step */                    \
-    _Pragma("unroll") for (int n_ = 0; n_ < 2 * (WM + WN); ++n_) { SGB(SG_MFMA, WM * WN / (WM + WN)) SGB(SG_DS_RD, 1) } \
-    /* first half of k-step 3: LDS stores of the next stage */                                    \
-    _Pragma("unroll") for (int n_ = 0; n_ < WM * WN / 2; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_WR, 3) } \
+    /* k-steps 1 and 2: per two MFMAs one fragment read of the next k-step, and a quarter of the \
+       next stage's LDS stores along the way */                                                   \
+    _Pragma("unroll") for (int n_ = 0; n_ < 2; ++n_) {                                            \
+      _Pragma("unroll") for (int q_ = 0; q_ < WM + WN; ++q_) {                                    \
+        SGB(SG_MFMA, WM * WN / (WM + WN)) SGB(SG_DS_RD, 1)                                        \
+        if (q_ % 2 == 1 || (A_CH + W_CH) / 4 >= WM + WN) SGB(SG_DS_WR, 1)                         \
+      }                                                                                           \
+    }                                                                                             \
+    /* first half of k-step 3: the rest of the LDS stores */                                      \
+    _Pragma("unroll") for (int n_ = 0; n_ < WM * WN / 2; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_WR, 2) } \
     __syncthreads();                                                                              \
-    if (H1) {                                                                                     \
-      SC_LOAD(0, kt_i + 1);                                                                       \
-      F_LOAD(0, (P) ^ 1, 0);                                                                      \
-    }                                                                                             \
-    if (H2) {                                                                                     \
-      G_LOAD(kt_i + 2);                                                                           \
-      if ((P) == 0) S_LOAD((kt_i + 2) >> 1);                                                      \
-    }                                                                                             \
+    SC_LOAD(0, kt_i + 1);                                                                         \
+    F_LOAD(0, (P) ^ 1, 0);                                                                        \
+    G_LOAD(kt_i + 2);                                                                             \
+    if ((P) == 0) S_LOAD(PHYS_KT(kt_i + 2) >> 1);                                                 \
     MFMA_HALF(1, 3, WN / 2, WN);                                                                  \
     /* second half of k-step 3: fragment and lo-scale reads of the next iteration first, then   \
        the buffer loads of the iteration after it */                                              \
     _Pragma("unroll") for (int n_ = 0; n_ < WM * WN / 2; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 2) SGB(SG_VMEM_RD, 3) } \
     __builtin_amdgcn_sched_barrier(0);                                                            \
   }
-  // steady state: both the next LDS stage and the global loads two iterations ahead exist
-  int kt = 0;
-  for (; kt + 3 < KT; kt += 2) {
-    ITER(0, kt, true, true);
-    ITER(1, kt + 1, true, true);
-  }
-  // tail: 1, 2 or 3 iterations left, kt even
-  const int left = KT - kt;
-  if (left == 1) {
-    ITER(0, kt, false, false);
-  } else if (left == 2) {
-    ITER(0, kt, true, false);
-    ITER(1, kt + 1, false, false);
-  } else {
-    ITER(0, kt, true, true);
-    ITER(1, kt + 1, true, false);
-    ITER(0, kt + 2, false, false);
+  // KTE = KT rounded up to even; an odd KT (only without FULLK) gets one all-zero iteration
+  const int KTE = (KT + 1) & ~1;
+  for (int kt = 0; kt < KTE; kt += 2) {
+    ITER(0, kt);
+    ITER(1, kt + 1);
   }
 #undef ITER
 #undef SGB
 
-  // ---- epilogue: acc[j][i][r] = out[m = .. + lane%32][n = .. + 8*(r/4) + 4*(lane/32) + r%4]
+  // ---- epilogue.  acc[j][i][r] = out[m = .. + lane%32][n = .. + 8*(r/4) + 4*(lane/32) + r%4]:
+  // a lane holds 8-byte pieces of one output row.  Storing those directly makes every 128-byte
+  // line of the output arrive in 16 separate partial writes, so the wave first transposes its
+  // piece through LDS (free after the last barrier of the k loop; each wave uses a private
+  // region) and then stores 16 bytes per lane with 8 adjacent lanes covering one full line.
+  {
+    constexpr int ROW_E = 64 * WN;               // bytes of one output row of this wave's piece
+    constexpr int PITCH_E = ROW_E + 16;
+    constexpr int CH_ROW = ROW_E / 16;           // 16-byte chunks per row
+    char *const ep = lds + wave * (32 * WM) * PITCH_E;
 #pragma unroll
-  for (int i = 0; i < WM; ++i) {
-    const int64_t m = m0 + (wy * WM + i) * 32 + lrow;
-    if (m >= M) continue;
+    for (int i = 0; i < WM; ++i)
 #pragma unroll
-    for (int j = 0; j < WN; ++j) {
-      const int64_t nb = n0 + (wx * WN + j) * 32 + 4 * g;
+      for (int j = 0; j < WN; ++j)
 #pragma unroll
-      for (int rr = 0; rr < 4; ++rr) {
-        const int64_t n = nb + 8 * rr;
-        bf16x4 v;
+        for (int rr = 0; rr < 4; ++rr) {
+          bf16x4 v;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) v[e] = (__bf16)acc[j][i][4 * rr + e];
-        uint16_t *dst = out + m * N + n;
-        if (n + 3 < N && ((N & 3) == 0)) {
-          *reinterpret_cast<bf16x4 *>(dst) = v;
-        } else {
-          const uint64_t bits = __builtin_bit_cast(uint64_t, v);
+          for (int e = 0; e < 4; ++e) v[e] = (__bf16)acc[j][i][4 * rr + e];
+          *reinterpret_cast<bf16x4 *>(ep + (i * 32 + lrow) * PITCH_E + (32 * j + 8 * rr + 4 * g) * 2) = v;
+        }
+    const bool vec_ok = (N & 7) == 0;
 #pragma unroll
-          for (int e = 0; e < 4; ++e)
-            if (n + e < N) dst[e] = (uint16_t)(bits >> (16 * e));
+    for (int i = 0; i < WM; ++i)
+#pragma unroll
+      for (int t = 0; t < 32 * CH_ROW / 64; ++t) {
+        const int idx = t * 64 + lane;
+        const int row = idx / CH_ROW, ch = idx % CH_ROW;
+        const u32x4 v = *reinterpret_cast<const u32x4 *>(ep + (i * 32 + row) * PITCH_E + ch * 16);
+        const int64_t m = m0 + (wy * WM + i) * 32 + row;
+        const int64_t n = n0 + wx * WN * 32 + ch * 8;
+        if (m < M) {
+          uint16_t *dst = out + m * N + n;
+          if (vec_ok && n + 8 <= N) {
+            *reinterpret_cast<u32x4 *>(dst) = v;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+              if (n + e < N) dst[e] = (uint16_t)(v[e >> 1] >> (16 * (e & 1)));
+          }
         }
       }
-    }
   }
 #undef G_LOAD
+#undef PHYS_KT
 #undef L_STORE
 #undef S_LOAD
 #undef S_STORE
@@ -313,9 +333,14 @@ static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint
   const size_t lds_bytes = 2 * (size_t)(BM + BN) * (128 + 16);
   auto kern = mxfp4_gemm_kernel<WM, WN, FULLK>;
   if (lds_bytes > 64 * 1024) {
-    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-    if (e != hipSuccess) return e;
+    // raise the dynamic LDS limit once per process and kernel variant (the call is slow)
+    static bool raised = false;
+    if (!raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(kern),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+      if (e != hipSuccess) return e;
+      raised = true;
+    }
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), lds_bytes, stream, A_q, A_s, W_q,
                      W_s, reinterpret_cast<uint16_t *>(out), M, N, d, (int)tiles_m, (int)tiles_n);
