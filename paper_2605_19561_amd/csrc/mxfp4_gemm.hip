@@ -77,10 +77,8 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
   const int lrow = lane & 31, g = lane >> 5;
   const int row_bytes = d / 2, srow_bytes = d / 32;
   const int KT = (d + 255) / 256;
-  // Every workgroup walks k from its own (even) starting iteration and wraps around: rows of a
-  // tile are d/2 bytes apart, a power of two for the usual d, so workgroups that sit at the same k
-  // would send all their loads to the same few L2 channels.
-  const int kt0 = FULLK ? 2 * (lid % (KT / 2)) : 0;
+  // Iterations past the end (the pipeline always loads two ahead) wrap around to a valid k.
+  const int kt0 = 0;
 #define PHYS_KT(KT_) (FULLK ? (((KT_) + kt0) % KT) : (KT_))
 
   // ---- global side: buffer resources over this tile's rows; reads past them return 0
@@ -95,19 +93,20 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
 
   u32x4 a_regs[A_CH], w_regs[W_CH], s_regs[S_CH];
 
-#define G_LOAD(KT_)                                                                               \
+#define G_LOAD_Q(KT_, Q_)                       /* quarter Q_ (0..3) of an iteration's chunks */ \
   {                                                                                               \
     const int kt_ = PHYS_KT(KT_);                                                                 \
     const bool ok_ = FULLK || (kt_ * 128 + c_chunk * 16 < row_bytes);                             \
-    _Pragma("unroll") for (int i = 0; i < A_CH; ++i) {                                            \
+    _Pragma("unroll") for (int i = (Q_) * A_CH / 4; i < ((Q_) + 1) * A_CH / 4; ++i) {             \
       a_regs[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, c_voff, i * 32 * row_bytes + kt_ * 128, 0); \
       if (!FULLK && !ok_) a_regs[i] = u32x4{0, 0, 0, 0};                                          \
     }                                                                                             \
-    _Pragma("unroll") for (int i = 0; i < W_CH; ++i) {                                            \
+    _Pragma("unroll") for (int i = (Q_) * W_CH / 4; i < ((Q_) + 1) * W_CH / 4; ++i) {             \
       w_regs[i] = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, c_voff, i * 32 * row_bytes + kt_ * 128, 0); \
       if (!FULLK && !ok_) w_regs[i] = u32x4{0, 0, 0, 0};                                          \
     }                                                                                             \
   }
+#define G_LOAD(KT_) { G_LOAD_Q(KT_, 0) G_LOAD_Q(KT_, 1) G_LOAD_Q(KT_, 2) G_LOAD_Q(KT_, 3) }
 #define L_STORE(P_, Q_)                         /* quarter Q_ (0..3) of the stage's chunks */    \
   {                                                                                               \
     _Pragma("unroll") for (int i = (Q_) * A_CH / 4; i < ((Q_) + 1) * A_CH / 4; ++i)               \
@@ -228,9 +227,11 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
     MFMA_HALF(0, 0, 0, WN);                                                                       \
     F_LOAD(0, P, 2);                                                                              \
     L_STORE((P) ^ 1, 0);                                                                          \
+    G_LOAD_Q(kt_i + 2, 0);                                                                        \
     MFMA_HALF(1, 1, 0, WN);                                                                       \
     F_LOAD(1, P, 3);                                                                              \
     L_STORE((P) ^ 1, 1);                                                                          \
+    G_LOAD_Q(kt_i + 2, 1);                                                                        \
     MFMA_HALF(0, 2, 0, WN);                                                                       \
     L_STORE((P) ^ 1, 2);                                                                          \
     L_STORE((P) ^ 1, 3);                                                                          \
@@ -239,12 +240,13 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
     /* k-step 0: its MFMAs hide the hi-scale reads and the fragment reads of k-step 1 */          \
     _Pragma("unroll") for (int n_ = 0; n_ < WM + WN + 4; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 1) } \
     SGB(SG_MFMA, WM * WN - (WM + WN + 4) > 0 ? WM * WN - (WM + WN + 4) : 0)                       \
-    /* k-steps 1 and 2: per two MFMAs one fragment read of the next k-step, and a quarter of the \
-       next stage's LDS stores along the way */                                                   \
+    /* k-steps 1 and 2: per two MFMAs one fragment read of the next k-step; a quarter of the     \
+       next stage's LDS stores along the way, each followed by the buffer loads that refill the  \
+       staging registers it freed (for the iteration after next) */                               \
     _Pragma("unroll") for (int n_ = 0; n_ < 2; ++n_) {                                            \
       _Pragma("unroll") for (int q_ = 0; q_ < WM + WN; ++q_) {                                    \
         SGB(SG_MFMA, WM * WN / (WM + WN)) SGB(SG_DS_RD, 1)                                        \
-        if (q_ % 2 == 1 || (A_CH + W_CH) / 4 >= WM + WN) SGB(SG_DS_WR, 1)                         \
+        if (q_ % 2 == 1) { SGB(SG_DS_WR, 1) SGB(SG_VMEM_RD, 1) }                                  \
       }                                                                                           \
     }                                                                                             \
     /* first half of k-step 3: the rest of the LDS stores */                                      \
@@ -252,12 +254,13 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
     __syncthreads();                                                                              \
     SC_LOAD(0, kt_i + 1);                                                                         \
     F_LOAD(0, (P) ^ 1, 0);                                                                        \
-    G_LOAD(kt_i + 2);                                                                             \
+    G_LOAD_Q(kt_i + 2, 2);                                                                        \
+    G_LOAD_Q(kt_i + 2, 3);                                                                        \
     if ((P) == 0) S_LOAD(PHYS_KT(kt_i + 2) >> 1);                                                 \
     MFMA_HALF(1, 3, WN / 2, WN);                                                                  \
     /* second half of k-step 3: fragment and lo-scale reads of the next iteration first, then   \
-       the buffer loads of the iteration after it */                                              \
-    _Pragma("unroll") for (int n_ = 0; n_ < WM * WN / 2; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 2) SGB(SG_VMEM_RD, 3) } \
+       the remaining buffer loads */                                                              \
+    _Pragma("unroll") for (int n_ = 0; n_ < WM * WN / 2; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 2) SGB(SG_VMEM_RD, 2) } \
     __builtin_amdgcn_sched_barrier(0);                                                            \
   }
   // KTE = KT rounded up to even; an odd KT (only without FULLK) gets one all-zero iteration
@@ -313,6 +316,7 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
       }
   }
 #undef G_LOAD
+#undef G_LOAD_Q
 #undef PHYS_KT
 #undef L_STORE
 #undef S_LOAD
