@@ -85,7 +85,7 @@ int torq_rotation_create(torq_rotation_t **out, int d, int G, const float *R_int
   r->G = G;
   r->KS = (G + 31) / 32;
   r->device = dev;
-  r->inter_hi = r->inter_lo = r->intra_hi = r->intra_lo = nullptr;
+  r->inter_hi = r->inter_lo = r->intra_hi = r->intra_lo = r->intra32_hi = r->intra32_lo = nullptr;
 
   // R_inter, bf16 hi/lo, [G][KS*32] with zero padding: row b is the B operand
   // "column" b of R_inter^T (Algorithm 3 step 2: Y[b] = sum_b' R_inter[b][b'] X[b']).
@@ -111,10 +111,26 @@ int torq_rotation_create(torq_rotation_t **out, int d, int G, const float *R_int
       }
     }
 
+  // The same for v_mfma_f32_32x32x16_bf16, k-step t = 0, 1: lane (m = l%32, h = l/32), slot jj
+  // holds R_intra[16t + 8(jj/4) + 4h + jj%4][kout] with kout = 16((m/4)%2) + 4(m/8) + m%4, so that
+  // after step 3 lane (b, h) holds Z[b][16h .. 16h + 15] in register order.
+  std::vector<uint16_t> a32h(2 * 64 * 8), a32l(2 * 64 * 8);
+  for (int t = 0; t < 2; ++t)
+    for (int l = 0; l < 64; ++l) {
+      const int m = l % 32, h = l / 32;
+      const int kout = 16 * ((m / 4) % 2) + 4 * (m / 8) + (m % 4);
+      for (int jj = 0; jj < 8; ++jj) {
+        const int kin = 16 * t + 8 * (jj / 4) + 4 * h + (jj % 4);
+        split_bf16(R_intra_host[kin * 32 + kout], &a32h[(t * 64 + l) * 8 + jj], &a32l[(t * 64 + l) * 8 + jj]);
+      }
+    }
+
   e = upload(&r->inter_hi, ih);
   if (e == hipSuccess) e = upload(&r->inter_lo, il);
   if (e == hipSuccess) e = upload(&r->intra_hi, ah);
   if (e == hipSuccess) e = upload(&r->intra_lo, al);
+  if (e == hipSuccess) e = upload(&r->intra32_hi, a32h);
+  if (e == hipSuccess) e = upload(&r->intra32_lo, a32l);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     torq_rotation_destroy(r);
@@ -130,6 +146,8 @@ void torq_rotation_destroy(torq_rotation_t *r) {
   if (r->inter_lo) (void)hipFree(r->inter_lo);
   if (r->intra_hi) (void)hipFree(r->intra_hi);
   if (r->intra_lo) (void)hipFree(r->intra_lo);
+  if (r->intra32_hi) (void)hipFree(r->intra32_hi);
+  if (r->intra32_lo) (void)hipFree(r->intra32_lo);
   delete r;
 }
 

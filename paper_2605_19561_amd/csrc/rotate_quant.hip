@@ -217,6 +217,208 @@ rotate_kernel(const uint4 *__restrict__ x, int64_t TG, int G,
   }
 }
 
+// ---------------------------------------------------------------------------
+// Variant for G a multiple of 32, on v_mfma_f32_32x32x16_bf16 (which sustains a higher rate than
+// the 16x16x32 form).  Same formulation; wave w owns the 32 output blocks b = 32 w .. 32 w + 31
+// and there are G/32 waves.  Two token-groups are processed together so that every MFMA has an
+// independent neighbour.  After step 3 a lane holds sixteen consecutive k of one block: two
+// lanes per block, one cross-lane step for the amax, 8 bytes of codes per lane.
+//
+// Layouts (lane l: n = l%32, h = l/32):
+//   step 2  A = X^T      lane (k = l%32, h), slot j:  X[b' = 16 s + 8 h + j][k]        (LDS, transposing read)
+//           B = R_inter^T lane (b = l%32, h), slot j:  R_inter[b][16 s + 8 h + j]
+//           D             lane (b, h), reg r:          Y^T[k' = 8 (r/4) + 4 h + r%4][b]
+//   step 3  B = Y^T       k-step t uses regs 8t..8t+7: slot jj <-> k' = 16 t + 8 (jj/4) + 4 h + jj%4
+//           A = R_intra^T lane (m, h), slot jj:        R_intra[that k'][kout(m)],
+//                         kout(m) = 16 ((m/4)%2) + 4 (m/8) + m%4
+//           D             lane (b, h), reg r:          Z[b][16 h + r]
+template <int KS16, bool QUANT>
+__global__ void __launch_bounds__(64 * (KS16 / 2))
+rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
+                const uint16_t *__restrict__ inter_hi, const uint16_t *__restrict__ inter_lo,
+                const uint4 *__restrict__ intra_hi_frag, const uint4 *__restrict__ intra_lo_frag,
+                uint2 *__restrict__ codes, uint8_t *__restrict__ scales, float *__restrict__ z_out) {
+  constexpr int TB = 2;                              // token-groups per batch, processed together
+  constexpr int TG_BYTES = KS16 * 16 * 64;           // one token-group: G rows of 64 bytes
+  constexpr int STAGE_BYTES = TB * TG_BYTES;
+  constexpr int NTHR = 64 * (KS16 / 2);
+  constexpr int CH = TG_BYTES / 16 / NTHR;           // 16-byte chunks per thread per token-group (= 2)
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, h = lane >> 5;
+
+  // ---- resident operands
+  bf16x8 Bh[KS16], Bl[KS16];
+  {
+    const int b = 32 * wave + col;
+#pragma unroll
+    for (int ks = 0; ks < KS16; ++ks) {
+      const size_t off = (size_t)b * (KS16 * 16) + 16 * ks + 8 * h;
+      Bh[ks] = *reinterpret_cast<const bf16x8 *>(inter_hi + off);
+      Bl[ks] = *reinterpret_cast<const bf16x8 *>(inter_lo + off);
+    }
+  }
+  bf16x8 Ah[2], Al[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    Ah[t] = __builtin_bit_cast(bf16x8, intra_hi_frag[t * 64 + lane]);
+    Al[t] = __builtin_bit_cast(bf16x8, intra_lo_frag[t * 64 + lane]);
+  }
+
+  // transposing-read address of this lane inside a token-group (k-step 0, first half)
+  const int blk = lane >> 4, s16 = lane & 15;
+  const int tr_off = ((8 * (blk >> 1) + (s16 >> 2)) * 32 + 16 * (blk & 1) + 4 * (s16 & 3)) * 2;
+
+  const int64_t nbatch = (TG + TB - 1) / TB;
+  uint4 stage_regs[TB][CH];
+  auto load_batch = [&](int64_t batch) {
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+      const int64_t tg = batch * TB + j;
+#pragma unroll
+      for (int i = 0; i < CH; ++i) {
+        if (tg < TG) stage_regs[j][i] = x[tg * (TG_BYTES / 16) + tid + i * NTHR];
+        else stage_regs[j][i] = make_uint4(0, 0, 0, 0);
+      }
+    }
+  };
+  auto store_batch = [&](int buf) {
+    char *base = lds + buf * STAGE_BYTES;
+#pragma unroll
+    for (int j = 0; j < TB; ++j)
+#pragma unroll
+      for (int i = 0; i < CH; ++i)
+        *reinterpret_cast<uint4 *>(base + j * TG_BYTES + (tid + i * NTHR) * 16) = stage_regs[j][i];
+  };
+
+  int64_t batch = blockIdx.x;
+  if (batch < nbatch) {
+    load_batch(batch);
+    store_batch(0);
+  }
+  __syncthreads();
+
+  int buf = 0;
+  for (; batch < nbatch; batch += gridDim.x, buf ^= 1) {
+    const int64_t next = batch + gridDim.x;
+    const bool have_next = next < nbatch;
+    if (have_next) load_batch(next);
+
+    const char *stage = lds + buf * STAGE_BYTES + tr_off;
+    // ---- step 2: Y^T = X^T R_inter^T for both token-groups
+    f32x16 acc[TB];
+#pragma unroll
+    for (int j = 0; j < TB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS16; ++ks) {
+      bf16x8 xa[TB];
+#pragma unroll
+      for (int j = 0; j < TB; ++j) {
+        const char *p = stage + j * TG_BYTES + ks * 16 * 64;
+        union { bf16x8 v; i16x4 q[2]; } u;
+        u.q[0] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4 *)(p));
+        u.q[1] = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_i16x4 *)(p + 4 * 64));
+        xa[j] = u.v;
+      }
+#pragma unroll
+      for (int j = 0; j < TB; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[j], Bh[ks], acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TB; ++j)
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[j], Bl[ks], acc[j], 0, 0, 0);
+    }
+
+    // ---- step 3: Z^T = R_intra^T Y^T with Y split into bf16 hi + lo; then step 4
+    f32x16 zacc[TB];
+    bf16x8 yh[TB][2], yl[TB][2];
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const float y0 = acc[j][8 * t + 2 * p], y1 = acc[j][8 * t + 2 * p + 1];
+          hi[p] = pack_bf16_rne(y0, y1);
+          lo[p] = pack_bf16_rne(y0 - __uint_as_float(hi[p] << 16), y1 - __uint_as_float(hi[p] & 0xFFFF0000u));
+        }
+        yh[j][t] = __builtin_bit_cast(bf16x8, i32x4{(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]});
+        yl[j][t] = __builtin_bit_cast(bf16x8, i32x4{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]});
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) zacc[j][r] = 0.f;
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+#pragma unroll
+      for (int j = 0; j < TB; ++j) zacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Al[t], yh[j][t], zacc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TB; ++j) zacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[t], yl[j][t], zacc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TB; ++j) zacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[t], yh[j][t], zacc[j], 0, 0, 0);
+    }
+
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+      const int64_t tg = batch * TB + j;
+      if (tg < TG) {                                            // uniform over the workgroup
+        const int64_t blkidx = tg * G + 32 * wave + col;        // global block index
+        float zz[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) zz[r] = zacc[j][r];
+        if constexpr (QUANT) {
+          float amax = fmaxf(amax8(zz), amax8(zz + 8));
+          // max with the other half-wave (lane ^ 32): swap the upper half of one copy with the
+          // lower half of the other, then every lane holds both partners' values
+          const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(amax), __float_as_uint(amax), false, false);
+          amax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+          const uint32_t byte = e8m0_from_amax(amax);
+          const float sc = e8m0_to_f32(byte);
+          codes[blkidx * 2 + h] = make_uint2(pack8_e2m1(zz, sc), pack8_e2m1(zz + 8, sc));
+          if (h == 0) scales[blkidx] = (uint8_t)byte;
+        } else {
+          float4 *o = reinterpret_cast<float4 *>(z_out + blkidx * 32 + 16 * h);
+#pragma unroll
+          for (int q = 0; q < 4; ++q) o[q] = make_float4(zz[4 * q], zz[4 * q + 1], zz[4 * q + 2], zz[4 * q + 3]);
+        }
+      }
+    }
+
+    if (have_next) store_batch(buf ^ 1);
+    __syncthreads();
+  }
+}
+
+template <int KS16>
+static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG, uint8_t *codes,
+                               uint8_t *scales, float *z_out, hipStream_t stream) {
+  constexpr int TB = 2;
+  const int nw = KS16 / 2;                               // = G / 32
+  const int64_t nbatch = (TG + TB - 1) / TB;
+  const size_t lds_bytes = 2 * (size_t)TB * KS16 * 16 * 64;
+  // resident workgroups per CU: limited by LDS (160 KiB) and by 8 waves per CU at these register counts
+  int per_cu = (int)((160 * 1024) / lds_bytes);
+  if (per_cu * nw > 8) per_cu = 8 / nw;
+  if (per_cu < 1) per_cu = 1;
+  int64_t grid = (int64_t)per_cu * 256;
+  if (grid > nbatch) grid = nbatch;
+  const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
+  const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
+  if (z_out)
+    hipLaunchKernelGGL((rotate_kernel32<KS16, false>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream,
+                       reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,
+                       nullptr, nullptr, z_out);
+  else
+    hipLaunchKernelGGL((rotate_kernel32<KS16, true>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream,
+                       reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,
+                       reinterpret_cast<uint2 *>(codes), scales, nullptr);
+  return hipGetLastError();
+}
+
 template <int KS, int NT>
 static hipError_t launch_cfg(const torq_rotation *r, const void *x, int64_t TG, uint8_t *codes,
                              uint8_t *scales, float *z_out, hipStream_t stream) {
@@ -243,14 +445,23 @@ hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, 
                          uint8_t *scales, float *z_out, hipStream_t stream) {
   const int64_t TG = M * (int64_t)(r->d / 32 / r->G);
   if (TG == 0) return hipSuccess;
-  const int tiles = r->G / 16;
-  // two tiles of 16 blocks per wave when that keeps the workgroup at >= 4 waves
-  const bool nt2 = (tiles % 2 == 0) && (tiles / 2 >= 4);
+  if (r->G % 32 == 0) {
+    switch (r->G / 16) {
+      case 2: return launch_cfg32<2>(r, x_bf16, TG, codes, scales, z_out, stream);
+      case 4: return launch_cfg32<4>(r, x_bf16, TG, codes, scales, z_out, stream);
+      case 6: return launch_cfg32<6>(r, x_bf16, TG, codes, scales, z_out, stream);
+      case 8: return launch_cfg32<8>(r, x_bf16, TG, codes, scales, z_out, stream);
+      case 10: return launch_cfg32<10>(r, x_bf16, TG, codes, scales, z_out, stream);
+      case 12: return launch_cfg32<12>(r, x_bf16, TG, codes, scales, z_out, stream);
+      case 14: return launch_cfg32<14>(r, x_bf16, TG, codes, scales, z_out, stream);
+      case 16: return launch_cfg32<16>(r, x_bf16, TG, codes, scales, z_out, stream);
+    }
+  }
+  // G = 16 * odd: the 16x16x32 kernel, one tile of 16 blocks per wave
   switch (r->KS) {
 #define TORQ_CASE(KS_)                                                                          \
   case KS_:                                                                                     \
-    return nt2 ? launch_cfg<KS_, 2>(r, x_bf16, TG, codes, scales, z_out, stream)                \
-               : launch_cfg<KS_, 1>(r, x_bf16, TG, codes, scales, z_out, stream);
+    return launch_cfg<KS_, 1>(r, x_bf16, TG, codes, scales, z_out, stream);
     TORQ_CASE(1) TORQ_CASE(2) TORQ_CASE(3) TORQ_CASE(4)
     TORQ_CASE(5) TORQ_CASE(6) TORQ_CASE(7) TORQ_CASE(8)
 #undef TORQ_CASE

@@ -15,6 +15,8 @@ struct torq_rotation {
   uint16_t *inter_hi, *inter_lo;
   // R_intra^T rows permuted for the accumulator layout, bf16 hi and lo, [32][32]
   uint16_t *intra_hi, *intra_lo;
+  // the same matrix as the A operand of v_mfma_f32_32x32x16_bf16 (two k-steps), bf16 hi and lo
+  uint16_t *intra32_hi, *intra32_lo;
 };
 
 namespace torq {
