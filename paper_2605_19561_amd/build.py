@@ -17,13 +17,18 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 
+# The rotate kernel post-processes its MFMA results with vector ALU code, so its accumulators are
+# kept in ordinary VGPRs (no v_accvgpr_read traffic); the GEMM needs the AGPR half for its tile.
+EXTRA = {"rotate_quant.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
 def build(verbose: bool = False) -> str:
     objs = []
     procs = []
     for s in SOURCES:
         obj = os.path.join(CSRC, s.replace(".hip", ".o"))
         objs.append(obj)
-        cmd = [HIPCC, *FLAGS, "-c", os.path.join(CSRC, s), "-o", obj]
+        cmd = [HIPCC, *FLAGS, *EXTRA.get(s, []), "-c", os.path.join(CSRC, s), "-o", obj]
         procs.append((cmd, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)))
     for cmd, p in procs:
         out, _ = p.communicate()

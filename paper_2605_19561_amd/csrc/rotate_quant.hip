@@ -233,7 +233,7 @@ rotate_kernel(const uint4 *__restrict__ x, int64_t TG, int G,
 //                         kout(m) = 16 ((m/4)%2) + 4 (m/8) + m%4
 //           D             lane (b, h), reg r:          Z[b][16 h + r]
 template <int KS16, bool QUANT>
-__global__ void __launch_bounds__(64 * (KS16 / 2))
+__global__ void __launch_bounds__(64 * (KS16 / 2), 2)   // at least two waves per SIMD
 rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
                 const uint16_t *__restrict__ inter_hi, const uint16_t *__restrict__ inter_lo,
                 const uint4 *__restrict__ intra_hi_frag, const uint4 *__restrict__ intra_lo_frag,
