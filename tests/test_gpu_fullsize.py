@@ -1,0 +1,161 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+The oracle cannot run these shapes whole in seconds, but every output row of
+rotate+quantise depends on one input row only and every GEMM output on one row
+of each operand, so sampled rows / outputs are recomputed exactly by the oracle.
+Inputs are seeded synthetic tensors generated on the device (same recipes as the
+benchmark); the sampled rows are copied to the host and handed to the oracle.
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_19561_amd import synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def tq():
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2605_19561_amd import binding
+    binding.lib()
+    return binding
+
+
+def _np(t):
+    return t.detach().cpu().numpy()
+
+
+def _bf16_bits_to_f64(bits):
+    return (bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+
+
+def _check_rows(oracle, tq, rot, x, rows, G, Ri, Ra):
+    """rotate and rotate+quantise on sampled rows against the oracle"""
+    d = x.shape[1]
+    xs = x[rows].contiguous()
+    xb = synth.bf16_bits(xs)
+    z_ref = oracle.rotate(xb, G, Ri, Ra)
+    want_c, want_s = oracle.quantize(z_ref)
+    return xs, z_ref, want_c, want_s, d
+
+
+ROT_FULL = [
+    ("llama3_70b_up", None),                       # [8192, 8192], G = 128: the benchmark's step
+    ("qwen3_32b", None),                           # [4096, 5120], G = 80, per-token log-normal scale
+    ("llama3_70b_down", 2048),                     # d = 28672, G = 128 (rows trimmed: generation time)
+]
+
+
+@pytest.mark.parametrize("name,M", ROT_FULL)
+def test_rotate_quantize_full_size_sampled_rows(tq, oracle, name, M):
+    x = synth.workload_activations(name, device=DEV, M=M)
+    M, d = x.shape
+    G = synth.default_G(d)
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    codes, scales = tq.torq_rotate_quantize(rot, x)
+    z = tq.torq_rotate(rot, x)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(17)
+    rows = np.unique(np.concatenate([[0, 1, M - 2, M - 1], rng.integers(0, M, size=12)]))
+    rows_t = torch.from_numpy(rows).to(DEV)
+    xs, z_ref, want_c, want_s, _ = _check_rows(oracle, tq, rot, x, rows_t, G, Ri, Ra)
+    got_z = _np(z[rows_t]).astype(np.float64)
+    zr = z_ref.astype(np.float64)
+    rms = np.sqrt((zr ** 2).mean(axis=1, keepdims=True))
+    assert (np.abs(got_z - zr) / rms).max() <= 1e-3
+    got_c, got_s = _np(codes[rows_t]), _np(scales[rows_t])
+    # the fused kernel equals the quantiser applied to its own rotated values, bit for bit ...
+    c2, s2 = tq.torq_quantize_f32(z[rows_t].contiguous())
+    assert np.array_equal(_np(c2), got_c) and np.array_equal(_np(s2), got_s)
+    # ... and differs from the oracle only where the oracle's value sits on a rounding boundary
+    n = len(rows)
+    tol = 1e-3 * rms
+    amax = np.abs(zr).reshape(n, d // 32, 32).max(axis=2)
+    e = np.floor(np.log2(amax))
+    pow2_dist = np.minimum(np.abs(amax - 2.0 ** e), np.abs(amax - 2.0 ** (e + 1)))
+    sdiff = got_s != want_s
+    assert np.all(pow2_dist[sdiff] <= tol.repeat(d // 32, axis=1)[sdiff])
+    unpack = lambda c: np.stack([c & 15, c >> 4], axis=-1).reshape(n, d)
+    gc, wc = unpack(got_c), unpack(want_c)
+    cdiff = (gc != wc) & ~np.repeat(sdiff, 32, axis=1)
+    s = np.repeat(np.ldexp(1.0, want_s.astype(np.int64) - 127), 32, axis=1)
+    bounds = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
+    slack = np.abs((np.abs(zr) / s)[..., None] - bounds).min(axis=-1) * s
+    near = (slack <= np.broadcast_to(tol, slack.shape)) | (np.abs(zr) <= np.broadcast_to(tol, zr.shape))
+    assert np.all(near[cdiff])
+    assert cdiff.mean() <= 0.005 and sdiff.mean() <= 0.002
+    rot.close()
+
+
+GEMM_FULL = [
+    (8192, 28672, 8192),      # LLaMA3-70B MLP up / gate: the benchmark's step
+    (8192, 8192, 28672),      # LLaMA3-70B MLP down
+    (2048, 14336, 4096),      # LLaMA3-8B MLP up, prefill
+    (16, 4096, 4096),         # decode-sized M
+    (1, 14336, 4096),
+    (4096, 5120, 25600),      # Qwen3-32B MLP down (d not a power of two)
+]
+
+
+@pytest.mark.parametrize("M,N,d", GEMM_FULL)
+def test_gemm_full_size_sampled_outputs(tq, oracle, M, N, d):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(synth.SEED_BASE + M + N + d)
+    A_q = torch.randint(0, 256, (M, d // 2), dtype=torch.uint8, device=DEV, generator=g)
+    W_q = torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=DEV, generator=g)
+    A_s = torch.randint(118, 136, (M, d // 32), dtype=torch.uint8, device=DEV, generator=g)
+    W_s = torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=DEV, generator=g)
+    out = tq.mxfp4_gemm(A_q, A_s, W_q, W_s)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(M + 3 * N)
+    n_s = 4096
+    ms = rng.integers(0, M, size=n_s)
+    ns = rng.integers(0, N, size=n_s)
+    # corners and tile edges as well
+    ms[:8] = [0, 0, M - 1, M - 1, min(255, M - 1), min(256, M - 1), M // 2, M - 1]
+    ns[:8] = [0, N - 1, 0, N - 1, min(255, N - 1), min(256, N - 1), N // 2, N // 2]
+    um, im = np.unique(ms, return_inverse=True)
+    un, inn = np.unique(ns, return_inverse=True)
+    Aq_h, As_h = _np(A_q[torch.from_numpy(um).to(DEV)]), _np(A_s[torch.from_numpy(um).to(DEV)])
+    Wq_h, Ws_h = _np(W_q[torch.from_numpy(un).to(DEV)]), _np(W_s[torch.from_numpy(un).to(DEV)])
+    want = oracle.gemm_sampled(Aq_h, As_h, Wq_h, Ws_h, im, inn)
+    got = _np(out[torch.from_numpy(ms).to(DEV), torch.from_numpy(ns).to(DEV)].view(torch.int16)).view(np.uint16)
+    gw, ww = _bf16_bits_to_f64(got), _bf16_bits_to_f64(want)
+    assert np.linalg.norm(gw - ww) / np.linalg.norm(ww) <= 1e-3
+    # fp32 accumulation of exactly representable products: almost every output is the correctly
+    # rounded bf16 value, the rest are one bf16 ulp off
+    assert np.mean(got == want) > 0.98
+    assert np.all(np.abs(gw - ww) <= np.abs(ww) * 2.0 ** -7 + 1e-3 * np.sqrt(np.mean(ww ** 2)))
+
+
+def test_linear_full_size_is_its_two_halves_and_matches_oracle_on_samples(tq, oracle):
+    name = "llama3_70b_up"
+    wl = synth.WORKLOADS[name]
+    M, d, N = wl["M"], wl["d"], 4096            # N trimmed: the weights are generated and prepared here
+    G = synth.default_G(d)
+    x = synth.workload_activations(name, device=DEV)
+    w = synth.workload_weights(name, device=DEV, N=N)
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    W_q, W_s = tq.torq_rotate_quantize(rot, w)
+    out = tq.torq_linear(rot, x, W_q, W_s)
+    A_q, A_s = tq.torq_rotate_quantize(rot, x)
+    out2 = tq.mxfp4_gemm(A_q, A_s, W_q, W_s)
+    torch.cuda.synchronize()
+    assert torch.equal(out, out2)
+    rng = np.random.default_rng(5)
+    rm = np.unique(rng.integers(0, M, size=12))
+    rn = np.unique(rng.integers(0, N, size=48))
+    rm_t, rn_t = torch.from_numpy(rm).to(DEV), torch.from_numpy(rn).to(DEV)
+    oA = oracle.rotate_quantize(synth.bf16_bits(x[rm_t]), G, Ri, Ra)
+    oW = oracle.rotate_quantize(synth.bf16_bits(w[rn_t]), G, Ri, Ra)
+    want = _bf16_bits_to_f64(oracle.gemm(oA[0], oA[1], oW[0], oW[1]))
+    got = _np(out[rm_t][:, rn_t].to(torch.float64))
+    # whole chain against the oracle's whole chain: a few boundary values may round differently
+    # on the two sides (see test_rotate_quantize_full_size_sampled_rows), hence 5e-3 instead of 1e-3
+    assert np.linalg.norm(got - want) / np.linalg.norm(want) <= 5e-3
+    rot.close()
