@@ -39,10 +39,13 @@ MEASURED_TRAFFIC = {
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
     ap.add_argument("--workload", default="llama3_70b_up")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic) so that a rocprofv3 --pmc run of this "
+                         "command carries its own scale for FETCH_SIZE / WRITE_SIZE")
     ap.add_argument("--sweep", action="store_true",
                     help="also print one line per rotate+quantise bandwidth-sweep shape ([16384, d])")
     args = ap.parse_args()
@@ -91,17 +94,28 @@ def main():
     flops = 2.0 * M * N * d
     value = flops / (ms_per_step * 1e-3) / 1e12
 
-    # ---- per-kernel durations: HIP events on the stream the kernels run on ----
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    # ---- per-kernel durations: HIP events on the stream the kernels run on (torch's current
+    # stream, which is the one handed to the library).  Each kernel is launched `steps` times back
+    # to back between two events, so launch gaps are not attributed to it.  rotate+quantise moves
+    # only 170 MB per launch, which would fit the 256 MB Infinity Cache: it cycles over three copies
+    # of the input so that every launch reads from HBM.
+    x_copies = [x, x.clone(), x.clone()]
+    e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
+    for i in range(3):
+        tq.torq_rotate_quantize(rot, x_copies[i], codes=codes, scales=scales)
+    e[0].record()
     for i in range(args.steps):
-        ev[i][0].record()
-        tq.torq_rotate_quantize(rot, x, codes=codes, scales=scales)
-        ev[i][1].record()
+        tq.torq_rotate_quantize(rot, x_copies[i % 3], codes=codes, scales=scales)
+    e[1].record()
+    tq.mxfp4_gemm(codes, scales, W_q, W_s, out=out)
+    e[2].record()
+    for i in range(args.steps):
         tq.mxfp4_gemm(codes, scales, W_q, W_s, out=out)
-        ev[i][2].record()
+    e[3].record()
     torch.cuda.synchronize()
-    rq_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / args.steps
-    gemm_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / args.steps
+    rq_ms = e[0].elapsed_time(e[1]) / args.steps
+    gemm_ms = e[2].elapsed_time(e[3]) / args.steps
+    del x_copies
 
     gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
     rq_bytes = M * d * RQ_BYTES_PER_ELEMENT
@@ -135,6 +149,14 @@ def main():
         result["cpu_baseline"] = cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d)
 
     print(json.dumps(result), flush=True)
+
+    if args.calibrate_copy:
+        src = torch.full((1 << 30,), 7, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     if args.sweep:
         for dd in (4096, 8192, 14336, 28672):
