@@ -29,10 +29,12 @@ BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 RQ_BYTES_PER_ELEMENT = 2.0 + 0.5 + 1.0 / 32.0   # bf16 in, packed nibble + 1/32 scale byte out
 
 # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a plain
-# copy kernel of known size; see the profiles/ summaries named below.  None until measured.
+# copy kernel of known size (bytes per launch); see the profiles/ summaries named below.
 MEASURED_TRAFFIC = {
-    "mxfp4_gemm/llama3_70b_up": None,
-    "torq_rotate_quantize/llama3_70b_up": None,
+    # profiles/mxfp4_gemm_llama3_70b_up.md: 1.633e9 B read + 4.734e8 B written per launch
+    "mxfp4_gemm/llama3_70b_up": 2.106e9,
+    # profiles/torq_rotate_quantize_llama3_70b_up.md: 1.348e8 B read + 3.566e7 B written per launch
+    "torq_rotate_quantize/llama3_70b_up": 1.705e8,
 }
 
 
@@ -172,7 +174,7 @@ def cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d):
     from paper_2605_19561_amd import synth
 
     rows = min(M, 8192)
-    gm, gn = min(M, 256), min(N, 2048)
+    gm, gn = min(M, 256), min(N, 4096)
     xb = synth.bf16_bits(x[:rows])
     t0 = time.perf_counter()
     A_q, A_s = oracle.rotate_quantize(xb, G, Ri, Ra)

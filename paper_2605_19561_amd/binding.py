@@ -101,9 +101,9 @@ class Rotation:
         self.handle, self.d, self.G = h, d, G
 
     def close(self):
-        if getattr(self, "handle", None):
-            lib().torq_rotation_destroy(self.handle)
-            self.handle = None
+        if getattr(self, "handle", None) and _lib is not None:
+            _lib.torq_rotation_destroy(self.handle)
+        self.handle = None
 
     __del__ = close
 
