@@ -149,22 +149,27 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[j][i][r] = 0.f;
 
-  // ---- fragment addressing.  Lane (lrow, g) reads chunk 2 ks + g of rows lrow + 32 i of its
-  // wave's strip; (row >> 1) & 7 is the same for all those rows, so one swizzled offset per ks
-  // serves every fragment and the row strips become immediate offsets.
+  // ---- fragment addressing.  The 64 k of one MFMA are two microscaling blocks: lanes 0..31
+  // (g = 0) supply one, lanes 32..63 (g = 1) the other.  Which two blocks of the iteration a
+  // k-step multiplies is free as long as both operands agree; k-step ks takes blocks ks (g = 0)
+  // and 4 + ks (g = 1), so that a lane's four scale bytes of the iteration are one aligned
+  // dword (bytes 4 g .. 4 g + 3 of the row's 8) and the byte select of the MFMA is just ks.
+  // Lane (lrow, g) reads chunk 4 g + ks of rows lrow + 32 i of its wave's strip; (row >> 1) & 7
+  // is the same for all those rows, so one swizzled offset per ks serves every fragment and the
+  // row strips become immediate offsets.
   const int f_sw = (lrow >> 1) & 7;
   int fa_off[4], fw_off[4];
 #pragma unroll
   for (int ks = 0; ks < 4; ++ks) {
-    const int ch = ((2 * ks + g) ^ f_sw) * 16;
+    const int ch = ((4 * g + ks) ^ f_sw) * 16;
     fa_off[ks] = (wy * WM * 32 + lrow) * 128 + ch;
     fw_off[ks] = W_BASE + (wx * WN * 32 + lrow) * 128 + ch;
   }
-  const int sa_off = S_BASE + (wy * WM * 32 + lrow) * 16;
-  const int sw_off = S_BASE + (BM + wx * WN * 32 + lrow) * 16;
+  const int sa_off = S_BASE + (wy * WM * 32 + lrow) * 16 + 4 * g;
+  const int sw_off = S_BASE + (BM + wx * WN * 32 + lrow) * 16 + 4 * g;
 
   i32x4 fa[2][WM], fw[2][WN];
-  uint32_t sa[WM][2], sw[WN][2];                   // [frag][lo/hi dword], already shifted by 8 g
+  uint32_t sa[2][WM], sw[2][WN];                   // [iteration parity][frag]: the lane's 4 scale bytes
 
 #define F_LOAD(SET_, P_, KS_)                                                                     \
   {                                                                                               \
@@ -173,25 +178,23 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
     _Pragma("unroll") for (int j = 0; j < WN; ++j)                                                \
         fw[SET_][j] = *reinterpret_cast<const i32x4 *>(lds + fw_off[KS_] + (P_) * W_STAGE + j * 32 * 128); \
   }
-  // the 8 scale bytes of a row for iteration KT_: dword H_ = 0 (blocks 0-3) or 1 (blocks 4-7)
-#define SC_LOAD(H_, KT_)                                                                          \
+  // this lane's 4 scale bytes of each row for iteration KT_, into register set PAR_
+#define SC_LOAD(PAR_, KT_)                                                                        \
   {                                                                                               \
-    const int o_ = (((KT_) >> 1) & 1) * SSTAGE + ((KT_) & 1) * 8 + (H_) * 4;                      \
+    const int o_ = (((KT_) >> 1) & 1) * SSTAGE + ((KT_) & 1) * 8;                                 \
     _Pragma("unroll") for (int i = 0; i < WM; ++i)                                                \
-        sa[i][H_] = *reinterpret_cast<const uint32_t *>(lds + sa_off + o_ + i * 32 * 16) >> (8 * g); \
+        sa[PAR_][i] = *reinterpret_cast<const uint32_t *>(lds + sa_off + o_ + i * 32 * 16);       \
     _Pragma("unroll") for (int j = 0; j < WN; ++j)                                                \
-        sw[j][H_] = *reinterpret_cast<const uint32_t *>(lds + sw_off + o_ + j * 32 * 16) >> (8 * g); \
+        sw[PAR_][j] = *reinterpret_cast<const uint32_t *>(lds + sw_off + o_ + j * 32 * 16);       \
   }
-  // lane (row, g) of a fragment carries block 2 ks + g of the iteration: byte (2 ks) & 3 of the
-  // shifted dword ks >> 1
-#define MFMA_ONE(SET_, KS_, J_, I_)                                                               \
+#define MFMA_ONE(SET_, PAR_, KS_, J_, I_)                                                         \
   acc[J_][I_] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(                                  \
       i32x8{fw[SET_][J_][0], fw[SET_][J_][1], fw[SET_][J_][2], fw[SET_][J_][3], 0, 0, 0, 0},      \
       i32x8{fa[SET_][I_][0], fa[SET_][I_][1], fa[SET_][I_][2], fa[SET_][I_][3], 0, 0, 0, 0},      \
-      acc[J_][I_], 4, 4, ((KS_) & 1) * 2, sw[J_][(KS_) >> 1], ((KS_) & 1) * 2, sa[I_][(KS_) >> 1]);
-#define MFMA_HALF(SET_, KS_, J0_, J1_)                                                            \
+      acc[J_][I_], 4, 4, KS_, sw[PAR_][J_], KS_, sa[PAR_][I_]);
+#define MFMA_HALF(SET_, PAR_, KS_, J0_, J1_)                                                      \
   _Pragma("unroll") for (int j = (J0_); j < (J1_); ++j)                                           \
-      _Pragma("unroll") for (int i = 0; i < WM; ++i) { MFMA_ONE(SET_, KS_, j, i) }
+      _Pragma("unroll") for (int i = 0; i < WM; ++i) { MFMA_ONE(SET_, PAR_, KS_, j, i) }
 
   // ---- prologue
   G_LOAD(0);
@@ -222,24 +225,23 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
 #define ITER(P, KT_)                                                                              \
   {                                                                                               \
     const int kt_i = (KT_);                                                                       \
-    SC_LOAD(1, kt_i);                       /* hi scale dword; the lo one came in after the barrier */ \
     F_LOAD(1, P, 1);                                                                              \
-    MFMA_HALF(0, 0, 0, WN);                                                                       \
+    MFMA_HALF(0, P, 0, 0, WN);                                                                    \
     F_LOAD(0, P, 2);                                                                              \
     L_STORE((P) ^ 1, 0);                                                                          \
     G_LOAD_Q(kt_i + 2, 0);                                                                        \
-    MFMA_HALF(1, 1, 0, WN);                                                                       \
+    MFMA_HALF(1, P, 1, 0, WN);                                                                    \
     F_LOAD(1, P, 3);                                                                              \
     L_STORE((P) ^ 1, 1);                                                                          \
     G_LOAD_Q(kt_i + 2, 1);                                                                        \
-    MFMA_HALF(0, 2, 0, WN);                                                                       \
+    MFMA_HALF(0, P, 2, 0, WN);                                                                    \
     L_STORE((P) ^ 1, 2);                                                                          \
     L_STORE((P) ^ 1, 3);                                                                          \
     if ((P) == 1) S_STORE(((kt_i + 1) >> 1) & 1);                                                 \
-    MFMA_HALF(1, 3, 0, WN / 2);                                                                   \
-    /* k-step 0: its MFMAs hide the hi-scale reads and the fragment reads of k-step 1 */          \
-    _Pragma("unroll") for (int n_ = 0; n_ < WM + WN + 4; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 1) } \
-    SGB(SG_MFMA, WM * WN - (WM + WN + 4) > 0 ? WM * WN - (WM + WN + 4) : 0)                       \
+    MFMA_HALF(1, P, 3, 0, WN / 2);                                                                \
+    /* k-step 0: its MFMAs hide the fragment reads of k-step 1 */                                 \
+    _Pragma("unroll") for (int n_ = 0; n_ < WM + WN; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 1) }   \
+    SGB(SG_MFMA, WM * WN - (WM + WN) > 0 ? WM * WN - (WM + WN) : 0)                               \
     /* k-steps 1 and 2: per two MFMAs one fragment read of the next k-step; a quarter of the     \
        next stage's LDS stores along the way, each followed by the buffer loads that refill the  \
        staging registers it freed (for the iteration after next) */                               \
@@ -252,13 +254,13 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
     /* first half of k-step 3: the rest of the LDS stores */                                      \
     _Pragma("unroll") for (int n_ = 0; n_ < WM * WN / 2; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_WR, 2) } \
     __syncthreads();                                                                              \
-    SC_LOAD(0, kt_i + 1);                                                                         \
+    SC_LOAD((P) ^ 1, kt_i + 1);                                                                   \
     F_LOAD(0, (P) ^ 1, 0);                                                                        \
     G_LOAD_Q(kt_i + 2, 2);                                                                        \
     G_LOAD_Q(kt_i + 2, 3);                                                                        \
     if ((P) == 0) S_LOAD(PHYS_KT(kt_i + 2) >> 1);                                                 \
-    MFMA_HALF(1, 3, WN / 2, WN);                                                                  \
-    /* second half of k-step 3: fragment and lo-scale reads of the next iteration first, then   \
+    MFMA_HALF(1, P, 3, WN / 2, WN);                                                               \
+    /* second half of k-step 3: fragment and scale reads of the next iteration first, then      \
        the remaining buffer loads */                                                              \
     _Pragma("unroll") for (int n_ = 0; n_ < WM * WN / 2; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 2) SGB(SG_VMEM_RD, 2) } \
     __builtin_amdgcn_sched_barrier(0);                                                            \
