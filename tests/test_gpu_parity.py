@@ -214,6 +214,34 @@ def test_gemm_random_codes(tq, oracle, M, N, d):
     assert _rel_fro(_bits(got), want) <= 1e-3
 
 
+# Few activation rows (M <= 64) take the weight-streaming kernel: one MFMA k-step only, an odd
+# number of k-steps, more k than one trip of a wave covers, every count of 16-row activation tiles
+# with a ragged last one, N not a multiple of 16 or of 4, and enough weight rows (with M >= 8) for
+# the two-strips-per-workgroup variant, ragged there as well.
+GEMM_FEW_ROWS = [(1, 16, 128), (1, 4099, 384), (2, 1000, 8192), (7, 130, 14336), (16, 12300, 256),
+                 (17, 12290, 384), (32, 515, 2048), (33, 257, 4096), (48, 100, 640), (64, 1030, 1152)]
+
+
+@pytest.mark.parametrize("M,N,d", GEMM_FEW_ROWS)
+def test_gemm_few_rows_random_codes(tq, oracle, M, N, d):
+    rng = np.random.default_rng(M * 11 + N + d)
+    A_q = rng.integers(0, 256, size=(M, d // 2), dtype=np.uint8)
+    W_q = rng.integers(0, 256, size=(N, d // 2), dtype=np.uint8)
+    A_s = rng.integers(118, 136, size=(M, d // 32), dtype=np.uint8)
+    W_s = rng.integers(110, 126, size=(N, d // 32), dtype=np.uint8)
+    want = oracle.gemm(A_q, A_s, W_q, W_s)
+    out = torch.full((M + 1, N), 7.0, dtype=torch.bfloat16, device=DEV)     # one guard row behind the output
+    tq.mxfp4_gemm(*(torch.from_numpy(a).to(DEV) for a in (A_q, A_s, W_q, W_s)), out=out[:M])
+    torch.cuda.synchronize()
+    got = _bits(out[:M])
+    assert _rel_fro(got, want) <= 1e-3
+    gw = (got.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    ww = (want.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    # fp32 accumulation of exact products: at most one bf16 ulp from the correctly rounded value
+    assert np.all(np.abs(gw - ww) <= np.abs(ww) * 2.0 ** -7 + 1e-3 * np.sqrt(np.mean(ww ** 2)))
+    assert torch.all(out[M] == 7.0)
+
+
 def test_gemm_tiny_config_from_oracle_quantised_operands(tq, oracle):
     # configuration 1: X [64, 4096] heavy-tailed, W [1024, 4096], both rotated + quantised by the oracle
     x = synth.workload_activations("tiny")
