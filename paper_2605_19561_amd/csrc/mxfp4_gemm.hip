@@ -14,7 +14,7 @@
 //
 // Workgroup = 4 waves (2 x 2), one per SIMD; each wave owns a (32 WM) x (32 WN)
 // piece of the (64 WM) x (64 WN) output tile and keeps it in accumulator
-// registers.  The k loop advances 256 elements per iteration (128 bytes of
+// registers (tiles: 256 x 256, 256 x 128, 128 x 128, chosen per problem size).  The k loop advances 256 elements per iteration (128 bytes of
 // codes per row = one full cache line, 8 scale bytes per row):
 //   * codes: buffer loads (tile-relative 32-bit offsets, hardware bounds check
 //     returns zero for rows past M or N) -> registers -> LDS, double-buffered in
@@ -48,9 +48,8 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
                   int tiles_m, int tiles_n) {
   constexpr int BM = 64 * WM, BN = 64 * WN;
   constexpr int A_CH = BM / 32, W_CH = BN / 32;          // 16-byte code chunks per thread per iteration
-  constexpr int ROWS = BM + BN;
-  static_assert(ROWS % 256 == 0, "every thread stages the same number of scale rows");
-  constexpr int S_CH = ROWS / 256;                       // 16-byte scale chunks per thread per 2 iterations
+  constexpr int ROWS = (BM + BN + 255) / 256 * 256;      // scale rows staged: padded so that every thread
+  constexpr int S_CH = ROWS / 256;                       // stages S_CH 16-byte chunks per 2 iterations
   // LDS map: [A stage 0 | A stage 1 | W stage 0 | W stage 1 | scales buffer 0 | scales buffer 1]
   constexpr int A_STAGE = BM * 128, W_STAGE = BN * 128;
   constexpr int W_BASE = 2 * A_STAGE;
@@ -121,7 +120,8 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
     const int sc_ = (SC_);                                                                        \
     _Pragma("unroll") for (int i = 0; i < S_CH; ++i) {                                            \
       const int r_ = tid + 256 * i;                                                               \
-      /* 64 divides BM, so a wave stages either A rows or W rows: a scalar choice */              \
+      /* 64 divides BM, so a wave stages either A rows or W rows: a scalar choice; padding rows  \
+         are past the end of the W buffer and read zeros */                                        \
       const bool is_a_ = __builtin_amdgcn_readfirstlane(r_) < BM;                                 \
       const int vo_ = (is_a_ ? r_ : r_ - BM) * srow_bytes;                                        \
       const __amdgpu_buffer_rsrc_t rs_ = is_a_ ? as_rsrc : ws_rsrc;                               \
@@ -336,7 +336,7 @@ static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint
   constexpr int BM = 64 * WM, BN = 64 * WN;
   const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   if (tiles_m * tiles_n > 0x7FFFFFFF) return hipErrorInvalidValue;
-  const size_t lds_bytes = 2 * (size_t)(BM + BN) * (128 + 16);
+  const size_t lds_bytes = 2 * (size_t)(BM + BN) * 128 + 2 * (size_t)((BM + BN + 255) / 256 * 256) * 16;
   auto kern = mxfp4_gemm_kernel<WM, WN, FULLK>;
   if (lds_bytes > 64 * 1024) {
     // raise the dynamic LDS limit once per process and kernel variant (the call is slow)
@@ -353,6 +353,20 @@ static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint
   return hipGetLastError();
 }
 
+// Which output tile: 0 = 256 x 256, 1 = 256 x 128, 2 = 128 x 128.  Every CU holds one workgroup
+// of the two larger tiles (or two of the smallest), so a launch takes ceil(tiles / 256) rounds;
+// a round of the three tile shapes costs 1 : 0.60 : 0.33 (measured at full rounds; the larger the
+// tile, the fewer operand bytes per flop).  Take the cheapest, the larger tile on a tie.
+static int choose_tile(int64_t M, int64_t N) {
+  auto rounds = [&](int bm, int bn) { return (double)((((M + bm - 1) / bm) * ((N + bn - 1) / bn) + 255) / 256); };
+  const double c0 = rounds(256, 256), c1 = 0.60 * rounds(256, 128), c2 = 0.33 * rounds(128, 128);
+  if (c0 <= c1 && c0 <= c2) return 0;
+  return c1 <= c2 ? 1 : 2;
+}
+#ifndef TILE_CFG
+#define TILE_CFG(M_, N_) choose_tile(M_, N_)
+#endif
+
 hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                              const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, int d,
                              hipStream_t stream) {
@@ -360,15 +374,16 @@ hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8
   if ((int64_t)d * 128 >= 0x7FFFFFFF) return hipErrorInvalidValue;
   // a handful of rows: stream the weights (mxfp4_gemm_skinny.hip)
   if (M <= 64) return launch_mxfp4_gemm_skinny(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
-  // large tile when it still gives every CU work; small tile otherwise.  The fast k loop needs
-  // whole 512-element pieces per row and 16-byte aligned scale rows.
+  // The fast k loop needs whole 512-element pieces per row and 16-byte aligned scale rows.
   const bool fullk = (d % 512 == 0) && ((reinterpret_cast<uintptr_t>(A_s) & 15u) == 0) &&
                      ((reinterpret_cast<uintptr_t>(W_s) & 15u) == 0);
-  const int64_t big_tiles = ((M + 255) / 256) * ((N + 255) / 256);
-  if (big_tiles >= 256) {
+  const int cfg = TILE_CFG(M, N);
+  if (cfg == 0)
     return fullk ? launch_tile<4, 4, true>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream)
                  : launch_tile<4, 4, false>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
-  }
+  if (cfg == 1)
+    return fullk ? launch_tile<4, 2, true>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream)
+                 : launch_tile<4, 2, false>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
   return fullk ? launch_tile<2, 2, true>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream)
                : launch_tile<2, 2, false>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
 }

@@ -98,6 +98,9 @@ GEMM_FULL = [
     (16, 4096, 4096),         # decode-sized M
     (1, 14336, 4096),
     (4096, 5120, 25600),      # Qwen3-32B MLP down (d not a power of two)
+    (2048, 4096, 4096),       # LLaMA3-8B attention projection, prefill: the 256 x 128 tile
+    (1000, 8100, 1024),       # 256 x 128 tile with ragged last tiles in both directions
+    (1000, 8100, 640),        # the same with a k range that is not a whole number of 512-element pieces
 ]
 
 
