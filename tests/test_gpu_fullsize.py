@@ -162,3 +162,63 @@ def test_linear_full_size_is_its_two_halves_and_matches_oracle_on_samples(tq, or
     # on the two sides (see test_rotate_quantize_full_size_sampled_rows), hence 5e-3 instead of 1e-3
     assert np.linalg.norm(got - want) / np.linalg.norm(want) <= 5e-3
     rot.close()
+
+
+# ------------------------------------------------- sizes past 2^31 / 2^32 ----
+# Element counts and byte offsets that do not fit 32 bits: every kernel indexes rows with 64-bit
+# arithmetic and only tile-relative offsets with 32 bits.
+
+def test_rotate_quantize_more_than_2_31_elements(tq, oracle):
+    M, d, G = 70000, 32768, 128                  # 2.29e9 elements, 4.6 GB of input
+    g = torch.Generator(device=DEV)
+    g.manual_seed(synth.SEED_BASE + 31)
+    x = torch.empty((M, d), dtype=torch.bfloat16, device=DEV)
+    for r0 in range(0, M, 10000):                # generated in slices: fp32 temporaries stay small
+        r1 = min(M, r0 + 10000)
+        x[r0:r1] = (torch.randn((r1 - r0, d), device=DEV, generator=g) *
+                    torch.exp(torch.randn((r1 - r0, 1), device=DEV, generator=g))).to(torch.bfloat16)
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    codes, scales = tq.torq_rotate_quantize(rot, x)
+    torch.cuda.synchronize()
+    rows = np.array([0, 65535, 65536, 65537, M - 1])      # element index of row 65536 is exactly 2^31
+    rows_t = torch.from_numpy(rows).to(DEV)
+    xs = x[rows_t].contiguous()
+    z_ref = oracle.rotate(synth.bf16_bits(xs), G, Ri, Ra)
+    want_c, want_s = oracle.quantize(z_ref)
+    got_c, got_s = _np(codes[rows_t]), _np(scales[rows_t])
+    # the kernel's own result on the gathered rows (small problem, same arithmetic) must be identical
+    c2, s2 = tq.torq_rotate_quantize(rot, xs)
+    assert np.array_equal(_np(c2), got_c) and np.array_equal(_np(s2), got_s)
+    # and close to the oracle: only boundary values may differ
+    assert (got_s != want_s).mean() <= 0.002
+    unpack = lambda c: np.stack([c & 15, c >> 4], axis=-1).reshape(len(rows), d)
+    assert (unpack(got_c) != unpack(want_c)).mean() <= 0.006
+    rot.close()
+
+
+@pytest.mark.parametrize("M,N,d", [(40000, 60000, 128),      # 2.4e9 outputs (tiled kernel)
+                                   (16, 300000, 32768)])     # 4.9 GB of weight codes (weight-streaming kernel)
+def test_gemm_more_than_2_31_outputs_or_weight_bytes(tq, oracle, M, N, d):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(synth.SEED_BASE + M + N)
+    A_q = torch.randint(0, 256, (M, d // 2), dtype=torch.uint8, device=DEV, generator=g)
+    W_q = torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=DEV, generator=g)
+    A_s = torch.randint(118, 136, (M, d // 32), dtype=torch.uint8, device=DEV, generator=g)
+    W_s = torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=DEV, generator=g)
+    out = tq.mxfp4_gemm(A_q, A_s, W_q, W_s)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(N)
+    n_s = 2048
+    ms = rng.integers(0, M, size=n_s)
+    ns = rng.integers(0, N, size=n_s)
+    ms[:4] = [0, M - 1, M - 1, M // 2]
+    ns[:4] = [0, N - 1, 0, N - 1]
+    um, im = np.unique(ms, return_inverse=True)
+    un, inn = np.unique(ns, return_inverse=True)
+    um_t, un_t = torch.from_numpy(um).to(DEV), torch.from_numpy(un).to(DEV)
+    want = oracle.gemm_sampled(_np(A_q[um_t]), _np(A_s[um_t]), _np(W_q[un_t]), _np(W_s[un_t]), im, inn)
+    got = _np(out[torch.from_numpy(ms).to(DEV), torch.from_numpy(ns).to(DEV)].view(torch.int16)).view(np.uint16)
+    gw, ww = _bf16_bits_to_f64(got), _bf16_bits_to_f64(want)
+    assert np.linalg.norm(gw - ww) / np.linalg.norm(ww) <= 1e-3
+    assert np.all(np.abs(gw - ww) <= np.abs(ww) * 2.0 ** -7 + 1e-3 * np.sqrt(np.mean(ww ** 2)))
