@@ -186,6 +186,40 @@ def test_rotate_quantize_empty_and_single_row(tq, oracle):
     rot.close()
 
 
+def test_non_finite_inputs_stay_local(tq, oracle):
+    # Inf / NaN are outside the contract (their block's codes are unspecified), but they must not
+    # disturb anything else: other blocks of the quantiser and other rows of the rotation keep
+    # their exact results, and nothing faults.
+    rng = np.random.default_rng(9)
+    z = rng.standard_normal((8, 256)).astype(np.float32)
+    bad = z.copy()
+    bad[2, 40] = np.inf
+    bad[5, 200] = np.nan
+    bad[7, 0] = -np.inf
+    want_c, want_s = oracle.quantize(z)
+    got_c, got_s = tq.torq_quantize_f32(torch.from_numpy(bad).to(DEV))
+    torch.cuda.synchronize()
+    got_c, got_s = _np(got_c), _np(got_s)
+    keep = np.ones((8, 8), bool)
+    keep[2, 1] = keep[5, 6] = keep[7, 0] = False
+    assert np.array_equal(got_s[keep], want_s[keep])
+    assert np.array_equal(got_c.reshape(8, 8, 16)[keep], want_c.reshape(8, 8, 16)[keep])
+    assert got_s[2, 1] == 253 and got_s[7, 0] == 253          # biased exponent 255, minus 2
+    d, G = 4096, 128
+    x = synth.activations(6, d, nu=3.0, outliers=20, outlier_scale=50.0, seed=4242).to(DEV)
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    c0, s0 = tq.torq_rotate_quantize(rot, x)
+    xb = x.clone()
+    xb[3, 1000] = float("nan")
+    xb[4, 7] = float("inf")
+    c1, s1 = tq.torq_rotate_quantize(rot, xb)
+    torch.cuda.synchronize()
+    ok = [0, 1, 2, 5]
+    assert torch.equal(c0[ok], c1[ok]) and torch.equal(s0[ok], s1[ok])
+    rot.close()
+
+
 # ---------------------------------------------------------------- GEMM -------
 
 def _rel_fro(got_bits, want_bits):
@@ -301,4 +335,43 @@ def test_linear_is_rotate_quantize_then_gemm(tq, oracle):
     plain = (x.to(torch.float64) @ w.to(torch.float64).T).numpy()
     o = _np(out.to(torch.float64))
     assert np.linalg.norm(o - plain) / np.linalg.norm(plain) < 0.25
+    rot.close()
+
+
+# --------------------------------------------------------------- graphs ------
+
+def test_linear_replays_from_a_hip_graph(tq):
+    # Every entry point only enqueues kernels on the caller's stream and allocates nothing, so a
+    # serving loop can capture it.  The graph is replayed several times, with eager work and
+    # synchronisations in between, and every replay must reproduce the eager result.
+    M, d, N, G = 48, 4096, 1536, 128
+    x = synth.activations(M, d, nu=3.0, outliers=20, outlier_scale=50.0, seed=99).to(DEV)
+    w = synth.weights(N, d, std=0.02, seed=98).to(DEV)
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    W_q, W_s = tq.torq_rotate_quantize(rot, w)
+    ws = torch.empty((tq.torq_linear_workspace_bytes(M, d),), dtype=torch.uint8, device=DEV)
+    eager = tq.torq_linear(rot, x, W_q, W_s, workspace=ws)
+    x2 = synth.activations(M, d, nu=3.0, outliers=20, outlier_scale=50.0, seed=100).to(DEV)
+    eager2 = tq.torq_linear(rot, x2, W_q, W_s, workspace=ws)
+    torch.cuda.synchronize()
+    x_in = x.clone()
+    out = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        tq.torq_linear(rot, x_in, W_q, W_s, out=out, workspace=ws)          # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    with torch.cuda.graph(graph, stream=side):
+        tq.torq_linear(rot, x_in, W_q, W_s, out=out, workspace=ws)
+    for rep in range(4):
+        src, want = (x, eager) if rep % 2 == 0 else (x2, eager2)
+        x_in.copy_(src)
+        out.fill_(1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {rep}"
     rot.close()
