@@ -119,6 +119,20 @@ def main():
     gemm_ms = e[2].elapsed_time(e[3]) / args.steps
     del x_copies
 
+    # ---- what the matrix cores sustain on this part with nothing else running, on this step's own
+    # operands (the weights' packed codes; the bf16 activations): the part lowers its clock under
+    # matrix work on non-trivial operands, so the published peaks are not reachable by any kernel
+    sink = torch.empty((tq.TORQ_DIAG_SINK_FLOATS,), dtype=torch.float32, device=dev)
+    sustained = {}
+    for kind, ops, iters in ((tq.TORQ_DIAG_FP4, W_q, 8000), (tq.TORQ_DIAG_BF16, x, 8000)):
+        tq.torq_diag_mfma_burn(kind, ops, 500, sink=sink)
+        e[0].record()
+        burn_flop = tq.torq_diag_mfma_burn(kind, ops, iters, sink=sink)
+        e[1].record()
+        torch.cuda.synchronize()
+        sustained[kind] = burn_flop / (e[0].elapsed_time(e[1]) * 1e-3) / 1e12
+    del sink
+
     gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
     rq_bytes = M * d * RQ_BYTES_PER_ELEMENT
     rq_gbs = rq_bytes / (rq_ms * 1e-3) / 1e9
@@ -138,13 +152,16 @@ def main():
         "roofline": {"kernel": "mxfp4_gemm", "bound": "mfma", "achieved": round(gemm_tflops, 1),
                      "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / FP4_PEAK_TFLOPS, 4),
                      "traffic": MEASURED_TRAFFIC.get(f"mxfp4_gemm/{args.workload}"),
-                     "avg_kernel_ms": round(gemm_ms, 4)},
+                     "avg_kernel_ms": round(gemm_ms, 4),
+                     "sustained_mfma_only": round(sustained[tq.TORQ_DIAG_FP4], 1),
+                     "frac_of_sustained": round(gemm_tflops / sustained[tq.TORQ_DIAG_FP4], 4)},
         "roofline_rotate_quant": {"kernel": "torq_rotate_quantize", "bound": "hbm", "achieved": round(rq_gbs, 1),
                                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(rq_gbs / HBM_PEAK_GBS, 4),
                                   "traffic": MEASURED_TRAFFIC.get(f"torq_rotate_quantize/{args.workload}"),
                                   "avg_kernel_ms": round(rq_ms, 4),
                                   "mfma_bf16_tflops": round(rq_mfma_tflops, 1),
-                                  "mfma_bf16_frac": round(rq_mfma_tflops / BF16_PEAK_TFLOPS, 4)},
+                                  "mfma_bf16_frac": round(rq_mfma_tflops / BF16_PEAK_TFLOPS, 4),
+                                  "mfma_bf16_sustained_mfma_only": round(sustained[tq.TORQ_DIAG_BF16], 1)},
     }
 
     if not args.no_cpu_baseline:

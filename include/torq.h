@@ -128,6 +128,31 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16,
                 int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
                 void *stream);
 
+/* ------------------------------------------------------------------------ */
+/* Diagnostics (not a step of Algorithm 3): the rate the matrix cores sustain on
+ * this machine with nothing else running, on operands the caller supplies --
+ * the ceiling to read the MFMA-bound kernels against, since the part lowers its
+ * clock under matrix work on non-trivial operands.
+ *
+ *   kind      TORQ_DIAG_FP4  the block-scaled e2m1 MFMA of mxfp4_gemm (unit scales), or
+ *             TORQ_DIAG_BF16 the bf16 MFMA of the rotation
+ *   operands  device, 4-byte aligned, n_bytes >= 128: every lane fills its operand
+ *             registers from it (packed codes for FP4, bf16 values for BF16;
+ *             wraps around)
+ *   iters     rounds of 16 MFMAs per wave, > 0
+ *   sink      device, TORQ_DIAG_SINK_FLOATS floats, overwritten
+ *
+ * Enqueues one kernel that executes TORQ_DIAG_FLOP_PER_ITER_FP4 (or _BF16) * iters
+ * floating-point operations; the caller times it.  Errors: TORQ_EINVAL, TORQ_EALIGN,
+ * TORQ_EHIP. */
+#define TORQ_DIAG_FP4  0
+#define TORQ_DIAG_BF16 1
+#define TORQ_DIAG_SINK_FLOATS (1024 * 256)
+#define TORQ_DIAG_FLOP_PER_ITER_FP4  (1024.0 * 4 * 16 * 2 * 32 * 32 * 64)
+#define TORQ_DIAG_FLOP_PER_ITER_BF16 (1024.0 * 4 * 16 * 2 * 32 * 32 * 16)
+int torq_diag_mfma_burn(int kind, const void *operands, size_t n_bytes, int iters, float *sink,
+                        void *stream);
+
 #ifdef __cplusplus
 }
 #endif

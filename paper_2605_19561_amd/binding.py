@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libtorq.so")
 EXPORTS = [
     "torq_status_string", "torq_rotation_create", "torq_rotation_destroy", "torq_rotation_d",
     "torq_rotation_G", "torq_rotate_quantize", "torq_rotate", "torq_quantize_f32", "mxfp4_gemm",
-    "torq_linear_workspace_bytes", "torq_linear",
+    "torq_linear_workspace_bytes", "torq_linear", "torq_diag_mfma_burn",
 ]
 
 TORQ_OK, TORQ_EINVAL, TORQ_EALIGN, TORQ_EWORKSPACE, TORQ_EHIP, TORQ_ENODEVICE = 0, -1, -2, -3, -4, -5
@@ -61,6 +61,8 @@ def lib():
         L.torq_linear_workspace_bytes.argtypes = [i64, i32]
         L.torq_linear.restype = i32
         L.torq_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, sz, vp]
+        L.torq_diag_mfma_burn.restype = i32
+        L.torq_diag_mfma_burn.argtypes = [i32, vp, sz, i32, vp, vp]
         _lib = L
     return _lib
 
@@ -173,3 +175,22 @@ def torq_linear(rot: Rotation, x_bf16, W_q, W_s, out=None, workspace=None, strea
                              _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)),
            "torq_linear")
     return out
+
+
+TORQ_DIAG_FP4, TORQ_DIAG_BF16 = 0, 1
+TORQ_DIAG_SINK_FLOATS = 1024 * 256
+TORQ_DIAG_FLOP_PER_ITER = {TORQ_DIAG_FP4: 1024.0 * 4 * 16 * 2 * 32 * 32 * 64,
+                           TORQ_DIAG_BF16: 1024.0 * 4 * 16 * 2 * 32 * 32 * 16}
+
+
+def torq_diag_mfma_burn(kind: int, operands: torch.Tensor, iters: int, sink=None, stream=None):
+    """Enqueue the matrix-core burn kernel on `operands` (any contiguous device tensor); returns
+    the number of floating-point operations it executes."""
+    if not (operands.is_cuda and operands.is_contiguous()):
+        raise ValueError("operands: expected a contiguous device tensor")
+    if sink is None:
+        sink = torch.empty((TORQ_DIAG_SINK_FLOATS,), dtype=torch.float32, device=operands.device)
+    _check(lib().torq_diag_mfma_burn(kind, C.c_void_p(operands.data_ptr()), operands.numel() * operands.element_size(),
+                                     iters, _dev(sink, torch.float32, "sink"), _stream(stream)),
+           "torq_diag_mfma_burn")
+    return TORQ_DIAG_FLOP_PER_ITER[kind] * iters

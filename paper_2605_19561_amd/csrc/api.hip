@@ -220,4 +220,15 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 
+int torq_diag_mfma_burn(int kind, const void *operands, size_t n_bytes, int iters, float *sink,
+                        void *stream) {
+  if ((kind != TORQ_DIAG_FP4 && kind != TORQ_DIAG_BF16) || !operands || !sink || n_bytes < 128 || iters <= 0)
+    return TORQ_EINVAL;
+  if ((reinterpret_cast<uintptr_t>(operands) & 3u) || (reinterpret_cast<uintptr_t>(sink) & 3u)) return TORQ_EALIGN;
+  const size_t n_words = n_bytes / 4 > 0x40000000u ? 0x40000000u : n_bytes / 4;
+  hipError_t e = torq::launch_mfma_burn(kind, static_cast<const uint32_t *>(operands), (uint32_t)n_words, iters,
+                                        sink, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
 }  // extern "C"

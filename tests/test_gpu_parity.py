@@ -375,3 +375,24 @@ def test_linear_replays_from_a_hip_graph(tq):
         torch.cuda.synchronize()
         assert torch.equal(out, want), f"replay {rep}"
     rot.close()
+
+
+# ---------------------------------------------------------- diagnostics ------
+
+def test_diag_mfma_burn_runs_and_validates(tq):
+    ops = torch.randint(0, 256, (1 << 16,), dtype=torch.uint8, device=DEV)
+    sink = torch.full((tq.TORQ_DIAG_SINK_FLOATS,), float("nan"), dtype=torch.float32, device=DEV)
+    flop = tq.torq_diag_mfma_burn(tq.TORQ_DIAG_FP4, ops, 4, sink=sink)
+    torch.cuda.synchronize()
+    assert flop == 4 * 1024 * 4 * 16 * 2 * 32 * 32 * 64
+    assert bool(torch.isfinite(sink).all())                 # every lane wrote; e2m1 products are finite
+    zeros = torch.zeros((256,), dtype=torch.uint8, device=DEV)
+    tq.torq_diag_mfma_burn(tq.TORQ_DIAG_BF16, zeros, 3, sink=sink)
+    torch.cuda.synchronize()
+    assert bool((sink == 0).all())
+    with pytest.raises(tq.TorqError):
+        tq.torq_diag_mfma_burn(7, ops, 4, sink=sink)
+    with pytest.raises(tq.TorqError):
+        tq.torq_diag_mfma_burn(tq.TORQ_DIAG_FP4, ops[:64], 4, sink=sink)
+    with pytest.raises(tq.TorqError):
+        tq.torq_diag_mfma_burn(tq.TORQ_DIAG_FP4, ops, 0, sink=sink)
