@@ -180,6 +180,8 @@ def main():
     if args.sweep:
         for dd in (4096, 8192, 14336, 28672):
             print(json.dumps(sweep_line(tq, synth, dd, args.steps, args.warmup)), flush=True)
+        # G = d/32: Algorithm 3 as printed (one R_inter over the whole row), a dense contraction
+        print(json.dumps(sweep_line(tq, synth, 8192, args.steps, args.warmup, G=256)), flush=True)
     rot.close()
 
 
@@ -211,12 +213,12 @@ def cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d):
             "gemm_GFLOPps": round(2.0 * gm * gn * d / t_gemm / 1e9, 3)}
 
 
-def sweep_line(tq, synth, d, steps, warmup):
+def sweep_line(tq, synth, d, steps, warmup, G=None):
     """rotate+quantise alone on X [16384, d] (the memory-bound sweep)."""
     import torch
     dev = "cuda:0"
     M = 16384
-    G = synth.default_G(d)
+    G = G or synth.default_G(d)
     x = synth.activations(M, d, nu=3.0, outliers=round(0.005 * d), outlier_scale=50.0, seed=synth.SEED_BASE + 5,
                           device=dev)
     Ri, Ra = synth.rotations(G)
@@ -236,7 +238,8 @@ def sweep_line(tq, synth, d, steps, warmup):
     rot.close()
     return {"metric": "torq_rotate_quantize bandwidth", "value": round(gbs, 1), "unit": "GB/s",
             "config": {"workload": f"sweep: X bf16 [{M}, {d}], G={G}"}, "ms": round(ms, 4),
-            "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+            "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+            "mfma_bf16_tflops": round(M * d * (2 * 2 * G + 3 * 64) / (ms * 1e-3) / 1e12, 1)}
 
 
 if __name__ == "__main__":

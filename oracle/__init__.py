@@ -18,8 +18,9 @@ _lib = None
 def lib():
     global _lib
     if _lib is None:
-        path = _build.LIB
-        if not os.path.exists(path):
+        # TORQ_ORACLE_LIB: the mutation test of the pins points this at a deliberately broken build
+        path = os.environ.get("TORQ_ORACLE_LIB") or _build.LIB
+        if path == _build.LIB and not os.path.exists(path):
             _build.build()
         L = C.CDLL(path)
         i64, i32, f32, f64, vp = C.c_int64, C.c_int, C.c_float, C.c_double, C.c_void_p

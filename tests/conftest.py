@@ -16,6 +16,7 @@ def pytest_configure(config):
 def oracle():
     import oracle as o
     from oracle import build
-    build.build(force=False)
+    if not os.environ.get("TORQ_ORACLE_LIB"):
+        build.build(force=False)
     o.lib()
     return o

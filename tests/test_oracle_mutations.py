@@ -1,0 +1,85 @@
+"""Do the pins bite?  Each case plants ONE plausible mistake in a temporary copy of the C oracle
+(a transposed operand, a dropped term, a wrong tie, a swapped nibble, an off-by-one exponent ...),
+builds it on the CPU and runs the oracle's pin tests against that build in a child process.  The
+pins are worth something only if every such build fails at least one of them.  The unmodified
+source must pass under the same harness.  Nothing here touches the GPU or the product library.
+"""
+import os
+import subprocess
+import sys
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+SRC = os.path.join(ROOT, "oracle", "torq_oracle.c")
+PIN_FILES = ["tests/test_oracle_formats.py", "tests/test_oracle_rotation.py", "tests/test_oracle_gemm.py"]
+
+# (name, text in torq_oracle.c, replacement)
+MUTATIONS = [
+    ("inter_transposed", "R_inter[b * G + bp] * X[(g0 + bp) * BLK + k]", "R_inter[bp * G + b] * X[(g0 + bp) * BLK + k]"),
+    ("inter_ignores_group", "R_inter[b * G + bp] * X[(g0 + bp) * BLK + k]", "R_inter[b * G + bp] * X[(bp) * BLK + k]"),
+    ("intra_transposed", "Y[b * BLK + kp] * (double)R_intra[kp * BLK + k]", "Y[b * BLK + kp] * (double)R_intra[k * BLK + kp]"),
+    ("intra_wrong_block", "Y[b * BLK + kp] * (double)R_intra[kp * BLK + k]", "Y[kp] * (double)R_intra[kp * BLK + k]"),
+    ("inter_in_float", "acc += (double)R_inter[b * G + bp] * X[(g0 + bp) * BLK + k];",
+     "acc = (float)(acc + (float)(R_inter[b * G + bp] * (float)X[(g0 + bp) * BLK + k]));"),
+    ("scale_bias_1", "int byte = field - 2;", "int byte = field - 1;"),
+    ("scale_bias_3", "int byte = field - 2;", "int byte = field - 3;"),
+    ("scale_no_floor_clamp", "if (byte < 0) byte = 0;", ""),
+    ("tie_0.25", "if      (m <= 0.25f) idx = 0;", "if      (m <  0.25f) idx = 0;"),
+    ("tie_0.75", "else if (m <  0.75f) idx = 1;", "else if (m <= 0.75f) idx = 1;"),
+    ("tie_1.25", "else if (m <= 1.25f) idx = 2;", "else if (m <  1.25f) idx = 2;"),
+    ("tie_1.75", "else if (m <  1.75f) idx = 3;", "else if (m <= 1.75f) idx = 3;"),
+    ("tie_2.5", "else if (m <= 2.5f)  idx = 4;", "else if (m <  2.5f)  idx = 4;"),
+    ("tie_3.5", "else if (m <  3.5f)  idx = 5;", "else if (m <= 3.5f)  idx = 5;"),
+    ("tie_5", "else if (m <= 5.0f)  idx = 6;", "else if (m <  5.0f)  idx = 6;"),
+    ("codebook_top", "3.0f, 4.0f, 6.0f};", "3.0f, 4.0f, 8.0f};"),
+    ("sign_dropped", "uint8_t sign = (uint8_t)((u >> 31) << 3);", "uint8_t sign = (a < 0.0f) ? 8 : 0;"),   # loses -0
+    ("amax_without_abs", "float v = fabsf(zr[b * BLK + k]);", "float v = zr[b * BLK + k];"),
+    ("normalise_off_by_one", "ldexpf(zr[b * BLK + k], 127 - (int)byte)", "ldexpf(zr[b * BLK + k], 126 - (int)byte)"),
+    ("pack_nibbles_swapped", "(uint8_t)(c[2 * j] | (c[2 * j + 1] << 4))", "(uint8_t)(c[2 * j + 1] | (c[2 * j] << 4))"),
+    ("dequant_nibbles_swapped", "uint8_t code = (j & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 15u);",
+     "uint8_t code = (j & 1) ? (uint8_t)(byte & 15u) : (uint8_t)(byte >> 4);"),
+    ("dequant_exponent", "int e = (int)scales[m * (int64_t)B + b] - 127;", "int e = (int)scales[m * (int64_t)B + b] - 126;"),
+    ("gemm_act_scale_bias", "(int)as[j / BLK] - 127", "(int)as[j / BLK] - 126"),
+    ("gemm_weight_scale_index", "(int)ws[j / BLK] - 127", "(int)ws[0] - 127"),
+    ("gemm_weight_nibbles_swapped", "uint8_t wc = (j & 1) ? (uint8_t)(wb >> 4) : (uint8_t)(wb & 15u);",
+     "uint8_t wc = (j & 1) ? (uint8_t)(wb & 15u) : (uint8_t)(wb >> 4);"),
+    ("gemm_in_float", "acc += av * wv;", "acc = (float)(acc + av * wv);"),
+    ("gemm_drops_last_block", "for (int j = 0; j < d; ++j) {\n        uint8_t ab", "for (int j = 0; j < d - BLK; ++j) {\n        uint8_t ab"),
+    ("bf16_truncates", "uint32_t up = (dropped > 0x8000u) || (dropped == 0x8000u && kept_lsb);", "uint32_t up = 0; (void)kept_lsb; (void)dropped;"),
+    ("bf16_ties_away", "(dropped == 0x8000u && kept_lsb)", "(dropped == 0x8000u)"),
+    ("equalize_other_root", "const double t = -(a - c) / (g + (g >= 0.0 ? D : -D));", "const double t = -(a - c) / (g - (g >= 0.0 ? D : -D) + 1e-300);"),
+    ("equalize_jacobi_angle", "const double t = -(a - c) / (g + (g >= 0.0 ? D : -D));",
+     "const double t = tan(0.5 * atan2(2.0 * g, a - b)); (void)D;"),
+    ("equalize_R_transposed", "R[i * B + q] = cs * ri + sn * rj;\n            R[j * B + q] = -sn * ri + cs * rj;",
+     "R[i * B + q] = cs * ri - sn * rj;\n            R[j * B + q] = sn * ri + cs * rj;"),
+]
+
+
+def _build(tmp_path, name, text):
+    src = tmp_path / f"{name}.c"
+    src.write_text(text)
+    lib = tmp_path / f"lib{name}.so"
+    subprocess.run(["gcc", "-O2", "-std=c99", "-fPIC", "-shared", "-fopenmp", "-ffp-contract=off",
+                    f"-I{os.path.join(ROOT, 'oracle')}", "-o", str(lib), str(src), "-lm"], check=True)
+    return str(lib)
+
+
+def _run_pins(lib):
+    env = dict(os.environ, TORQ_ORACLE_LIB=lib, OMP_NUM_THREADS="2")
+    return subprocess.run([sys.executable, "-m", "pytest", "-x", "-q", "-m", "not gpu", "-p", "no:cacheprovider",
+                           *PIN_FILES], cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
+
+
+def test_unmodified_oracle_passes_under_the_same_harness(tmp_path):
+    r = _run_pins(_build(tmp_path, "clean", open(SRC).read()))
+    assert r.returncode == 0, r.stdout[-2000:]
+
+
+@pytest.mark.parametrize("name,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
+def test_a_planted_mistake_fails_a_pin(tmp_path, name, old, new):
+    text = open(SRC).read()
+    assert text.count(old) >= 1, f"mutation target not found in torq_oracle.c: {old!r}"
+    r = _run_pins(_build(tmp_path, name, text.replace(old, new)))
+    assert r.returncode == 1, f"no pin noticed '{name}' (pytest exit {r.returncode}):\n{r.stdout[-1500:]}"
+    assert " failed" in r.stdout
