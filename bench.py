@@ -182,6 +182,10 @@ def main():
             print(json.dumps(sweep_line(tq, synth, dd, args.steps, args.warmup)), flush=True)
         # G = d/32: Algorithm 3 as printed (one R_inter over the whole row), a dense contraction
         print(json.dumps(sweep_line(tq, synth, 8192, args.steps, args.warmup, G=256)), flush=True)
+        # decode-sized linear layers (few activation rows: weight streaming, HBM bound), timed as
+        # replays of a HIP graph of 20 calls so that Python's launch overhead is not in the figure
+        for (mm, nn, dd) in ((1, 14336, 4096), (16, 14336, 4096), (16, 4096, 14336), (16, 28672, 8192)):
+            print(json.dumps(decode_line(tq, synth, mm, nn, dd)), flush=True)
     rot.close()
 
 
@@ -240,6 +244,52 @@ def sweep_line(tq, synth, d, steps, warmup, G=None):
             "config": {"workload": f"sweep: X bf16 [{M}, {d}], G={G}"}, "ms": round(ms, 4),
             "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
             "mfma_bf16_tflops": round(M * d * (2 * 2 * G + 3 * 64) / (ms * 1e-3) / 1e12, 1)}
+
+
+def decode_line(tq, synth, M, N, d):
+    """torq_linear (rotate + quantise + GEMM) on M activation rows: microseconds per call and the rate at
+    which the packed weights stream through.  Six weight copies rotate so that the Infinity Cache cannot
+    hold them."""
+    import torch
+    dev = "cuda:0"
+    G = synth.default_G(d)
+    x = synth.activations(M, d, nu=3.0, outliers=round(0.005 * d), outlier_scale=50.0, seed=synth.SEED_BASE + 7,
+                          device=dev)
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(synth.SEED_BASE + N + d)
+    n_copies = 6
+    W_q = [torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=dev, generator=gen) for _ in range(n_copies)]
+    W_s = [torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=dev, generator=gen) for _ in range(n_copies)]
+    out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty((tq.torq_linear_workspace_bytes(M, d),), dtype=torch.uint8, device=dev)
+    calls = 24
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for i in range(n_copies):
+            tq.torq_linear(rot, x, W_q[i], W_s[i], out=out, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for i in range(calls):
+            tq.torq_linear(rot, x, W_q[i % n_copies], W_s[i % n_copies], out=out, workspace=ws)
+    graph.replay()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    reps = 10
+    e0.record()
+    for _ in range(reps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    us = e0.elapsed_time(e1) * 1e3 / (reps * calls)
+    wbytes = N * d * 0.53125
+    rot.close()
+    return {"metric": "torq_linear, decode", "value": round(us, 2), "unit": "us per call", "higher_is_better": False,
+            "config": {"workload": f"decode: X bf16 [{M}, {d}], G={G}, W [{N}, {d}] packed MXFP4 ({wbytes / 1e6:.1f} MB)"},
+            "weight_stream_GBps": round(wbytes / us / 1e3, 1), "frac_hbm_peak": round(wbytes / us / 1e3 / HBM_PEAK_GBS, 4)}
 
 
 if __name__ == "__main__":
