@@ -373,7 +373,7 @@ hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8
   // a tile's rows must be addressable with 32-bit offsets: 256 rows of d/2 bytes
   if ((int64_t)d * 128 >= 0x7FFFFFFF) return hipErrorInvalidValue;
   // a handful of rows: stream the weights (mxfp4_gemm_skinny.hip)
-  if (M <= 64) return launch_mxfp4_gemm_skinny(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
+  if (mxfp4_gemm_skinny_fits(M, d)) return launch_mxfp4_gemm_skinny(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
   // The fast k loop needs whole 512-element pieces per row and 16-byte aligned scale rows.
   const bool fullk = (d % 512 == 0) && ((reinterpret_cast<uintptr_t>(A_s) & 15u) == 0) &&
                      ((reinterpret_cast<uintptr_t>(W_s) & 15u) == 0);

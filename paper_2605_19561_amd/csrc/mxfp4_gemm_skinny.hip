@@ -30,6 +30,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 #define LDSP(x) ((__attribute__((address_space(3))) void *)(x))
 
 constexpr int WAVES = 8;              // waves per workgroup = ways the k range is split
+constexpr size_t SKINNY_MAX_LDS = 160 * 1024;
 constexpr int SKINNY_MIN_GROUPS = 384; // fewer workgroups than this leave CUs without work (256 CUs)
 
 // a voffset that the range check of any buffer used here rejects (the load then delivers zeros)
@@ -186,7 +187,17 @@ static hipError_t launch_cfg(const uint8_t *A_q, const uint8_t *A_s, const uint8
   const size_t scale_bytes = (size_t)((16 * NS * pd + 63) / 64 + (16 * MT * pd + 63) / 64) * 256;
   const size_t red_bytes = (size_t)(WAVES - 1) * NS * MT * 4 * 64 * sizeof(float);
   const size_t lds_bytes = scale_bytes > red_bytes ? scale_bytes : red_bytes;
-  if (lds_bytes > 64 * 1024) return hipErrorInvalidValue;
+  if (lds_bytes > SKINNY_MAX_LDS) return hipErrorInvalidValue;
+  if (lds_bytes > 64 * 1024) {
+    // raise the dynamic LDS limit once per process and kernel variant (the call is slow)
+    static bool raised = false;
+    if (!raised) {
+      hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(mxfp4_gemm_skinny_kernel<MT, NS, PT>),
+                                         hipFuncAttributeMaxDynamicSharedMemorySize, (int)SKINNY_MAX_LDS);
+      if (e != hipSuccess) return e;
+      raised = true;
+    }
+  }
   hipLaunchKernelGGL((mxfp4_gemm_skinny_kernel<MT, NS, PT>), dim3((unsigned)groups), dim3(64 * WAVES), lds_bytes,
                      stream, A_q, A_s, W_q, W_s, reinterpret_cast<uint16_t *>(out), (int)M, N, d);
   return hipGetLastError();
@@ -215,9 +226,16 @@ static hipError_t launch_mt(const uint8_t *A_q, const uint8_t *A_s, const uint8_
   return launch_mt_ns<MT, 1>(A_q, A_s, W_q, W_s, out, M, N, d, stream);
 }
 
+// Whether the scale rows of (up to two) strips and of the activations fit the LDS.
+bool mxfp4_gemm_skinny_fits(int64_t M, int d) {
+  const int MT = (int)((M + 15) / 16), NS = MT <= 2 ? 2 : 1;
+  const int pd = d / 128 + 1;
+  return M >= 1 && M <= 64 &&
+         (size_t)((16 * NS * pd + 63) / 64 + (16 * MT * pd + 63) / 64) * 256 <= SKINNY_MAX_LDS;
+}
+
 // 1 <= M <= 64; d a multiple of 128 with 64 rows of d / 2 bytes addressable in 32 bits (the caller
-// checks both); the scale rows of the strip and of the activations must fit 64 KiB of LDS
-// (d <= 406 thousand at M <= 64), else hipErrorInvalidValue.
+// checks both) and mxfp4_gemm_skinny_fits(M, d).
 hipError_t launch_mxfp4_gemm_skinny(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                                     const uint8_t *W_s, void *out, int64_t M, int64_t N, int d,
                                     hipStream_t stream) {

@@ -34,7 +34,9 @@ hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8
                              const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, int d,
                              hipStream_t stream);
 
-// The same product for 1 <= M <= 64 (weight-streaming layout); called by launch_mxfp4_gemm.
+// The same product for 1 <= M <= 64 (weight-streaming layout); called by launch_mxfp4_gemm when
+// mxfp4_gemm_skinny_fits (the scale rows it stages fit the LDS).
+bool mxfp4_gemm_skinny_fits(int64_t M, int d);
 hipError_t launch_mxfp4_gemm_skinny(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                                     const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, int d,
                                     hipStream_t stream);

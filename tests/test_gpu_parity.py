@@ -253,7 +253,9 @@ def test_gemm_random_codes(tq, oracle, M, N, d):
 # with a ragged last one, N not a multiple of 16 or of 4, and enough weight rows (with M >= 8) for
 # the two-strips-per-workgroup variant, ragged there as well.
 GEMM_FEW_ROWS = [(1, 16, 128), (1, 4099, 384), (2, 1000, 8192), (7, 130, 14336), (16, 12300, 256),
-                 (17, 12290, 384), (32, 515, 2048), (33, 257, 4096), (48, 100, 640), (64, 1030, 1152)]
+                 (17, 12290, 384), (32, 515, 2048), (33, 257, 4096), (48, 100, 640), (64, 1030, 1152),
+                 (64, 300, 28672),       # scale rows need more than 64 KiB of LDS
+                 (4, 40, 131072)]        # ... more than a CU has: served by the tiled kernel
 
 
 @pytest.mark.parametrize("M,N,d", GEMM_FEW_ROWS)
