@@ -48,6 +48,9 @@ def main():
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that a rocprofv3 --pmc run of this "
                          "command carries its own scale for FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--library-gemm", action="store_true",
+                    help="also time the vendor library's block-scaled fp4 GEMM (torch._scaled_mm -> hipBLASLt) on "
+                         "the same operands, for context; its first call takes about half a minute")
     ap.add_argument("--sweep", action="store_true",
                     help="also print one line per rotate+quantise bandwidth-sweep shape ([16384, d])")
     args = ap.parse_args()
@@ -164,6 +167,9 @@ def main():
                                   "mfma_bf16_sustained_mfma_only": round(sustained[tq.TORQ_DIAG_BF16], 1)},
     }
 
+    if args.library_gemm:
+        result["roofline"]["library_gemm"] = library_gemm(torch, codes, scales, W_q, W_s, M, N, d, args.steps)
+
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d)
 
@@ -187,6 +193,29 @@ def main():
         for (mm, nn, dd) in ((1, 14336, 4096), (16, 14336, 4096), (16, 4096, 14336), (16, 28672, 8192)):
             print(json.dumps(decode_line(tq, synth, mm, nn, dd)), flush=True)
     rot.close()
+
+
+def library_gemm(torch, A_q, A_s, W_q, W_s, M, N, d, steps):
+    """The same product through the vendor library (hipBLASLt behind torch._scaled_mm), same packed
+    operands and scale bytes.  Context only: nothing in the measured path calls it."""
+    try:
+        a = A_q.view(torch.float4_e2m1fn_x2)
+        b = W_q.view(torch.float4_e2m1fn_x2)
+        sa, sb = A_s.view(torch.float8_e8m0fnu), W_s.view(torch.float8_e8m0fnu)
+        f = lambda: torch._scaled_mm(a, b.t(), scale_a=sa, scale_b=sb, out_dtype=torch.bfloat16)
+        for _ in range(3):
+            f()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / steps
+        return {"what": "torch._scaled_mm (hipBLASLt), same operands", "avg_kernel_ms": round(ms, 4),
+                "achieved": round(2.0 * M * N * d / (ms * 1e-3) / 1e12, 1), "unit": "TFLOP/s"}
+    except Exception as ex:  # not every build of the library has this path
+        return {"what": "torch._scaled_mm (hipBLASLt)", "error": repr(ex)[:200]}
 
 
 def cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d):
