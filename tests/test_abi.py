@@ -69,6 +69,12 @@ def test_compute_calls_reject_bad_arguments_without_launching():
     assert L.torq_rotate(None, good, 4, good, None) == binding.TORQ_EINVAL
     assert L.torq_linear(None, good, good, good, good, 4, 4, good, 1 << 20, None) == binding.TORQ_EINVAL
     assert L.torq_rotation_d(None) == binding.TORQ_EINVAL
+    odd2 = C.c_void_p(0x1002)
+    assert L.torq_diag_mfma_burn(7, good, 4096, 4, good, None) == binding.TORQ_EINVAL          # unknown kind
+    assert L.torq_diag_mfma_burn(0, None, 4096, 4, good, None) == binding.TORQ_EINVAL
+    assert L.torq_diag_mfma_burn(0, good, 64, 4, good, None) == binding.TORQ_EINVAL            # too few operand bytes
+    assert L.torq_diag_mfma_burn(1, good, 4096, 0, good, None) == binding.TORQ_EINVAL
+    assert L.torq_diag_mfma_burn(1, odd2, 4096, 4, good, None) == binding.TORQ_EALIGN
 
 
 def test_workspace_size():
