@@ -52,6 +52,8 @@ def lib():
         L.torq_o_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i32, vp, vp]
         L.torq_o_gemm_sampled.restype = None
         L.torq_o_gemm_sampled.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, vp]
+        L.torq_o_block_gram.restype = None
+        L.torq_o_block_gram.argtypes = [vp, i64, i32, i32, vp]
         L.torq_o_equalize.restype = i32
         L.torq_o_equalize.argtypes = [vp, i32, f64, vp]
         L.torq_o_threads.restype = i32
@@ -209,6 +211,16 @@ def gemm_sampled(A_q, A_s, W_q, W_s, ms, ns, want_f64=False):
     lib().torq_o_gemm_sampled(_p(A_q), _p(A_s), _p(W_q), _p(W_s), d, ms.size,
                               _p(ms), _p(ns), _p(out), _p(o64))
     return (out, o64) if want_f64 else out
+
+
+def block_gram(x_bf16, G):
+    """x_bf16: uint16 [M, d] -> Sigma float64 [G, G], the mean Gram matrix of the runs of G blocks."""
+    x = _arr(x_bf16, np.uint16)
+    M, d = x.shape
+    assert d % 32 == 0 and (d // 32) % G == 0
+    S = np.empty((G, G), np.float64)
+    lib().torq_o_block_gram(_p(x), M, d, G, _p(S))
+    return S
 
 
 def equalize(Sigma, eps=0.0):

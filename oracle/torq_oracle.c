@@ -305,6 +305,32 @@ void torq_o_gemm_sampled(const uint8_t *A_q, const uint8_t *A_s,
 
 /* ------------------------------------------------- variance equalisation -- */
 
+/* Section 5.1: the covariance of the block view that Algorithm 1 equalises.  With one shared
+ * R_inter for all in-block positions, the quantity that R_inter acts on is the Gram matrix of
+ * the blocks, Sigma[b][b'] = E <x_b, x_b'>; diag(R Sigma R^T) are then the block energies
+ * sigma_b^2 = E ||z_b||^2 of Theorem 4.1 after the rotation.  The expectation is the plain mean
+ * over all runs of G blocks in the sample. */
+void torq_o_block_gram(const uint16_t *x_bf16, int64_t M, int d, int G, double *Sigma)
+{
+    const int B = d / BLK;
+    const int64_t groups = M * (int64_t)(B / G);
+    for (int i = 0; i < G * G; ++i) Sigma[i] = 0.0;
+    for (int64_t m = 0; m < M; ++m)
+        for (int g0 = 0; g0 < B; g0 += G) {
+            const uint16_t *X = x_bf16 + m * (int64_t)d + (int64_t)g0 * BLK;
+            for (int b = 0; b < G; ++b)
+                for (int bp = 0; bp < G; ++bp) {
+                    double acc = 0.0;
+                    for (int k = 0; k < BLK; ++k)
+                        acc += (double)torq_o_bf16_to_f32(X[b * BLK + k]) *
+                               (double)torq_o_bf16_to_f32(X[bp * BLK + k]);
+                    Sigma[b * G + bp] += acc;
+                }
+        }
+    if (groups > 0)
+        for (int i = 0; i < G * G; ++i) Sigma[i] /= (double)groups;
+}
+
 /* Algorithm 1 (Section 5.1): plane rotations until diag(R Sigma R^T) = c 1,
  * c = tr(Sigma) / B.  Each step takes the block i furthest above c and the
  * block j furthest below it (opposite deviation signs, as the algorithm asks)

@@ -95,6 +95,12 @@ void torq_o_gemm_sampled(const uint8_t *A_q, const uint8_t *A_s,
                          const int64_t *ms, const int64_t *ns,
                          uint16_t *out_bf16, double *out_f64);
 
+/* The statistic Algorithm 1 starts from (Section 5.1; Section 4.2, sigma_b^2 = E||z_b||^2): the
+ * block Gram matrix Sigma[b][b'] = mean over token-groups of <x_b, x_b'>, a token-group being one
+ * run of G consecutive 32-element blocks of one row (every row of [M, d] holds d/32/G of them).
+ * Sigma is G x G, row-major, double.  Its diagonal holds the mean block energies. */
+void torq_o_block_gram(const uint16_t *x_bf16, int64_t M, int d, int G, double *Sigma);
+
 /* Algorithm 1 with the equalising angle (the printed Jacobi angle separates
  * the two diagonal entries instead of moving one onto the target).  Sigma is
  * B x B symmetric, overwritten by R Sigma R^T; R receives the rotation.

@@ -48,6 +48,11 @@ MUTATIONS = [
     ("gemm_drops_last_block", "for (int j = 0; j < d; ++j) {\n        uint8_t ab", "for (int j = 0; j < d - BLK; ++j) {\n        uint8_t ab"),
     ("bf16_truncates", "uint32_t up = (dropped > 0x8000u) || (dropped == 0x8000u && kept_lsb);", "uint32_t up = 0; (void)kept_lsb; (void)dropped;"),
     ("bf16_ties_away", "(dropped == 0x8000u && kept_lsb)", "(dropped == 0x8000u)"),
+    ("gram_ignores_later_runs", "const uint16_t *X = x_bf16 + m * (int64_t)d + (int64_t)g0 * BLK;",
+     "const uint16_t *X = x_bf16 + m * (int64_t)d;"),
+    ("gram_sum_not_mean", "for (int i = 0; i < G * G; ++i) Sigma[i] /= (double)groups;",
+     "for (int i = 0; i < G * G; ++i) Sigma[i] /= (double)M;"),
+    ("gram_wrong_partner", "(double)torq_o_bf16_to_f32(X[bp * BLK + k]);", "(double)torq_o_bf16_to_f32(X[bp * BLK + (k ^ 1)]);"),
     ("equalize_other_root", "const double t = -(a - c) / (g + (g >= 0.0 ? D : -D));", "const double t = -(a - c) / (g - (g >= 0.0 ? D : -D) + 1e-300);"),
     ("equalize_jacobi_angle", "const double t = -(a - c) / (g + (g >= 0.0 ? D : -D));",
      "const double t = tan(0.5 * atan2(2.0 * g, a - b)); (void)D;"),

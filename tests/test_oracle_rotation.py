@@ -193,3 +193,61 @@ def test_equalizer_trivial_cases(oracle):
     assert steps == 1
     assert np.allclose(np.abs(R), np.sqrt(0.5))
     assert np.allclose(np.diag(S), 3.0)
+
+
+# ------------------------------------------------- block Gram (Section 5.1) -
+
+def test_block_gram_against_its_definition_and_invariants(oracle):
+    # several runs of G blocks per row, outlier channels: compared with the same contraction written
+    # with numpy's einsum on the widened values (a library routine, not the oracle's loops)
+    M, d, G = 24, 3072, 32
+    x = synth.activations(M, d, nu=3.0, outliers=12, outlier_scale=50.0, seed=41)
+    S = oracle.block_gram(synth.bf16_bits(x), G)
+    X = x.to(torch.float64).numpy().reshape(M * (d // 32 // G), G, 32)
+    want = np.einsum("tbk,tck->bc", X, X) / X.shape[0]
+    assert np.abs(S - want).max() <= 1e-12 * np.abs(want).max()
+    assert np.array_equal(S, S.T)                                       # same products, same order
+    assert np.linalg.eigvalsh(S).min() > -1e-9 * np.trace(S)            # a Gram matrix
+    # the diagonal is the mean block energy; the trace the mean energy of a run
+    assert np.allclose(np.diag(S), (X ** 2).sum(axis=2).mean(axis=0), rtol=1e-12)
+    assert abs(np.trace(S) - (X ** 2).sum() / X.shape[0]) <= 1e-12 * np.trace(S)
+
+
+def test_block_gram_closed_forms(oracle):
+    G = 16
+    # every block equal to one vector v: Sigma = |v|^2 * ones (rank one)
+    v = np.arange(1, 33, dtype=np.float32) / 8.0                          # exact in bf16
+    x = torch.from_numpy(np.tile(v, (5, G))).to(torch.bfloat16)
+    S = oracle.block_gram(synth.bf16_bits(x), G)
+    assert np.array_equal(S, np.full((G, G), float((v.astype(np.float64) ** 2).sum())))
+    # one-hot rows: row m has a 1 at element 32 * (m % G): Sigma = I / G (mean over G rows)
+    x = torch.zeros((G, 32 * G), dtype=torch.bfloat16)
+    for m in range(G):
+        x[m, 32 * m] = 1.0
+    assert np.array_equal(oracle.block_gram(synth.bf16_bits(x), G), np.eye(G) / G)
+    # blocks b and b+1 carry the same vector with opposite sign in one run: off-diagonal -|v|^2
+    x = torch.zeros((1, 32 * G), dtype=torch.bfloat16)
+    x[0, 32 * 3:32 * 4] = torch.from_numpy(v).to(torch.bfloat16)
+    x[0, 32 * 4:32 * 5] = -torch.from_numpy(v).to(torch.bfloat16)
+    S = oracle.block_gram(synth.bf16_bits(x), G)
+    e = float((v.astype(np.float64) ** 2).sum())
+    assert S[3, 3] == e and S[4, 4] == e and S[3, 4] == -e and S[4, 3] == -e and np.count_nonzero(S) == 4
+
+
+def test_rotating_with_the_equalizer_of_the_sample_gram_equalizes_block_energies(oracle):
+    # Sections 4.2 / 5.1 end to end on the oracle: Gram of a sample -> Algorithm 1 -> rotate that
+    # sample -> Gram of the result has a constant diagonal (and is R Sigma R^T)
+    M, d, G = 96, 2048, 32
+    x = synth.activations(M, d, nu=3.0, outliers=10, outlier_scale=50.0, seed=43)
+    xb = synth.bf16_bits(x)
+    Sigma = oracle.block_gram(xb, G)
+    c = np.trace(Sigma) / G
+    R, _, steps = oracle.equalize(Sigma, eps=1e-12 * c)
+    assert 0 < steps <= G - 1
+    X = x.to(torch.float64).numpy()
+    Y = oracle.rotate_inter(X, G, R.astype(np.float32))
+    Yg = Y.reshape(M * (d // 32 // G), G, 32)
+    energies = (Yg ** 2).sum(axis=2).mean(axis=0)
+    assert np.abs(energies - c).max() < 1e-5 * c
+    before = np.diag(Sigma)
+    assert before.max() / before.min() > 20.0
