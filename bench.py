@@ -188,6 +188,8 @@ def main():
             print(json.dumps(sweep_line(tq, synth, dd, args.steps, args.warmup)), flush=True)
         # G = d/32: Algorithm 3 as printed (one R_inter over the whole row), a dense contraction
         print(json.dumps(sweep_line(tq, synth, 8192, args.steps, args.warmup, G=256)), flush=True)
+        # calibration statistic (Section 5.1): block Gram matrix of the benchmark's activations, HBM bound
+        print(json.dumps(gram_line(tq, x, G, args.steps, args.warmup)), flush=True)
         # decode-sized linear layers (few activation rows: weight streaming, HBM bound), timed as
         # replays of a HIP graph of 20 calls so that Python's launch overhead is not in the figure
         for (mm, nn, dd) in ((1, 14336, 4096), (16, 14336, 4096), (16, 4096, 14336), (16, 28672, 8192)):
@@ -273,6 +275,28 @@ def sweep_line(tq, synth, d, steps, warmup, G=None):
             "config": {"workload": f"sweep: X bf16 [{M}, {d}], G={G}"}, "ms": round(ms, 4),
             "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
             "mfma_bf16_tflops": round(M * d * (2 * 2 * G + 3 * 64) / (ms * 1e-3) / 1e12, 1)}
+
+
+def gram_line(tq, x, G, steps, warmup):
+    """torq_block_gram on the step's activations: 2 bytes per element read once."""
+    import torch
+    M, d = x.shape
+    xs = [x, x.clone(), x.clone()]                   # 3 x 134 MB: more than the Infinity Cache holds
+    Sigma = torch.empty((G, G), dtype=torch.float64, device=x.device)
+    ws = torch.empty((tq.torq_block_gram_workspace_bytes(G),), dtype=torch.uint8, device=x.device)
+    for i in range(warmup):
+        tq.torq_block_gram(xs[i % 3], G, Sigma=Sigma, workspace=ws)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        tq.torq_block_gram(xs[i % 3], G, Sigma=Sigma, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    gbs = M * d * 2.0 / (ms * 1e-3) / 1e9
+    return {"metric": "torq_block_gram bandwidth", "value": round(gbs, 1), "unit": "GB/s",
+            "config": {"workload": f"calibration statistic: X bf16 [{M}, {d}], G={G}"}, "ms": round(ms, 4),
+            "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
 
 
 def decode_line(tq, synth, M, N, d):

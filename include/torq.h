@@ -36,7 +36,10 @@ enum {
     TORQ_EALIGN      = -2,  /* a device pointer is not 16-byte aligned */
     TORQ_EWORKSPACE  = -3,  /* workspace smaller than torq_linear_workspace_bytes() */
     TORQ_EHIP        = -4,  /* the HIP runtime reported an error (allocation, copy or launch) */
-    TORQ_ENODEVICE   = -5   /* no gfx950 device is current */
+    TORQ_ENODEVICE   = -5,  /* no gfx950 device is current */
+    TORQ_ECONVERGE   = -6   /* torq_equalize_inter: no pair of blocks with deviations of opposite sign is
+                               left although the tolerance is not met (Sigma not symmetric, or eps below
+                               what double precision can reach) */
 };
 
 #define TORQ_BLOCK 32       /* elements per microscaling block (the paper's K) */
@@ -127,6 +130,36 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16,
                 const uint8_t *W_q, const uint8_t *W_s, void *out_bf16,
                 int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
                 void *stream);
+
+/* ------------------------------------------------------------------------ */
+/* Calibration of the inter-block rotation (Section 5.1, Algorithm 1).  Not part of the online
+ * path: run once on calibration activations to obtain R_inter for torq_rotation_create.
+ *
+ * torq_block_gram: the statistic Algorithm 1 equalises,
+ *   Sigma[b][b'] = mean over token-groups of sum_k X[b][k] X[b'][k],
+ * a token-group being one run of G consecutive blocks of one row of x (Section 4.2: the diagonal
+ * holds the block energies sigma_b^2 = E||x_b||^2 of Theorem 4.1).
+ *   x_bf16     device, [M][d] bf16 row-major, 16-byte aligned; d % 32 == 0, (d/32) % G == 0,
+ *              G a multiple of 16, at most TORQ_MAX_G
+ *   Sigma      device, G*G doubles, row-major, overwritten (symmetric)
+ *   workspace  device, at least torq_block_gram_workspace_bytes(G) bytes, 16-byte aligned, scratch
+ * M = 0 is TORQ_EINVAL (a mean over nothing).  Sums are fp32 inside a workgroup and double across
+ * workgroups, in a fixed order: the result is deterministic.
+ *
+ * torq_equalize_inter: Algorithm 1 on the HOST, in double.  Plane rotations of the pair (block
+ * furthest above the mean energy c = tr(Sigma)/G, block furthest below it) until every diagonal
+ * entry of R Sigma R^T is within eps of c; at most G-1 of them.  The rotation angle is the one that
+ * puts the first block exactly on c (the angle printed in Algorithm 1 diagonalises the pair, which
+ * moves the two energies apart and cannot meet the algorithm's own output condition).
+ *   Sigma_host    HOST, G*G doubles, symmetric, not modified
+ *   eps           absolute tolerance on the diagonal, >= 0 (e.g. 1e-12 * c)
+ *   R_inter_host  HOST, G*G floats out, row-major, for torq_rotation_create (Y = R_inter X)
+ *   steps         HOST, optional: number of plane rotations used
+ * Returns TORQ_OK, TORQ_EINVAL or TORQ_ECONVERGE. */
+size_t torq_block_gram_workspace_bytes(int G);
+int torq_block_gram(const void *x_bf16, int64_t M, int d, int G, double *Sigma,
+                    void *workspace, size_t workspace_bytes, void *stream);
+int torq_equalize_inter(const double *Sigma_host, int G, double eps, float *R_inter_host, int *steps);
 
 /* ------------------------------------------------------------------------ */
 /* Diagnostics (not a step of Algorithm 3): the rate the matrix cores sustain on

@@ -15,10 +15,11 @@ LIB_PATH = os.path.join(_HERE, "libtorq.so")
 EXPORTS = [
     "torq_status_string", "torq_rotation_create", "torq_rotation_destroy", "torq_rotation_d",
     "torq_rotation_G", "torq_rotate_quantize", "torq_rotate", "torq_quantize_f32", "mxfp4_gemm",
-    "torq_linear_workspace_bytes", "torq_linear", "torq_diag_mfma_burn",
+    "torq_linear_workspace_bytes", "torq_linear", "torq_block_gram_workspace_bytes", "torq_block_gram",
+    "torq_equalize_inter", "torq_diag_mfma_burn",
 ]
 
-TORQ_OK, TORQ_EINVAL, TORQ_EALIGN, TORQ_EWORKSPACE, TORQ_EHIP, TORQ_ENODEVICE = 0, -1, -2, -3, -4, -5
+TORQ_OK, TORQ_EINVAL, TORQ_EALIGN, TORQ_EWORKSPACE, TORQ_EHIP, TORQ_ENODEVICE, TORQ_ECONVERGE = 0, -1, -2, -3, -4, -5, -6
 
 _lib = None
 
@@ -61,6 +62,12 @@ def lib():
         L.torq_linear_workspace_bytes.argtypes = [i64, i32]
         L.torq_linear.restype = i32
         L.torq_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, sz, vp]
+        L.torq_block_gram_workspace_bytes.restype = sz
+        L.torq_block_gram_workspace_bytes.argtypes = [i32]
+        L.torq_block_gram.restype = i32
+        L.torq_block_gram.argtypes = [vp, i64, i32, i32, vp, vp, sz, vp]
+        L.torq_equalize_inter.restype = i32
+        L.torq_equalize_inter.argtypes = [vp, i32, C.c_double, vp, C.POINTER(i32)]
         L.torq_diag_mfma_burn.restype = i32
         L.torq_diag_mfma_burn.argtypes = [i32, vp, sz, i32, vp, vp]
         _lib = L
@@ -194,3 +201,35 @@ def torq_diag_mfma_burn(kind: int, operands: torch.Tensor, iters: int, sink=None
                                      iters, _dev(sink, torch.float32, "sink"), _stream(stream)),
            "torq_diag_mfma_burn")
     return TORQ_DIAG_FLOP_PER_ITER[kind] * iters
+
+
+def torq_block_gram_workspace_bytes(G: int) -> int:
+    return int(lib().torq_block_gram_workspace_bytes(G))
+
+
+def torq_block_gram(x_bf16: torch.Tensor, G: int, Sigma=None, workspace=None, stream=None):
+    """Sigma [G, G] float64 on the device: mean Gram matrix of the runs of G blocks of x's rows."""
+    M, d = x_bf16.shape
+    if Sigma is None:
+        Sigma = torch.empty((G, G), dtype=torch.float64, device=x_bf16.device)
+    if workspace is None:
+        workspace = torch.empty((max(torq_block_gram_workspace_bytes(G), 16),), dtype=torch.uint8,
+                                device=x_bf16.device)
+    _check(lib().torq_block_gram(_dev(x_bf16, torch.bfloat16, "x"), M, d, G, _dev(Sigma, torch.float64, "Sigma"),
+                                 _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)),
+           "torq_block_gram")
+    return Sigma
+
+
+def torq_equalize_inter(Sigma, eps: float = 0.0):
+    """Algorithm 1 on the host.  Sigma: [G, G] array-like (float64).  Returns (R_inter float32 [G, G], steps)."""
+    import numpy as np
+    S = np.ascontiguousarray(Sigma, dtype=np.float64)
+    G = S.shape[0]
+    if S.shape != (G, G):
+        raise ValueError("Sigma must be square")
+    R = np.empty((G, G), np.float32)
+    steps = C.c_int(0)
+    _check(lib().torq_equalize_inter(S.ctypes.data_as(C.c_void_p), G, float(eps), R.ctypes.data_as(C.c_void_p),
+                                     C.byref(steps)), "torq_equalize_inter")
+    return R, steps.value

@@ -58,6 +58,7 @@ const char *torq_status_string(int status) {
     case TORQ_EWORKSPACE: return "workspace too small";
     case TORQ_EHIP: return g_hip_msg[0] ? g_hip_msg : "HIP runtime error";
     case TORQ_ENODEVICE: return "no gfx950 device is current";
+    case TORQ_ECONVERGE: return "variance equalisation did not converge (Sigma not symmetric, or eps too small)";
     default: return "unknown status";
   }
 }
@@ -218,6 +219,79 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q
   if (e != hipSuccess) return hip_fail(e);
   e = torq::launch_mxfp4_gemm(codes, scales, W_q, W_s, out_bf16, M, N, r->d, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+size_t torq_block_gram_workspace_bytes(int G) {
+  if (G <= 0 || G % 16 != 0 || G > TORQ_MAX_G) return 0;
+  return torq::block_gram_workspace_bytes(G);
+}
+
+int torq_block_gram(const void *x_bf16, int64_t M, int d, int G, double *Sigma, void *workspace,
+                    size_t workspace_bytes, void *stream) {
+  if (M <= 0 || d <= 0 || d % TORQ_BLOCK != 0) return TORQ_EINVAL;
+  if (G <= 0 || G % 16 != 0 || G > TORQ_MAX_G || (d / TORQ_BLOCK) % G != 0) return TORQ_EINVAL;
+  if (!x_bf16 || !Sigma || !workspace) return TORQ_EINVAL;
+  if (misaligned(x_bf16) || misaligned(workspace) || (reinterpret_cast<uintptr_t>(Sigma) & 7u)) return TORQ_EALIGN;
+  if (workspace_bytes < torq::block_gram_workspace_bytes(G)) return TORQ_EWORKSPACE;
+  const int64_t TG = M * (int64_t)(d / TORQ_BLOCK / G);
+  hipError_t e = torq::launch_block_gram(x_bf16, TG, G, Sigma, workspace, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+// Algorithm 1 (Section 5.1) with the equalising angle.  One step takes the block p furthest above
+// the target c and the block n furthest below it and turns the (p, n) plane by theta with
+//   c = cos^2 a + 2 sin cos g + sin^2 b      (a = S_pp, b = S_nn, g = S_pn),
+// i.e. t = tan theta solves (b - c) t^2 + 2 g t + (a - c) = 0; (a - c)(b - c) < 0 makes the
+// discriminant positive, and the root of smaller magnitude is t = -(a - c) / (g + sgn(g) D).
+// After the step S_pp = c exactly and S_nn = a + b - c (the trace is conserved), so at most G - 1
+// steps are needed.
+int torq_equalize_inter(const double *Sigma_host, int G, double eps, float *R_inter_host, int *steps_out) {
+  if (!Sigma_host || !R_inter_host || G < 1 || G > 4096 || !(eps >= 0.0)) return TORQ_EINVAL;
+  const size_t n = (size_t)G;
+  std::vector<double> S(Sigma_host, Sigma_host + n * n), R(n * n, 0.0);
+  for (size_t i = 0; i < n; ++i) R[i * n + i] = 1.0;
+  double trace = 0.0;
+  for (size_t i = 0; i < n; ++i) trace += S[i * n + i];
+  const double c = trace / (double)G;
+
+  int steps = 0;
+  for (;;) {
+    int p = -1, q = -1;
+    double above = 0.0, below = 0.0, worst = 0.0;
+    for (int i = 0; i < G; ++i) {
+      const double dev = S[(size_t)i * n + i] - c;
+      worst = std::fmax(worst, std::fabs(dev));
+      if (dev > above) { above = dev; p = i; }
+      if (dev < below) { below = dev; q = i; }
+    }
+    if (worst <= eps) break;
+    if (p < 0 || q < 0 || steps >= 4 * G) return TORQ_ECONVERGE;
+
+    const double a = S[(size_t)p * n + p], b = S[(size_t)q * n + q], g = S[(size_t)p * n + q];
+    const double disc = std::sqrt(g * g - (a - c) * (b - c));
+    const double t = -(a - c) / (g + (g >= 0.0 ? disc : -disc));
+    const double cs = 1.0 / std::sqrt(1.0 + t * t), sn = t * cs;
+    // S <- J S J^T, R <- J R with J = the plane rotation of rows p and q
+    auto rotate_rows = [&](std::vector<double> &A) {
+      double *rp = &A[(size_t)p * n], *rq = &A[(size_t)q * n];
+      for (size_t j = 0; j < n; ++j) {
+        const double u = rp[j], v = rq[j];
+        rp[j] = cs * u + sn * v;
+        rq[j] = cs * v - sn * u;
+      }
+    };
+    rotate_rows(S);
+    rotate_rows(R);
+    for (size_t i = 0; i < n; ++i) {
+      const double u = S[i * n + p], v = S[i * n + q];
+      S[i * n + p] = cs * u + sn * v;
+      S[i * n + q] = cs * v - sn * u;
+    }
+    ++steps;
+  }
+  for (size_t i = 0; i < n * n; ++i) R_inter_host[i] = (float)R[i];
+  if (steps_out) *steps_out = steps;
+  return TORQ_OK;
 }
 
 int torq_diag_mfma_burn(int kind, const void *operands, size_t n_bytes, int iters, float *sink,

@@ -1,0 +1,142 @@
+// torq_block_gram: the statistic that the inter-block calibration starts from (Section 5.1,
+// Algorithm 1 input; Section 4.2, sigma_b^2 = E ||z_b||^2):
+//
+//   Sigma[b][b'] = mean over token-groups of  sum_k X[b][k] X[b'][k]
+//
+// where a token-group is one run of G consecutive 32-element blocks of one row, i.e. G rows of
+// 64 contiguous bytes.  The contraction index is the position inside a block (K = 32), which is
+// exactly one v_mfma_f32_16x16x32_bf16: lane (m = l % 16, q = l / 16) of an operand holds the 8
+// consecutive elements 8 q .. 8 q + 7 of block row m -- 16 contiguous bytes of the row-major input,
+// so both operands are plain global loads and nothing is staged or transposed.  bf16 products are
+// exact in fp32; the sums are fp32 per workgroup and fp64 across workgroups.
+//
+// Workgroup = ceil(G / 32) waves; wave w owns the block rows 32 w .. 32 w + 31 (two 16-row tiles)
+// against all G columns (NT = G / 16 tiles): 2 NT accumulator tiles of 4 registers.  Workgroups
+// are persistent over the token-groups; each writes its partial Sigma to the workspace, and two small
+// kernels add the partials in a fixed order in double and divide by the number of token-groups.
+// HBM bound: 2 bytes per element read once (the waves of a workgroup re-read the group from the L1).
+#include "torq_device.h"
+#include "torq_internal.h"
+
+namespace torq {
+
+constexpr int GRAM_MAX_WG = 512;      // partial results (2 resident workgroups per CU)
+
+template <int NT>
+__global__ void __launch_bounds__(64 * ((NT + 1) / 2))
+block_gram_kernel(const bf16x8 *__restrict__ x, int64_t TG, float *__restrict__ partial) {
+  constexpr int G = 16 * NT;
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int m = lane & 15, q = lane >> 4;
+  const int rt0 = 2 * wave, rt1 = 2 * wave + 1;          // this wave's row tiles; rt1 may not exist
+  const bool has1 = rt1 < NT;
+
+  f32x4 acc0[NT], acc1[NT];
+#pragma unroll
+  for (int ct = 0; ct < NT; ++ct) acc0[ct] = acc1[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  // one token-group = G rows of 64 bytes = 4 G operand chunks of 16 bytes; chunk (row r, q) = 4 r + q.
+  // U token-groups per trip: all their loads are issued before the first MFMA (a group past the end
+  // re-reads the last one with a zero weight on its row operand, so the trip has no branches).
+  constexpr int U = (NT <= 4) ? 8 : (NT <= 8) ? 4 : (NT <= 12) ? 2 : 1;
+  for (int64_t tg = blockIdx.x; tg < TG; tg += (int64_t)U * gridDim.x) {
+    bf16x8 col[U][NT], a0[U], a1[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const int64_t t = tg + (int64_t)u * gridDim.x;
+      const bool in = t < TG;
+      const bf16x8 *g = x + (in ? t : tg) * (4 * G);
+#pragma unroll
+      for (int ct = 0; ct < NT; ++ct) col[u][ct] = g[4 * (16 * ct + m) + q];
+      a0[u] = g[4 * (16 * rt0 + m) + q];
+      a1[u] = g[4 * (16 * (has1 ? rt1 : rt0) + m) + q];
+      if (!in) a0[u] = a1[u] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    }
+    __builtin_amdgcn_sched_barrier(0);             // every load of the trip is issued before the first wait
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int ct = 0; ct < NT; ++ct) {
+        acc0[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[u], col[u][ct], acc0[ct], 0, 0, 0);
+        acc1[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], col[u][ct], acc1[ct], 0, 0, 0);
+      }
+  }
+
+  // accumulator lane (n = l % 16, q), register r: row 4 q + r of the row tile, column n of the column tile
+  float *out = partial + (size_t)blockIdx.x * (G * G);
+#pragma unroll
+  for (int ct = 0; ct < NT; ++ct)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      out[(16 * rt0 + 4 * q + r) * G + 16 * ct + m] = acc0[ct][r];
+      if (has1) out[(16 * rt1 + 4 * q + r) * G + 16 * ct + m] = acc1[ct][r];
+    }
+}
+
+// Two-stage sum of the partial results, in double and in a fixed order.  Stage 1: slice s of
+// GRAM_SLICES adds its share of the workgroups' partials; stage 2 adds the slices and divides by
+// the number of token-groups.
+constexpr int GRAM_SLICES = 16;
+
+__global__ void __launch_bounds__(256)
+block_gram_reduce1_kernel(const float *__restrict__ partial, int n_partial, int GG, double *__restrict__ slices) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= GG) return;
+  const int per = (n_partial + GRAM_SLICES - 1) / GRAM_SLICES;
+  const int p0 = blockIdx.y * per, p1 = (p0 + per < n_partial) ? p0 + per : n_partial;
+  double s = 0.0;
+  for (int p = p0; p < p1; ++p) s += (double)partial[(size_t)p * GG + i];
+  slices[(size_t)blockIdx.y * GG + i] = s;
+}
+
+__global__ void __launch_bounds__(256)
+block_gram_reduce2_kernel(const double *__restrict__ slices, int GG, double inv_groups, double *__restrict__ Sigma) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i >= GG) return;
+  double s = 0.0;
+#pragma unroll
+  for (int p = 0; p < GRAM_SLICES; ++p) s += slices[(size_t)p * GG + i];
+  Sigma[i] = s * inv_groups;
+}
+
+// [GRAM_MAX_WG][G * G] floats, then [GRAM_SLICES][G * G] doubles
+size_t block_gram_workspace_bytes(int G) {
+  return (size_t)GRAM_MAX_WG * G * G * sizeof(float) + (size_t)GRAM_SLICES * G * G * sizeof(double);
+}
+
+template <int NT>
+static hipError_t launch_nt(const void *x, int64_t TG, double *Sigma, void *workspace, hipStream_t stream) {
+  constexpr int G = 16 * NT;
+  float *partial = static_cast<float *>(workspace);
+  double *slices = reinterpret_cast<double *>(static_cast<char *>(workspace) + (size_t)GRAM_MAX_WG * G * G * sizeof(float));
+  const int n_wg = (int)(TG < GRAM_MAX_WG ? TG : GRAM_MAX_WG);
+  hipLaunchKernelGGL((block_gram_kernel<NT>), dim3(n_wg), dim3(64 * ((NT + 1) / 2)), 0, stream,
+                     reinterpret_cast<const bf16x8 *>(x), TG, partial);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(block_gram_reduce1_kernel, dim3((G * G + 255) / 256, GRAM_SLICES), dim3(256), 0, stream, partial,
+                     n_wg, G * G, slices);
+  e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(block_gram_reduce2_kernel, dim3((G * G + 255) / 256), dim3(256), 0, stream, slices, G * G,
+                     1.0 / (double)TG, Sigma);
+  return hipGetLastError();
+}
+
+// G a multiple of 16 in [16, 256], TG > 0 token-groups, workspace of block_gram_workspace_bytes(G)
+hipError_t launch_block_gram(const void *x_bf16, int64_t TG, int G, double *Sigma, void *workspace,
+                             hipStream_t stream) {
+  switch (G / 16) {
+#define TORQ_GRAM_CASE(NT_) \
+  case NT_: return launch_nt<NT_>(x_bf16, TG, Sigma, workspace, stream);
+    TORQ_GRAM_CASE(1) TORQ_GRAM_CASE(2) TORQ_GRAM_CASE(3) TORQ_GRAM_CASE(4)
+    TORQ_GRAM_CASE(5) TORQ_GRAM_CASE(6) TORQ_GRAM_CASE(7) TORQ_GRAM_CASE(8)
+    TORQ_GRAM_CASE(9) TORQ_GRAM_CASE(10) TORQ_GRAM_CASE(11) TORQ_GRAM_CASE(12)
+    TORQ_GRAM_CASE(13) TORQ_GRAM_CASE(14) TORQ_GRAM_CASE(15) TORQ_GRAM_CASE(16)
+#undef TORQ_GRAM_CASE
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace torq

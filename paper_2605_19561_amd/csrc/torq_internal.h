@@ -41,6 +41,11 @@ hipError_t launch_mxfp4_gemm_skinny(const uint8_t *A_q, const uint8_t *A_s, cons
                                     const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, int d,
                                     hipStream_t stream);
 
+// Block Gram matrix of the runs of G blocks (block_gram.hip): TG token-groups of G * 32 bf16 each.
+size_t block_gram_workspace_bytes(int G);
+hipError_t launch_block_gram(const void *x_bf16, int64_t TG, int G, double *Sigma, void *workspace,
+                             hipStream_t stream);
+
 // 1024 x 256 lanes issue iters x 16 MFMAs each on operands taken from `words` (see diag.hip).
 hipError_t launch_mfma_burn(int kind, const uint32_t *words, uint32_t n_words, int iters, float *sink,
                             hipStream_t stream);

@@ -1,0 +1,58 @@
+"""torq_equalize_inter (Algorithm 1 on the host, in the product library) against the oracle's
+equaliser and against the algorithm's own output condition.  Pure host code: runs without a GPU."""
+import ctypes as C
+
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_19561_amd import binding, synth
+
+
+def _gram(M, G, seed):
+    x = synth.activations(M, 32 * G, nu=3.0, outliers=max(1, G // 8), outlier_scale=50.0, seed=seed)
+    X = x.to(torch.float64).numpy().reshape(M, G, 32)
+    return np.einsum("mbk,mck->bc", X, X) / M
+
+
+@pytest.mark.parametrize("G,seed", [(16, 1), (48, 2), (80, 3), (128, 4), (256, 5)])
+def test_equalize_inter_matches_the_oracle_and_the_output_condition(oracle, G, seed):
+    Sigma = _gram(192, G, seed)
+    c = np.trace(Sigma) / G
+    R, steps = binding.torq_equalize_inter(Sigma, eps=1e-12 * c)
+    R_o, _, steps_o = oracle.equalize(Sigma, eps=1e-12 * c)
+    assert steps == steps_o and 0 < steps <= G - 1
+    assert np.abs(R.astype(np.float64) - R_o).max() <= 1e-6            # R is handed back in fp32
+    Rd = R.astype(np.float64)
+    assert np.abs(Rd @ Rd.T - np.eye(G)).max() <= 1e-5
+    assert np.abs(np.diag(Rd @ Sigma @ Rd.T) - c).max() <= 1e-5 * c      # diag(R Sigma R^T) = c 1
+    before = np.diag(Sigma)
+    assert before.max() / before.min() > 20.0
+
+
+def test_equalize_inter_trivial_and_invalid_inputs():
+    R, steps = binding.torq_equalize_inter(np.eye(8) * 3.0)
+    assert steps == 0 and np.array_equal(R, np.eye(8, dtype=np.float32))
+    R, steps = binding.torq_equalize_inter(np.diag([4.0, 2.0]), eps=1e-15)
+    assert steps == 1 and np.allclose(np.abs(R), np.sqrt(0.5))
+    L = binding.lib()
+    S = np.eye(4)
+    Rbuf = np.empty((4, 4), np.float32)
+    p = lambda a: a.ctypes.data_as(C.c_void_p)
+    assert L.torq_equalize_inter(None, 4, 0.0, p(Rbuf), None) == binding.TORQ_EINVAL
+    assert L.torq_equalize_inter(p(S), 4, 0.0, None, None) == binding.TORQ_EINVAL
+    assert L.torq_equalize_inter(p(S), 0, 0.0, p(Rbuf), None) == binding.TORQ_EINVAL
+    assert L.torq_equalize_inter(p(S), 4, -1.0, p(Rbuf), None) == binding.TORQ_EINVAL
+    assert L.torq_equalize_inter(p(S), 4, float("nan"), p(Rbuf), None) == binding.TORQ_EINVAL
+    # a tolerance that double precision cannot meet: the routine gives up instead of looping
+    S = _gram(64, 16, 9)
+    with pytest.raises(binding.TorqError) as ei:
+        binding.torq_equalize_inter(S, eps=0.0)
+    assert ei.value.status == binding.TORQ_ECONVERGE
+    assert binding.torq_block_gram_workspace_bytes(128) >= 512 * 128 * 128 * 4
+    assert binding.torq_block_gram_workspace_bytes(24) == 0 and binding.torq_block_gram_workspace_bytes(512) == 0
+    good = C.c_void_p(0x1000)
+    assert L.torq_block_gram(good, 0, 4096, 128, good, good, 1 << 30, None) == binding.TORQ_EINVAL
+    assert L.torq_block_gram(good, 4, 4096, 48, good, good, 1 << 30, None) == binding.TORQ_EINVAL   # 128 % 48
+    assert L.torq_block_gram(good, 4, 4096, 128, good, good, 16, None) == binding.TORQ_EWORKSPACE
+    assert L.torq_block_gram(C.c_void_p(0x1004), 4, 4096, 128, good, good, 1 << 30, None) == binding.TORQ_EALIGN

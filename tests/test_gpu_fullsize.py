@@ -222,3 +222,19 @@ def test_gemm_more_than_2_31_outputs_or_weight_bytes(tq, oracle, M, N, d):
     gw, ww = _bf16_bits_to_f64(got), _bf16_bits_to_f64(want)
     assert np.linalg.norm(gw - ww) / np.linalg.norm(ww) <= 1e-3
     assert np.all(np.abs(gw - ww) <= np.abs(ww) * 2.0 ** -7 + 1e-3 * np.sqrt(np.mean(ww ** 2)))
+
+
+def test_block_gram_many_token_groups_per_workgroup(tq, oracle):
+    # 2048 token-groups: every workgroup accumulates several in fp32 before the double reduction
+    M, d, G = 1024, 8192, 128
+    x = synth.workload_activations("llama3_70b_up", device=DEV, M=M)
+    want = oracle.block_gram(synth.bf16_bits(x), G)
+    got = _np(tq.torq_block_gram(x, G))
+    torch.cuda.synchronize()
+    assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
+    # the full benchmark input: symmetric, and its trace is the mean energy of a token-group
+    xf = synth.workload_activations("llama3_70b_up", device=DEV)
+    Sf = _np(tq.torq_block_gram(xf, G))
+    assert np.array_equal(Sf, Sf.T)
+    energy = float((xf.double() ** 2).sum().item()) / (xf.shape[0] * (xf.shape[1] // 32 // G))
+    assert abs(np.trace(Sf) - energy) <= 1e-5 * energy

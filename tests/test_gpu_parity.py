@@ -398,3 +398,42 @@ def test_diag_mfma_burn_runs_and_validates(tq):
         tq.torq_diag_mfma_burn(tq.TORQ_DIAG_FP4, ops[:64], 4, sink=sink)
     with pytest.raises(tq.TorqError):
         tq.torq_diag_mfma_burn(tq.TORQ_DIAG_FP4, ops, 0, sink=sink)
+
+
+# --------------------------------------------- calibration (Section 5.1) ----
+
+GRAM_CASES = [(5, 512, 16), (33, 1024, 32), (7, 3072, 48), (9, 5120, 80), (6, 14336, 112), (40, 8192, 128),
+              (700, 4096, 128), (5, 5120, 160), (12, 8192, 256)]
+
+
+@pytest.mark.parametrize("M,d,G", GRAM_CASES)
+def test_block_gram_against_oracle(tq, oracle, M, d, G):
+    x = synth.activations(M, d, nu=3.0, outliers=max(2, d // 200), outlier_scale=50.0, seed=300 + G + M)
+    want = oracle.block_gram(synth.bf16_bits(x), G)
+    got = _np(tq.torq_block_gram(x.to(DEV), G))
+    torch.cuda.synchronize()
+    # bf16 products are exact in fp32; fp32 sums inside a workgroup (at most a few token-groups of 32
+    # products here), double across workgroups: 1e-5 of the largest entry is generous
+    assert np.abs(got - want).max() <= 1e-5 * np.abs(want).max()
+    assert np.array_equal(got, got.T)
+    # deterministic: a second call gives the same bits
+    assert np.array_equal(_np(tq.torq_block_gram(x.to(DEV), G)), got)
+
+
+def test_calibrated_rotation_equalizes_block_energies_on_the_gpu(tq, oracle):
+    # Gram of a sample (GPU) -> Algorithm 1 (host) -> rotation handle -> rotate the sample (GPU):
+    # the rotated sample's block energies are all tr(Sigma) / G (Theorem 4.1's equality condition)
+    M, d, G = 256, 4096, 128
+    x = synth.activations(M, d, nu=3.0, outliers=20, outlier_scale=50.0, seed=77).to(DEV)
+    Sigma = _np(tq.torq_block_gram(x, G))
+    c = np.trace(Sigma) / G
+    assert np.diag(Sigma).max() / np.diag(Sigma).min() > 20.0
+    R, steps = tq.torq_equalize_inter(Sigma, eps=1e-12 * c)
+    assert 0 < steps <= G - 1
+    R_o, _, _ = oracle.equalize(oracle.block_gram(synth.bf16_bits(x.cpu()), G), eps=1e-12 * c)
+    assert np.abs(R.astype(np.float64) - R_o).max() <= 1e-4             # same pair sequence on both sides
+    rot = tq.Rotation(d, G, R, np.eye(32, dtype=np.float32))
+    z = tq.torq_rotate(rot, x)
+    energies = (z.double().reshape(M, G, 32) ** 2).sum(dim=2).mean(dim=0).cpu().numpy()
+    assert np.abs(energies - c).max() <= 2e-3 * c                       # rotation error bar is 1e-3 of the RMS
+    rot.close()
