@@ -190,6 +190,9 @@ def main():
         print(json.dumps(sweep_line(tq, synth, 8192, args.steps, args.warmup, G=256)), flush=True)
         # calibration statistic (Section 5.1): block Gram matrix of the benchmark's activations, HBM bound
         print(json.dumps(gram_line(tq, x, G, args.steps, args.warmup)), flush=True)
+        xl = torch.cat([x, x, x, x], dim=0)             # a longer calibration sample: [32768, d]
+        print(json.dumps(gram_line(tq, xl, G, args.steps, args.warmup)), flush=True)
+        del xl
         # decode-sized linear layers (few activation rows: weight streaming, HBM bound), timed as
         # replays of a HIP graph of 20 calls so that Python's launch overhead is not in the figure
         for (mm, nn, dd) in ((1, 14336, 4096), (16, 14336, 4096), (16, 4096, 14336), (16, 28672, 8192)):

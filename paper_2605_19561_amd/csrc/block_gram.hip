@@ -7,27 +7,38 @@
 // 64 contiguous bytes.  The contraction index is the position inside a block (K = 32), which is
 // exactly one v_mfma_f32_16x16x32_bf16: lane (m = l % 16, q = l / 16) of an operand holds the 8
 // consecutive elements 8 q .. 8 q + 7 of block row m -- 16 contiguous bytes of the row-major input,
-// so both operands are plain global loads and nothing is staged or transposed.  bf16 products are
-// exact in fp32; the sums are fp32 per workgroup and fp64 across workgroups.
+// so an operand is 16 rows x one 16-byte chunk and nothing is transposed.  bf16 products are exact
+// in fp32; the sums are fp32 per workgroup and fp64 across workgroups.
 //
 // Workgroup = ceil(G / 32) waves; wave w owns the block rows 32 w .. 32 w + 31 (two 16-row tiles)
-// against all G columns (NT = G / 16 tiles): 2 NT accumulator tiles of 4 registers.  Workgroups
-// are persistent over the token-groups; each writes its partial Sigma to the workspace, and two small
-// kernels add the partials in a fixed order in double and divide by the number of token-groups.
-// HBM bound: 2 bytes per element read once (the waves of a workgroup re-read the group from the L1).
+// against all G columns (NT = G / 16 tiles): 2 NT accumulator tiles of 4 registers.  Every wave
+// needs the whole token-group as its column operand, so the workgroup stages it once through LDS
+// (global -> registers -> LDS, two stages, one barrier per trip of two token-groups) instead of
+// letting each wave fetch it from the L1 (that version was bound by the L1's request rate, 5 requests
+// per byte).  Workgroups are persistent; each writes its partial Sigma to the workspace, and two
+// small kernels add the partials in a fixed order in double and divide by the number of
+// token-groups.  HBM bound: 2 bytes per element, read once.
 #include "torq_device.h"
 #include "torq_internal.h"
 
 namespace torq {
 
 constexpr int GRAM_MAX_WG = 512;      // partial results (2 resident workgroups per CU)
+constexpr int GRAM_GROUPS_PER_TRIP = 2;
 
 template <int NT>
 __global__ void __launch_bounds__(64 * ((NT + 1) / 2))
-block_gram_kernel(const bf16x8 *__restrict__ x, int64_t TG, float *__restrict__ partial) {
+block_gram_kernel(const uint4 *__restrict__ x, int64_t TG, float *__restrict__ partial) {
   constexpr int G = 16 * NT;
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  constexpr int NTHR = 64 * ((NT + 1) / 2);
+  constexpr int CHUNKS = 4 * G;                          // 16-byte chunks of one token-group
+  constexpr int CH = (CHUNKS + NTHR - 1) / NTHR;         // chunks per thread per token-group (2)
+  constexpr int U = GRAM_GROUPS_PER_TRIP;
+  constexpr int TG_BYTES = G * 64, STAGE_BYTES = U * TG_BYTES;
+  extern __shared__ __attribute__((aligned(16))) char lds[];   // two stages of U token-groups
+
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int m = lane & 15, q = lane >> 4;
   const int rt0 = 2 * wave, rt1 = 2 * wave + 1;          // this wave's row tiles; rt1 may not exist
   const bool has1 = rt1 < NT;
@@ -36,31 +47,66 @@ block_gram_kernel(const bf16x8 *__restrict__ x, int64_t TG, float *__restrict__ 
 #pragma unroll
   for (int ct = 0; ct < NT; ++ct) acc0[ct] = acc1[ct] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // one token-group = G rows of 64 bytes = 4 G operand chunks of 16 bytes; chunk (row r, q) = 4 r + q.
-  // U token-groups per trip: all their loads are issued before the first MFMA (a group past the end
-  // re-reads the last one with a zero weight on its row operand, so the trip has no branches).
-  constexpr int U = (NT <= 4) ? 8 : (NT <= 8) ? 4 : (NT <= 12) ? 2 : 1;
-  for (int64_t tg = blockIdx.x; tg < TG; tg += (int64_t)U * gridDim.x) {
-    bf16x8 col[U][NT], a0[U], a1[U];
+  // Chunk c of a token-group = (block row c / 4, elements 8 (c % 4) .. + 7).  In LDS the chunk
+  // index inside a 64-byte row is XORed with (row >> 2) & 3, so that the 16 lanes that read one
+  // operand (16 consecutive rows, same chunk) hit 16 different bank groups.  For a tile's rows
+  // 16 t + m that term is (m >> 2) & 3: one lane offset serves every tile.
+  const int frag_off = m * 64 + ((q ^ ((m >> 2) & 3)) * 16);
+  int st_off[CH];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int c = tid + i * NTHR, r = c >> 2;
+    st_off[i] = r * 64 + (((c & 3) ^ ((r >> 2) & 3)) * 16);
+  }
+
+  // a trip = U token-groups; trips are dealt to the workgroups round robin
+  const int64_t ntrip = (TG + U - 1) / U;
+  uint4 regs[U][CH];
+  auto load_trip = [&](int64_t trip) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
-      const int64_t t = tg + (int64_t)u * gridDim.x;
-      const bool in = t < TG;
-      const bf16x8 *g = x + (in ? t : tg) * (4 * G);
+      const int64_t tg = trip * U + u;
 #pragma unroll
-      for (int ct = 0; ct < NT; ++ct) col[u][ct] = g[4 * (16 * ct + m) + q];
-      a0[u] = g[4 * (16 * rt0 + m) + q];
-      a1[u] = g[4 * (16 * (has1 ? rt1 : rt0) + m) + q];
-      if (!in) a0[u] = a1[u] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      for (int i = 0; i < CH; ++i) {
+        const int c = tid + i * NTHR;
+        regs[u][i] = (tg < TG && c < CHUNKS) ? x[tg * CHUNKS + c] : make_uint4(0, 0, 0, 0);
+      }
     }
-    __builtin_amdgcn_sched_barrier(0);             // every load of the trip is issued before the first wait
+  };
+  auto store_trip = [&](int stage) {
 #pragma unroll
     for (int u = 0; u < U; ++u)
 #pragma unroll
+      for (int i = 0; i < CH; ++i)
+        if (tid + i * NTHR < CHUNKS)
+          *reinterpret_cast<uint4 *>(lds + stage * STAGE_BYTES + u * TG_BYTES + st_off[i]) = regs[u][i];
+  };
+
+  int64_t trip = blockIdx.x;
+  if (trip < ntrip) {
+    load_trip(trip);
+    store_trip(0);
+  }
+  __syncthreads();
+  int stage = 0;
+  for (; trip < ntrip; trip += gridDim.x, stage ^= 1) {
+    const int64_t next = trip + gridDim.x;
+    const bool have_next = next < ntrip;
+    if (have_next) load_trip(next);
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+      const char *g = lds + stage * STAGE_BYTES + u * TG_BYTES + frag_off;
+      const bf16x8 a0 = *reinterpret_cast<const bf16x8 *>(g + rt0 * 1024);
+      const bf16x8 a1 = *reinterpret_cast<const bf16x8 *>(g + (has1 ? rt1 : rt0) * 1024);
+#pragma unroll
       for (int ct = 0; ct < NT; ++ct) {
-        acc0[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0[u], col[u][ct], acc0[ct], 0, 0, 0);
-        acc1[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1[u], col[u][ct], acc1[ct], 0, 0, 0);
+        const bf16x8 col = *reinterpret_cast<const bf16x8 *>(g + ct * 1024);
+        acc0[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, col, acc0[ct], 0, 0, 0);
+        acc1[ct] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, col, acc1[ct], 0, 0, 0);
       }
+    }
+    if (have_next) store_trip(stage ^ 1);
+    __syncthreads();
   }
 
   // accumulator lane (n = l % 16, q), register r: row 4 q + r of the row tile, column n of the column tile
@@ -110,9 +156,11 @@ static hipError_t launch_nt(const void *x, int64_t TG, double *Sigma, void *work
   constexpr int G = 16 * NT;
   float *partial = static_cast<float *>(workspace);
   double *slices = reinterpret_cast<double *>(static_cast<char *>(workspace) + (size_t)GRAM_MAX_WG * G * G * sizeof(float));
-  const int n_wg = (int)(TG < GRAM_MAX_WG ? TG : GRAM_MAX_WG);
-  hipLaunchKernelGGL((block_gram_kernel<NT>), dim3(n_wg), dim3(64 * ((NT + 1) / 2)), 0, stream,
-                     reinterpret_cast<const bf16x8 *>(x), TG, partial);
+  const int64_t ntrip = (TG + GRAM_GROUPS_PER_TRIP - 1) / GRAM_GROUPS_PER_TRIP;
+  const int n_wg = (int)(ntrip < GRAM_MAX_WG ? ntrip : GRAM_MAX_WG);
+  const size_t lds_bytes = 2 * (size_t)GRAM_GROUPS_PER_TRIP * G * 64;
+  hipLaunchKernelGGL((block_gram_kernel<NT>), dim3(n_wg), dim3(64 * ((NT + 1) / 2)), lds_bytes, stream,
+                     reinterpret_cast<const uint4 *>(x), TG, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(block_gram_reduce1_kernel, dim3((G * G + 255) / 256, GRAM_SLICES), dim3(256), 0, stream, partial,
