@@ -56,6 +56,19 @@ def lib():
         L.torq_o_block_gram.argtypes = [vp, i64, i32, i32, vp]
         L.torq_o_equalize.restype = i32
         L.torq_o_equalize.argtypes = [vp, i32, f64, vp]
+        u64p = C.POINTER(C.c_uint64)
+        L.torq_o_code_histogram.restype = None
+        L.torq_o_code_histogram.argtypes = [vp, i64, i32, vp]
+        L.torq_o_code_loss.restype = f64
+        L.torq_o_code_loss.argtypes = [vp]
+        L.torq_o_pair_scores.restype = None
+        L.torq_o_pair_scores.argtypes = [vp, f64, vp, vp]
+        L.torq_o_best_angle.restype = i64
+        L.torq_o_best_angle.argtypes = [vp, vp, i64, vp, C.POINTER(f64), C.POINTER(f64)]
+        L.torq_o_mag_code.restype = i32
+        L.torq_o_mag_code.argtypes = [f64]
+        L.torq_o_intra_rotation.restype = None
+        L.torq_o_intra_rotation.argtypes = [vp, i64, i32, i32, i32, f64, f64, vp, vp, C.POINTER(i32)]
         L.torq_o_threads.restype = i32
         L.torq_o_threads.argtypes = []
         _lib = L
@@ -231,6 +244,58 @@ def equalize(Sigma, eps=0.0):
     R = np.empty((B, B), np.float64)
     steps = lib().torq_o_equalize(_p(S), B, float(eps), _p(R))
     return R, S, steps
+
+
+def code_histogram(codes, d):
+    """codes: uint8 [M, d/2] -> uint64 [32, 8]: occupancy of the 8 magnitude codewords per in-block position."""
+    c = _arr(codes, np.uint8)
+    M = c.shape[0]
+    assert c.shape == (M, d // 2)
+    out = np.empty((32, 8), np.uint64)
+    lib().torq_o_code_histogram(_p(c), M, d, _p(out))
+    return out
+
+
+def code_loss(n):
+    n = _arr(n, np.uint64)
+    assert n.shape == (8,)
+    return float(lib().torq_o_code_loss(_p(n)))
+
+
+def pair_scores(counts, lam):
+    cts = _arr(counts, np.uint64)
+    assert cts.shape == (32, 8)
+    h = np.empty((32,), np.float64)
+    H = np.empty((32, 32), np.float64)
+    lib().torq_o_pair_scores(_p(cts), float(lam), _p(h), _p(H))
+    return h, H
+
+
+def best_angle(u, v, rest):
+    """Appendix A.4 for one column pair.  Returns (theta, loss, intervals)."""
+    u = _arr(u, np.float64)
+    v = _arr(v, np.float64)
+    rest = _arr(rest, np.uint64)
+    assert u.shape == v.shape and u.ndim == 1 and rest.shape == (8,)
+    th, lo = C.c_double(0.0), C.c_double(0.0)
+    k = lib().torq_o_best_angle(_p(u), _p(v), u.shape[0], _p(rest), C.byref(th), C.byref(lo))
+    return th.value, lo.value, int(k)
+
+
+def mag_code(a: float) -> int:
+    return int(lib().torq_o_mag_code(float(a)))
+
+
+def intra_rotation(X, max_iter, k_top, P, lam, eps):
+    """Algorithm 2 on sample blocks X [n, 32].  Returns (R_intra [32, 32], losses per evaluation)."""
+    X = _arr(X, np.float64)
+    n = X.shape[0]
+    assert X.shape == (n, 32)
+    R = np.empty((32, 32), np.float64)
+    losses = np.zeros((max_iter + 1,), np.float64)
+    k = C.c_int32(0)
+    lib().torq_o_intra_rotation(_p(X), n, max_iter, k_top, P, float(lam), float(eps), _p(R), _p(losses), C.byref(k))
+    return R, losses[: k.value].copy()
 
 
 def threads() -> int:

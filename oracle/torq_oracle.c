@@ -14,6 +14,7 @@
 #include <omp.h>
 #endif
 
+#define PI 3.14159265358979323846
 #define BLK 32 /* K in the paper's notation: elements per microscaling block */
 
 /* ------------------------------------------------------------------ bf16 -- */
@@ -391,6 +392,268 @@ int torq_o_equalize(double *Sigma, int B, double eps, double *R)
         ++steps;
     }
     return steps;
+}
+
+/* ------------------------------------------- intra-block calibration -- */
+
+void torq_o_code_histogram(const uint8_t *codes, int64_t M, int d, uint64_t *counts)
+{
+    for (int i = 0; i < BLK * 8; ++i) counts[i] = 0;
+    for (int64_t m = 0; m < M; ++m)
+        for (int j = 0; j < d; ++j) {
+            uint8_t byte = codes[m * (int64_t)(d / 2) + j / 2];
+            uint8_t code = (j & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 15u);
+            counts[(j % BLK) * 8 + (code & 7u)] += 1;
+        }
+}
+
+double torq_o_code_loss(const uint64_t n[8])
+{
+    double total = 0.0, loss = 0.0;
+    for (int j = 0; j < 8; ++j) total += (double)n[j];
+    if (total == 0.0) return 0.0;
+    for (int j = 0; j < 8; ++j) {
+        double dev = (double)n[j] / total - 1.0 / 8.0;
+        loss += dev * dev;
+    }
+    return loss;
+}
+
+void torq_o_pair_scores(const uint64_t *counts, double lambda, double *h, double *H)
+{
+    double dev[BLK][8];
+    for (int k = 0; k < BLK; ++k) {
+        double total = 0.0;
+        for (int j = 0; j < 8; ++j) total += (double)counts[k * 8 + j];
+        h[k] = 0.0;
+        for (int j = 0; j < 8; ++j) {
+            dev[k][j] = (total > 0.0 ? (double)counts[k * 8 + j] / total : 0.0) - 1.0 / 8.0;
+            h[k] += dev[k][j] * dev[k][j];
+        }
+    }
+    for (int k = 0; k < BLK; ++k)
+        for (int l = 0; l < BLK; ++l) {
+            double c = 0.0;
+            for (int j = 0; j < 8; ++j) c -= dev[k][j] * dev[l][j];
+            H[k * BLK + l] = h[k] + h[l] + lambda * c;
+        }
+}
+
+/* Magnitude codeword of a normalised value: the index j of the interval I_j between the decision
+ * boundaries d_j (the midpoints of neighbouring e2m1 magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6) that
+ * holds |a|; a value on a boundary goes to the neighbour with the even mantissa, as round-to-
+ * nearest-even does. */
+int torq_o_mag_code(double a)
+{
+    const double m = fabs(a);
+    if (m <= 0.25) return 0;
+    if (m < 0.75) return 1;
+    if (m <= 1.25) return 2;
+    if (m < 1.75) return 3;
+    if (m <= 2.5) return 4;
+    if (m < 3.5) return 5;
+    if (m <= 5.0) return 6;
+    return 7;
+}
+
+/* occupancy of the 8 codewords when the pair (u, v) is turned by theta, on top of `rest` */
+static void counts_at(const double *u, const double *v, int64_t n, const uint64_t rest[8], double theta,
+                      uint64_t cnt[8])
+{
+    const double c = cos(theta), s = sin(theta);
+    for (int j = 0; j < 8; ++j) cnt[j] = rest[j];
+    for (int64_t b = 0; b < n; ++b) {
+        cnt[torq_o_mag_code(u[b] * c + v[b] * s)] += 1;
+        cnt[torq_o_mag_code(-u[b] * s + v[b] * c)] += 1;
+    }
+}
+
+/* sum_j n_j^2: because sum_j n_j does not depend on theta, the loss sum_j (n_j / N - 1/8)^2 =
+ * (sum_j n_j^2) / N^2 - 1/8 orders the angles exactly as this integer does, so angles are compared
+ * on it and equal losses are recognised exactly */
+static unsigned __int128 sum_squares(const uint64_t cnt[8])
+{
+    unsigned __int128 t = 0;
+    for (int j = 0; j < 8; ++j) t += (unsigned __int128)cnt[j] * cnt[j];
+    return t;
+}
+
+static int cmp_double(const void *a, const void *b)
+{
+    double x = *(const double *)a, y = *(const double *)b;
+    return (x > y) - (x < y);
+}
+
+int64_t torq_o_best_angle(const double *u, const double *v, int64_t n, const uint64_t rest[8],
+                          double *theta, double *loss)
+{
+    static const double bound[7] = {0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0};
+    const double two_pi = 2.0 * PI;
+    uint64_t cnt[8];
+    /* at most 7 boundaries x 2 axes x 4 angles per sample */
+    double *tau = (double *)malloc(sizeof(double) * (size_t)(n * 56 + 1));
+    int64_t count = 0;
+    for (int64_t b = 0; b < n; ++b) {
+        const double r = sqrt(u[b] * u[b] + v[b] * v[b]);
+        const double phi = atan2(v[b], u[b]);
+        for (int j = 0; j < 7; ++j) {
+            if (r < bound[j]) continue;
+            const double alpha = acos(bound[j] / r);
+            for (int axis = 0; axis < 2; ++axis) {
+                /* |cos(phi_axis - theta)| = d / r: theta = phi_axis -+ alpha, and the same + pi */
+                const double base = phi - (axis ? PI / 2.0 : 0.0);
+                const double cand[4] = {base - alpha, base + alpha, base - alpha + PI, base + alpha + PI};
+                for (int t = 0; t < 4; ++t) {
+                    double a = fmod(cand[t], two_pi);
+                    if (a < 0.0) a += two_pi;
+                    if (a >= two_pi) a -= two_pi;
+                    tau[count++] = a;
+                }
+            }
+        }
+    }
+    if (count == 0) {
+        counts_at(u, v, n, rest, 0.0, cnt);
+        *theta = 0.0;
+        *loss = torq_o_code_loss(cnt);
+        free(tau);
+        return 0;
+    }
+    qsort(tau, (size_t)count, sizeof(double), cmp_double);
+    int64_t uniq = 1;
+    for (int64_t i = 1; i < count; ++i)
+        if (tau[i] != tau[uniq - 1]) tau[uniq++] = tau[i];
+    double best_theta = 0.0;
+    unsigned __int128 best_key = 0;
+    int have = 0;
+    /* i = -1 is the interval that wraps around 2 pi, from the last critical angle to the first */
+    for (int64_t i = -1; i + 1 < uniq; ++i) {
+        double mid;
+        if (i < 0) {
+            mid = 0.5 * (tau[uniq - 1] + tau[0] + two_pi);
+            if (mid >= two_pi) mid -= two_pi;
+        } else {
+            mid = 0.5 * (tau[i] + tau[i + 1]);
+        }
+        counts_at(u, v, n, rest, mid, cnt);
+        const unsigned __int128 key = sum_squares(cnt);
+        if (!have || key < best_key || (key == best_key && mid < best_theta)) {
+            best_key = key;
+            best_theta = mid;
+            have = 1;
+        }
+    }
+    counts_at(u, v, n, rest, best_theta, cnt);
+    *theta = best_theta;
+    *loss = torq_o_code_loss(cnt);
+    free(tau);
+    return uniq;
+}
+
+/* Algorithm 2.  X: n blocks of 32 values (after the inter-block rotation).  Each pass evaluates the
+ * current rotation (S-step: s_b from the block maximum of Z = X R by the quantiser's own rule;
+ * histograms and the loss of Z / s), stops when the loss fell by no more than eps since the last
+ * pass, and otherwise takes the R-step: the k_top most imbalanced columns form the pool, the P
+ * best-scoring disjoint pairs of the pool are taken in order of their score, and each pair is turned
+ * by its exact best angle (the histograms follow every turn).  A last evaluation follows the last
+ * R-step.  losses[i] is the loss seen by evaluation i (at most max_iter + 1 of them, *n_eval says
+ * how many); R is the rotation of the evaluation with the smallest loss, the earliest among equals. */
+void torq_o_intra_rotation(const double *X, int64_t n, int max_iter, int k_top, int P, double lambda,
+                           double eps, double *R_out, double *losses, int *n_eval)
+{
+    double R[BLK][BLK], best_R[BLK][BLK];
+    double *Z = (double *)malloc(sizeof(double) * (size_t)n * BLK);
+    double *u = (double *)malloc(sizeof(double) * (size_t)n);
+    double *v = (double *)malloc(sizeof(double) * (size_t)n);
+    double h[BLK], H[BLK * BLK], best_loss = 0.0;
+    uint64_t counts[BLK * 8], total[8];
+    for (int i = 0; i < BLK; ++i)
+        for (int j = 0; j < BLK; ++j) R[i][j] = (i == j) ? 1.0 : 0.0;
+    *n_eval = 0;
+    for (int iter = 0;; ++iter) {
+        /* S-step and evaluation: Z = S^-1 X R */
+        for (int64_t b = 0; b < n; ++b) {
+            double amax = 0.0;
+            for (int k = 0; k < BLK; ++k) {
+                double acc = 0.0;
+                for (int i = 0; i < BLK; ++i) acc += X[b * BLK + i] * R[i][k];
+                Z[b * BLK + k] = acc;
+                if (fabs(acc) > amax) amax = fabs(acc);
+            }
+            const double s = ldexp(1.0, (int)torq_o_e8m0_from_amax((float)amax) - 127);
+            for (int k = 0; k < BLK; ++k) Z[b * BLK + k] /= s;
+        }
+        for (int i = 0; i < BLK * 8; ++i) counts[i] = 0;
+        for (int64_t b = 0; b < n; ++b)
+            for (int k = 0; k < BLK; ++k) counts[k * 8 + torq_o_mag_code(Z[b * BLK + k])] += 1;
+        for (int j = 0; j < 8; ++j) {
+            total[j] = 0;
+            for (int k = 0; k < BLK; ++k) total[j] += counts[k * 8 + j];
+        }
+        const double loss = torq_o_code_loss(total);
+        losses[*n_eval] = loss;
+        if (*n_eval == 0 || loss < best_loss) {
+            best_loss = loss;
+            memcpy(best_R, R, sizeof(R));
+        }
+        *n_eval += 1;
+        if (iter >= max_iter) break;
+        if (iter > 0 && !(losses[iter - 1] - loss > eps)) break;
+
+        /* R-step: pool, pairs */
+        torq_o_pair_scores(counts, lambda, h, H);
+        int in_pool[BLK], used[BLK];
+        for (int k = 0; k < BLK; ++k) in_pool[k] = used[k] = 0;
+        for (int t = 0; t < k_top && t < BLK; ++t) {
+            int arg = -1;
+            for (int k = 0; k < BLK; ++k)
+                if (!in_pool[k] && (arg < 0 || h[k] > h[arg])) arg = k;
+            in_pool[arg] = 1;
+        }
+        for (int l = 0; l < P; ++l) {
+            int bp = -1, bq = -1;
+            for (int p = 0; p < BLK; ++p)
+                for (int q = p + 1; q < BLK; ++q) {
+                    if (!in_pool[p] || !in_pool[q] || used[p] || used[q]) continue;
+                    if (bp < 0 || H[p * BLK + q] > H[bp * BLK + bq]) {
+                        bp = p;
+                        bq = q;
+                    }
+                }
+            if (bp < 0) break;
+            used[bp] = used[bq] = 1;
+            /* the pair's columns, the occupancy of all the others, the exact angle */
+            uint64_t rest[8];
+            for (int j = 0; j < 8; ++j) rest[j] = total[j] - counts[bp * 8 + j] - counts[bq * 8 + j];
+            for (int64_t b = 0; b < n; ++b) {
+                u[b] = Z[b * BLK + bp];
+                v[b] = Z[b * BLK + bq];
+            }
+            double theta, l_pair;
+            torq_o_best_angle(u, v, n, rest, &theta, &l_pair);
+            /* R <- R G_(p,q)(theta), Z <- Z G_(p,q)(theta): column p becomes p cos + q sin,
+             * column q becomes -p sin + q cos */
+            const double c = cos(theta), sn = sin(theta);
+            for (int i = 0; i < BLK; ++i) {
+                const double rp = R[i][bp], rq = R[i][bq];
+                R[i][bp] = rp * c + rq * sn;
+                R[i][bq] = -rp * sn + rq * c;
+            }
+            for (int j = 0; j < 8; ++j) counts[bp * 8 + j] = counts[bq * 8 + j] = 0;
+            for (int64_t b = 0; b < n; ++b) {
+                const double zp = u[b] * c + v[b] * sn, zq = -u[b] * sn + v[b] * c;
+                Z[b * BLK + bp] = zp;
+                Z[b * BLK + bq] = zq;
+                counts[bp * 8 + torq_o_mag_code(zp)] += 1;
+                counts[bq * 8 + torq_o_mag_code(zq)] += 1;
+            }
+            for (int j = 0; j < 8; ++j) total[j] = rest[j] + counts[bp * 8 + j] + counts[bq * 8 + j];
+        }
+    }
+    memcpy(R_out, best_R, sizeof(best_R));
+    free(Z);
+    free(u);
+    free(v);
 }
 
 int torq_o_threads(void)

@@ -20,7 +20,12 @@
  *
  * Parity status of the pieces:
  *   - bf16 conversion, E8M0 scale, e2m1 rounding, nibble packing, rotation,
- *     reference GEMM, variance equaliser: pinned by tests/test_oracle_*.py.
+ *     reference GEMM, variance equaliser, block Gram matrix, code histogram,
+ *     occupancy loss, pair scores, exact angle solver and the Algorithm 2 loop:
+ *     pinned by tests/test_oracle_*.py.  Algorithm 2 leaves its loop control
+ *     open (what the loss change is measured between, which rotation is
+ *     returned, the rounding rule of the scale): the definition of
+ *     torq_o_intra_rotation states the reading taken.
  *   - rotations that the paper would obtain by calibrating on real model
  *     activations: parity unpinned (no such data exists here); seeded random
  *     orthogonal matrices and the equaliser below stand in for them.
@@ -107,6 +112,39 @@ void torq_o_block_gram(const uint16_t *x_bf16, int64_t M, int d, int G, double *
  * Returns the number of plane rotations used (at most B-1), or -1 if a pair
  * with opposite deviation signs could not be found. */
 int torq_o_equalize(double *Sigma, int B, double eps, double *R);
+
+/* ---- intra-block calibration (Section 5.2, Algorithm 2, Appendix A.4 / A.5) ---- */
+
+/* Column-wise codebook histogram (Appendix A.5, N_j^(k)): counts[k * 8 + j] = number of blocks,
+ * over all rows, whose element k carries the magnitude codeword j (the code's low three bits). */
+void torq_o_code_histogram(const uint8_t *codes, int64_t M, int d, uint64_t *counts);
+
+/* Codebook occupancy equilibrium loss (Section 5.2): sum_j (p_j - 1/8)^2 with p_j = n[j] / sum n. */
+double torq_o_code_loss(const uint64_t n[8]);
+
+/* Appendix A.5: imbalance h_k of every column, and the pair score
+ * H[k][l] = h_k + h_l + lambda * c_kl, c_kl = - sum_j (p_j^(k) - 1/8)(p_j^(l) - 1/8). */
+void torq_o_pair_scores(const uint64_t *counts /* [32][8] */, double lambda, double *h /* [32] */,
+                        double *H /* [32][32] */);
+
+/* Index j of the magnitude interval I_j (Section 5.2, decision boundaries d_j) that holds |a|. */
+int torq_o_mag_code(double a);
+
+/* Appendix A.4: the Givens angle that minimises the occupancy loss for one column pair.
+ * u, v: the n normalised values z / s of the two columns (S is fixed in the R-step); rest[j]:
+ * occupancy counts of all other columns.  Under the angle theta the columns become
+ * u cos + v sin and -u sin + v cos.  Every critical angle (a sample's projected magnitude on
+ * either axis equal to a decision boundary) is enumerated, the occupancy is counted afresh at the
+ * midpoint of every interval between neighbouring critical angles (including the one that wraps
+ * around 2 pi), and the smallest loss wins, the smallest angle among equals.  Returns the number of
+ * intervals examined; with no critical angle at all the loss is constant and theta = 0. */
+int64_t torq_o_best_angle(const double *u, const double *v, int64_t n, const uint64_t rest[8],
+                          double *theta, double *loss);
+
+/* Algorithm 2 on n sample blocks X[n][32]; see the definition for the reading of the loop. */
+void torq_o_intra_rotation(const double *X, int64_t n, int max_iter, int k_top, int P, double lambda,
+                           double eps, double *R /* [32][32] */, double *losses /* [max_iter + 1] */,
+                           int *n_eval);
 
 /* number of OpenMP threads the row loops will use */
 int torq_o_threads(void);

@@ -12,7 +12,8 @@ import pytest
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "torq_oracle.c")
-PIN_FILES = ["tests/test_oracle_formats.py", "tests/test_oracle_rotation.py", "tests/test_oracle_gemm.py"]
+PIN_FILES = ["tests/test_oracle_formats.py", "tests/test_oracle_rotation.py", "tests/test_oracle_gemm.py",
+             "tests/test_oracle_intra.py"]
 
 # (name, text in torq_oracle.c, replacement)
 MUTATIONS = [
@@ -58,6 +59,24 @@ MUTATIONS = [
      "const double t = tan(0.5 * atan2(2.0 * g, a - b)); (void)D;"),
     ("equalize_R_transposed", "R[i * B + q] = cs * ri + sn * rj;\n            R[j * B + q] = -sn * ri + cs * rj;",
      "R[i * B + q] = cs * ri - sn * rj;\n            R[j * B + q] = sn * ri + cs * rj;"),
+    ("hist_counts_sign_bit", "counts[(j % BLK) * 8 + (code & 7u)] += 1;", "counts[(j % BLK) * 8 + ((code >> 1) & 7u)] += 1;"),
+    ("hist_position_of_row_not_block", "counts[(j % BLK) * 8 + (code & 7u)] += 1;", "counts[(j % 16) * 8 + (code & 7u)] += 1;"),
+    ("loss_not_centred", "double dev = (double)n[j] / total - 1.0 / 8.0;", "double dev = (double)n[j] / total;"),
+    ("complementarity_sign", "for (int j = 0; j < 8; ++j) c -= dev[k][j] * dev[l][j];", "for (int j = 0; j < 8; ++j) c += dev[k][j] * dev[l][j];"),
+    ("score_drops_partner", "H[k * BLK + l] = h[k] + h[l] + lambda * c;", "H[k * BLK + l] = h[k] + lambda * c;"),
+    ("mag_tie_2.5", "if (m <= 2.5) return 4;", "if (m < 2.5) return 4;"),
+    ("angle_second_axis_sign", "cnt[torq_o_mag_code(-u[b] * s + v[b] * c)] += 1;", "cnt[torq_o_mag_code(u[b] * s - v[b] * s)] += 1;"),
+    ("angle_no_second_axis", "for (int axis = 0; axis < 2; ++axis) {", "for (int axis = 0; axis < 1; ++axis) {"),
+    ("angle_no_plus_pi", "const double cand[4] = {base - alpha, base + alpha, base - alpha + PI, base + alpha + PI};",
+     "const double cand[4] = {base - alpha, base + alpha, base - alpha, base + alpha};"),
+    ("angle_drops_wrap_interval", "for (int64_t i = -1; i + 1 < uniq; ++i) {\n        double mid;", "for (int64_t i = 0; i + 1 < uniq; ++i) {\n        double mid;"),
+    ("angle_ignores_rest", "for (int j = 0; j < 8; ++j) cnt[j] = rest[j];", "for (int j = 0; j < 8; ++j) cnt[j] = 0 * rest[j];"),
+    ("angle_maximises", "if (!have || key < best_key || (key == best_key && mid < best_theta)) {", "if (!have || key > best_key) {"),
+    ("alg2_givens_transposed", "R[i][bp] = rp * c + rq * sn;\n                R[i][bq] = -rp * sn + rq * c;",
+     "R[i][bp] = rp * c - rq * sn;\n                R[i][bq] = rp * sn + rq * c;"),
+    ("alg2_scale_from_unrotated", "if (fabs(acc) > amax) amax = fabs(acc);", "if (fabs(X[b * BLK + k]) > amax) amax = fabs(X[b * BLK + k]);"),
+    ("alg2_pool_least_imbalanced", "if (!in_pool[k] && (arg < 0 || h[k] > h[arg])) arg = k;", "if (!in_pool[k] && (arg < 0 || h[k] < h[arg])) arg = k;"),
+    ("alg2_stale_rest", "for (int j = 0; j < 8; ++j) total[j] = rest[j] + counts[bp * 8 + j] + counts[bq * 8 + j];", ""),
 ]
 
 
