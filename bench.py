@@ -193,6 +193,10 @@ def main():
         xl = torch.cat([x, x, x, x], dim=0)             # a longer calibration sample: [32768, d]
         print(json.dumps(gram_line(tq, xl, G, args.steps, args.warmup)), flush=True)
         del xl
+        # calibration statistic (Section 5.2): codeword histogram per in-block position of the step's
+        # packed codes, and of a set eight times as long; HBM bound at half a byte per element
+        print(json.dumps(hist_line(tq, codes, d, args.steps, args.warmup)), flush=True)
+        print(json.dumps(hist_line(tq, torch.cat([codes] * 8, dim=0), d, args.steps, args.warmup)), flush=True)
         # decode-sized linear layers (few activation rows: weight streaming, HBM bound), timed as
         # replays of a HIP graph of 20 calls so that Python's launch overhead is not in the figure
         for (mm, nn, dd) in ((1, 14336, 4096), (16, 14336, 4096), (16, 4096, 14336), (16, 28672, 8192)):
@@ -299,6 +303,29 @@ def gram_line(tq, x, G, steps, warmup):
     gbs = M * d * 2.0 / (ms * 1e-3) / 1e9
     return {"metric": "torq_block_gram bandwidth", "value": round(gbs, 1), "unit": "GB/s",
             "config": {"workload": f"calibration statistic: X bf16 [{M}, {d}], G={G}"}, "ms": round(ms, 4),
+            "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def hist_line(tq, codes, d, steps, warmup):
+    """torq_code_histogram on packed codes: half a byte per element read once."""
+    import torch
+    M = codes.shape[0]
+    copies = max(3, int(600e6 // codes.numel()) + 1)   # rotate through more than the Infinity Cache holds
+    cs = [codes] + [codes.clone() for _ in range(copies - 1)]
+    counts = torch.empty((32, 8), dtype=torch.int64, device=codes.device)
+    ws = torch.empty((tq.torq_code_histogram_workspace_bytes(),), dtype=torch.uint8, device=codes.device)
+    for i in range(warmup):
+        tq.torq_code_histogram(cs[i % copies], d, counts=counts, workspace=ws)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for i in range(steps):
+        tq.torq_code_histogram(cs[i % copies], d, counts=counts, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    gbs = M * d * 0.5 / (ms * 1e-3) / 1e9
+    return {"metric": "torq_code_histogram bandwidth", "value": round(gbs, 1), "unit": "GB/s",
+            "config": {"workload": f"calibration statistic: packed codes [{M}, {d}/2]"}, "ms": round(ms, 4),
             "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
 
 

@@ -162,6 +162,58 @@ int torq_block_gram(const void *x_bf16, int64_t M, int d, int G, double *Sigma,
 int torq_equalize_inter(const double *Sigma_host, int G, double eps, float *R_inter_host, int *steps);
 
 /* ------------------------------------------------------------------------ */
+/* Calibration of the intra-block rotation (Section 5.2, Algorithm 2; Appendix A.4, A.5).  Not part
+ * of the online path: run once to obtain R_intra for torq_rotation_create.
+ *
+ * torq_code_histogram: the column-wise codebook histogram N_j^(k) of Appendix A.5 over packed codes
+ * as the quantiser wrote them (the S-step of Section 5.2 is the quantiser's own scale, so the codes
+ * of torq_rotate_quantize under the current R_intra are the occupancy that the loss of Section 5.2
+ * measures):  counts[k * 8 + j] = number of 32-element blocks whose element k has the magnitude
+ * codeword j = code & 7 (the sign bit is ignored).
+ *   codes      device, [M][d/2] bytes as torq_rotate_quantize writes them, 16-byte aligned
+ *   counts     device, 256 uint64, 8-byte aligned, overwritten
+ *   workspace  device, at least torq_code_histogram_workspace_bytes() bytes, 16-byte aligned, scratch
+ * M = 0 gives all-zero counts.  Integer work: the result is exact and deterministic.
+ *
+ * The remaining entry points run on the HOST, in double, on HOST arrays.
+ *
+ * torq_intra_pair_scores (Appendix A.5): h[k] = sum_j (p_j^(k) - 1/8)^2 and
+ * H[k][l] = h[k] + h[l] + lambda * c_kl with c_kl = -sum_j (p_j^(k) - 1/8)(p_j^(l) - 1/8), from
+ * counts[32][8] (a column without counts has p = 0).  h: 32 doubles, H: 32*32 doubles.
+ *
+ * torq_intra_best_angle (Appendix A.4): for the n normalised values (u, v) of one column pair and
+ * the occupancy `rest` (8 counts) of all other columns, the angle theta in [0, 2 pi) that minimises
+ * the loss when the pair becomes (u cos + v sin, -u sin + v cos): the midpoint of the best interval
+ * between neighbouring critical angles, the smallest such midpoint among equally good intervals;
+ * theta = 0 if there is no critical angle.  Equal losses are recognised exactly (the comparison is
+ * made on the integer sum of squared counts).  `critical` (optional) receives the number of distinct
+ * critical angles.  n <= TORQ_INTRA_MAX_SAMPLE; up to 56 events of 16 bytes per sample are held.
+ *
+ * torq_calibrate_intra (Algorithm 2) on a sample of n blocks X[n][32] (fp32, after the inter-block
+ * rotation, e.g. rows of torq_rotate's output under R_intra = I).  Readings of the loop that
+ * Algorithm 2 leaves open: an evaluation is the S-step (scale of each block from the maximum of
+ * Z = X R by the quantiser's rule 2^(floor(log2 amax) - 2)) followed by the loss of Z / s; the loop
+ * stops after max_iter R-steps or when the loss fell by no more than eps since the previous
+ * evaluation; one R-step takes the k_top columns of largest h as the pool and turns the P
+ * best-scoring disjoint pairs of the pool in order of their score, each by its exact angle with the
+ * occupancy as the earlier turns left it (lower index first among equal scores); the result is the
+ * rotation of the evaluation with the smallest loss.
+ *   R_intra_host  32*32 floats out, row-major, Z = X R_intra (the layout torq_rotation_create takes)
+ *   losses_host   max_iter + 1 doubles out: the loss of every evaluation
+ *   n_eval        out: how many evaluations were made
+ *   1 <= k_top <= 32, 1 <= P <= 16, 0 <= max_iter <= 1000, lambda >= 0, eps >= 0
+ * All return TORQ_OK or TORQ_EINVAL (torq_code_histogram also TORQ_EALIGN, TORQ_EWORKSPACE, TORQ_EHIP). */
+#define TORQ_INTRA_MAX_SAMPLE (1 << 22)
+size_t torq_code_histogram_workspace_bytes(void);
+int torq_code_histogram(const uint8_t *codes, int64_t M, int d, uint64_t *counts, void *workspace,
+                        size_t workspace_bytes, void *stream);
+int torq_intra_pair_scores(const uint64_t *counts_host, double lambda, double *h_host, double *H_host);
+int torq_intra_best_angle(const double *u_host, const double *v_host, int64_t n, const uint64_t *rest_host,
+                          double *theta, double *loss, int64_t *critical);
+int torq_calibrate_intra(const float *X_host, int64_t n, int max_iter, int k_top, int P, double lambda,
+                         double eps, float *R_intra_host, double *losses_host, int *n_eval);
+
+/* ------------------------------------------------------------------------ */
 /* Diagnostics (not a step of Algorithm 3): the rate the matrix cores sustain on
  * this machine with nothing else running, on operands the caller supplies --
  * the ceiling to read the MFMA-bound kernels against, since the part lowers its

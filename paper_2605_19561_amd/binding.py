@@ -16,7 +16,8 @@ EXPORTS = [
     "torq_status_string", "torq_rotation_create", "torq_rotation_destroy", "torq_rotation_d",
     "torq_rotation_G", "torq_rotate_quantize", "torq_rotate", "torq_quantize_f32", "mxfp4_gemm",
     "torq_linear_workspace_bytes", "torq_linear", "torq_block_gram_workspace_bytes", "torq_block_gram",
-    "torq_equalize_inter", "torq_diag_mfma_burn",
+    "torq_equalize_inter", "torq_code_histogram_workspace_bytes", "torq_code_histogram", "torq_intra_pair_scores",
+    "torq_intra_best_angle", "torq_calibrate_intra", "torq_diag_mfma_burn",
 ]
 
 TORQ_OK, TORQ_EINVAL, TORQ_EALIGN, TORQ_EWORKSPACE, TORQ_EHIP, TORQ_ENODEVICE, TORQ_ECONVERGE = 0, -1, -2, -3, -4, -5, -6
@@ -68,6 +69,17 @@ def lib():
         L.torq_block_gram.argtypes = [vp, i64, i32, i32, vp, vp, sz, vp]
         L.torq_equalize_inter.restype = i32
         L.torq_equalize_inter.argtypes = [vp, i32, C.c_double, vp, C.POINTER(i32)]
+        L.torq_code_histogram_workspace_bytes.restype = sz
+        L.torq_code_histogram_workspace_bytes.argtypes = []
+        L.torq_code_histogram.restype = i32
+        L.torq_code_histogram.argtypes = [vp, i64, i32, vp, vp, sz, vp]
+        L.torq_intra_pair_scores.restype = i32
+        L.torq_intra_pair_scores.argtypes = [vp, C.c_double, vp, vp]
+        L.torq_intra_best_angle.restype = i32
+        L.torq_intra_best_angle.argtypes = [vp, vp, i64, vp, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                            C.POINTER(i64)]
+        L.torq_calibrate_intra.restype = i32
+        L.torq_calibrate_intra.argtypes = [vp, i64, i32, i32, i32, C.c_double, C.c_double, vp, vp, C.POINTER(i32)]
         L.torq_diag_mfma_burn.restype = i32
         L.torq_diag_mfma_burn.argtypes = [i32, vp, sz, i32, vp, vp]
         _lib = L
@@ -233,3 +245,66 @@ def torq_equalize_inter(Sigma, eps: float = 0.0):
     _check(lib().torq_equalize_inter(S.ctypes.data_as(C.c_void_p), G, float(eps), R.ctypes.data_as(C.c_void_p),
                                      C.byref(steps)), "torq_equalize_inter")
     return R, steps.value
+
+
+def torq_code_histogram_workspace_bytes() -> int:
+    return int(lib().torq_code_histogram_workspace_bytes())
+
+
+def torq_code_histogram(codes: torch.Tensor, d: int, counts: torch.Tensor = None, workspace: torch.Tensor = None,
+                        stream=None):
+    """codes: uint8 [M, d/2] device (packed e2m1).  Returns counts int64 [32, 8] device (N_j^(k), Appendix A.5)."""
+    M = codes.shape[0]
+    if codes.dim() != 2 or codes.shape[1] * 2 != d:
+        raise ValueError("codes must be [M, d/2]")
+    if counts is None:
+        counts = torch.empty((32, 8), dtype=torch.int64, device=codes.device)
+    if workspace is None:
+        workspace = torch.empty(torq_code_histogram_workspace_bytes(), dtype=torch.uint8, device=codes.device)
+    _check(lib().torq_code_histogram(_dev(codes, torch.uint8, "codes"), M, d, _dev(counts, torch.int64, "counts"),
+                                     _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)),
+           "torq_code_histogram")
+    return counts
+
+
+def torq_intra_pair_scores(counts, lam: float):
+    """counts: [32, 8] array-like of non-negative integers (host).  Returns (h [32], H [32, 32]) float64."""
+    import numpy as np
+    c = np.ascontiguousarray(counts, dtype=np.uint64)
+    if c.shape != (32, 8):
+        raise ValueError("counts must be [32, 8]")
+    h = np.empty((32,), np.float64)
+    H = np.empty((32, 32), np.float64)
+    _check(lib().torq_intra_pair_scores(c.ctypes.data_as(C.c_void_p), float(lam), h.ctypes.data_as(C.c_void_p),
+                                        H.ctypes.data_as(C.c_void_p)), "torq_intra_pair_scores")
+    return h, H
+
+
+def torq_intra_best_angle(u, v, rest):
+    """Appendix A.4 on the host.  Returns (theta, loss, number of distinct critical angles)."""
+    import numpy as np
+    u = np.ascontiguousarray(u, dtype=np.float64)
+    v = np.ascontiguousarray(v, dtype=np.float64)
+    r = np.ascontiguousarray(rest, dtype=np.uint64)
+    if u.ndim != 1 or u.shape != v.shape or r.shape != (8,):
+        raise ValueError("u, v must be vectors of one length and rest 8 counts")
+    th, lo, k = C.c_double(0.0), C.c_double(0.0), C.c_int64(0)
+    _check(lib().torq_intra_best_angle(u.ctypes.data_as(C.c_void_p), v.ctypes.data_as(C.c_void_p), u.shape[0],
+                                       r.ctypes.data_as(C.c_void_p), C.byref(th), C.byref(lo), C.byref(k)),
+           "torq_intra_best_angle")
+    return th.value, lo.value, k.value
+
+
+def torq_calibrate_intra(X, max_iter: int, k_top: int, P: int, lam: float, eps: float):
+    """Algorithm 2 on the host.  X: [n, 32] float32 sample blocks.  Returns (R_intra float32 [32, 32], losses)."""
+    import numpy as np
+    X = np.ascontiguousarray(X, dtype=np.float32)
+    if X.ndim != 2 or X.shape[1] != 32:
+        raise ValueError("X must be [n, 32]")
+    R = np.empty((32, 32), np.float32)
+    losses = np.zeros((max(int(max_iter), 0) + 1,), np.float64)
+    k = C.c_int(0)
+    _check(lib().torq_calibrate_intra(X.ctypes.data_as(C.c_void_p), X.shape[0], int(max_iter), int(k_top), int(P),
+                                      float(lam), float(eps), R.ctypes.data_as(C.c_void_p),
+                                      losses.ctypes.data_as(C.c_void_p), C.byref(k)), "torq_calibrate_intra")
+    return R, losses[: k.value].copy()

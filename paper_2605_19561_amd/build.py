@@ -9,7 +9,8 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtorq.so")
-SOURCES = ["api.hip", "quantize.hip", "rotate_quant.hip", "mxfp4_gemm.hip", "mxfp4_gemm_skinny.hip", "block_gram.hip", "diag.hip"]
+SOURCES = ["api.hip", "quantize.hip", "rotate_quant.hip", "mxfp4_gemm.hip", "mxfp4_gemm_skinny.hip", "block_gram.hip", "code_histogram.hip",
+           "intra_calib.hip", "diag.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
          # packed fp32 arithmetic is kept off for all device code

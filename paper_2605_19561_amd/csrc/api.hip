@@ -1,5 +1,6 @@
 // C-ABI entry points of libtorq: argument validation, the rotation handle, and
-// dispatch to the kernel launchers.  No compute happens on the host.
+// dispatch to the kernel launchers.  The online path computes nothing on the host; the calibration
+// entry points that are documented as host routines do.
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -291,6 +292,51 @@ int torq_equalize_inter(const double *Sigma_host, int G, double eps, float *R_in
   }
   for (size_t i = 0; i < n * n; ++i) R_inter_host[i] = (float)R[i];
   if (steps_out) *steps_out = steps;
+  return TORQ_OK;
+}
+
+size_t torq_code_histogram_workspace_bytes(void) { return torq::code_histogram_workspace_bytes(); }
+
+int torq_code_histogram(const uint8_t *codes, int64_t M, int d, uint64_t *counts, void *workspace,
+                        size_t workspace_bytes, void *stream) {
+  if (M < 0 || d <= 0 || d % TORQ_BLOCK != 0 || !counts || !workspace) return TORQ_EINVAL;
+  if (M > 0 && !codes) return TORQ_EINVAL;
+  if (misaligned(codes) || misaligned(workspace) || (reinterpret_cast<uintptr_t>(counts) & 7u)) return TORQ_EALIGN;
+  if (workspace_bytes < torq::code_histogram_workspace_bytes()) return TORQ_EWORKSPACE;
+  // M = 0 launches the same kernels over no blocks: every count comes out zero
+  hipError_t e = torq::launch_code_histogram(codes, M * (int64_t)(d / TORQ_BLOCK), counts, workspace,
+                                             (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+int torq_intra_pair_scores(const uint64_t *counts_host, double lambda, double *h_host, double *H_host) {
+  if (!counts_host || !h_host || !H_host || !(lambda >= 0.0)) return TORQ_EINVAL;
+  torq::intra_pair_scores(counts_host, lambda, h_host, H_host);
+  return TORQ_OK;
+}
+
+int torq_intra_best_angle(const double *u_host, const double *v_host, int64_t n, const uint64_t *rest_host,
+                          double *theta, double *loss, int64_t *critical) {
+  if (n < 0 || n > TORQ_INTRA_MAX_SAMPLE || !rest_host || !theta || !loss) return TORQ_EINVAL;
+  if (n > 0 && (!u_host || !v_host)) return TORQ_EINVAL;
+  for (int64_t b = 0; b < n; ++b)
+    if (!std::isfinite(u_host[b]) || !std::isfinite(v_host[b])) return TORQ_EINVAL;
+  const int64_t k = torq::intra_best_angle(u_host, v_host, n, rest_host, theta, loss);
+  if (critical) *critical = k;
+  return TORQ_OK;
+}
+
+int torq_calibrate_intra(const float *X_host, int64_t n, int max_iter, int k_top, int P, double lambda,
+                         double eps, float *R_intra_host, double *losses_host, int *n_eval) {
+  if (!X_host || !R_intra_host || !losses_host || !n_eval) return TORQ_EINVAL;
+  if (n < 1 || n > TORQ_INTRA_MAX_SAMPLE || max_iter < 0 || max_iter > 1000) return TORQ_EINVAL;
+  if (k_top < 1 || k_top > TORQ_BLOCK || P < 1 || P > TORQ_BLOCK / 2) return TORQ_EINVAL;
+  if (!(lambda >= 0.0) || !(eps >= 0.0)) return TORQ_EINVAL;
+  for (int64_t i = 0; i < n * TORQ_BLOCK; ++i)
+    if (!std::isfinite(X_host[i])) return TORQ_EINVAL;
+  double R[TORQ_BLOCK * TORQ_BLOCK];
+  torq::intra_rotation(X_host, n, max_iter, k_top, P, lambda, eps, R, losses_host, n_eval);
+  for (int i = 0; i < TORQ_BLOCK * TORQ_BLOCK; ++i) R_intra_host[i] = (float)R[i];
   return TORQ_OK;
 }
 

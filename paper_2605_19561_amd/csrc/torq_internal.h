@@ -46,6 +46,18 @@ size_t block_gram_workspace_bytes(int G);
 hipError_t launch_block_gram(const void *x_bf16, int64_t TG, int G, double *Sigma, void *workspace,
                              hipStream_t stream);
 
+// Codeword histogram per in-block position (code_histogram.hip): nblk blocks of 16 code bytes.
+size_t code_histogram_workspace_bytes();
+hipError_t launch_code_histogram(const uint8_t *codes, int64_t nblk, uint64_t *counts, void *workspace,
+                                 hipStream_t stream);
+
+// Host side of the intra-block calibration (intra_calib.hip).
+void intra_pair_scores(const uint64_t *counts, double lambda, double *h, double *H);
+int64_t intra_best_angle(const double *u, const double *v, int64_t n, const uint64_t rest[8], double *theta,
+                         double *loss);
+void intra_rotation(const float *X, int64_t n, int max_iter, int k_top, int P, double lambda, double eps,
+                    double *R_out, double *losses, int *n_eval);
+
 // 1024 x 256 lanes issue iters x 16 MFMAs each on operands taken from `words` (see diag.hip).
 hipError_t launch_mfma_burn(int kind, const uint32_t *words, uint32_t n_words, int iters, float *sink,
                             hipStream_t stream);

@@ -238,3 +238,30 @@ def test_block_gram_many_token_groups_per_workgroup(tq, oracle):
     assert np.array_equal(Sf, Sf.T)
     energy = float((xf.double() ** 2).sum().item()) / (xf.shape[0] * (xf.shape[1] // 32 // G))
     assert abs(np.trace(Sf) - energy) <= 1e-5 * energy
+
+
+def test_code_histogram_more_than_255_blocks_per_lane(tq, oracle):
+    # 35.8 M blocks: every lane counts more blocks than a byte counter holds, so the workgroup sum
+    # through LDS runs more than once; the last span is ragged
+    M, d = 39999, 28672
+    g = torch.Generator(device=DEV).manual_seed(6100)
+    codes = torch.randint(0, 256, (M, d // 2), dtype=torch.uint8, device=DEV, generator=g)
+    codes.view(M, d // 32, 16)[:, :, 0] &= 0xF8     # position 0 of every block carries codeword 0 (or -0)
+    got = _np(tq.torq_code_histogram(codes, d)).astype(np.uint64)
+    torch.cuda.synchronize()
+    want = oracle.code_histogram(_np(codes), d)
+    assert np.array_equal(got, want)
+    assert got[0, 0] == M * (d // 32) and got.sum() == M * d
+
+
+def test_code_histogram_of_the_benchmark_step(tq, oracle):
+    # the packed codes of the benchmark's rotate + quantise: exact against the oracle's count
+    x = synth.workload_activations("llama3_70b_up", device=DEV)
+    M, d = x.shape
+    G = synth.default_G(d)
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    codes, _ = tq.torq_rotate_quantize(rot, x)
+    got = _np(tq.torq_code_histogram(codes, d)).astype(np.uint64)
+    assert np.array_equal(got, oracle.code_histogram(_np(codes), d))
+    rot.close()

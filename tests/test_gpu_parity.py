@@ -437,3 +437,110 @@ def test_calibrated_rotation_equalizes_block_energies_on_the_gpu(tq, oracle):
     energies = (z.double().reshape(M, G, 32) ** 2).sum(dim=2).mean(dim=0).cpu().numpy()
     assert np.abs(energies - c).max() <= 2e-3 * c                       # rotation error bar is 1e-3 of the RMS
     rot.close()
+
+
+# --------------------------------------------- calibration (Section 5.2) ----
+
+# blocks: 1, below one chunk per lane, ragged around the 256 x 15 blocks of a workgroup's chunk,
+# several workgroups, several chunks per lane (the cap of 1024 workgroups is 3.9 M blocks)
+HIST_CASES = [(1, 32), (3, 96), (17, 4096), (30, 4096), (31, 4096), (61, 2016), (256, 8192), (1111, 14336),
+              (40000, 3200)]
+
+
+@pytest.mark.parametrize("M,d", HIST_CASES)
+def test_code_histogram_against_oracle(tq, oracle, M, d):
+    g = torch.Generator().manual_seed(4000 + M + d)
+    # skewed nibbles, sign bits included: low magnitudes frequent, as quantised activations are
+    mag = torch.multinomial(torch.tensor([30.0, 20, 14, 10, 8, 6, 4, 2]), M * d, replacement=True, generator=g)
+    sign = torch.randint(0, 2, (M * d,), generator=g) * 8
+    el = (mag + sign).to(torch.uint8).reshape(M, d)
+    codes = (el[:, 0::2] | (el[:, 1::2] << 4)).contiguous()
+    want = oracle.code_histogram(codes.numpy(), d)
+    got = _np(tq.torq_code_histogram(codes.to(DEV), d))
+    torch.cuda.synchronize()
+    assert np.array_equal(got.astype(np.uint64), want)
+    assert got.sum() == M * d
+
+
+def test_code_histogram_extremes(tq, oracle):
+    d = 256
+    for fill, code in ((0x00, 0), (0xFF, 7), (0x88, 0), (0x7F, 7), (0x25, None)):
+        codes = torch.full((77, d // 2), fill, dtype=torch.uint8)
+        got = _np(tq.torq_code_histogram(codes.to(DEV), d))
+        assert np.array_equal(got.astype(np.uint64), oracle.code_histogram(codes.numpy(), d))
+        if code is not None:
+            assert np.all(got[:, code] == 77 * d // 32)
+    # no rows: every count is zero, and stale workspace contents do not leak in
+    ws = torch.full((tq.torq_code_histogram_workspace_bytes(),), 0xFF, dtype=torch.uint8, device=DEV)
+    got = tq.torq_code_histogram(torch.empty((0, d // 2), dtype=torch.uint8, device=DEV), d, workspace=ws)
+    assert int(got.abs().sum()) == 0
+
+
+def test_code_histogram_argument_checks(tq):
+    L = tq.lib()
+    d = 64
+    codes = torch.zeros((4, d // 2), dtype=torch.uint8, device=DEV)
+    counts = torch.zeros((32, 8), dtype=torch.int64, device=DEV)
+    ws = torch.empty(tq.torq_code_histogram_workspace_bytes(), dtype=torch.uint8, device=DEV)
+    import ctypes as C
+    vp = C.c_void_p
+    ok = (vp(codes.data_ptr()), 4, d, vp(counts.data_ptr()), vp(ws.data_ptr()), ws.numel(), None)
+    assert L.torq_code_histogram(*ok) == tq.TORQ_OK
+    assert L.torq_code_histogram(ok[0], -1, d, *ok[3:]) == tq.TORQ_EINVAL
+    assert L.torq_code_histogram(ok[0], 4, 48, *ok[3:]) == tq.TORQ_EINVAL
+    assert L.torq_code_histogram(None, 4, d, *ok[3:]) == tq.TORQ_EINVAL
+    assert L.torq_code_histogram(ok[0], 4, d, None, ok[4], ok[5], None) == tq.TORQ_EINVAL
+    assert L.torq_code_histogram(vp(codes.data_ptr() + 4), 4, d, *ok[3:]) == tq.TORQ_EALIGN
+    assert L.torq_code_histogram(ok[0], 4, d, vp(counts.data_ptr() + 4), ok[4], ok[5], None) == tq.TORQ_EALIGN
+    assert L.torq_code_histogram(ok[0], 4, d, ok[3], ok[4], ws.numel() - 1, None) == tq.TORQ_EWORKSPACE
+    torch.cuda.synchronize()
+
+
+def test_histogram_of_the_quantisers_codes_is_the_oracles(tq, oracle):
+    # rotate + quantise on the GPU, then the histogram of those codes, against the oracle's whole chain
+    M, d, G = 300, 2048, 64
+    x = synth.activations(M, d, nu=3.0, outliers=10, outlier_scale=50.0, seed=91)
+    R_inter, R_intra = synth.rotations(G, seed=92)
+    rot = tq.Rotation(d, G, R_inter, R_intra)
+    codes, _ = tq.torq_rotate_quantize(rot, x.to(DEV))
+    got = _np(tq.torq_code_histogram(codes, d)).astype(np.uint64)
+    assert np.array_equal(got, oracle.code_histogram(_np(codes), d))          # same codes: exact
+    # the oracle's own codes differ from the GPU's only where the rotation's rounding crosses a
+    # boundary: the two occupancy losses agree to that
+    codes_o, _ = oracle.rotate_quantize(synth.bf16_bits(x), G, R_inter, R_intra)
+    lo_o = oracle.code_loss(oracle.code_histogram(codes_o, d).sum(axis=0))
+    lo = oracle.code_loss(got.sum(axis=0))
+    assert abs(lo - lo_o) <= 1e-3 * lo_o
+    rot.close()
+
+
+def test_calibrated_intra_rotation_lowers_the_occupancy_loss_on_the_gpu(tq, oracle):
+    # Algorithm 2 end to end: rotated activations of a calibration set (GPU) -> sample of blocks ->
+    # torq_calibrate_intra (host) -> new handle -> quantise ALL the data (GPU) -> histogram (GPU):
+    # the loss over the full set, not only over the sample, falls.  R_inter = I here (the intra-only
+    # arm of the paper's ablation): a random R_inter mixes 128 blocks into near-Gaussian columns that
+    # all look alike, and turning two alike Gaussian columns changes nothing; the raw synthetic
+    # activations keep their outlier channels, which is what Algorithm 2 has to spread.
+    M, d, G = 512, 4096, 16
+    x = synth.activations(M, d, nu=3.0, outliers=20, outlier_scale=50.0, seed=93).to(DEV)
+    R_inter = np.eye(G, dtype=np.float32)
+    eye = np.eye(32, dtype=np.float32)
+    rot0 = tq.Rotation(d, G, R_inter, eye)
+    z = tq.torq_rotate(rot0, x)
+    blocks = z.reshape(-1, 32)
+    pick = torch.randperm(blocks.shape[0], generator=torch.Generator().manual_seed(95))[:6000].to(DEV)
+    sample = blocks[pick].cpu().numpy()
+    R_intra, losses = tq.torq_calibrate_intra(sample, 6, 16, 8, 1.0, 1e-7)
+    assert len(losses) >= 3 and losses[-1] < 0.5 * losses[0]
+
+    def full_loss(rot):
+        codes, _ = tq.torq_rotate_quantize(rot, x)
+        n = _np(tq.torq_code_histogram(codes, d)).astype(np.uint64).sum(axis=0)
+        return oracle.code_loss(n)
+
+    rot1 = tq.Rotation(d, G, R_inter, R_intra)
+    before, after = full_loss(rot0), full_loss(rot1)
+    assert before == pytest.approx(losses[0], rel=0.1)        # the sample stands for the set
+    assert after < 0.5 * before
+    rot0.close()
+    rot1.close()
