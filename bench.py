@@ -199,7 +199,8 @@ def main():
         print(json.dumps(hist_line(tq, torch.cat([codes] * 8, dim=0), d, args.steps, args.warmup)), flush=True)
         # decode-sized linear layers (few activation rows: weight streaming, HBM bound), timed as
         # replays of a HIP graph of 20 calls so that Python's launch overhead is not in the figure
-        for (mm, nn, dd) in ((1, 14336, 4096), (16, 14336, 4096), (16, 4096, 14336), (16, 28672, 8192)):
+        for (mm, nn, dd) in ((1, 14336, 4096), (16, 14336, 4096), (16, 4096, 14336), (16, 28672, 8192),
+                             (64, 28672, 8192), (128, 8192, 28672), (256, 4096, 14336)):
             print(json.dumps(decode_line(tq, synth, mm, nn, dd)), flush=True)
     rot.close()
 
@@ -346,7 +347,7 @@ def decode_line(tq, synth, M, N, d):
     W_q = [torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=dev, generator=gen) for _ in range(n_copies)]
     W_s = [torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=dev, generator=gen) for _ in range(n_copies)]
     out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
-    ws = torch.empty((tq.torq_linear_workspace_bytes(M, d),), dtype=torch.uint8, device=dev)
+    ws = torch.empty((tq.torq_linear_workspace_bytes_n(M, N, d),), dtype=torch.uint8, device=dev)
     calls = 24
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
@@ -370,8 +371,11 @@ def decode_line(tq, synth, M, N, d):
     us = e0.elapsed_time(e1) * 1e3 / (reps * calls)
     wbytes = N * d * 0.53125
     rot.close()
+    streaming, tile_m, tile_n, pieces = tq.mxfp4_gemm_plan(M, N, d, tq.mxfp4_gemm_workspace_bytes(M, N, d))
+    kernel = "weight-streaming" if streaming else f"tiled {tile_m}x{tile_n}" + (f", k cut in {pieces}" if pieces > 1 else "")
     return {"metric": "torq_linear, decode", "value": round(us, 2), "unit": "us per call", "higher_is_better": False,
-            "config": {"workload": f"decode: X bf16 [{M}, {d}], G={G}, W [{N}, {d}] packed MXFP4 ({wbytes / 1e6:.1f} MB)"},
+            "config": {"workload": f"decode: X bf16 [{M}, {d}], G={G}, W [{N}, {d}] packed MXFP4 ({wbytes / 1e6:.1f} MB)",
+                       "gemm_kernel": kernel},
             "weight_stream_GBps": round(wbytes / us / 1e3, 1), "frac_hbm_peak": round(wbytes / us / 1e3 / HBM_PEAK_GBS, 4)}
 
 

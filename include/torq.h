@@ -120,12 +120,33 @@ int mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s,
                const uint8_t *W_q, const uint8_t *W_s,
                void *out_bf16, int64_t M, int64_t N, int d, void *stream);
 
+/* mxfp4_gemm with scratch memory.  Same operands, same result up to the order of the fp32 sums.
+ * When the output has too few tiles to occupy the GPU and the reduction is long (a few hundred
+ * activation rows, e.g. a decode batch or a prefill chunk against a down projection), the k range
+ * is cut into pieces that run as separate workgroups; their fp32 tiles go through `workspace` and a
+ * second kernel adds them in a fixed order (deterministic) and rounds once to bf16.
+ *   workspace  device, 16-byte aligned, at least mxfp4_gemm_workspace_bytes(M, N, d) bytes (0 for
+ *              shapes that are not cut); NULL or too small: exactly mxfp4_gemm. */
+size_t mxfp4_gemm_workspace_bytes(int64_t M, int64_t N, int d);
+/* Which kernel the product of that shape runs on, given a workspace of that many bytes (0: as
+ * mxfp4_gemm) and 16-byte aligned scale arrays: *weight_streaming = 1 for the kernel that streams
+ * 16-row weight strips (at most 64 activation rows), else 0 and *tile_m x *tile_n is the output
+ * tile; *k_pieces > 1 if the k range is cut.  Host only, launches nothing; for logs and tests. */
+int mxfp4_gemm_plan(int64_t M, int64_t N, int d, size_t workspace_bytes, int *weight_streaming, int *tile_m,
+                    int *tile_n, int *k_pieces);
+int mxfp4_gemm_ws(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                  void *out_bf16, int64_t M, int64_t N, int d, void *workspace, size_t workspace_bytes,
+                  void *stream);
+
 /* Algorithm 3 end to end ("output of the linear layer"): torq_rotate_quantize
  * into `workspace`, then mxfp4_gemm, on one stream.  workspace is device
  * memory of at least torq_linear_workspace_bytes(M, d) bytes, 256-byte aligned
  * sizes; its contents afterwards are the packed activations (codes, then
  * scales at offset M*d/2 rounded up to 256). */
 size_t torq_linear_workspace_bytes(int64_t M, int d);
+/* The same plus the scratch that lets the GEMM inside cut its k range (see mxfp4_gemm_ws);
+ * torq_linear uses whatever it is given beyond torq_linear_workspace_bytes(M, d) for that. */
+size_t torq_linear_workspace_bytes_n(int64_t M, int64_t N, int d);
 int torq_linear(const torq_rotation_t *r, const void *x_bf16,
                 const uint8_t *W_q, const uint8_t *W_s, void *out_bf16,
                 int64_t M, int64_t N, void *workspace, size_t workspace_bytes,

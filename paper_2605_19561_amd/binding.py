@@ -15,7 +15,8 @@ LIB_PATH = os.path.join(_HERE, "libtorq.so")
 EXPORTS = [
     "torq_status_string", "torq_rotation_create", "torq_rotation_destroy", "torq_rotation_d",
     "torq_rotation_G", "torq_rotate_quantize", "torq_rotate", "torq_quantize_f32", "mxfp4_gemm",
-    "torq_linear_workspace_bytes", "torq_linear", "torq_block_gram_workspace_bytes", "torq_block_gram",
+    "torq_linear_workspace_bytes", "torq_linear", "mxfp4_gemm_workspace_bytes", "mxfp4_gemm_ws", "mxfp4_gemm_plan",
+    "torq_linear_workspace_bytes_n", "torq_block_gram_workspace_bytes", "torq_block_gram",
     "torq_equalize_inter", "torq_code_histogram_workspace_bytes", "torq_code_histogram", "torq_intra_pair_scores",
     "torq_intra_best_angle", "torq_calibrate_intra", "torq_diag_mfma_burn",
 ]
@@ -59,6 +60,14 @@ def lib():
         L.torq_quantize_f32.argtypes = [vp, i64, i32, vp, vp, vp]
         L.mxfp4_gemm.restype = i32
         L.mxfp4_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp]
+        L.mxfp4_gemm_workspace_bytes.restype = sz
+        L.mxfp4_gemm_workspace_bytes.argtypes = [i64, i64, i32]
+        L.mxfp4_gemm_plan.restype = i32
+        L.mxfp4_gemm_plan.argtypes = [i64, i64, i32, sz] + [C.POINTER(i32)] * 4
+        L.mxfp4_gemm_ws.restype = i32
+        L.mxfp4_gemm_ws.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp, sz, vp]
+        L.torq_linear_workspace_bytes_n.restype = sz
+        L.torq_linear_workspace_bytes_n.argtypes = [i64, i64, i32]
         L.torq_linear_workspace_bytes.restype = sz
         L.torq_linear_workspace_bytes.argtypes = [i64, i32]
         L.torq_linear.restype = i32
@@ -176,17 +185,49 @@ def mxfp4_gemm(A_q, A_s, W_q, W_s, out=None, stream=None):
     return out
 
 
+def mxfp4_gemm_workspace_bytes(M: int, N: int, d: int) -> int:
+    return int(lib().mxfp4_gemm_workspace_bytes(M, N, d))
+
+
+def mxfp4_gemm_plan(M: int, N: int, d: int, workspace_bytes: int = 0):
+    """Returns (weight_streaming, tile_m, tile_n, k_pieces) for a product of that shape."""
+    v = [C.c_int(0) for _ in range(4)]
+    _check(lib().mxfp4_gemm_plan(M, N, d, workspace_bytes, *(C.byref(x) for x in v)), "mxfp4_gemm_plan")
+    return bool(v[0].value), v[1].value, v[2].value, v[3].value
+
+
+def mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=None, workspace=None, stream=None):
+    """mxfp4_gemm with scratch memory for cutting the k range (allocated here if not given)."""
+    M, half = A_q.shape
+    N = W_q.shape[0]
+    d = half * 2
+    assert W_q.shape == (N, half) and A_s.shape == (M, d // 32) and W_s.shape == (N, d // 32)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=A_q.device)
+    if workspace is None:
+        workspace = torch.empty((max(mxfp4_gemm_workspace_bytes(M, N, d), 16),), dtype=torch.uint8, device=A_q.device)
+    _check(lib().mxfp4_gemm_ws(_dev(A_q, torch.uint8, "A_q"), _dev(A_s, torch.uint8, "A_s"),
+                               _dev(W_q, torch.uint8, "W_q"), _dev(W_s, torch.uint8, "W_s"),
+                               _dev(out, torch.bfloat16, "out"), M, N, d, _dev(workspace, torch.uint8, "workspace"),
+                               workspace.numel(), _stream(stream)), "mxfp4_gemm_ws")
+    return out
+
+
 def torq_linear_workspace_bytes(M: int, d: int) -> int:
     return int(lib().torq_linear_workspace_bytes(M, d))
+
+
+def torq_linear_workspace_bytes_n(M: int, N: int, d: int) -> int:
+    return int(lib().torq_linear_workspace_bytes_n(M, N, d))
 
 
 def torq_linear(rot: Rotation, x_bf16, W_q, W_s, out=None, workspace=None, stream=None):
     M, d = x_bf16.shape
     N = W_q.shape[0]
     assert d == rot.d and W_q.shape == (N, d // 2) and W_s.shape == (N, d // 32)
-    need = torq_linear_workspace_bytes(M, d)
     if workspace is None:
-        workspace = torch.empty((max(need, 1),), dtype=torch.uint8, device=x_bf16.device)
+        workspace = torch.empty((max(torq_linear_workspace_bytes_n(M, N, d), 1),), dtype=torch.uint8,
+                                device=x_bf16.device)
     if out is None:
         out = torch.empty((M, N), dtype=torch.bfloat16, device=x_bf16.device)
     _check(lib().torq_linear(rot.handle, _dev(x_bf16, torch.bfloat16, "x"), _dev(W_q, torch.uint8, "W_q"),

@@ -193,7 +193,33 @@ int mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const
   if (!A_q || !A_s || !W_q || !W_s || !out_bf16) return TORQ_EINVAL;
   if (misaligned(A_q) || misaligned(W_q) || misaligned(out_bf16)) return TORQ_EALIGN;
   if ((reinterpret_cast<uintptr_t>(A_s) & 3u) || (reinterpret_cast<uintptr_t>(W_s) & 3u)) return TORQ_EALIGN;
-  hipError_t e = torq::launch_mxfp4_gemm(A_q, A_s, W_q, W_s, out_bf16, M, N, d, (hipStream_t)stream);
+  hipError_t e = torq::launch_mxfp4_gemm(A_q, A_s, W_q, W_s, out_bf16, M, N, d, nullptr, 0, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+size_t mxfp4_gemm_workspace_bytes(int64_t M, int64_t N, int d) {
+  if (M <= 0 || N <= 0 || d <= 0 || d % 128 != 0) return 0;
+  return torq::mxfp4_gemm_workspace_bytes(M, N, d);
+}
+
+int mxfp4_gemm_plan(int64_t M, int64_t N, int d, size_t workspace_bytes, int *weight_streaming, int *tile_m,
+                    int *tile_n, int *k_pieces) {
+  if (M <= 0 || N <= 0 || d <= 0 || d % 128 != 0) return TORQ_EINVAL;
+  if (!weight_streaming || !tile_m || !tile_n || !k_pieces) return TORQ_EINVAL;
+  torq::mxfp4_gemm_plan(M, N, d, workspace_bytes, weight_streaming, tile_m, tile_n, k_pieces);
+  return TORQ_OK;
+}
+
+int mxfp4_gemm_ws(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                  void *out_bf16, int64_t M, int64_t N, int d, void *workspace, size_t workspace_bytes,
+                  void *stream) {
+  if (M < 0 || N < 0 || d <= 0 || d % 128 != 0) return TORQ_EINVAL;
+  if (M == 0 || N == 0) return TORQ_OK;
+  if (!A_q || !A_s || !W_q || !W_s || !out_bf16) return TORQ_EINVAL;
+  if (misaligned(A_q) || misaligned(W_q) || misaligned(out_bf16) || misaligned(workspace)) return TORQ_EALIGN;
+  if ((reinterpret_cast<uintptr_t>(A_s) & 3u) || (reinterpret_cast<uintptr_t>(W_s) & 3u)) return TORQ_EALIGN;
+  hipError_t e = torq::launch_mxfp4_gemm(A_q, A_s, W_q, W_s, out_bf16, M, N, d, workspace,
+                                         workspace ? workspace_bytes : 0, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 
@@ -218,8 +244,17 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q
   uint8_t *scales = codes + (((size_t)M * (size_t)(r->d / 2) + 255) & ~(size_t)255);
   hipError_t e = torq::launch_rotate(r, x_bf16, M, codes, scales, nullptr, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
-  e = torq::launch_mxfp4_gemm(codes, scales, W_q, W_s, out_bf16, M, N, r->d, (hipStream_t)stream);
+  // whatever the caller gave beyond the packed activations serves the GEMM's split-k pieces
+  const size_t used = torq_linear_workspace_bytes(M, r->d);
+  e = torq::launch_mxfp4_gemm(codes, scales, W_q, W_s, out_bf16, M, N, r->d, static_cast<char *>(workspace) + used,
+                              workspace_bytes - used, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+size_t torq_linear_workspace_bytes_n(int64_t M, int64_t N, int d) {
+  const size_t base = torq_linear_workspace_bytes(M, d);
+  if (base == 0 || N <= 0 || d % 128 != 0) return base;
+  return base + torq::mxfp4_gemm_workspace_bytes(M, N, d);
 }
 
 size_t torq_block_gram_workspace_bytes(int G) {

@@ -40,12 +40,16 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint3
   return __builtin_amdgcn_make_buffer_rsrc(const_cast<void *>(p), 0, (int)bytes, 0x00020000);
 }
 
-template <int WM, int WN, bool FULLK>
+// SPLIT: blockIdx.y = which of gridDim.y equal pieces of the k range this workgroup multiplies
+// (each a whole, even number of iterations); the tile's fp32 sums go to partial[blockIdx.y][M][N]
+// and mxfp4_gemm_splitk_reduce_kernel adds the pieces.  Needs FULLK.
+template <int WM, int WN, bool FULLK, bool SPLIT>
 __global__ void __launch_bounds__(256)
 mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A_s,
                   const uint8_t *__restrict__ W_q, const uint8_t *__restrict__ W_s,
-                  uint16_t *__restrict__ out, int64_t M, int64_t N, int d,
+                  uint16_t *__restrict__ out, float *__restrict__ partial, int64_t M, int64_t N, int d,
                   int tiles_m, int tiles_n) {
+  static_assert(FULLK || !SPLIT, "split-k needs whole iterations");
   constexpr int BM = 64 * WM, BN = 64 * WN;
   constexpr int A_CH = BM / 32, W_CH = BN / 32;          // 16-byte code chunks per thread per iteration
   constexpr int ROWS = (BM + BN + 255) / 256 * 256;      // scale rows staged: padded so that every thread
@@ -77,7 +81,8 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
   const int row_bytes = d / 2, srow_bytes = d / 32;
   const int KT = (d + 255) / 256;
   // Iterations past the end (the pipeline always loads two ahead) wrap around to a valid k.
-  const int kt0 = 0;
+  const int kt_count = SPLIT ? KT / (int)gridDim.y : ((KT + 1) & ~1);   // even; odd KT only without FULLK
+  const int kt0 = SPLIT ? (int)blockIdx.y * kt_count : 0;
 #define PHYS_KT(KT_) (FULLK ? (((KT_) + kt0) % KT) : (KT_))
 
   // ---- global side: buffer resources over this tile's rows; reads past them return 0
@@ -265,9 +270,8 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
     _Pragma("unroll") for (int n_ = 0; n_ < WM * WN / 2; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 2) SGB(SG_VMEM_RD, 2) } \
     __builtin_amdgcn_sched_barrier(0);                                                            \
   }
-  // KTE = KT rounded up to even; an odd KT (only without FULLK) gets one all-zero iteration
-  const int KTE = (KT + 1) & ~1;
-  for (int kt = 0; kt < KTE; kt += 2) {
+  // an odd KT (only without FULLK) gets one all-zero iteration
+  for (int kt = 0; kt < kt_count; kt += 2) {
     ITER(0, kt);
     ITER(1, kt + 1);
   }
@@ -279,7 +283,23 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
   // line of the output arrive in 16 separate partial writes, so the wave first transposes its
   // piece through LDS (free after the last barrier of the k loop; each wave uses a private
   // region) and then stores 16 bytes per lane with 8 adjacent lanes covering one full line.
-  {
+  if (SPLIT) {
+    // fp32 sums of this k piece: 16 bytes per lane and register quad, straight from the accumulators
+    float *const dstp = partial + (size_t)blockIdx.y * (size_t)M * (size_t)N;
+#pragma unroll
+    for (int i = 0; i < WM; ++i) {
+      const int64_t m = m0 + (wy * WM + i) * 32 + lrow;
+#pragma unroll
+      for (int j = 0; j < WN; ++j)
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr) {
+          const int64_t n = n0 + (wx * WN + j) * 32 + 8 * rr + 4 * g;
+          if (m < M && n + 4 <= N)
+            *reinterpret_cast<f32x4 *>(dstp + m * N + n) =
+                f32x4{acc[j][i][4 * rr], acc[j][i][4 * rr + 1], acc[j][i][4 * rr + 2], acc[j][i][4 * rr + 3]};
+        }
+    }
+  } else {
     constexpr int ROW_E = 64 * WN;               // bytes of one output row of this wave's piece
     constexpr int PITCH_E = ROW_E + 16;
     constexpr int CH_ROW = ROW_E / 16;           // 16-byte chunks per row
@@ -329,15 +349,35 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
 #undef MFMA_HALF
 }
 
-template <int WM, int WN, bool FULLK>
+// out[m][n] = bf16(sum over the k pieces, in order, of partial[s][m][n]); 8 outputs per thread
+__global__ void __launch_bounds__(256)
+mxfp4_gemm_splitk_reduce_kernel(const float *__restrict__ partial, int splits, int64_t MN, uint16_t *__restrict__ out) {
+  const int64_t e0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
+  if (e0 >= MN) return;                          // MN is a multiple of 8
+  f32x4 lo = *reinterpret_cast<const f32x4 *>(partial + e0), hi = *reinterpret_cast<const f32x4 *>(partial + e0 + 4);
+  for (int s = 1; s < splits; ++s) {
+    lo += *reinterpret_cast<const f32x4 *>(partial + (size_t)s * MN + e0);
+    hi += *reinterpret_cast<const f32x4 *>(partial + (size_t)s * MN + e0 + 4);
+  }
+  bf16x4 a, b;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    a[e] = (__bf16)lo[e];
+    b[e] = (__bf16)hi[e];
+  }
+  typedef __attribute__((__vector_size__(2 * sizeof(uint64_t)))) uint64_t u64x2;
+  *reinterpret_cast<u64x2 *>(out + e0) = u64x2{__builtin_bit_cast(uint64_t, a), __builtin_bit_cast(uint64_t, b)};
+}
+
+template <int WM, int WN, bool FULLK, bool SPLIT>
 static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
-                              const uint8_t *W_s, void *out, int64_t M, int64_t N, int d,
-                              hipStream_t stream) {
+                              const uint8_t *W_s, void *out, float *partial, int splits, int64_t M, int64_t N,
+                              int d, hipStream_t stream) {
   constexpr int BM = 64 * WM, BN = 64 * WN;
   const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   if (tiles_m * tiles_n > 0x7FFFFFFF) return hipErrorInvalidValue;
   const size_t lds_bytes = 2 * (size_t)(BM + BN) * 128 + 2 * (size_t)((BM + BN + 255) / 256 * 256) * 16;
-  auto kern = mxfp4_gemm_kernel<WM, WN, FULLK>;
+  auto kern = mxfp4_gemm_kernel<WM, WN, FULLK, SPLIT>;
   if (lds_bytes > 64 * 1024) {
     // raise the dynamic LDS limit once per process and kernel variant (the call is slow)
     static bool raised = false;
@@ -348,8 +388,13 @@ static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint
       raised = true;
     }
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n)), dim3(256), lds_bytes, stream, A_q, A_s, W_q,
-                     W_s, reinterpret_cast<uint16_t *>(out), M, N, d, (int)tiles_m, (int)tiles_n);
+  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n), SPLIT ? splits : 1), dim3(256), lds_bytes, stream, A_q,
+                     A_s, W_q, W_s, reinterpret_cast<uint16_t *>(out), partial, M, N, d, (int)tiles_m, (int)tiles_n);
+  hipError_t e = hipGetLastError();
+  if (!SPLIT || e != hipSuccess) return e;
+  const int64_t MN = M * N;
+  hipLaunchKernelGGL(mxfp4_gemm_splitk_reduce_kernel, dim3((unsigned)((MN / 8 + 255) / 256)), dim3(256), 0, stream,
+                     partial, splits, MN, reinterpret_cast<uint16_t *>(out));
   return hipGetLastError();
 }
 
@@ -363,29 +408,106 @@ static int choose_tile(int64_t M, int64_t N) {
   if (c0 <= c1 && c0 <= c2) return 0;
   return c1 <= c2 ? 1 : 2;
 }
-#ifndef TILE_CFG
-#define TILE_CFG(M_, N_) choose_tile(M_, N_)
+// How a product is run: the weight-streaming kernel (mxfp4_gemm_skinny.hip), or the tiled kernel
+// with tile shape `cfg` and its k range cut into `splits` pieces (1 = not cut).
+struct GemmPlan {
+  bool skinny;
+  int cfg;
+  int splits;
+};
+
+// Below one full round of tiles the tiled kernel is bound by how fast one workgroup can stream
+// its operand rows (about 0.9 us per 256-element iteration of the 128 x 128 tile, 1.1 of the
+// 256 x 128 one, with one workgroup per CU; proportionally slower once CUs are shared), so a long
+// reduction over few tiles is cut along k into pieces that run side by side.  A piece is a whole
+// even number of iterations; the pieces' fp32 tiles go through the caller's workspace and cost a
+// second launch plus their own traffic.  With at most 64 activation rows the weight-streaming
+// kernel competes: its time grows with the weight bytes and with the number of 16-row activation
+// tiles.  All figures in microseconds, fitted to measurements of 4096 ... 28672-wide layers;
+// the choice only has to land near the best, not predict it.
+static GemmPlan choose_plan(int64_t M, int64_t N, int d, bool allow_split) {
+  GemmPlan plan{false, choose_tile(M, N), 1};
+  static const int BM[3] = {256, 256, 128}, BN[3] = {256, 128, 128};
+  static const double T_ITER[3] = {1.5, 1.1, 0.9};
+  auto tiles_of = [&](int cfg) { return (double)(((M + BM[cfg] - 1) / BM[cfg]) * ((N + BN[cfg] - 1) / BN[cfg])); };
+  const bool can_skinny = mxfp4_gemm_skinny_fits(M, d);
+  if (tiles_of(plan.cfg) >= 512.0 && !can_skinny) return plan;      // two full rounds: nothing to gain
+
+  const double KT = (d + 255) / 256;
+  auto tiled_us = [&](int cfg, int s) {
+    const double wgs = tiles_of(cfg) * s, share = wgs <= 256.0 ? 1.0 : wgs / 256.0;
+    const double pieces = s > 1 ? 4.0 + (double)s * (double)M * (double)N * 8.0 / 5e6 : 0.0;
+    const double t = 2.0 + T_ITER[cfg] * (KT / s) * share + pieces;
+    return t < 8.0 ? 8.0 : t;                      // launch, prologue and epilogue
+  };
+  double best = tiled_us(plan.cfg, 1);
+  const bool may_split = allow_split && d % 512 == 0 && N % 8 == 0;
+  for (int cfg = 2; cfg >= 0; --cfg) {
+    if (tiles_of(cfg) >= 512.0 && cfg != plan.cfg) continue;
+    const int pairs = d / 512;
+    for (int s = 1; s <= 16 && s <= (may_split && cfg != 0 ? pairs : 1); ++s) {   // the largest tile is never cut
+      if (s > 1 && pairs % s != 0) continue;
+      // a cut has to promise a tenth: small products run from the caches, faster than the model
+      const double t = tiled_us(cfg, s) / (s > 1 ? 0.9 : 1.0);
+      if (t < best) {
+        best = t;
+        plan.cfg = cfg;
+        plan.splits = s;
+      }
+    }
+  }
+  if (can_skinny) {
+    static const double per_mb[4] = {0.21, 0.31, 0.45, 0.58};      // by 16-row activation tiles
+    const double w_mb = (double)N * (double)d * 0.53125 / 1e6;
+    const double t = 4.0 + w_mb * per_mb[(M - 1) / 16];
+    if ((t < 6.5 ? 6.5 : t) <= best) plan = GemmPlan{true, 0, 1};
+  }
+  return plan;
+}
+#ifndef GEMM_PLAN
+#define GEMM_PLAN(M_, N_, d_, allow_) choose_plan(M_, N_, d_, allow_)
 #endif
+
+void mxfp4_gemm_plan(int64_t M, int64_t N, int d, size_t workspace_bytes, int *skinny, int *tile_m, int *tile_n,
+                     int *splits) {
+  GemmPlan plan = GEMM_PLAN(M, N, d, d % 512 == 0);
+  if (plan.splits > 1 && workspace_bytes < (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(float))
+    plan = GEMM_PLAN(M, N, d, false);
+  *skinny = plan.skinny;
+  *tile_m = plan.skinny ? 0 : (plan.cfg == 2 ? 128 : 256);
+  *tile_n = plan.skinny ? 16 : (plan.cfg == 0 ? 256 : 128);
+  *splits = plan.splits;
+}
+
+size_t mxfp4_gemm_workspace_bytes(int64_t M, int64_t N, int d) {
+  const GemmPlan plan = GEMM_PLAN(M, N, d, true);
+  return plan.splits > 1 ? (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
 
 hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                              const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, int d,
-                             hipStream_t stream) {
+                             void *workspace, size_t workspace_bytes, hipStream_t stream) {
   // a tile's rows must be addressable with 32-bit offsets: 256 rows of d/2 bytes
   if ((int64_t)d * 128 >= 0x7FFFFFFF) return hipErrorInvalidValue;
-  // a handful of rows: stream the weights (mxfp4_gemm_skinny.hip)
-  if (mxfp4_gemm_skinny_fits(M, d)) return launch_mxfp4_gemm_skinny(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
   // The fast k loop needs whole 512-element pieces per row and 16-byte aligned scale rows.
   const bool fullk = (d % 512 == 0) && ((reinterpret_cast<uintptr_t>(A_s) & 15u) == 0) &&
                      ((reinterpret_cast<uintptr_t>(W_s) & 15u) == 0);
-  const int cfg = TILE_CFG(M, N);
-  if (cfg == 0)
-    return fullk ? launch_tile<4, 4, true>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream)
-                 : launch_tile<4, 4, false>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
-  if (cfg == 1)
-    return fullk ? launch_tile<4, 2, true>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream)
-                 : launch_tile<4, 2, false>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
-  return fullk ? launch_tile<2, 2, true>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream)
-               : launch_tile<2, 2, false>(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
+  // cut along k only with a workspace that holds the pieces (16-byte aligned fp32 rows)
+  const bool ws_ok = fullk && workspace && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0;
+  GemmPlan plan = GEMM_PLAN(M, N, d, ws_ok);
+  if (plan.splits > 1 && workspace_bytes < (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(float))
+    plan = GEMM_PLAN(M, N, d, false);
+  if (plan.skinny) return launch_mxfp4_gemm_skinny(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
+  const int splits = plan.splits;
+  float *partial = static_cast<float *>(workspace);
+#define TORQ_GEMM_LAUNCH(WM_, WN_)                                                                             \
+  return splits > 1 ? launch_tile<WM_, WN_, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream) \
+         : fullk    ? launch_tile<WM_, WN_, true, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream)     \
+                    : launch_tile<WM_, WN_, false, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream);
+  if (plan.cfg == 0) { TORQ_GEMM_LAUNCH(4, 4) }
+  if (plan.cfg == 1) { TORQ_GEMM_LAUNCH(4, 2) }
+  TORQ_GEMM_LAUNCH(2, 2)
+#undef TORQ_GEMM_LAUNCH
 }
 
 }  // namespace torq

@@ -30,9 +30,15 @@ hipError_t launch_quantize_f32(const float *z, int64_t nblk, uint8_t *codes, uin
 hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M,
                          uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream);
 
+// workspace: optional device scratch of mxfp4_gemm_workspace_bytes(M, N, d) bytes; with it, shapes
+// with few output tiles and a long reduction are cut along k (fp32 pieces added in a fixed order).
+size_t mxfp4_gemm_workspace_bytes(int64_t M, int64_t N, int d);
+// what launch_mxfp4_gemm would do with a workspace of that size (operands assumed 16-byte aligned)
+void mxfp4_gemm_plan(int64_t M, int64_t N, int d, size_t workspace_bytes, int *skinny, int *tile_m, int *tile_n,
+                     int *splits);
 hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                              const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, int d,
-                             hipStream_t stream);
+                             void *workspace, size_t workspace_bytes, hipStream_t stream);
 
 // The same product for 1 <= M <= 64 (weight-streaming layout); called by launch_mxfp4_gemm when
 // mxfp4_gemm_skinny_fits (the scale rows it stages fit the LDS).

@@ -95,3 +95,27 @@ def test_rotation_create_without_device_reports_it():
     Ra = np.eye(32, dtype=np.float32)
     st = L.torq_rotation_create(C.byref(h), 512, 16, Ri.ctypes.data_as(C.c_void_p), Ra.ctypes.data_as(C.c_void_p))
     assert st == binding.TORQ_ENODEVICE and not h.value
+
+
+def test_gemm_workspace_entry_points_validate_and_plan_on_the_host():
+    L = binding.lib()
+    good, odd = C.c_void_p(0x1000), C.c_void_p(0x1004)
+    assert L.mxfp4_gemm_ws(good, good, good, good, good, 4, 4, 96, good, 1 << 20, None) == binding.TORQ_EINVAL
+    assert L.mxfp4_gemm_ws(good, good, good, good, None, 4, 4, 128, good, 1 << 20, None) == binding.TORQ_EINVAL
+    assert L.mxfp4_gemm_ws(good, good, good, good, good, 4, 4, 128, odd, 1 << 20, None) == binding.TORQ_EALIGN
+    assert L.mxfp4_gemm_ws(good, good, good, good, good, 0, 4, 128, None, 0, None) == binding.TORQ_OK
+    # the plan and the workspace size are pure host functions of the shape
+    assert binding.mxfp4_gemm_workspace_bytes(8192, 28672, 8192) == 0            # plenty of tiles: never cut
+    assert binding.mxfp4_gemm_plan(8192, 28672, 8192) == (False, 256, 256, 1)
+    assert binding.mxfp4_gemm_plan(1, 14336, 4096)[0] is True                    # a decode row streams the weights
+    need = binding.mxfp4_gemm_workspace_bytes(128, 8192, 28672)
+    streaming, tm, tn, pieces = binding.mxfp4_gemm_plan(128, 8192, 28672, need)
+    assert not streaming and pieces > 1 and need == pieces * 128 * 8192 * 4
+    assert (28672 // 512) % pieces == 0                                          # whole, even runs of iterations
+    assert binding.mxfp4_gemm_plan(128, 8192, 28672, need - 1)[3] == 1           # too small: not cut
+    assert binding.mxfp4_gemm_workspace_bytes(96, 512, 4100) == 0                # invalid d: nothing to size
+    assert binding.mxfp4_gemm_workspace_bytes(96, 516, 4096) == 0                # N % 8 != 0: fp32 rows not 16-byte aligned
+    assert binding.torq_linear_workspace_bytes_n(128, 8192, 28672) == binding.torq_linear_workspace_bytes(128, 28672) + need
+    v = [C.c_int() for _ in range(4)]
+    assert L.mxfp4_gemm_plan(0, 4, 128, 0, *(C.byref(x) for x in v)) == binding.TORQ_EINVAL
+    assert L.mxfp4_gemm_plan(4, 4, 128, 0, None, C.byref(v[1]), C.byref(v[2]), C.byref(v[3])) == binding.TORQ_EINVAL

@@ -278,6 +278,58 @@ def test_gemm_few_rows_random_codes(tq, oracle, M, N, d):
     assert torch.all(out[M] == 7.0)
 
 
+# Few output tiles against a long reduction: with a workspace the k range is cut into pieces.
+# (M, N, d, expected pieces > 1); N = 1032, 264 exercise ragged tiles, 131072 the longest rows.
+GEMM_SPLIT_K = [(96, 512, 4096), (100, 264, 5120), (300, 1000, 14336), (40, 4096, 14336), (130, 1032, 8192),
+                (4, 40, 131072), (257, 2048, 7168)]
+
+
+@pytest.mark.parametrize("M,N,d", GEMM_SPLIT_K)
+def test_gemm_with_workspace_cut_along_k(tq, oracle, M, N, d):
+    rng = np.random.default_rng(M * 13 + N + d)
+    A_q = rng.integers(0, 256, size=(M, d // 2), dtype=np.uint8)
+    W_q = rng.integers(0, 256, size=(N, d // 2), dtype=np.uint8)
+    A_s = rng.integers(118, 136, size=(M, d // 32), dtype=np.uint8)
+    W_s = rng.integers(110, 126, size=(N, d // 32), dtype=np.uint8)
+    want = oracle.gemm(A_q, A_s, W_q, W_s)
+    ops = [torch.from_numpy(a).to(DEV) for a in (A_q, A_s, W_q, W_s)]
+    need = tq.mxfp4_gemm_workspace_bytes(M, N, d)
+    assert need > 0 and tq.mxfp4_gemm_plan(M, N, d, need)[3] > 1 and tq.mxfp4_gemm_plan(M, N, d, 0)[3] == 1
+    ws = torch.full((need + 256,), 0xA5, dtype=torch.uint8, device=DEV)      # stale contents must not matter
+    out = torch.full((M + 1, N), 7.0, dtype=torch.bfloat16, device=DEV)
+    tq.mxfp4_gemm_ws(*ops, out=out[:M], workspace=ws[:need])
+    torch.cuda.synchronize()
+    got = _bits(out[:M])
+    assert _rel_fro(got, want) <= 1e-3
+    gw = (got.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    ww = (want.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    assert np.all(np.abs(gw - ww) <= np.abs(ww) * 2.0 ** -7 + 1e-3 * np.sqrt(np.mean(ww ** 2)))
+    assert torch.all(out[M] == 7.0)
+    assert torch.all(ws[need:] == 0xA5)                                      # nothing written past the stated size
+    # the pieces are added in a fixed order: a second call gives the same bits
+    again = tq.mxfp4_gemm_ws(*ops, workspace=ws[:need])
+    assert torch.equal(again, out[:M])
+    # too small a workspace: exactly mxfp4_gemm
+    small = tq.mxfp4_gemm_ws(*ops, workspace=ws[: need - 16])
+    assert torch.equal(small, tq.mxfp4_gemm(*ops))
+    assert _rel_fro(_bits(small), want) <= 1e-3
+
+
+def test_linear_uses_the_rest_of_its_workspace_for_the_gemm(tq):
+    M, d, N, G = 96, 4096, 512, 128
+    x = synth.activations(M, d, nu=3.0, outliers=20, outlier_scale=50.0, seed=41).to(DEV)
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    W_q, W_s = tq.torq_rotate_quantize(rot, synth.weights(N, d, seed=42).to(DEV))
+    A_q, A_s = tq.torq_rotate_quantize(rot, x)
+    base, full = tq.torq_linear_workspace_bytes(M, d), tq.torq_linear_workspace_bytes_n(M, N, d)
+    assert full == base + tq.mxfp4_gemm_workspace_bytes(M, N, d) > base
+    ws = torch.empty((full,), dtype=torch.uint8, device=DEV)
+    assert torch.equal(tq.torq_linear(rot, x, W_q, W_s, workspace=ws), tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s))
+    assert torch.equal(tq.torq_linear(rot, x, W_q, W_s, workspace=ws[:base]), tq.mxfp4_gemm(A_q, A_s, W_q, W_s))
+    rot.close()
+
+
 def test_gemm_tiny_config_from_oracle_quantised_operands(tq, oracle):
     # configuration 1: X [64, 4096] heavy-tailed, W [1024, 4096], both rotated + quantised by the oracle
     x = synth.workload_activations("tiny")
