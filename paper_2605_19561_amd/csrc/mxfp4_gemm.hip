@@ -408,6 +408,7 @@ static int choose_tile(int64_t M, int64_t N) {
   if (c0 <= c1 && c0 <= c2) return 0;
   return c1 <= c2 ? 1 : 2;
 }
+
 // How a product is run: the weight-streaming kernel (mxfp4_gemm_skinny.hip), or the tiled kernel
 // with tile shape `cfg` and its k range cut into `splits` pieces (1 = not cut).
 struct GemmPlan {

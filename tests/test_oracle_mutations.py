@@ -95,15 +95,35 @@ def _run_pins(lib):
                            *PIN_FILES], cwd=ROOT, env=env, capture_output=True, text=True, timeout=600)
 
 
-def test_unmodified_oracle_passes_under_the_same_harness(tmp_path):
-    r = _run_pins(_build(tmp_path, "clean", open(SRC).read()))
+@pytest.fixture(scope="module")
+def outcomes(tmp_path_factory):
+    """Build every mutant (and the unmodified source) and run the pins against each, four child
+    processes at a time: the runs are independent and mostly wait on the interpreter start-up."""
+    from concurrent.futures import ThreadPoolExecutor
+    tmp = tmp_path_factory.mktemp("mutants")
+    text = open(SRC).read()
+    jobs = [("clean", text)]
+    for name, old, new in MUTATIONS:
+        jobs.append((name, text.replace(old, new) if text.count(old) >= 1 else None))
+
+    def one(job):
+        name, src = job
+        if src is None:
+            return name, None
+        return name, _run_pins(_build(tmp, name, src))
+
+    with ThreadPoolExecutor(max_workers=4) as pool:
+        return dict(pool.map(one, jobs))
+
+
+def test_unmodified_oracle_passes_under_the_same_harness(outcomes):
+    r = outcomes["clean"]
     assert r.returncode == 0, r.stdout[-2000:]
 
 
 @pytest.mark.parametrize("name,old,new", MUTATIONS, ids=[m[0] for m in MUTATIONS])
-def test_a_planted_mistake_fails_a_pin(tmp_path, name, old, new):
-    text = open(SRC).read()
-    assert text.count(old) >= 1, f"mutation target not found in torq_oracle.c: {old!r}"
-    r = _run_pins(_build(tmp_path, name, text.replace(old, new)))
+def test_a_planted_mistake_fails_a_pin(outcomes, name, old, new):
+    r = outcomes[name]
+    assert r is not None, f"mutation target not found in torq_oracle.c: {old!r}"
     assert r.returncode == 1, f"no pin noticed '{name}' (pytest exit {r.returncode}):\n{r.stdout[-1500:]}"
     assert " failed" in r.stdout
