@@ -43,7 +43,7 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint3
 // SPLIT: blockIdx.y = which of gridDim.y equal pieces of the k range this workgroup multiplies
 // (each a whole, even number of iterations); the tile's fp32 sums go to partial[blockIdx.y][M][N]
 // and mxfp4_gemm_splitk_reduce_kernel adds the pieces.  Needs FULLK.
-template <int WM, int WN, bool FULLK, bool SPLIT>
+template <int WM, int WN, bool FULLK, bool SPLIT, bool DEEP = false>
 __global__ void __launch_bounds__(256)
 mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A_s,
                   const uint8_t *__restrict__ W_q, const uint8_t *__restrict__ W_s,
@@ -95,28 +95,36 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
   const int c_voff = c_row * row_bytes + c_chunk * 16;   // + 32 i rows + 128 kt via the scalar offset
   const int c_lds = c_row * 128 + ((c_chunk ^ ((c_row >> 1) & 7)) * 16);   // + 32 i * 128 (same swizzle)
 
-  u32x4 a_regs[A_CH], w_regs[W_CH], s_regs[S_CH];
+  // DEEP: two sets of staging registers, filled alternately, so that the codes of an iteration
+  // are requested three iterations before they are multiplied instead of two (for the shapes
+  // whose pace is set by the latency of the weight stream; costs A_CH + W_CH more registers)
+  constexpr int NSET = DEEP ? 2 : 1;
+  constexpr int AHEAD = DEEP ? 3 : 2;
+  u32x4 a_regs[NSET][A_CH], w_regs[NSET][W_CH], s_regs[S_CH];
 
-#define G_LOAD_Q(KT_, Q_)                       /* quarter Q_ (0..3) of an iteration's chunks */ \
+  // The codes of iteration k pass through register set k % NSET and LDS stage k % 2.
+#define G_LOAD_Q(SET_, KT_, Q_)                 /* quarter Q_ (0..3) of an iteration's chunks */ \
   {                                                                                               \
     const int kt_ = PHYS_KT(KT_);                                                                 \
+    constexpr int set_ = DEEP ? (SET_) : 0;                                                       \
     const bool ok_ = FULLK || (kt_ * 128 + c_chunk * 16 < row_bytes);                             \
     _Pragma("unroll") for (int i = (Q_) * A_CH / 4; i < ((Q_) + 1) * A_CH / 4; ++i) {             \
-      a_regs[i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, c_voff, i * 32 * row_bytes + kt_ * 128, 0); \
-      if (!FULLK && !ok_) a_regs[i] = u32x4{0, 0, 0, 0};                                          \
+      a_regs[set_][i] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, c_voff, i * 32 * row_bytes + kt_ * 128, 0); \
+      if (!FULLK && !ok_) a_regs[set_][i] = u32x4{0, 0, 0, 0};                                    \
     }                                                                                             \
     _Pragma("unroll") for (int i = (Q_) * W_CH / 4; i < ((Q_) + 1) * W_CH / 4; ++i) {             \
-      w_regs[i] = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, c_voff, i * 32 * row_bytes + kt_ * 128, 0); \
-      if (!FULLK && !ok_) w_regs[i] = u32x4{0, 0, 0, 0};                                          \
+      w_regs[set_][i] = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, c_voff, i * 32 * row_bytes + kt_ * 128, 0); \
+      if (!FULLK && !ok_) w_regs[set_][i] = u32x4{0, 0, 0, 0};                                    \
     }                                                                                             \
   }
-#define G_LOAD(KT_) { G_LOAD_Q(KT_, 0) G_LOAD_Q(KT_, 1) G_LOAD_Q(KT_, 2) G_LOAD_Q(KT_, 3) }
-#define L_STORE(P_, Q_)                         /* quarter Q_ (0..3) of the stage's chunks */    \
+#define G_LOAD(SET_, KT_) { G_LOAD_Q(SET_, KT_, 0) G_LOAD_Q(SET_, KT_, 1) G_LOAD_Q(SET_, KT_, 2) G_LOAD_Q(SET_, KT_, 3) }
+#define L_STORE(P_, Q_)                         /* quarter Q_ (0..3) of stage P_'s chunks */     \
   {                                                                                               \
+    constexpr int set_ = DEEP ? (P_) : 0;                                                         \
     _Pragma("unroll") for (int i = (Q_) * A_CH / 4; i < ((Q_) + 1) * A_CH / 4; ++i)               \
-        *reinterpret_cast<u32x4 *>(lds + c_lds + (P_) * A_STAGE + i * 32 * 128) = a_regs[i];      \
+        *reinterpret_cast<u32x4 *>(lds + c_lds + (P_) * A_STAGE + i * 32 * 128) = a_regs[set_][i]; \
     _Pragma("unroll") for (int i = (Q_) * W_CH / 4; i < ((Q_) + 1) * W_CH / 4; ++i)               \
-        *reinterpret_cast<u32x4 *>(lds + c_lds + W_BASE + (P_) * W_STAGE + i * 32 * 128) = w_regs[i]; \
+        *reinterpret_cast<u32x4 *>(lds + c_lds + W_BASE + (P_) * W_STAGE + i * 32 * 128) = w_regs[set_][i]; \
   }
   // scales of iterations 2 SC_ and 2 SC_ + 1: 16 bytes per row; staged row id = tid + 256 i
   // (A rows first, then W rows)
@@ -202,14 +210,15 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
       _Pragma("unroll") for (int i = 0; i < WM; ++i) { MFMA_ONE(SET_, PAR_, KS_, j, i) }
 
   // ---- prologue
-  G_LOAD(0);
+  G_LOAD(0, 0);
   S_LOAD(PHYS_KT(0) >> 1);
   L_STORE(0, 0);
   L_STORE(0, 1);
   L_STORE(0, 2);
   L_STORE(0, 3);
   S_STORE(0);
-  G_LOAD(1);
+  G_LOAD(1, 1);
+  if (DEEP) G_LOAD(0, 2);
   __syncthreads();
   SC_LOAD(0, 0);
   F_LOAD(0, 0, 0);
@@ -234,11 +243,11 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
     MFMA_HALF(0, P, 0, 0, WN);                                                                    \
     F_LOAD(0, P, 2);                                                                              \
     L_STORE((P) ^ 1, 0);                                                                          \
-    G_LOAD_Q(kt_i + 2, 0);                                                                        \
+    G_LOAD_Q((P) ^ 1, kt_i + AHEAD, 0);                                                           \
     MFMA_HALF(1, P, 1, 0, WN);                                                                    \
     F_LOAD(1, P, 3);                                                                              \
     L_STORE((P) ^ 1, 1);                                                                          \
-    G_LOAD_Q(kt_i + 2, 1);                                                                        \
+    G_LOAD_Q((P) ^ 1, kt_i + AHEAD, 1);                                                           \
     MFMA_HALF(0, P, 2, 0, WN);                                                                    \
     L_STORE((P) ^ 1, 2);                                                                          \
     L_STORE((P) ^ 1, 3);                                                                          \
@@ -261,8 +270,8 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
     __syncthreads();                                                                              \
     SC_LOAD((P) ^ 1, kt_i + 1);                                                                   \
     F_LOAD(0, (P) ^ 1, 0);                                                                        \
-    G_LOAD_Q(kt_i + 2, 2);                                                                        \
-    G_LOAD_Q(kt_i + 2, 3);                                                                        \
+    G_LOAD_Q((P) ^ 1, kt_i + AHEAD, 2);                                                           \
+    G_LOAD_Q((P) ^ 1, kt_i + AHEAD, 3);                                                           \
     if ((P) == 0) S_LOAD(PHYS_KT(kt_i + 2) >> 1);                                                 \
     MFMA_HALF(1, P, 3, WN / 2, WN);                                                               \
     /* second half of k-step 3: fragment and scale reads of the next iteration first, then      \
@@ -369,7 +378,7 @@ mxfp4_gemm_splitk_reduce_kernel(const float *__restrict__ partial, int splits, i
   *reinterpret_cast<u64x2 *>(out + e0) = u64x2{__builtin_bit_cast(uint64_t, a), __builtin_bit_cast(uint64_t, b)};
 }
 
-template <int WM, int WN, bool FULLK, bool SPLIT>
+template <int WM, int WN, bool FULLK, bool SPLIT, bool DEEP = false>
 static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                               const uint8_t *W_s, void *out, float *partial, int splits, int64_t M, int64_t N,
                               int d, hipStream_t stream) {
@@ -377,7 +386,7 @@ static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint
   const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   if (tiles_m * tiles_n > 0x7FFFFFFF) return hipErrorInvalidValue;
   const size_t lds_bytes = 2 * (size_t)(BM + BN) * 128 + 2 * (size_t)((BM + BN + 255) / 256 * 256) * 16;
-  auto kern = mxfp4_gemm_kernel<WM, WN, FULLK, SPLIT>;
+  auto kern = mxfp4_gemm_kernel<WM, WN, FULLK, SPLIT, DEEP>;
   if (lds_bytes > 64 * 1024) {
     // raise the dynamic LDS limit once per process and kernel variant (the call is slow)
     static bool raised = false;
@@ -415,6 +424,7 @@ struct GemmPlan {
   bool skinny;
   int cfg;
   int splits;
+  bool deep;      // the tiled kernel's deeper load pipeline (128-row-wide tiles, weight-bound shapes)
 };
 
 // Below one full round of tiles the tiled kernel is bound by how fast one workgroup can stream
@@ -427,7 +437,7 @@ struct GemmPlan {
 // tiles.  All figures in microseconds, fitted to measurements of 4096 ... 28672-wide layers;
 // the choice only has to land near the best, not predict it.
 static GemmPlan choose_plan(int64_t M, int64_t N, int d, bool allow_split) {
-  GemmPlan plan{false, choose_tile(M, N), 1};
+  GemmPlan plan{false, choose_tile(M, N), 1, false};
   static const int BM[3] = {256, 256, 128}, BN[3] = {256, 128, 128};
   static const double T_ITER[3] = {1.5, 1.1, 0.9};
   auto tiles_of = [&](int cfg) { return (double)(((M + BM[cfg] - 1) / BM[cfg]) * ((N + BN[cfg] - 1) / BN[cfg])); };
@@ -435,10 +445,13 @@ static GemmPlan choose_plan(int64_t M, int64_t N, int d, bool allow_split) {
   if (tiles_of(plan.cfg) >= 512.0 && !can_skinny) return plan;      // two full rounds: nothing to gain
 
   const double KT = (d + 255) / 256;
+  // the 128 x 128 tile alone on its CU, not cut: the deeper load pipeline gains an eighth
+  auto deep_pays = [&](int cfg, int s) { return cfg == 2 && s == 1 && tiles_of(cfg) <= 256.0; };
   auto tiled_us = [&](int cfg, int s) {
     const double wgs = tiles_of(cfg) * s, share = wgs <= 256.0 ? 1.0 : wgs / 256.0;
+    const double t_iter = deep_pays(cfg, s) ? 0.78 : T_ITER[cfg];
     const double pieces = s > 1 ? 4.0 + (double)s * (double)M * (double)N * 8.0 / 5e6 : 0.0;
-    const double t = 2.0 + T_ITER[cfg] * (KT / s) * share + pieces;
+    const double t = 2.0 + t_iter * (KT / s) * share + pieces;
     return t < 8.0 ? 8.0 : t;                      // launch, prologue and epilogue
   };
   double best = tiled_us(plan.cfg, 1);
@@ -457,11 +470,12 @@ static GemmPlan choose_plan(int64_t M, int64_t N, int d, bool allow_split) {
       }
     }
   }
+  plan.deep = deep_pays(plan.cfg, plan.splits);
   if (can_skinny) {
     static const double per_mb[4] = {0.21, 0.31, 0.45, 0.58};      // by 16-row activation tiles
     const double w_mb = (double)N * (double)d * 0.53125 / 1e6;
     const double t = 4.0 + w_mb * per_mb[(M - 1) / 16];
-    if ((t < 6.5 ? 6.5 : t) <= best) plan = GemmPlan{true, 0, 1};
+    if ((t < 6.5 ? 6.5 : t) <= best) plan = GemmPlan{true, 0, 1, false};
   }
   return plan;
 }
@@ -501,6 +515,8 @@ hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8
   if (plan.skinny) return launch_mxfp4_gemm_skinny(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
   const int splits = plan.splits;
   float *partial = static_cast<float *>(workspace);
+  if (plan.deep && fullk && splits == 1)
+    return launch_tile<2, 2, true, false, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream);
 #define TORQ_GEMM_LAUNCH(WM_, WN_)                                                                             \
   return splits > 1 ? launch_tile<WM_, WN_, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream) \
          : fullk    ? launch_tile<WM_, WN_, true, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream)     \
