@@ -449,7 +449,7 @@ static GemmPlan choose_plan(int64_t M, int64_t N, int d, bool allow_split) {
   auto deep_pays = [&](int cfg, int s) { return cfg == 2 && s == 1 && tiles_of(cfg) <= 256.0; };
   auto tiled_us = [&](int cfg, int s) {
     const double wgs = tiles_of(cfg) * s, share = wgs <= 256.0 ? 1.0 : wgs / 256.0;
-    const double t_iter = deep_pays(cfg, s) ? 0.78 : T_ITER[cfg];
+    const double t_iter = deep_pays(cfg, s) ? 0.85 : T_ITER[cfg];
     const double pieces = s > 1 ? 4.0 + (double)s * (double)M * (double)N * 8.0 / 5e6 : 0.0;
     const double t = 2.0 + t_iter * (KT / s) * share + pieces;
     return t < 8.0 ? 8.0 : t;                      // launch, prologue and epilogue
@@ -475,7 +475,8 @@ static GemmPlan choose_plan(int64_t M, int64_t N, int d, bool allow_split) {
     static const double per_mb[4] = {0.21, 0.31, 0.45, 0.58};      // by 16-row activation tiles
     const double w_mb = (double)N * (double)d * 0.53125 / 1e6;
     const double t = 4.0 + w_mb * per_mb[(M - 1) / 16];
-    if ((t < 6.5 ? 6.5 : t) <= best) plan = GemmPlan{true, 0, 1, false};
+    // near a tie the streaming kernel wins: one launch, no tile padding
+    if (0.95 * (t < 6.5 ? 6.5 : t) <= best) plan = GemmPlan{true, 0, 1, false};
   }
   return plan;
 }

@@ -232,7 +232,8 @@ def _bits(t):
     return _np(t.view(torch.int16)).view(np.uint16)
 
 
-GEMM_RANDOM = [(1, 128, 128), (16, 256, 384), (100, 200, 512), (64, 1024, 4096), (300, 520, 1280), (257, 129, 256)]
+GEMM_RANDOM = [(1, 128, 128), (16, 256, 384), (100, 200, 512), (64, 1024, 4096), (300, 520, 1280), (257, 129, 256),
+               (129, 300, 1024), (70, 130, 1536)]    # the deeper load pipeline at 4 and 6 iterations
 
 
 @pytest.mark.parametrize("M,N,d", GEMM_RANDOM)
