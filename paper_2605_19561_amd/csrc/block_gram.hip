@@ -132,7 +132,15 @@ block_gram_reduce1_kernel(const float *__restrict__ partial, int n_partial, int 
   const int per = (n_partial + GRAM_SLICES - 1) / GRAM_SLICES;
   const int p0 = blockIdx.y * per, p1 = (p0 + per < n_partial) ? p0 + per : n_partial;
   double s = 0.0;
-  for (int p = p0; p < p1; ++p) s += (double)partial[(size_t)p * GG + i];
+  int p = p0;
+  for (; p + 8 <= p1; p += 8) {                  // eight loads in flight, added in order
+    float v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = partial[(size_t)(p + u) * GG + i];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) s += (double)v[u];
+  }
+  for (; p < p1; ++p) s += (double)partial[(size_t)p * GG + i];
   slices[(size_t)blockIdx.y * GG + i] = s;
 }
 
