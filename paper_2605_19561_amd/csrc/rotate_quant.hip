@@ -426,7 +426,16 @@ static hipError_t launch_cfg(const torq_rotation *r, const void *x, int64_t TG, 
   const int nw = r->G / 16 / NT;
   const int64_t nbatch = (TG + Cfg::TB - 1) / Cfg::TB;
   const size_t lds_bytes = 2 * (size_t)Cfg::STAGE_BYTES;
-  int64_t grid = 2 * 256;                 // two resident workgroups per CU at most
+  // Resident workgroups per CU (measured on X [16384, d]): two for 4 to 8 waves per workgroup, one
+  // beyond (two would not fit 16 waves per CU at these register counts); a small G has few waves
+  // per workgroup and needs as many workgroups as LDS and 16 waves allow to keep the CU busy
+  // (G = 16: 1.4 -> 2.7 TB/s, G = 48: 3.2 -> 3.8 TB/s against two workgroups).
+  int per_cu = nw >= 9 ? 1 : 2;
+  if (nw <= 3) {
+    per_cu = (int)((160 * 1024) / lds_bytes);
+    if (per_cu * nw > 16) per_cu = 16 / nw;
+  }
+  int64_t grid = (int64_t)per_cu * 256;
   if (grid > nbatch) grid = nbatch;
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra_lo);
