@@ -188,6 +188,10 @@ def main():
             print(json.dumps(sweep_line(tq, synth, dd, args.steps, args.warmup)), flush=True)
         # G = d/32: Algorithm 3 as printed (one R_inter over the whole row), a dense contraction
         print(json.dumps(sweep_line(tq, synth, 8192, args.steps, args.warmup, G=256)), flush=True)
+        # smaller inter-block rotations (Appendix A.7 counts with B = 32): less contraction per byte,
+        # the kernel moves towards the HBM roofline
+        for dd, gg in ((4096, 32), (8192, 32), (8192, 64)):
+            print(json.dumps(sweep_line(tq, synth, dd, args.steps, args.warmup, G=gg)), flush=True)
         # calibration statistic (Section 5.1): block Gram matrix of the benchmark's activations, HBM bound
         print(json.dumps(gram_line(tq, x, G, args.steps, args.warmup)), flush=True)
         xl = torch.cat([x, x, x, x], dim=0)             # a longer calibration sample: [32768, d]
