@@ -46,6 +46,18 @@ def lib():
         L.torq_o_quantize.argtypes = [vp, i64, i32, vp, vp]
         L.torq_o_dequantize.restype = None
         L.torq_o_dequantize.argtypes = [vp, vp, i64, i32, vp]
+        L.torq_o_e4m3_value.restype = f32
+        L.torq_o_e4m3_value.argtypes = [C.c_uint8]
+        L.torq_o_e4m3_from_f32.restype = C.c_uint8
+        L.torq_o_e4m3_from_f32.argtypes = [f32]
+        L.torq_o_quantize_mxint4.restype = None
+        L.torq_o_quantize_mxint4.argtypes = [vp, i64, i32, vp, vp]
+        L.torq_o_dequantize_mxint4.restype = None
+        L.torq_o_dequantize_mxint4.argtypes = [vp, vp, i64, i32, vp]
+        L.torq_o_quantize_nvfp4.restype = None
+        L.torq_o_quantize_nvfp4.argtypes = [vp, i64, i32, f32, vp, vp]
+        L.torq_o_dequantize_nvfp4.restype = None
+        L.torq_o_dequantize_nvfp4.argtypes = [vp, vp, i64, i32, f32, vp]
         L.torq_o_rotate_quantize.restype = None
         L.torq_o_rotate_quantize.argtypes = [vp, i64, i32, i32, vp, vp, vp, vp]
         L.torq_o_gemm.restype = None
@@ -174,6 +186,54 @@ def quantize(z):
     scales = np.empty((M, d // 32), np.uint8)
     lib().torq_o_quantize(_p(z), M, d, _p(codes), _p(scales))
     return codes, scales
+
+
+def e4m3_value(code: int) -> float:
+    return float(lib().torq_o_e4m3_value(int(code)))
+
+
+def e4m3_from_f32(t: float) -> int:
+    return int(lib().torq_o_e4m3_from_f32(float(t)))
+
+
+def quantize_mxint4(z):
+    """z fp32 [M, d] -> (codes uint8 [M, d/2] two's-complement nibbles, scales uint8 [M, d/32] E8M0)."""
+    z = _arr(z, np.float32)
+    M, d = z.shape
+    assert d % 32 == 0
+    codes = np.empty((M, d // 2), np.uint8)
+    scales = np.empty((M, d // 32), np.uint8)
+    lib().torq_o_quantize_mxint4(_p(z), M, d, _p(codes), _p(scales))
+    return codes, scales
+
+
+def dequantize_mxint4(codes, scales):
+    codes = _arr(codes, np.uint8)
+    scales = _arr(scales, np.uint8)
+    M, half = codes.shape
+    out = np.empty((M, half * 2), np.float32)
+    lib().torq_o_dequantize_mxint4(_p(codes), _p(scales), M, half * 2, _p(out))
+    return out
+
+
+def quantize_nvfp4(z, global_scale):
+    """z fp32 [M, d] -> (codes uint8 [M, d/2] e2m1, scales uint8 [M, d/16] E4M3)."""
+    z = _arr(z, np.float32)
+    M, d = z.shape
+    assert d % 16 == 0
+    codes = np.empty((M, d // 2), np.uint8)
+    scales = np.empty((M, d // 16), np.uint8)
+    lib().torq_o_quantize_nvfp4(_p(z), M, d, float(global_scale), _p(codes), _p(scales))
+    return codes, scales
+
+
+def dequantize_nvfp4(codes, scales, global_scale):
+    codes = _arr(codes, np.uint8)
+    scales = _arr(scales, np.uint8)
+    M, half = codes.shape
+    out = np.empty((M, half * 2), np.float32)
+    lib().torq_o_dequantize_nvfp4(_p(codes), _p(scales), M, half * 2, float(global_scale), _p(out))
+    return out
 
 
 def dequantize(codes, scales):

@@ -240,6 +240,111 @@ void torq_o_dequantize(const uint8_t *codes, const uint8_t *scales,
         }
 }
 
+/* ------------------------------------------------- other 4-bit formats -- */
+/* Section 6 ("Generalizability to Other Formats", Table 5) applies the same rotations in front
+ * of two other block formats.  The paper defines neither; the readings taken are stated here.
+ *
+ * MXINT4: the microscaling layout of MXFP4 (32 elements, one E8M0 scale chosen by the same rule)
+ * with integer elements: a = z / s rounded to the nearest integer, ties to even, clamped to
+ * [-7, 7] (symmetric), stored as a two's-complement nibble.
+ *
+ * NVFP4: blocks of 16 elements, each with an FP8 E4M3 scale, on top of one fp32 scale s_g for the
+ * whole tensor (an input here), elements e2m1.  Block scale: the E4M3 value nearest to
+ * amax / (6 s_g) (ties to the even code, saturating at 448); effective scale S = value * s_g;
+ * a = z / S; e2m1 code as for MXFP4.  All of it in fp32, in exactly this order of operations. */
+
+/* OCP FP8 E4M3: 1 sign, 4 exponent (bias 7), 3 mantissa bits; no infinities, S.1111.111 is NaN,
+ * so the largest magnitude is S.1111.110 = 448; exponent field 0 = subnormals m/8 * 2^-6. */
+float torq_o_e4m3_value(uint8_t code)
+{
+    int e = (code >> 3) & 15, m = code & 7;
+    float v = e ? ldexpf(1.0f + (float)m / 8.0f, e - 7) : ldexpf((float)m / 8.0f, -6);
+    return (code & 0x80u) ? -v : v;
+}
+
+/* nearest non-negative E4M3 value to t >= 0: a search over all 127 of them; of two equally near
+ * neighbours the one with the even code; anything above 448 gives 448 */
+uint8_t torq_o_e4m3_from_f32(float t)
+{
+    uint8_t best = 0;
+    double best_err = fabs((double)t - 0.0);
+    for (int c = 1; c <= 0x7E; ++c) {
+        double err = fabs((double)t - (double)torq_o_e4m3_value((uint8_t)c));
+        if (err < best_err || (err == best_err && (c & 1) == 0)) {
+            best_err = err;
+            best = (uint8_t)c;
+        }
+    }
+    return best;
+}
+
+void torq_o_quantize_mxint4(const float *z, int64_t M, int d, uint8_t *codes, uint8_t *scales)
+{
+    const int B = d / BLK;
+    for (int64_t m = 0; m < M; ++m)
+        for (int b = 0; b < B; ++b) {
+            const float *zb = z + m * (int64_t)d + b * BLK;
+            float amax = 0.0f;
+            for (int k = 0; k < BLK; ++k)
+                if (fabsf(zb[k]) > amax) amax = fabsf(zb[k]);
+            uint8_t byte = torq_o_e8m0_from_amax(amax);
+            scales[m * (int64_t)B + b] = byte;
+            uint8_t c[BLK];
+            for (int k = 0; k < BLK; ++k) {
+                float r = rintf(ldexpf(zb[k], 127 - (int)byte));   /* to nearest, ties to even */
+                if (r > 7.0f) r = 7.0f;
+                if (r < -7.0f) r = -7.0f;
+                c[k] = (uint8_t)((int)r & 15);
+            }
+            for (int j = 0; j < BLK / 2; ++j)
+                codes[m * (int64_t)(d / 2) + b * (BLK / 2) + j] = (uint8_t)(c[2 * j] | (c[2 * j + 1] << 4));
+        }
+}
+
+void torq_o_dequantize_mxint4(const uint8_t *codes, const uint8_t *scales, int64_t M, int d, float *zhat)
+{
+    for (int64_t j = 0; j < M * (int64_t)d; ++j) {
+        uint8_t byte = codes[j / 2];
+        int nib = (j & 1) ? (byte >> 4) : (byte & 15);
+        int v = nib >= 8 ? nib - 16 : nib;
+        zhat[j] = ldexpf((float)v, (int)scales[j / BLK] - 127);
+    }
+}
+
+void torq_o_quantize_nvfp4(const float *z, int64_t M, int d, float global_scale, uint8_t *codes,
+                           uint8_t *scales_e4m3)
+{
+    const int B16 = d / 16;
+    const float D = 6.0f * global_scale;
+    for (int64_t m = 0; m < M; ++m)
+        for (int b = 0; b < B16; ++b) {
+            const float *zb = z + m * (int64_t)d + b * 16;
+            float amax = 0.0f;
+            for (int k = 0; k < 16; ++k)
+                if (fabsf(zb[k]) > amax) amax = fabsf(zb[k]);
+            const uint8_t q = torq_o_e4m3_from_f32(amax / D);
+            scales_e4m3[m * (int64_t)B16 + b] = q;
+            const float S = torq_o_e4m3_value(q) * global_scale;
+            uint8_t c[16];
+            for (int k = 0; k < 16; ++k) {
+                /* a block whose scale rounds to zero keeps only the signs */
+                c[k] = (S > 0.0f) ? torq_o_e2m1_from_f32(zb[k] / S) : torq_o_e2m1_from_f32(copysignf(0.0f, zb[k]));
+            }
+            for (int j = 0; j < 8; ++j)
+                codes[m * (int64_t)(d / 2) + b * 8 + j] = (uint8_t)(c[2 * j] | (c[2 * j + 1] << 4));
+        }
+}
+
+void torq_o_dequantize_nvfp4(const uint8_t *codes, const uint8_t *scales_e4m3, int64_t M, int d,
+                             float global_scale, float *zhat)
+{
+    for (int64_t j = 0; j < M * (int64_t)d; ++j) {
+        uint8_t byte = codes[j / 2];
+        uint8_t code = (j & 1) ? (uint8_t)(byte >> 4) : (uint8_t)(byte & 15u);
+        zhat[j] = torq_o_e2m1_value(code) * (torq_o_e4m3_value(scales_e4m3[j / 16]) * global_scale);
+    }
+}
+
 void torq_o_rotate_quantize(const uint16_t *x_bf16, int64_t M, int d, int G,
                             const float *R_inter, const float *R_intra,
                             uint8_t *codes, uint8_t *scales)

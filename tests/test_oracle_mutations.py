@@ -13,7 +13,7 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "torq_oracle.c")
 PIN_FILES = ["tests/test_oracle_formats.py", "tests/test_oracle_rotation.py", "tests/test_oracle_gemm.py",
-             "tests/test_oracle_intra.py"]
+             "tests/test_oracle_intra.py", "tests/test_oracle_other_formats.py"]
 
 # (name, text in torq_oracle.c, replacement)
 MUTATIONS = [
@@ -77,6 +77,15 @@ MUTATIONS = [
     ("alg2_scale_from_unrotated", "if (fabs(acc) > amax) amax = fabs(acc);", "if (fabs(X[b * BLK + k]) > amax) amax = fabs(X[b * BLK + k]);"),
     ("alg2_pool_least_imbalanced", "if (!in_pool[k] && (arg < 0 || h[k] > h[arg])) arg = k;", "if (!in_pool[k] && (arg < 0 || h[k] < h[arg])) arg = k;"),
     ("alg2_stale_rest", "for (int j = 0; j < 8; ++j) total[j] = rest[j] + counts[bp * 8 + j] + counts[bq * 8 + j];", ""),
+    ("e4m3_ties_to_odd", "if (err < best_err || (err == best_err && (c & 1) == 0)) {", "if (err < best_err || (err == best_err && (c & 1) == 1)) {"),
+    ("e4m3_bias_8", "ldexpf(1.0f + (float)m / 8.0f, e - 7)", "ldexpf(1.0f + (float)m / 8.0f, e - 8)"),
+    ("e4m3_allows_nan_code", "for (int c = 1; c <= 0x7E; ++c) {", "for (int c = 1; c <= 0x7F; ++c) {"),
+    ("mxint4_allows_minus_8", "if (r < -7.0f) r = -7.0f;", "if (r < -8.0f) r = -8.0f;"),
+    ("mxint4_truncates", "float r = rintf(ldexpf(zb[k], 127 - (int)byte));", "float r = truncf(ldexpf(zb[k], 127 - (int)byte));"),
+    ("mxint4_rounds_half_away", "float r = rintf(ldexpf(zb[k], 127 - (int)byte));", "float r = roundf(ldexpf(zb[k], 127 - (int)byte));"),
+    ("nvfp4_scale_to_amax", "const float D = 6.0f * global_scale;", "const float D = 1.0f * global_scale;"),
+    ("nvfp4_ignores_global_scale_in_S", "const float S = torq_o_e4m3_value(q) * global_scale;", "const float S = torq_o_e4m3_value(q);"),
+    ("nvfp4_dequant_block_of_32", "(torq_o_e4m3_value(scales_e4m3[j / 16]) * global_scale)", "(torq_o_e4m3_value(scales_e4m3[j / 32]) * global_scale)"),
 ]
 
 
