@@ -192,6 +192,9 @@ def main():
         # the kernel moves towards the HBM roofline
         for dd, gg in ((4096, 32), (8192, 32), (8192, 64)):
             print(json.dumps(sweep_line(tq, synth, dd, args.steps, args.warmup, G=gg)), flush=True)
+        # the other block formats of Section 6 through the same kernel
+        for ff in (1, 2):
+            print(json.dumps(sweep_line(tq, synth, 8192, args.steps, args.warmup, fmt=ff)), flush=True)
         # calibration statistic (Section 5.1): block Gram matrix of the benchmark's activations, HBM bound
         print(json.dumps(gram_line(tq, x, G, args.steps, args.warmup)), flush=True)
         xl = torch.cat([x, x, x, x], dim=0)             # a longer calibration sample: [32768, d]
@@ -260,8 +263,8 @@ def cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d):
             "gemm_GFLOPps": round(2.0 * gm * gn * d / t_gemm / 1e9, 3)}
 
 
-def sweep_line(tq, synth, d, steps, warmup, G=None):
-    """rotate+quantise alone on X [16384, d] (the memory-bound sweep)."""
+def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0):
+    """rotate+quantise alone on X [16384, d] (the memory-bound sweep); fmt 1 / 2: MXINT4 / NVFP4 output."""
     import torch
     dev = "cuda:0"
     M = 16384
@@ -271,20 +274,29 @@ def sweep_line(tq, synth, d, steps, warmup, G=None):
     Ri, Ra = synth.rotations(G)
     rot = tq.Rotation(d, G, Ri, Ra)
     codes = torch.empty((M, d // 2), dtype=torch.uint8, device=dev)
-    scales = torch.empty((M, d // 32), dtype=torch.uint8, device=dev)
+    scales = torch.empty((M, d // (16 if fmt == 2 else 32)), dtype=torch.uint8, device=dev)
+    gs = 0.01                                          # NVFP4's tensor-wide scale (unused otherwise)
+
+    def call():
+        if fmt == 0:
+            tq.torq_rotate_quantize(rot, x, codes=codes, scales=scales)
+        else:
+            tq.torq_rotate_quantize_fmt(rot, x, fmt, gs, codes=codes, scales=scales)
     for _ in range(warmup):
-        tq.torq_rotate_quantize(rot, x, codes=codes, scales=scales)
+        call()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(steps):
-        tq.torq_rotate_quantize(rot, x, codes=codes, scales=scales)
+        call()
     e1.record()
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / steps
-    gbs = M * d * RQ_BYTES_PER_ELEMENT / (ms * 1e-3) / 1e9
+    bytes_per_element = 2.0 + 0.5 + (1.0 / 16 if fmt == 2 else 1.0 / 32)
+    gbs = M * d * bytes_per_element / (ms * 1e-3) / 1e9
     rot.close()
+    name = ("", " -> MXINT4", " -> NVFP4")[fmt]
     return {"metric": "torq_rotate_quantize bandwidth", "value": round(gbs, 1), "unit": "GB/s",
-            "config": {"workload": f"sweep: X bf16 [{M}, {d}], G={G}"}, "ms": round(ms, 4),
+            "config": {"workload": f"sweep: X bf16 [{M}, {d}], G={G}{name}"}, "ms": round(ms, 4),
             "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
             "mfma_bf16_tflops": round(M * d * (2 * 2 * G + 3 * 64) / (ms * 1e-3) / 1e12, 1)}
 

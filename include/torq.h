@@ -120,6 +120,27 @@ int mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s,
                const uint8_t *W_q, const uint8_t *W_s,
                void *out_bf16, int64_t M, int64_t N, int d, void *stream);
 
+/* The same two calls for the other 4-bit block formats that Section 6 ("Generalizability to Other
+ * Formats", Table 5) puts behind the rotations.  The paper names the formats without defining them;
+ * the readings taken (all arithmetic in fp32, in this order):
+ *   TORQ_FMT_MXFP4   as torq_rotate_quantize / torq_quantize_f32.
+ *   TORQ_FMT_MXINT4  32-element blocks and the E8M0 scale of MXFP4; elements round(z / scale) to the
+ *                    nearest integer, ties to even, clamped to [-7, 7], two's-complement nibbles.
+ *   TORQ_FMT_NVFP4   16-element blocks, each with an OCP FP8 E4M3 scale byte, scales [M][d/16], on
+ *                    top of the tensor-wide fp32 `global_scale` (finite, > 0; ignored by the other
+ *                    formats): byte = E4M3 nearest to amax / (6 * global_scale) (ties to the even
+ *                    code, saturating at 448 = 0x7E), S = value(byte) * global_scale, element = e2m1
+ *                    code of z / S as in MXFP4 (a block whose byte is 0 keeps only the signs).
+ * Nibble packing, alignment and error codes as above; an unknown format is TORQ_EINVAL.  Only the
+ * quantisers exist for these formats: the GEMM of this library consumes MXFP4. */
+#define TORQ_FMT_MXFP4  0
+#define TORQ_FMT_MXINT4 1
+#define TORQ_FMT_NVFP4  2
+int torq_rotate_quantize_fmt(const torq_rotation_t *r, const void *x_bf16, int64_t M, int format,
+                             float global_scale, uint8_t *codes, uint8_t *scales, void *stream);
+int torq_quantize_f32_fmt(const float *z_f32, int64_t M, int d, int format, float global_scale,
+                          uint8_t *codes, uint8_t *scales, void *stream);
+
 /* mxfp4_gemm with scratch memory.  Same operands, same result up to the order of the fp32 sums.
  * When the output has too few tiles to occupy the GPU and the reduction is long (a few hundred
  * activation rows, e.g. a decode batch or a prefill chunk against a down projection), the k range

@@ -16,6 +16,7 @@ EXPORTS = [
     "torq_status_string", "torq_rotation_create", "torq_rotation_destroy", "torq_rotation_d",
     "torq_rotation_G", "torq_rotate_quantize", "torq_rotate", "torq_quantize_f32", "mxfp4_gemm",
     "torq_linear_workspace_bytes", "torq_linear", "mxfp4_gemm_workspace_bytes", "mxfp4_gemm_ws", "mxfp4_gemm_plan",
+    "torq_rotate_quantize_fmt", "torq_quantize_f32_fmt",
     "torq_linear_workspace_bytes_n", "torq_block_gram_workspace_bytes", "torq_block_gram",
     "torq_equalize_inter", "torq_code_histogram_workspace_bytes", "torq_code_histogram", "torq_intra_pair_scores",
     "torq_intra_best_angle", "torq_calibrate_intra", "torq_diag_mfma_burn",
@@ -62,6 +63,10 @@ def lib():
         L.mxfp4_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp]
         L.mxfp4_gemm_workspace_bytes.restype = sz
         L.mxfp4_gemm_workspace_bytes.argtypes = [i64, i64, i32]
+        L.torq_rotate_quantize_fmt.restype = i32
+        L.torq_rotate_quantize_fmt.argtypes = [vp, vp, i64, i32, C.c_float, vp, vp, vp]
+        L.torq_quantize_f32_fmt.restype = i32
+        L.torq_quantize_f32_fmt.argtypes = [vp, i64, i32, i32, C.c_float, vp, vp, vp]
         L.mxfp4_gemm_plan.restype = i32
         L.mxfp4_gemm_plan.argtypes = [i64, i64, i32, sz] + [C.POINTER(i32)] * 4
         L.mxfp4_gemm_ws.restype = i32
@@ -169,6 +174,40 @@ def torq_quantize_f32(z: torch.Tensor, codes=None, scales=None, stream=None):
         scales = torch.empty((M, d // 32), dtype=torch.uint8, device=z.device)
     _check(lib().torq_quantize_f32(_dev(z, torch.float32, "z"), M, d, _dev(codes, torch.uint8, "codes"),
                                    _dev(scales, torch.uint8, "scales"), _stream(stream)), "torq_quantize_f32")
+    return codes, scales
+
+
+TORQ_FMT_MXFP4, TORQ_FMT_MXINT4, TORQ_FMT_NVFP4 = 0, 1, 2
+
+
+def _scale_cols(d: int, fmt: int) -> int:
+    return d // 16 if fmt == TORQ_FMT_NVFP4 else d // 32
+
+
+def torq_rotate_quantize_fmt(rot: Rotation, x_bf16: torch.Tensor, fmt: int, global_scale: float = 1.0,
+                             codes=None, scales=None, stream=None):
+    M, d = x_bf16.shape
+    assert d == rot.d
+    if codes is None:
+        codes = torch.empty((M, d // 2), dtype=torch.uint8, device=x_bf16.device)
+    if scales is None:
+        scales = torch.empty((M, _scale_cols(d, fmt)), dtype=torch.uint8, device=x_bf16.device)
+    _check(lib().torq_rotate_quantize_fmt(rot.handle, _dev(x_bf16, torch.bfloat16, "x"), M, int(fmt),
+                                          float(global_scale), _dev(codes, torch.uint8, "codes"),
+                                          _dev(scales, torch.uint8, "scales"), _stream(stream)),
+           "torq_rotate_quantize_fmt")
+    return codes, scales
+
+
+def torq_quantize_f32_fmt(z: torch.Tensor, fmt: int, global_scale: float = 1.0, codes=None, scales=None, stream=None):
+    M, d = z.shape
+    if codes is None:
+        codes = torch.empty((M, d // 2), dtype=torch.uint8, device=z.device)
+    if scales is None:
+        scales = torch.empty((M, _scale_cols(d, fmt)), dtype=torch.uint8, device=z.device)
+    _check(lib().torq_quantize_f32_fmt(_dev(z, torch.float32, "z"), M, d, int(fmt), float(global_scale),
+                                       _dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"),
+                                       _stream(stream)), "torq_quantize_f32_fmt")
     return codes, scales
 
 

@@ -162,7 +162,7 @@ int torq_rotate_quantize(const torq_rotation_t *r, const void *x_bf16, int64_t M
   if (M == 0) return TORQ_OK;
   if (!x_bf16 || !codes || !scales) return TORQ_EINVAL;
   if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return TORQ_EALIGN;
-  hipError_t e = torq::launch_rotate(r, x_bf16, M, codes, scales, nullptr, (hipStream_t)stream);
+  hipError_t e = torq::launch_rotate(r, x_bf16, M, TORQ_FMT_MXFP4, 1.0f, codes, scales, nullptr, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 
@@ -171,7 +171,7 @@ int torq_rotate(const torq_rotation_t *r, const void *x_bf16, int64_t M, float *
   if (M == 0) return TORQ_OK;
   if (!x_bf16 || !z_f32) return TORQ_EINVAL;
   if (misaligned(x_bf16) || misaligned(z_f32)) return TORQ_EALIGN;
-  hipError_t e = torq::launch_rotate(r, x_bf16, M, nullptr, nullptr, z_f32, (hipStream_t)stream);
+  hipError_t e = torq::launch_rotate(r, x_bf16, M, TORQ_FMT_MXFP4, 1.0f, nullptr, nullptr, z_f32, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 
@@ -181,7 +181,7 @@ int torq_quantize_f32(const float *z_f32, int64_t M, int d, uint8_t *codes, uint
   if (M == 0) return TORQ_OK;
   if (!z_f32 || !codes || !scales) return TORQ_EINVAL;
   if (misaligned(z_f32) || misaligned(codes) || misaligned(scales)) return TORQ_EALIGN;
-  hipError_t e = torq::launch_quantize_f32(z_f32, M * (int64_t)(d / TORQ_BLOCK), codes, scales,
+  hipError_t e = torq::launch_quantize_f32(z_f32, M * (int64_t)(d / TORQ_BLOCK), TORQ_FMT_MXFP4, 1.0f, codes, scales,
                                            (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
@@ -194,6 +194,32 @@ int mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const
   if (misaligned(A_q) || misaligned(W_q) || misaligned(out_bf16)) return TORQ_EALIGN;
   if ((reinterpret_cast<uintptr_t>(A_s) & 3u) || (reinterpret_cast<uintptr_t>(W_s) & 3u)) return TORQ_EALIGN;
   hipError_t e = torq::launch_mxfp4_gemm(A_q, A_s, W_q, W_s, out_bf16, M, N, d, nullptr, 0, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+static bool valid_format(int format, float global_scale) {
+  if (format == TORQ_FMT_MXFP4 || format == TORQ_FMT_MXINT4) return true;
+  return format == TORQ_FMT_NVFP4 && std::isfinite(global_scale) && global_scale > 0.0f;
+}
+
+int torq_rotate_quantize_fmt(const torq_rotation_t *r, const void *x_bf16, int64_t M, int format, float global_scale,
+                             uint8_t *codes, uint8_t *scales, void *stream) {
+  if (!r || M < 0 || !valid_format(format, global_scale)) return TORQ_EINVAL;
+  if (M == 0) return TORQ_OK;
+  if (!x_bf16 || !codes || !scales) return TORQ_EINVAL;
+  if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return TORQ_EALIGN;
+  hipError_t e = torq::launch_rotate(r, x_bf16, M, format, global_scale, codes, scales, nullptr, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+int torq_quantize_f32_fmt(const float *z_f32, int64_t M, int d, int format, float global_scale, uint8_t *codes,
+                          uint8_t *scales, void *stream) {
+  if (M < 0 || d <= 0 || d % TORQ_BLOCK != 0 || !valid_format(format, global_scale)) return TORQ_EINVAL;
+  if (M == 0) return TORQ_OK;
+  if (!z_f32 || !codes || !scales) return TORQ_EINVAL;
+  if (misaligned(z_f32) || misaligned(codes) || misaligned(scales)) return TORQ_EALIGN;
+  hipError_t e = torq::launch_quantize_f32(z_f32, M * (int64_t)(d / TORQ_BLOCK), format, global_scale, codes, scales,
+                                           (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 
@@ -242,7 +268,7 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q
   if (workspace_bytes < torq_linear_workspace_bytes(M, r->d)) return TORQ_EWORKSPACE;
   uint8_t *codes = static_cast<uint8_t *>(workspace);
   uint8_t *scales = codes + (((size_t)M * (size_t)(r->d / 2) + 255) & ~(size_t)255);
-  hipError_t e = torq::launch_rotate(r, x_bf16, M, codes, scales, nullptr, (hipStream_t)stream);
+  hipError_t e = torq::launch_rotate(r, x_bf16, M, TORQ_FMT_MXFP4, 1.0f, codes, scales, nullptr, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
   // whatever the caller gave beyond the packed activations serves the GEMM's split-k pieces
   const size_t used = torq_linear_workspace_bytes(M, r->d);

@@ -63,12 +63,14 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
   return __builtin_bit_cast(uint32_t, v);
 }
 
-template <int KS, int NT, bool QUANT>
+// FMT: FMT_NONE writes the rotated fp32 values, else the 4-bit format of step 4 (torq_device.h)
+template <int KS, int NT, int FMT>
 __global__ void __launch_bounds__(64 * ((2 * KS) / NT > 16 ? 16 : (2 * KS) / NT))
 rotate_kernel(const uint4 *__restrict__ x, int64_t TG, int G,
               const uint16_t *__restrict__ inter_hi, const uint16_t *__restrict__ inter_lo,
               const uint4 *__restrict__ intra_hi_frag, const uint4 *__restrict__ intra_lo_frag,
-              uint32_t *__restrict__ codes, uint8_t *__restrict__ scales, float *__restrict__ z_out) {
+              uint32_t *__restrict__ codes, uint8_t *__restrict__ scales, float *__restrict__ z_out,
+              float global_scale) {
   using Cfg = RotCfg<KS>;
   constexpr int TB = Cfg::TB;
   extern __shared__ __attribute__((aligned(16))) char lds[];
@@ -196,13 +198,20 @@ rotate_kernel(const uint4 *__restrict__ x, int64_t TG, int G,
         const float zz[8] = {zacc[0][0], zacc[0][1], zacc[0][2], zacc[0][3],
                              zacc[1][0], zacc[1][1], zacc[1][2], zacc[1][3]};
         const int64_t blk = tg * G + 16 * (wave * NT + i) + col;   // global block index
-        if constexpr (QUANT) {
-          // ---- step 4: MXFP4 (Section 4, Eq. 1) ------------------------------
+        if constexpr (FMT == FMT_NVFP4) {
+          // ---- step 4 for 16-element blocks: lanes q and q ^ 1 share one, E4M3 scale byte each
+          float amax = amax8(zz);
+          amax = fmaxf(amax, __shfl_xor(amax, 16));
+          const uint32_t sc = e4m3_from_f32(__fdiv_rn(amax, 6.0f * global_scale));
+          codes[blk * 4 + q] = pack8_nvfp4(zz, e4m3_to_f32(sc) * global_scale);
+          if ((q & 1) == 0) scales[blk * 2 + (q >> 1)] = (uint8_t)sc;
+        } else if constexpr (FMT != FMT_NONE) {
+          // ---- step 4: MXFP4 (Section 4, Eq. 1), or MXINT4 on the same scale -----
           float amax = amax8(zz);
           amax = fmaxf(amax, __shfl_xor(amax, 16));
           amax = fmaxf(amax, __shfl_xor(amax, 32));
           const uint32_t byte = e8m0_from_amax(amax);
-          codes[blk * 4 + q] = pack8_e2m1(zz, e8m0_to_f32(byte));
+          codes[blk * 4 + q] = (FMT == FMT_MXINT4) ? pack8_int4(zz, e8m0_inverse_f32(byte)) : pack8_e2m1(zz, e8m0_to_f32(byte));
           if (q == 0) scales[blk] = (uint8_t)byte;
         } else {
           float4 *o = reinterpret_cast<float4 *>(z_out + blk * 32 + 8 * q);
@@ -232,12 +241,13 @@ rotate_kernel(const uint4 *__restrict__ x, int64_t TG, int G,
 //           A = R_intra^T lane (m, h), slot jj:        R_intra[that k'][kout(m)],
 //                         kout(m) = 16 ((m/4)%2) + 4 (m/8) + m%4
 //           D             lane (b, h), reg r:          Z[b][16 h + r]
-template <int KS16, bool QUANT>
+template <int KS16, int FMT>
 __global__ void __launch_bounds__(64 * (KS16 / 2), 2)   // at least two waves per SIMD
 rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
                 const uint16_t *__restrict__ inter_hi, const uint16_t *__restrict__ inter_lo,
                 const uint4 *__restrict__ intra_hi_frag, const uint4 *__restrict__ intra_lo_frag,
-                uint2 *__restrict__ codes, uint8_t *__restrict__ scales, float *__restrict__ z_out) {
+                uint2 *__restrict__ codes, uint8_t *__restrict__ scales, float *__restrict__ z_out,
+                float global_scale) {
   constexpr int TB = 2;                              // token-groups per batch, processed together
   constexpr int TG_BYTES = KS16 * 16 * 64;           // one token-group: G rows of 64 bytes
   constexpr int STAGE_BYTES = TB * TG_BYTES;
@@ -370,15 +380,27 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
         float zz[16];
 #pragma unroll
         for (int r = 0; r < 16; ++r) zz[r] = zacc[j][r];
-        if constexpr (QUANT) {
+        if constexpr (FMT == FMT_NVFP4) {
+          // the lane's sixteen values are one 16-element block: no cross-lane step
+          const float amax = fmaxf(amax8(zz), amax8(zz + 8));
+          const uint32_t sc = e4m3_from_f32(__fdiv_rn(amax, 6.0f * global_scale));
+          const float S = e4m3_to_f32(sc) * global_scale;
+          codes[blkidx * 2 + h] = make_uint2(pack8_nvfp4(zz, S), pack8_nvfp4(zz + 8, S));
+          scales[blkidx * 2 + h] = (uint8_t)sc;
+        } else if constexpr (FMT != FMT_NONE) {
           float amax = fmaxf(amax8(zz), amax8(zz + 8));
           // max with the other half-wave (lane ^ 32): swap the upper half of one copy with the
           // lower half of the other, then every lane holds both partners' values
           const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(amax), __float_as_uint(amax), false, false);
           amax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
           const uint32_t byte = e8m0_from_amax(amax);
-          const float sc = e8m0_to_f32(byte);
-          codes[blkidx * 2 + h] = make_uint2(pack8_e2m1(zz, sc), pack8_e2m1(zz + 8, sc));
+          if constexpr (FMT == FMT_MXINT4) {
+            const float inv = e8m0_inverse_f32(byte);
+            codes[blkidx * 2 + h] = make_uint2(pack8_int4(zz, inv), pack8_int4(zz + 8, inv));
+          } else {
+            const float sc = e8m0_to_f32(byte);
+            codes[blkidx * 2 + h] = make_uint2(pack8_e2m1(zz, sc), pack8_e2m1(zz + 8, sc));
+          }
           if (h == 0) scales[blkidx] = (uint8_t)byte;
         } else {
           float4 *o = reinterpret_cast<float4 *>(z_out + blkidx * 32 + 16 * h);
@@ -393,9 +415,36 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
   }
 }
 
+// launch KERNEL_<..., FMT> for the runtime format (FMT_NONE when the fp32 output is asked for)
+#define TORQ_LAUNCH_FMT(KERNEL_, CODES_T_, ...)                                                                  \
+  switch (z_out ? FMT_NONE : format) {                                                                          \
+    case FMT_NONE:                                                                                              \
+      hipLaunchKernelGGL((KERNEL_<__VA_ARGS__, FMT_NONE>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream, \
+                         reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,        \
+                         (CODES_T_ *)nullptr, (uint8_t *)nullptr, z_out, 1.0f);                                 \
+      break;                                                                                                    \
+    case FMT_MXFP4:                                                                                             \
+      hipLaunchKernelGGL((KERNEL_<__VA_ARGS__, FMT_MXFP4>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream, \
+                         reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,        \
+                         reinterpret_cast<CODES_T_ *>(codes), scales, (float *)nullptr, 1.0f);                  \
+      break;                                                                                                    \
+    case FMT_MXINT4:                                                                                            \
+      hipLaunchKernelGGL((KERNEL_<__VA_ARGS__, FMT_MXINT4>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream, \
+                         reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,        \
+                         reinterpret_cast<CODES_T_ *>(codes), scales, (float *)nullptr, 1.0f);                  \
+      break;                                                                                                    \
+    case FMT_NVFP4:                                                                                             \
+      hipLaunchKernelGGL((KERNEL_<__VA_ARGS__, FMT_NVFP4>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream, \
+                         reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,        \
+                         reinterpret_cast<CODES_T_ *>(codes), scales, (float *)nullptr, global_scale);          \
+      break;                                                                                                    \
+    default: return hipErrorInvalidValue;                                                                       \
+  }                                                                                                             \
+  return hipGetLastError();
+
 template <int KS16>
-static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG, uint8_t *codes,
-                               uint8_t *scales, float *z_out, hipStream_t stream) {
+static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG, int format, float global_scale,
+                               uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
   constexpr int TB = 2;
   const int nw = KS16 / 2;                               // = G / 32
   const int64_t nbatch = (TG + TB - 1) / TB;
@@ -408,20 +457,12 @@ static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG
   if (grid > nbatch) grid = nbatch;
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
-  if (z_out)
-    hipLaunchKernelGGL((rotate_kernel32<KS16, false>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream,
-                       reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,
-                       nullptr, nullptr, z_out);
-  else
-    hipLaunchKernelGGL((rotate_kernel32<KS16, true>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream,
-                       reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,
-                       reinterpret_cast<uint2 *>(codes), scales, nullptr);
-  return hipGetLastError();
+  TORQ_LAUNCH_FMT(rotate_kernel32, uint2, KS16)
 }
 
 template <int KS, int NT>
-static hipError_t launch_cfg(const torq_rotation *r, const void *x, int64_t TG, uint8_t *codes,
-                             uint8_t *scales, float *z_out, hipStream_t stream) {
+static hipError_t launch_cfg(const torq_rotation *r, const void *x, int64_t TG, int format, float global_scale,
+                             uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
   using Cfg = RotCfg<KS>;
   const int nw = r->G / 16 / NT;
   const int64_t nbatch = (TG + Cfg::TB - 1) / Cfg::TB;
@@ -439,38 +480,28 @@ static hipError_t launch_cfg(const torq_rotation *r, const void *x, int64_t TG, 
   if (grid > nbatch) grid = nbatch;
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra_lo);
-  if (z_out)
-    hipLaunchKernelGGL((rotate_kernel<KS, NT, false>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream,
-                       reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,
-                       nullptr, nullptr, z_out);
-  else
-    hipLaunchKernelGGL((rotate_kernel<KS, NT, true>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream,
-                       reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,
-                       reinterpret_cast<uint32_t *>(codes), scales, nullptr);
-  return hipGetLastError();
+  TORQ_LAUNCH_FMT(rotate_kernel, uint32_t, KS, NT)
 }
+#undef TORQ_LAUNCH_FMT
 
-hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, uint8_t *codes,
-                         uint8_t *scales, float *z_out, hipStream_t stream) {
+// Exactly one of (codes, scales) / z_out is used; `format` (FMT_*) picks step 4's block format.
+hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, int format, float global_scale,
+                         uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
   const int64_t TG = M * (int64_t)(r->d / 32 / r->G);
   if (TG == 0) return hipSuccess;
   if (r->G % 32 == 0) {
     switch (r->G / 16) {
-      case 2: return launch_cfg32<2>(r, x_bf16, TG, codes, scales, z_out, stream);
-      case 4: return launch_cfg32<4>(r, x_bf16, TG, codes, scales, z_out, stream);
-      case 6: return launch_cfg32<6>(r, x_bf16, TG, codes, scales, z_out, stream);
-      case 8: return launch_cfg32<8>(r, x_bf16, TG, codes, scales, z_out, stream);
-      case 10: return launch_cfg32<10>(r, x_bf16, TG, codes, scales, z_out, stream);
-      case 12: return launch_cfg32<12>(r, x_bf16, TG, codes, scales, z_out, stream);
-      case 14: return launch_cfg32<14>(r, x_bf16, TG, codes, scales, z_out, stream);
-      case 16: return launch_cfg32<16>(r, x_bf16, TG, codes, scales, z_out, stream);
+#define TORQ_CASE32(K16_) \
+  case K16_: return launch_cfg32<K16_>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
+      TORQ_CASE32(2) TORQ_CASE32(4) TORQ_CASE32(6) TORQ_CASE32(8)
+      TORQ_CASE32(10) TORQ_CASE32(12) TORQ_CASE32(14) TORQ_CASE32(16)
+#undef TORQ_CASE32
     }
   }
   // G = 16 * odd: the 16x16x32 kernel, one tile of 16 blocks per wave
   switch (r->KS) {
-#define TORQ_CASE(KS_)                                                                          \
-  case KS_:                                                                                     \
-    return launch_cfg<KS_, 1>(r, x_bf16, TG, codes, scales, z_out, stream);
+#define TORQ_CASE(KS_) \
+  case KS_: return launch_cfg<KS_, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
     TORQ_CASE(1) TORQ_CASE(2) TORQ_CASE(3) TORQ_CASE(4)
     TORQ_CASE(5) TORQ_CASE(6) TORQ_CASE(7) TORQ_CASE(8)
 #undef TORQ_CASE

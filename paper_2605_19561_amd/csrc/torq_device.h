@@ -52,6 +52,49 @@ __device__ __forceinline__ float amax8(const float z[8]) {
   return fmaxf(a, fabsf(z[7]));
 }
 
+// ---------------------------------------------------------------------------
+// The other 4-bit block formats of Section 6 ("Generalizability to Other Formats").  The paper names
+// them without defining them; the readings are those of include/torq.h.
+
+constexpr int FMT_NONE = -1, FMT_MXFP4 = 0, FMT_MXINT4 = 1, FMT_NVFP4 = 2;
+
+// MXINT4: eight values -> eight two's-complement nibbles.  inv_scale = 2^(127 - byte) (the product is
+// exact), round to nearest even, clamp to [-7, 7].
+__device__ __forceinline__ float e8m0_inverse_f32(uint32_t byte) {   // byte <= 252 for finite input
+  return __uint_as_float((254u - byte) << 23);
+}
+__device__ __forceinline__ uint32_t pack8_int4(const float z[8], float inv_scale) {
+  uint32_t r = 0;
+#pragma unroll
+  for (int i = 0; i < 8; ++i) {
+    const float a = fminf(fmaxf(rintf(z[i] * inv_scale), -7.0f), 7.0f);
+    r |= ((uint32_t)(int)a & 15u) << (4 * i);
+  }
+  return r;
+}
+
+// OCP FP8 E4M3 (bias 7, largest value 448 = 0x7E, 0x7F is NaN) of t >= 0: round to nearest even
+// on three mantissa bits, saturating.  Below 2^-6 the codes are the multiples of 2^-9.
+__device__ __forceinline__ uint32_t e4m3_from_f32(float t) {
+  if (t < 0.015625f) return (uint32_t)rintf(t * 512.0f);          // 0 .. 8; 8 is the first normal
+  uint32_t u = __float_as_uint(t);
+  u += 0x7FFFFu + ((u >> 20) & 1u);
+  const uint32_t code = (u >> 20) - (120u << 3);
+  return code < 0x7Eu ? code : 0x7Eu;
+}
+__device__ __forceinline__ float e4m3_to_f32(uint32_t code) {     // code <= 0x7E
+  return (code >> 3) ? __uint_as_float(((code >> 3) + 120u) << 23 | (code & 7u) << 20)
+                     : (float)code * 0.001953125f;
+}
+// NVFP4: eight values of a block with effective scale S = e4m3 value * tensor scale.  IEEE
+// division, then the e2m1 rounding of pack8_e2m1; a block whose scale rounded to zero keeps signs.
+__device__ __forceinline__ uint32_t pack8_nvfp4(const float z[8], float S) {
+  float a[8];
+#pragma unroll
+  for (int i = 0; i < 8; ++i) a[i] = (S > 0.0f) ? __fdiv_rn(z[i], S) : copysignf(0.0f, z[i]);
+  return pack8_e2m1(a, 1.0f);
+}
+
 // bf16 <-> fp32 bit moves
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t h) { return __uint_as_float(h << 16); }
 

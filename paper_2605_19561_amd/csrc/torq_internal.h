@@ -21,13 +21,14 @@ struct torq_rotation {
 
 namespace torq {
 
-// fp32 rows -> MXFP4.  nblk = number of 32-element blocks (M * d / 32).
-hipError_t launch_quantize_f32(const float *z, int64_t nblk, uint8_t *codes, uint8_t *scales,
-                               hipStream_t stream);
+// fp32 rows -> a 4-bit block format (FMT_* of torq_device.h = TORQ_FMT_* of torq.h).  nblk = number
+// of 32-element blocks (M * d / 32); global_scale is NVFP4's tensor-wide scale, else ignored.
+hipError_t launch_quantize_f32(const float *z, int64_t nblk, int format, float global_scale, uint8_t *codes,
+                               uint8_t *scales, hipStream_t stream);
 
 // Two-level rotation (+ quantisation).  Exactly one of (codes, scales) / z_out is used:
-// z_out != nullptr writes the rotated fp32 values instead of quantising.
-hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M,
+// z_out != nullptr writes the rotated fp32 values instead of quantising to `format`.
+hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, int format, float global_scale,
                          uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream);
 
 // workspace: optional device scratch of mxfp4_gemm_workspace_bytes(M, N, d) bytes; with it, shapes

@@ -119,3 +119,18 @@ def test_gemm_workspace_entry_points_validate_and_plan_on_the_host():
     v = [C.c_int() for _ in range(4)]
     assert L.mxfp4_gemm_plan(0, 4, 128, 0, *(C.byref(x) for x in v)) == binding.TORQ_EINVAL
     assert L.mxfp4_gemm_plan(4, 4, 128, 0, None, C.byref(v[1]), C.byref(v[2]), C.byref(v[3])) == binding.TORQ_EINVAL
+
+
+def test_format_entry_points_reject_unknown_formats_and_bad_scales():
+    L = binding.lib()
+    good = C.c_void_p(0x1000)
+    f = C.c_float
+    assert L.torq_quantize_f32_fmt(good, 4, 64, 3, f(1.0), good, good, None) == binding.TORQ_EINVAL      # unknown format
+    assert L.torq_quantize_f32_fmt(good, 4, 64, -1, f(1.0), good, good, None) == binding.TORQ_EINVAL
+    assert L.torq_quantize_f32_fmt(good, 4, 64, 2, f(0.0), good, good, None) == binding.TORQ_EINVAL      # NVFP4 needs a positive scale
+    assert L.torq_quantize_f32_fmt(good, 4, 64, 2, f(-1.0), good, good, None) == binding.TORQ_EINVAL
+    assert L.torq_quantize_f32_fmt(good, 4, 64, 2, f(float("inf")), good, good, None) == binding.TORQ_EINVAL
+    assert L.torq_quantize_f32_fmt(good, 4, 48, 1, f(1.0), good, good, None) == binding.TORQ_EINVAL      # d % 32
+    assert L.torq_quantize_f32_fmt(good, 0, 64, 1, f(0.0), None, None, None) == binding.TORQ_OK          # empty; scale unused
+    assert L.torq_quantize_f32_fmt(C.c_void_p(0x1004), 4, 64, 1, f(1.0), good, good, None) == binding.TORQ_EALIGN
+    assert L.torq_rotate_quantize_fmt(None, good, 4, 1, f(1.0), good, good, None) == binding.TORQ_EINVAL

@@ -597,3 +597,74 @@ def test_calibrated_intra_rotation_lowers_the_occupancy_loss_on_the_gpu(tq, orac
     assert after < 0.5 * before
     rot0.close()
     rot1.close()
+
+
+# --------------------------------------------- other block formats (Section 6) ----
+
+FMT_SHAPES = [(1, 32), (3, 96), (40, 4096), (129, 2048), (7, 14336)]
+
+
+def _format_input(M, d, seed):
+    rng = np.random.default_rng(seed)
+    z = (rng.standard_t(3, size=(M, d)) * np.exp(rng.normal(size=(M, 1)) * 2)).astype(np.float32)
+    z[:, :8] = [0.25, 0.75, 1.25, 2.5, -3.5, 5.0, 6.0, 7.5]          # rounding ties at scale 1 (if amax allows)
+    z[0, 16:32] = 0.0                                                  # an all-zero 16-element block
+    if M > 2:
+        z[2, :] = 0.0                                                  # an all-zero row
+        z[1, 5] = 3e38                                                 # a huge value
+        z[1, 40 % d] = 1e-40                                           # a subnormal one
+    return z
+
+
+@pytest.mark.parametrize("M,d", FMT_SHAPES)
+def test_quantize_mxint4_bit_exact(tq, oracle, M, d):
+    z = _format_input(M, d, 500 + M)
+    want_c, want_s = oracle.quantize_mxint4(z)
+    c, s = tq.torq_quantize_f32_fmt(torch.from_numpy(z).to(DEV), tq.TORQ_FMT_MXINT4)
+    torch.cuda.synchronize()
+    assert np.array_equal(_np(s), want_s) and np.array_equal(_np(c), want_c)
+
+
+@pytest.mark.parametrize("M,d", FMT_SHAPES)
+@pytest.mark.parametrize("gs", [1.0, 0.0123, 2.0 ** -20])
+def test_quantize_nvfp4_bit_exact(tq, oracle, M, d, gs):
+    z = _format_input(M, d, 600 + M)
+    z[np.abs(z) > 1e30] = 1000.0                                       # keep z / S finite: the format's range is 448 * 6 * gs
+    want_c, want_s = oracle.quantize_nvfp4(z, gs)
+    c, s = tq.torq_quantize_f32_fmt(torch.from_numpy(z).to(DEV), tq.TORQ_FMT_NVFP4, gs)
+    torch.cuda.synchronize()
+    assert s.shape == (M, d // 16)
+    assert np.array_equal(_np(s), want_s) and np.array_equal(_np(c), want_c)
+
+
+def test_quantize_fmt_mxfp4_is_the_plain_entry_point(tq):
+    z = torch.from_numpy(_format_input(33, 1024, 7)).to(DEV)
+    c0, s0 = tq.torq_quantize_f32(z)
+    c1, s1 = tq.torq_quantize_f32_fmt(z, tq.TORQ_FMT_MXFP4)
+    assert torch.equal(c0, c1) and torch.equal(s0, s1)
+
+
+@pytest.mark.parametrize("d,G", [(4096, 128), (5120, 80), (1024, 32), (512, 16)])
+@pytest.mark.parametrize("fmt", [1, 2])
+def test_rotate_quantize_fmt_is_rotate_then_quantize(tq, oracle, d, G, fmt):
+    # the fused kernel's step 4 in the other formats = the stand-alone quantiser on the fused
+    # kernel's own rotated values, bit for bit (both kernel families: 32x32 and 16x16 MFMA)
+    M = 37
+    x = synth.activations(M, d, nu=3.0, outliers=6, outlier_scale=50.0, seed=700 + G).to(DEV)
+    Ri, Ra = synth.rotations(G, seed=71 + G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    gs = 0.05
+    z = tq.torq_rotate(rot, x)
+    c0, s0 = tq.torq_quantize_f32_fmt(z, fmt, gs)
+    c1, s1 = tq.torq_rotate_quantize_fmt(rot, x, fmt, gs)
+    torch.cuda.synchronize()
+    assert torch.equal(s0, s1) and torch.equal(c0, c1)
+    # and against the oracle on those same fp32 values
+    zc = _np(z)
+    want = oracle.quantize_mxint4(zc) if fmt == 1 else oracle.quantize_nvfp4(zc, gs)
+    assert np.array_equal(_np(c1), want[0]) and np.array_equal(_np(s1), want[1])
+    # format 0 through the same entry point is torq_rotate_quantize
+    c2, s2 = tq.torq_rotate_quantize_fmt(rot, x, tq.TORQ_FMT_MXFP4)
+    c3, s3 = tq.torq_rotate_quantize(rot, x)
+    assert torch.equal(c2, c3) and torch.equal(s2, s3)
+    rot.close()
