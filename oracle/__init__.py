@@ -69,6 +69,8 @@ def lib():
         L.torq_o_equalize.restype = i32
         L.torq_o_equalize.argtypes = [vp, i32, f64, vp]
         u64p = C.POINTER(C.c_uint64)
+        L.torq_o_equalize_butterfly.restype = None
+        L.torq_o_equalize_butterfly.argtypes = [vp, i32, vp, vp]
         L.torq_o_code_histogram.restype = None
         L.torq_o_code_histogram.argtypes = [vp, i64, i32, vp]
         L.torq_o_code_loss.restype = f64
@@ -304,6 +306,18 @@ def equalize(Sigma, eps=0.0):
     R = np.empty((B, B), np.float64)
     steps = lib().torq_o_equalize(_p(S), B, float(eps), _p(R))
     return R, S, steps
+
+
+def equalize_butterfly(Sigma):
+    """Butterfly variance equaliser.  Returns (R [B, B], R Sigma R^T, tangents [log2 B, B/2])."""
+    S = _arr(Sigma, np.float64).copy()
+    B = S.shape[0]
+    assert S.shape == (B, B) and B >= 2 and (B & (B - 1)) == 0
+    R = np.empty((B, B), np.float64)
+    L = B.bit_length() - 1
+    tangents = np.empty((L, B // 2), np.float64)
+    lib().torq_o_equalize_butterfly(_p(S), B, _p(R), _p(tangents))
+    return R, S, tangents
 
 
 def code_histogram(codes, d):

@@ -499,6 +499,54 @@ int torq_o_equalize(double *Sigma, int B, double eps, double *R)
     return steps;
 }
 
+/* The same goal -- an orthogonal R with diag(R Sigma R^T) = c 1 (Theorem 4.1, Section 5.1) --
+ * reached with plane rotations arranged as a butterfly, so that the result can be applied online
+ * in log2(B) rounds of B/2 independent plane rotations instead of as a dense matrix (Algorithm 1
+ * picks its pairs greedily, one after the other; the Schur-Horn argument does not care which
+ * orthogonal matrix reaches the constant diagonal).  B is a power of two.  Round t = 0, 1, ...
+ * pairs row p with row q = p + h, h = B / 2^(t+1), for every p whose bit h is clear, and turns
+ * the pair by the angle that makes its two diagonal entries EQUAL:
+ *
+ *   row_p' = cos row_p + sin row_q,  row_q' = -sin row_p + cos row_q
+ *   s_pp' - s_qq' = (a - b) cos 2theta + 2 g sin 2theta = 0   (a, b, g = s_pp, s_qq, s_pq)
+ *   theta = atan((b - a) / (2 g)) / 2 in (-pi/4, pi/4);  g = 0: pi/4 if a != b, else 0.
+ *
+ * After round t the diagonal is constant on every residue class of the row index modulo h (the
+ * mean of the 2^(t+1) entries it replaces), so after the last round it is the overall mean c.
+ * tangents[t * B/2 + i] = tan(theta) of the i-th pair (in increasing p) of round t. */
+void torq_o_equalize_butterfly(double *Sigma, int B, double *R, double *tangents)
+{
+    for (int i = 0; i < B; ++i)
+        for (int j = 0; j < B; ++j) R[i * B + j] = (i == j) ? 1.0 : 0.0;
+    int round = 0;
+    for (int h = B / 2; h >= 1; h /= 2, ++round) {
+        int pair = 0;
+        for (int p = 0; p < B; ++p) {
+            if (p & h) continue;
+            const int q = p + h;
+            const double a = Sigma[p * B + p], b = Sigma[q * B + q], g = Sigma[p * B + q];
+            double theta;
+            if (g != 0.0) theta = 0.5 * atan((b - a) / (2.0 * g));
+            else theta = (a != b) ? PI / 4.0 : 0.0;
+            const double cs = cos(theta), sn = sin(theta);
+            tangents[round * (B / 2) + pair++] = tan(theta);
+            for (int k = 0; k < B; ++k) {             /* rows of Sigma and of R */
+                double sp = Sigma[p * B + k], sq = Sigma[q * B + k];
+                Sigma[p * B + k] = cs * sp + sn * sq;
+                Sigma[q * B + k] = -sn * sp + cs * sq;
+                double rp = R[p * B + k], rq = R[q * B + k];
+                R[p * B + k] = cs * rp + sn * rq;
+                R[q * B + k] = -sn * rp + cs * rq;
+            }
+            for (int k = 0; k < B; ++k) {             /* columns of Sigma */
+                double sp = Sigma[k * B + p], sq = Sigma[k * B + q];
+                Sigma[k * B + p] = cs * sp + sn * sq;
+                Sigma[k * B + q] = -sn * sp + cs * sq;
+            }
+        }
+    }
+}
+
 /* ------------------------------------------- intra-block calibration -- */
 
 void torq_o_code_histogram(const uint8_t *codes, int64_t M, int d, uint64_t *counts)

@@ -127,6 +127,12 @@ void torq_o_block_gram(const uint16_t *x_bf16, int64_t M, int d, int G, double *
  * with opposite deviation signs could not be found. */
 int torq_o_equalize(double *Sigma, int B, double eps, double *R);
 
+/* The same output condition reached by a butterfly of plane rotations (B a power of two): round t
+ * turns the B/2 pairs (p, p + B / 2^(t+1)) by the angles that make each pair's two diagonal entries
+ * equal.  Sigma is overwritten with R Sigma R^T; R: B*B; tangents: log2(B) * B/2, the tangent of
+ * every pair's angle, rounds in order, pairs in increasing p. */
+void torq_o_equalize_butterfly(double *Sigma, int B, double *R, double *tangents);
+
 /* ---- intra-block calibration (Section 5.2, Algorithm 2, Appendix A.4 / A.5) ---- */
 
 /* Column-wise codebook histogram (Appendix A.5, N_j^(k)): counts[k * 8 + j] = number of blocks,

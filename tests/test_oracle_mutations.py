@@ -13,7 +13,8 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "oracle", "torq_oracle.c")
 PIN_FILES = ["tests/test_oracle_formats.py", "tests/test_oracle_rotation.py", "tests/test_oracle_gemm.py",
-             "tests/test_oracle_intra.py", "tests/test_oracle_other_formats.py"]
+             "tests/test_oracle_intra.py", "tests/test_oracle_other_formats.py",
+             "tests/test_oracle_butterfly.py"]
 
 # (name, text in torq_oracle.c, replacement)
 MUTATIONS = [
@@ -86,6 +87,13 @@ MUTATIONS = [
     ("nvfp4_scale_to_amax", "const float D = 6.0f * global_scale;", "const float D = 1.0f * global_scale;"),
     ("nvfp4_ignores_global_scale_in_S", "const float S = torq_o_e4m3_value(q) * global_scale;", "const float S = torq_o_e4m3_value(q);"),
     ("nvfp4_dequant_block_of_32", "(torq_o_e4m3_value(scales_e4m3[j / 16]) * global_scale)", "(torq_o_e4m3_value(scales_e4m3[j / 32]) * global_scale)"),
+    ("butterfly_angle_sign", "if (g != 0.0) theta = 0.5 * atan((b - a) / (2.0 * g));", "if (g != 0.0) theta = 0.5 * atan((a - b) / (2.0 * g));"),
+    ("butterfly_jacobi_angle", "if (g != 0.0) theta = 0.5 * atan((b - a) / (2.0 * g));", "if (g != 0.0) theta = 0.5 * atan(2.0 * g / (a - b + 1e-300));"),
+    ("butterfly_wrong_partner", "const int q = p + h;\n            const double a = Sigma[p * B + p], b = Sigma[q * B + q], g = Sigma[p * B + q];\n            double theta;",
+     "const int q = p + h;\n            const double a = Sigma[p * B + p], b = Sigma[q * B + q], g = Sigma[q * B + p ^ 1];\n            double theta;"),
+    ("butterfly_R_transposed", "R[p * B + k] = cs * rp + sn * rq;\n                R[q * B + k] = -sn * rp + cs * rq;",
+     "R[p * B + k] = cs * rp - sn * rq;\n                R[q * B + k] = sn * rp + cs * rq;"),
+    ("butterfly_skips_last_round", "for (int h = B / 2; h >= 1; h /= 2, ++round) {", "for (int h = B / 2; h >= 2; h /= 2, ++round) {"),
 ]
 
 
