@@ -198,6 +198,27 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16,
  *   R_inter_host  HOST, G*G floats out, row-major, for torq_rotation_create (Y = R_inter X)
  *   steps         HOST, optional: number of plane rotations used
  * Returns TORQ_OK, TORQ_EINVAL or TORQ_ECONVERGE. */
+/* The inter-block rotation as a BUTTERFLY of plane rotations (what Section 5.1 calls an efficient
+ * implementation of R_inter; Algorithm 1 itself picks its pairs greedily, one after the other, which
+ * leaves a dense G x G matrix to multiply online).  Round t = 0 .. log2(G) - 1 turns the G/2
+ * independent pairs of block rows (p, p + G / 2^(t+1)) by the angle that makes each pair's two
+ * diagonal entries of Sigma equal; after the last round diag(R Sigma R^T) = tr(Sigma)/G * 1, the
+ * same output condition (the equality case of Theorem 4.1).  Online this costs 2 fused multiply-adds
+ * per pair and element in fp32 instead of a dense contraction: torq_rotate_quantize on such a handle
+ * is bound by HBM at any G.
+ *
+ * torq_equalize_inter_butterfly (HOST, double):
+ *   Sigma_host     G*G doubles, symmetric, finite, not modified; G in {32, 64, 128, 256}
+ *   R_inter_host   optional, G*G floats out: the dense matrix of the returned tangents, for the
+ *                  oracle, for weights prepared elsewhere, or for torq_rotation_create
+ *   tangents_host  log2(G) * G/2 floats out: tan(theta) of every pair, rounds in order, pairs in
+ *                  increasing p; |tan| <= 1
+ * torq_rotation_create_butterfly: a handle whose inter-block rotation is that butterfly (any finite
+ * tangents are accepted: the rotation is orthogonal whatever they are).  Every entry point that takes
+ * a handle works on it; destroy it with torq_rotation_destroy.  Errors as torq_rotation_create. */
+int torq_equalize_inter_butterfly(const double *Sigma_host, int G, float *R_inter_host, float *tangents_host);
+int torq_rotation_create_butterfly(torq_rotation_t **out, int d, int G, const float *tangents_host,
+                                   const float *R_intra_host);
 size_t torq_block_gram_workspace_bytes(int G);
 int torq_block_gram(const void *x_bf16, int64_t M, int d, int G, double *Sigma,
                     void *workspace, size_t workspace_bytes, void *stream);

@@ -16,7 +16,8 @@ EXPORTS = [
     "torq_status_string", "torq_rotation_create", "torq_rotation_destroy", "torq_rotation_d",
     "torq_rotation_G", "torq_rotate_quantize", "torq_rotate", "torq_quantize_f32", "mxfp4_gemm",
     "torq_linear_workspace_bytes", "torq_linear", "mxfp4_gemm_workspace_bytes", "mxfp4_gemm_ws", "mxfp4_gemm_plan",
-    "torq_rotate_quantize_fmt", "torq_quantize_f32_fmt",
+    "torq_rotate_quantize_fmt", "torq_quantize_f32_fmt", "torq_equalize_inter_butterfly",
+    "torq_rotation_create_butterfly",
     "torq_linear_workspace_bytes_n", "torq_block_gram_workspace_bytes", "torq_block_gram",
     "torq_equalize_inter", "torq_code_histogram_workspace_bytes", "torq_code_histogram", "torq_intra_pair_scores",
     "torq_intra_best_angle", "torq_calibrate_intra", "torq_diag_mfma_burn",
@@ -63,6 +64,10 @@ def lib():
         L.mxfp4_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp]
         L.mxfp4_gemm_workspace_bytes.restype = sz
         L.mxfp4_gemm_workspace_bytes.argtypes = [i64, i64, i32]
+        L.torq_equalize_inter_butterfly.restype = i32
+        L.torq_equalize_inter_butterfly.argtypes = [vp, i32, vp, vp]
+        L.torq_rotation_create_butterfly.restype = i32
+        L.torq_rotation_create_butterfly.argtypes = [C.POINTER(vp), i32, i32, vp, vp]
         L.torq_rotate_quantize_fmt.restype = i32
         L.torq_rotate_quantize_fmt.argtypes = [vp, vp, i64, i32, C.c_float, vp, vp, vp]
         L.torq_quantize_f32_fmt.restype = i32
@@ -141,6 +146,35 @@ class Rotation:
         self.handle = None
 
     __del__ = close
+
+
+class ButterflyRotation(Rotation):
+    """Handle whose inter-block rotation is a butterfly of plane rotations (tangents [log2 G, G/2])."""
+
+    def __init__(self, d: int, G: int, tangents, R_intra):
+        import numpy as np
+        T = np.ascontiguousarray(tangents, dtype=np.float32)
+        Ra = np.ascontiguousarray(R_intra, dtype=np.float32)
+        if T.shape != (G.bit_length() - 1, G // 2) or Ra.shape != (32, 32):
+            raise ValueError("tangents must be [log2 G, G/2] and R_intra [32, 32]")
+        h = C.c_void_p()
+        _check(lib().torq_rotation_create_butterfly(C.byref(h), d, G, T.ctypes.data_as(C.c_void_p),
+                                                    Ra.ctypes.data_as(C.c_void_p)), "torq_rotation_create_butterfly")
+        self.handle, self.d, self.G = h, d, G
+
+
+def torq_equalize_inter_butterfly(Sigma):
+    """Butterfly equaliser on the host.  Returns (R_inter float32 [G, G], tangents float32 [log2 G, G/2])."""
+    import numpy as np
+    S = np.ascontiguousarray(Sigma, dtype=np.float64)
+    G = S.shape[0]
+    if S.shape != (G, G):
+        raise ValueError("Sigma must be square")
+    R = np.empty((G, G), np.float32)
+    T = np.empty((max(G.bit_length() - 1, 1), max(G // 2, 1)), np.float32)
+    _check(lib().torq_equalize_inter_butterfly(S.ctypes.data_as(C.c_void_p), G, R.ctypes.data_as(C.c_void_p),
+                                               T.ctypes.data_as(C.c_void_p)), "torq_equalize_inter_butterfly")
+    return R, T
 
 
 def torq_rotate_quantize(rot: Rotation, x_bf16: torch.Tensor, codes=None, scales=None, stream=None):

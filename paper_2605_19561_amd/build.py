@@ -9,7 +9,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtorq.so")
-SOURCES = ["api.hip", "quantize.hip", "rotate_quant.hip", "mxfp4_gemm.hip", "mxfp4_gemm_skinny.hip", "block_gram.hip", "code_histogram.hip",
+SOURCES = ["api.hip", "quantize.hip", "rotate_quant.hip", "rotate_butterfly.hip", "mxfp4_gemm.hip", "mxfp4_gemm_skinny.hip", "block_gram.hip", "code_histogram.hip",
            "intra_calib.hip", "diag.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
@@ -20,7 +20,8 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
 
 # The rotate kernel post-processes its MFMA results with vector ALU code, so its accumulators are
 # kept in ordinary VGPRs (no v_accvgpr_read traffic); the GEMM needs the AGPR half for its tile.
-EXTRA = {"rotate_quant.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+EXTRA = {"rotate_quant.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+         "rotate_butterfly.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def build(verbose: bool = False) -> str:

@@ -47,6 +47,13 @@ int hip_fail(hipError_t e) {
   return TORQ_EHIP;
 }
 
+// the dense-matrix kernels, or the butterfly kernel for a handle made by torq_rotation_create_butterfly
+hipError_t rotate_any(const torq_rotation *r, const void *x_bf16, int64_t M, int format, float global_scale,
+                      uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
+  return r->butterfly ? torq::launch_rotate_butterfly(r, x_bf16, M, format, global_scale, codes, scales, z_out, stream)
+                      : torq::launch_rotate(r, x_bf16, M, format, global_scale, codes, scales, z_out, stream);
+}
+
 }  // namespace
 
 extern "C" {
@@ -88,6 +95,7 @@ int torq_rotation_create(torq_rotation_t **out, int d, int G, const float *R_int
   r->KS = (G + 31) / 32;
   r->device = dev;
   r->inter_hi = r->inter_lo = r->intra_hi = r->intra_lo = r->intra32_hi = r->intra32_lo = nullptr;
+  r->butterfly = nullptr;
 
   // R_inter, bf16 hi/lo, [G][KS*32] with zero padding: row b is the B operand
   // "column" b of R_inter^T (Algorithm 3 step 2: Y[b] = sum_b' R_inter[b][b'] X[b']).
@@ -150,7 +158,131 @@ void torq_rotation_destroy(torq_rotation_t *r) {
   if (r->intra_lo) (void)hipFree(r->intra_lo);
   if (r->intra32_hi) (void)hipFree(r->intra32_hi);
   if (r->intra32_lo) (void)hipFree(r->intra32_lo);
+  if (r->butterfly) (void)hipFree(r->butterfly);
   delete r;
+}
+
+// ---- R_inter as a butterfly of plane rotations -------------------------------------------------
+namespace {
+
+inline bool butterfly_size(int G) { return G == 32 || G == 64 || G == 128 || G == 256; }
+inline int log2i(int v) { int l = 0; while ((1 << l) < v) ++l; return l; }
+// position of the pair that holds row p in a round of stride h, pairs counted in increasing p
+inline int pair_index(int p, int h) { return ((p / (2 * h)) * h) + (p % h); }
+
+// R = J_last ... J_first in double; round t turns rows (p, p + G / 2^(t+1)) by atan(tan[t][pair])
+void butterfly_dense(const float *tangents, int G, std::vector<double> &R) {
+  R.assign((size_t)G * G, 0.0);
+  for (int i = 0; i < G; ++i) R[(size_t)i * G + i] = 1.0;
+  int t = 0;
+  for (int h = G / 2; h >= 1; h /= 2, ++t)
+    for (int p = 0; p < G; ++p) {
+      if (p & h) continue;
+      const double tn = tangents[t * (G / 2) + pair_index(p, h)];
+      const double cs = 1.0 / std::sqrt(1.0 + tn * tn), sn = tn * cs;
+      double *rp = &R[(size_t)p * G], *rq = &R[(size_t)(p + h) * G];
+      for (int k = 0; k < G; ++k) {
+        const double a = rp[k], b = rq[k];
+        rp[k] = cs * a + sn * b;
+        rq[k] = -sn * a + cs * b;
+      }
+    }
+}
+
+}  // namespace
+
+// The output condition of Algorithm 1 reached with a butterfly: round t makes the two diagonal
+// entries of every pair (p, p + G / 2^(t+1)) equal,
+//   (a - b) cos 2 theta + 2 g sin 2 theta = 0,  theta = atan((b - a) / (2 g)) / 2 in (-pi/4, pi/4)
+// (g = 0: pi/4 unless a = b), so that after round t the diagonal is constant on the residue classes of
+// the row index modulo the stride, and after the last round constant.
+int torq_equalize_inter_butterfly(const double *Sigma_host, int G, float *R_inter_host, float *tangents_host) {
+  if (!Sigma_host || !tangents_host || !butterfly_size(G)) return TORQ_EINVAL;
+  const size_t n = (size_t)G;
+  for (size_t i = 0; i < n * n; ++i)
+    if (!std::isfinite(Sigma_host[i])) return TORQ_EINVAL;
+  std::vector<double> S(Sigma_host, Sigma_host + n * n);
+  int t = 0;
+  for (int h = G / 2; h >= 1; h /= 2, ++t) {
+    // the pairs of a round are disjoint: angles first, then all rows, then all columns
+    std::vector<double> cs((size_t)G / 2), sn((size_t)G / 2);
+    for (int p = 0; p < G; ++p) {
+      if (p & h) continue;
+      const int q = p + h, i = pair_index(p, h);
+      const double a = S[p * n + p], b = S[q * n + q], g = S[p * n + q];
+      const double theta = g != 0.0 ? 0.5 * std::atan((b - a) / (2.0 * g)) : (a != b ? 0.78539816339744830962 : 0.0);
+      cs[i] = std::cos(theta);
+      sn[i] = std::sin(theta);
+      tangents_host[(size_t)t * (G / 2) + i] = (float)std::tan(theta);
+    }
+    for (int p = 0; p < G; ++p) {
+      if (p & h) continue;
+      const int i = pair_index(p, h);
+      double *rp = &S[p * n], *rq = &S[(size_t)(p + h) * n];
+      for (size_t k = 0; k < n; ++k) {
+        const double u = rp[k], v = rq[k];
+        rp[k] = cs[i] * u + sn[i] * v;
+        rq[k] = -sn[i] * u + cs[i] * v;
+      }
+    }
+    for (size_t k = 0; k < n; ++k) {
+      double *row = &S[k * n];
+      for (int p = 0; p < G; ++p) {
+        if (p & h) continue;
+        const int i = pair_index(p, h);
+        const double u = row[p], v = row[p + h];
+        row[p] = cs[i] * u + sn[i] * v;
+        row[p + h] = -sn[i] * u + cs[i] * v;
+      }
+    }
+  }
+  if (R_inter_host) {
+    // the dense matrix of the tangents as handed back (fp32), which is what the handle applies
+    std::vector<double> R;
+    butterfly_dense(tangents_host, G, R);
+    for (size_t i = 0; i < n * n; ++i) R_inter_host[i] = (float)R[i];
+  }
+  return TORQ_OK;
+}
+
+int torq_rotation_create_butterfly(torq_rotation_t **out, int d, int G, const float *tangents_host,
+                                   const float *R_intra_host) {
+  if (!out) return TORQ_EINVAL;
+  *out = nullptr;
+  if (!tangents_host || !R_intra_host || !butterfly_size(G)) return TORQ_EINVAL;
+  const int L = log2i(G), NJ = G / 32;
+  for (int i = 0; i < L * (G / 2); ++i)
+    if (!std::isfinite(tangents_host[i])) return TORQ_EINVAL;
+  std::vector<double> Rd;
+  butterfly_dense(tangents_host, G, Rd);
+  std::vector<float> Rf(Rd.begin(), Rd.end());
+  const int status = torq_rotation_create(out, d, G, Rf.data(), R_intra_host);
+  if (status != TORQ_OK) return status;
+
+  // per-row coefficients (rotate_butterfly.hip): the kernel carries u = value / sigma, sigma = the
+  // product of the cosines the row has met, so round t's update of row p with partner q = p ^ h is
+  // u_p += (+-tan theta) (sigma_q / sigma_p) u_q; lane b0 owns the rows 32 j + b0
+  const int NC = torq::butterfly_coef_count(G);
+  std::vector<float> coef((size_t)NC * 32, 0.f);
+  std::vector<double> sigma((size_t)G, 1.0), cosine((size_t)G);
+  int t = 0;
+  for (int h = G / 2; h >= 1; h /= 2, ++t) {
+    for (int p = 0; p < G; ++p) {
+      const bool low = (p & h) == 0;
+      const double tn = tangents_host[t * (G / 2) + pair_index(low ? p : p - h, h)];
+      coef[(size_t)(t * NJ + p / 32) * 32 + p % 32] = (float)((low ? tn : -tn) * sigma[p ^ h] / sigma[p]);
+      cosine[p] = 1.0 / std::sqrt(1.0 + tn * tn);
+    }
+    for (int p = 0; p < G; ++p) sigma[p] *= cosine[p];
+  }
+  for (int p = 0; p < G; ++p) coef[(size_t)(L * NJ + p / 32) * 32 + p % 32] = (float)sigma[p];
+  hipError_t e = upload(&(*out)->butterfly, coef);
+  if (e != hipSuccess) {
+    torq_rotation_destroy(*out);
+    *out = nullptr;
+    return hip_fail(e);
+  }
+  return TORQ_OK;
 }
 
 int torq_rotation_d(const torq_rotation_t *r) { return r ? r->d : TORQ_EINVAL; }
@@ -162,7 +294,7 @@ int torq_rotate_quantize(const torq_rotation_t *r, const void *x_bf16, int64_t M
   if (M == 0) return TORQ_OK;
   if (!x_bf16 || !codes || !scales) return TORQ_EINVAL;
   if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return TORQ_EALIGN;
-  hipError_t e = torq::launch_rotate(r, x_bf16, M, TORQ_FMT_MXFP4, 1.0f, codes, scales, nullptr, (hipStream_t)stream);
+  hipError_t e = rotate_any(r, x_bf16, M, TORQ_FMT_MXFP4, 1.0f, codes, scales, nullptr, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 
@@ -171,7 +303,7 @@ int torq_rotate(const torq_rotation_t *r, const void *x_bf16, int64_t M, float *
   if (M == 0) return TORQ_OK;
   if (!x_bf16 || !z_f32) return TORQ_EINVAL;
   if (misaligned(x_bf16) || misaligned(z_f32)) return TORQ_EALIGN;
-  hipError_t e = torq::launch_rotate(r, x_bf16, M, TORQ_FMT_MXFP4, 1.0f, nullptr, nullptr, z_f32, (hipStream_t)stream);
+  hipError_t e = rotate_any(r, x_bf16, M, TORQ_FMT_MXFP4, 1.0f, nullptr, nullptr, z_f32, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 
@@ -208,7 +340,7 @@ int torq_rotate_quantize_fmt(const torq_rotation_t *r, const void *x_bf16, int64
   if (M == 0) return TORQ_OK;
   if (!x_bf16 || !codes || !scales) return TORQ_EINVAL;
   if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return TORQ_EALIGN;
-  hipError_t e = torq::launch_rotate(r, x_bf16, M, format, global_scale, codes, scales, nullptr, (hipStream_t)stream);
+  hipError_t e = rotate_any(r, x_bf16, M, format, global_scale, codes, scales, nullptr, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 
@@ -268,7 +400,7 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q
   if (workspace_bytes < torq_linear_workspace_bytes(M, r->d)) return TORQ_EWORKSPACE;
   uint8_t *codes = static_cast<uint8_t *>(workspace);
   uint8_t *scales = codes + (((size_t)M * (size_t)(r->d / 2) + 255) & ~(size_t)255);
-  hipError_t e = torq::launch_rotate(r, x_bf16, M, TORQ_FMT_MXFP4, 1.0f, codes, scales, nullptr, (hipStream_t)stream);
+  hipError_t e = rotate_any(r, x_bf16, M, TORQ_FMT_MXFP4, 1.0f, codes, scales, nullptr, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
   // whatever the caller gave beyond the packed activations serves the GEMM's split-k pieces
   const size_t used = torq_linear_workspace_bytes(M, r->d);

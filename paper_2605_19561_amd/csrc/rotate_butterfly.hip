@@ -1,0 +1,248 @@
+// Rotate + quantise for an inter-block rotation that is a BUTTERFLY of plane rotations
+// (torq_equalize_inter_butterfly: log2 G rounds, round t turning the G/2 independent pairs of block
+// rows (p, p + G / 2^(t+1))), i.e. Algorithm 3's Y = R_inter X without the dense G x G contraction:
+// 2 fused multiply-adds per pair and element instead of 2 G per element on the matrix cores.  With it
+// the kernel is bound by HBM again at any G (Section 5.1's "efficient implementation" of R_inter;
+// Appendix A.7 counts O(B^2 K) for the dense form).
+//
+// The two rotations commute (R_inter mixes blocks, R_intra mixes positions), so the kernel applies
+// R_intra FIRST: X is exact in bf16, which makes the intra rotation two MFMA passes (R_intra split
+// into bf16 hi + lo) and leaves the result in fp32 registers in the layout the butterfly wants.
+//
+// One wave = one token-group (G blocks of 32) at a time; workgroups are persistent.
+//   * global -> registers (16 bytes per lane, coalesced) -> LDS (wave-private, 16-byte chunks of a
+//     64-byte row XOR-swizzled with (row >> 1) & 3), the next token-group's loads in flight while the
+//     current one is computed;
+//   * Z'^T = R_intra^T X^T per tile of 32 blocks on v_mfma_f32_32x32x16_bf16: B operand = two 8-byte
+//     LDS reads of row b per k-step; afterwards lane (b0 = l % 32, h = l / 32) holds
+//     v[j][r] = Z'[32 j + b0][16 h + r], j < G / 32, r < 16;
+//   * butterfly over the block index b = 32 j + b0 with the cosines deferred: a row carries
+//     u = (true value) / sigma, sigma = the product of the cosines of the pairs it has been in, and
+//         p' = c (p + t q)  becomes  u_p' = u_p + (t sigma_q / sigma_p) u_q,
+//         q' = c (q - t p)  becomes  u_q' = u_q - (t sigma_p / sigma_q) u_p      (t = tan theta),
+//     one FMA per value and round with a per-row coefficient from a host-built table; the final
+//     sigma multiplies once at the end.  Rounds with stride >= 32 pair registers of the same lane,
+//     rounds with stride 16 .. 1 pair lanes (DPP row rotate / quad permute for 8, 2, 1; ds_swizzle
+//     for 16 and 4);
+//   * step 4 as in rotate_kernel32: a lane holds sixteen consecutive positions of one block.
+#include "torq_device.h"
+#include "torq_internal.h"
+
+namespace torq {
+
+namespace {
+
+template <int PATTERN>
+__device__ __forceinline__ float swizzle_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), PATTERN));
+}
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+// the value of lane l ^ S (S < 32; lanes 0..31 and 32..63 separately)
+template <int S>
+__device__ __forceinline__ float lane_xor(float v) {
+  if constexpr (S == 1) return dpp_f32<0xB1>(v);          // quad_perm [1, 0, 3, 2]
+  else if constexpr (S == 2) return dpp_f32<0x4E>(v);     // quad_perm [2, 3, 0, 1]
+  else if constexpr (S == 8) return dpp_f32<0x128>(v);    // row_ror 8: i <- i + 8 mod 16
+  else if constexpr (S == 4) return swizzle_f32<0x101F>(v);   // bit mode: and 0x1f, xor 4
+  else return swizzle_f32<0x401F>(v);                         // xor 16
+}
+
+}  // namespace
+
+// coefficient table, [NC][32] floats, lane b0 reads column b0 (row 32 j + b0 of the butterfly):
+//   round t = 0 .. log2 G - 1, entry t NJ + j:  the row's coefficient of that round (signed: + on the
+//                                               row with the stride bit clear, - on its partner)
+//   entry (log2 G) NJ + j:                      the row's final sigma
+// G = 256 needs 128 accumulators, 64 staging registers and 72 coefficients per lane: one workgroup
+// per CU there (512 registers per lane), two otherwise.
+template <int NJ, int FMT>
+__global__ void __launch_bounds__(256, NJ == 8 ? 1 : 2)
+rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__restrict__ coef,
+                        const uint4 *__restrict__ intra_hi_frag, const uint4 *__restrict__ intra_lo_frag,
+                        uint2 *__restrict__ codes, uint8_t *__restrict__ scales, float *__restrict__ z_out,
+                        float global_scale) {
+  constexpr int G = 32 * NJ;
+  constexpr int LJ = NJ == 1 ? 0 : NJ == 2 ? 1 : NJ == 4 ? 2 : 3;     // rounds inside a lane
+  constexpr int NC = (LJ + 6) * NJ;
+  constexpr int TG_BYTES = G * 64;
+  constexpr int CH = TG_BYTES / 16 / 64;                               // 16-byte chunks per lane (= 2 NJ)
+  extern __shared__ __attribute__((aligned(16))) char lds[];
+
+  const int lane = threadIdx.x & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const int b0 = lane & 31, h = lane >> 5;
+  char *const my = lds + wave * TG_BYTES;                              // this wave's token-group
+
+  float cf[NC];
+#pragma unroll
+  for (int c = 0; c < NC; ++c) cf[c] = coef[c * 32 + b0];
+  bf16x8 Ah[2], Al[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    Ah[t] = __builtin_bit_cast(bf16x8, intra_hi_frag[t * 64 + lane]);
+    Al[t] = __builtin_bit_cast(bf16x8, intra_lo_frag[t * 64 + lane]);
+  }
+
+  // chunk c = lane + 64 i of the token-group: row c / 4, 16-byte part c % 4
+  int st_off[CH];
+#pragma unroll
+  for (int i = 0; i < CH; ++i) {
+    const int c = lane + 64 * i, row = c >> 2;
+    st_off[i] = row * 64 + (((c & 3) ^ ((row >> 1) & 3)) * 16);
+  }
+  // B operand of k-step t, tile j: the 8-byte pieces at positions 16 t + 4 h and 16 t + 8 + 4 h of
+  // row 32 j + b0, i.e. 16-byte part 2 t (+ 1), half h; (row >> 1) & 3 does not depend on j
+  int rd_off[2][2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t)
+#pragma unroll
+    for (int u = 0; u < 2; ++u) rd_off[t][u] = b0 * 64 + (((2 * t + u) ^ ((b0 >> 1) & 3)) * 16) + 8 * h;
+
+  const int64_t wave_id = (int64_t)blockIdx.x * 4 + wave, nwave = (int64_t)gridDim.x * 4;
+  // (a plain vector type: an array of the HIP struct type assigned under a condition is not
+  // promoted to registers)
+  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 *xv = reinterpret_cast<const u32x4 *>(x);
+  u32x4 stage[CH];
+#define TORQ_LOAD_TG(TG_)                                                                     \
+  _Pragma("unroll") for (int i = 0; i < CH; ++i) stage[i] = xv[(TG_) * (TG_BYTES / 16) + lane + 64 * i];
+
+  int64_t tg = wave_id;
+  if (tg < TG) { TORQ_LOAD_TG(tg) }
+  for (; tg < TG; tg += nwave) {
+    // the wave is the only user of its LDS region: its own reads of the previous token-group
+    // have returned (their values were consumed), so the stores need no barrier
+#pragma unroll
+    for (int i = 0; i < CH; ++i) *reinterpret_cast<u32x4 *>(my + st_off[i]) = stage[i];
+    if (tg + nwave < TG) { TORQ_LOAD_TG(tg + nwave) }
+
+    // ---- intra-block rotation: Z'^T = R_intra^T X^T, two passes (R_intra hi, lo)
+    float v[NJ][16];
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      f32x16 acc;
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const uint2 lo8 = *reinterpret_cast<const uint2 *>(my + j * 32 * 64 + rd_off[t][0]);
+        const uint2 hi8 = *reinterpret_cast<const uint2 *>(my + j * 32 * 64 + rd_off[t][1]);
+        const bf16x8 xb = __builtin_bit_cast(bf16x8, make_uint4(lo8.x, lo8.y, hi8.x, hi8.y));
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Al[t], xb, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[t], xb, acc, 0, 0, 0);
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) v[j][r] = acc[r];
+    }
+
+    // ---- inter-block rotation: the butterfly over b = 32 j + b0 (all indices are literals after
+    // unrolling: cf stays in registers)
+#pragma unroll
+    for (int m = 0; m < LJ; ++m) {                             // strides 32 hj: pairs of tiles
+      const int hj = NJ >> (m + 1);
+#pragma unroll
+      for (int j = 0; j < NJ; ++j)
+        if ((j & hj) == 0) {
+          const float tp = cf[m * NJ + j], tq = cf[m * NJ + j + hj];
+#pragma unroll
+          for (int r = 0; r < 16; ++r) {
+            const float p = v[j][r], q = v[j + hj][r];
+            v[j][r] = fmaf(tp, q, p);
+            v[j + hj][r] = fmaf(tq, p, q);
+          }
+        }
+    }
+#define TORQ_LANE_ROUND(IDX_, S_)                                               \
+  _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                              \
+    const float t = cf[(LJ + (IDX_)) * NJ + j];                               \
+    _Pragma("unroll") for (int r = 0; r < 16; ++r) v[j][r] = fmaf(t, lane_xor<S_>(v[j][r]), v[j][r]); \
+  }
+    TORQ_LANE_ROUND(0, 16) TORQ_LANE_ROUND(1, 8) TORQ_LANE_ROUND(2, 4) TORQ_LANE_ROUND(3, 2) TORQ_LANE_ROUND(4, 1)
+#undef TORQ_LANE_ROUND
+
+    // ---- the rows' sigma, then step 4
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {
+      const float rs = cf[(LJ + 5) * NJ + j];
+      float zz[16];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) zz[r] = v[j][r] * rs;
+      const int64_t blkidx = tg * G + 32 * j + b0;              // global block index
+      if constexpr (FMT == FMT_NVFP4) {
+        const float amax = fmaxf(amax8(zz), amax8(zz + 8));
+        const uint32_t sc = e4m3_from_f32(__fdiv_rn(amax, 6.0f * global_scale));
+        const float S = e4m3_to_f32(sc) * global_scale;
+        codes[blkidx * 2 + h] = make_uint2(pack8_nvfp4(zz, S), pack8_nvfp4(zz + 8, S));
+        scales[blkidx * 2 + h] = (uint8_t)sc;
+      } else if constexpr (FMT != FMT_NONE) {
+        float amax = fmaxf(amax8(zz), amax8(zz + 8));
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(amax), __float_as_uint(amax), false, false);
+        amax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        const uint32_t byte = e8m0_from_amax(amax);
+        if constexpr (FMT == FMT_MXINT4) {
+          const float inv = e8m0_inverse_f32(byte);
+          codes[blkidx * 2 + h] = make_uint2(pack8_int4(zz, inv), pack8_int4(zz + 8, inv));
+        } else {
+          const float sc = e8m0_to_f32(byte);
+          codes[blkidx * 2 + h] = make_uint2(pack8_e2m1(zz, sc), pack8_e2m1(zz + 8, sc));
+        }
+        if (h == 0) scales[blkidx] = (uint8_t)byte;
+      } else {
+        float4 *o = reinterpret_cast<float4 *>(z_out + blkidx * 32 + 16 * h);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) o[q] = make_float4(zz[4 * q], zz[4 * q + 1], zz[4 * q + 2], zz[4 * q + 3]);
+      }
+    }
+  }
+}
+
+#undef TORQ_LOAD_TG
+
+int butterfly_coef_count(int G) {
+  const int NJ = G / 32, LJ = NJ == 1 ? 0 : NJ == 2 ? 1 : NJ == 4 ? 2 : 3;
+  return (LJ + 6) * NJ;
+}
+
+template <int NJ>
+static hipError_t launch_nj(const torq_rotation *r, const void *x, int64_t TG, int format, float global_scale,
+                            uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
+  const size_t lds_bytes = 4 * (size_t)NJ * 32 * 64;
+  int64_t grid = (NJ == 8 ? 1 : 2) * 256;                     // resident workgroups of 4 waves
+  if (grid * 4 > TG) grid = (TG + 3) / 4;
+  const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
+  const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
+  const uint4 *xx = reinterpret_cast<const uint4 *>(x);
+  uint2 *cc = reinterpret_cast<uint2 *>(codes);
+  switch (z_out ? FMT_NONE : format) {
+#define TORQ_BF_CASE(F_, GS_)                                                                                  \
+  case F_:                                                                                                     \
+    hipLaunchKernelGGL((rotate_butterfly_kernel<NJ, F_>), dim3((unsigned)grid), dim3(256), lds_bytes, stream, xx, TG, \
+                       r->butterfly, ih, il, cc, scales, z_out, GS_);                                          \
+    break;
+    TORQ_BF_CASE(FMT_NONE, 1.0f) TORQ_BF_CASE(FMT_MXFP4, 1.0f) TORQ_BF_CASE(FMT_MXINT4, 1.0f)
+    TORQ_BF_CASE(FMT_NVFP4, global_scale)
+#undef TORQ_BF_CASE
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
+}
+
+// r->butterfly holds the coefficient table; G in {32, 64, 128, 256}
+hipError_t launch_rotate_butterfly(const torq_rotation *r, const void *x_bf16, int64_t M, int format,
+                                   float global_scale, uint8_t *codes, uint8_t *scales, float *z_out,
+                                   hipStream_t stream) {
+  const int64_t TG = M * (int64_t)(r->d / 32 / r->G);
+  if (TG == 0) return hipSuccess;
+  switch (r->G / 32) {
+    case 1: return launch_nj<1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
+    case 2: return launch_nj<2>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
+    case 4: return launch_nj<4>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
+    case 8: return launch_nj<8>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
+  }
+  return hipErrorInvalidValue;
+}
+
+}  // namespace torq

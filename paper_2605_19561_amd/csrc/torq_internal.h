@@ -17,6 +17,9 @@ struct torq_rotation {
   uint16_t *intra_hi, *intra_lo;
   // the same matrix as the A operand of v_mfma_f32_32x32x16_bf16 (two k-steps), bf16 hi and lo
   uint16_t *intra32_hi, *intra32_lo;
+  // optional: R_inter as a butterfly of plane rotations (rotate_butterfly.hip), the per-lane
+  // coefficient table [butterfly_coef_count(G)][32]; nullptr for a dense R_inter
+  float *butterfly;
 };
 
 namespace torq {
@@ -30,6 +33,12 @@ hipError_t launch_quantize_f32(const float *z, int64_t nblk, int format, float g
 // z_out != nullptr writes the rotated fp32 values instead of quantising to `format`.
 hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, int format, float global_scale,
                          uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream);
+
+// The same for a handle whose R_inter is a butterfly (r->butterfly != nullptr; G in 32, 64, 128, 256).
+int butterfly_coef_count(int G);
+hipError_t launch_rotate_butterfly(const torq_rotation *r, const void *x_bf16, int64_t M, int format,
+                                   float global_scale, uint8_t *codes, uint8_t *scales, float *z_out,
+                                   hipStream_t stream);
 
 // workspace: optional device scratch of mxfp4_gemm_workspace_bytes(M, N, d) bytes; with it, shapes
 // with few output tiles and a long reduction are cut along k (fp32 pieces added in a fixed order).

@@ -56,3 +56,71 @@ def test_equalize_inter_trivial_and_invalid_inputs():
     assert L.torq_block_gram(good, 4, 4096, 48, good, good, 1 << 30, None) == binding.TORQ_EINVAL   # 128 % 48
     assert L.torq_block_gram(good, 4, 4096, 128, good, good, 16, None) == binding.TORQ_EWORKSPACE
     assert L.torq_block_gram(C.c_void_p(0x1004), 4, 4096, 128, good, good, 1 << 30, None) == binding.TORQ_EALIGN
+
+
+# ---- the butterfly equaliser (Section 5.1's output condition, reached in log2 G rounds) ------------
+@pytest.mark.parametrize("G,seed", [(32, 11), (64, 12), (128, 13), (256, 14)])
+def test_equalize_inter_butterfly_matches_the_oracle_and_the_output_condition(oracle, G, seed):
+    Sigma = _gram(192, G, seed)
+    c = np.trace(Sigma) / G
+    R, T = binding.torq_equalize_inter_butterfly(Sigma)
+    R_o, S_o, T_o = oracle.equalize_butterfly(Sigma)
+    L = G.bit_length() - 1
+    assert T.shape == (L, G // 2) and T.dtype == np.float32
+    assert np.abs(T.astype(np.float64) - T_o).max() <= 1e-6            # |tan theta| <= 1, handed back in fp32
+    assert np.abs(T).max() <= 1.0 + 1e-6
+    assert np.abs(R.astype(np.float64) - R_o).max() <= 2e-6
+    Rd = R.astype(np.float64)
+    assert np.abs(Rd @ Rd.T - np.eye(G)).max() <= 1e-5
+    assert np.abs(np.diag(Rd @ Sigma @ Rd.T) - c).max() <= 2e-5 * c
+    before = np.diag(Sigma)
+    assert before.max() / before.min() > 20.0
+
+
+def test_equalize_inter_butterfly_dense_matrix_is_the_product_of_the_rounds():
+    """R handed back = the plane rotations of the tangents handed back, round after round, round t
+    pairing rows (p, p + G / 2^(t+1)) with the pairs counted in increasing p."""
+    G = 32
+    Sigma = _gram(96, G, 21)
+    R, T = binding.torq_equalize_inter_butterfly(Sigma)
+    P = np.eye(G)
+    h, t = G // 2, 0
+    while h >= 1:
+        J = np.eye(G)
+        i = 0
+        for p in range(G):
+            if p & h:
+                continue
+            th = np.arctan(float(T[t, i]))
+            J[p, p] = J[p + h, p + h] = np.cos(th)
+            J[p, p + h] = np.sin(th)
+            J[p + h, p] = -np.sin(th)
+            i += 1
+        P = J @ P
+        h //= 2
+        t += 1
+    assert np.abs(P - R).max() <= 1e-6
+
+
+def test_equalize_inter_butterfly_trivial_and_invalid_inputs():
+    R, T = binding.torq_equalize_inter_butterfly(np.eye(32) * 2.5)
+    assert np.array_equal(R, np.eye(32, dtype=np.float32)) and not T.any()
+    L = binding.lib()
+    p = lambda a: a.ctypes.data_as(C.c_void_p)
+    S = np.eye(32)
+    Rbuf = np.empty((32, 32), np.float32)
+    Tbuf = np.empty((5, 16), np.float32)
+    assert L.torq_equalize_inter_butterfly(None, 32, p(Rbuf), p(Tbuf)) == binding.TORQ_EINVAL
+    assert L.torq_equalize_inter_butterfly(p(S), 32, p(Rbuf), None) == binding.TORQ_EINVAL
+    assert L.torq_equalize_inter_butterfly(p(S), 32, None, p(Tbuf)) == binding.TORQ_OK     # R is optional
+    for G in (0, 16, 48, 96, 512):
+        assert L.torq_equalize_inter_butterfly(p(S), G, p(Rbuf), p(Tbuf)) == binding.TORQ_EINVAL
+    S[3, 4] = np.nan
+    assert L.torq_equalize_inter_butterfly(p(S), 32, p(Rbuf), p(Tbuf)) == binding.TORQ_EINVAL
+    # handle creation validates before it touches a device
+    h = C.c_void_p()
+    Ri = np.eye(32, dtype=np.float32)
+    assert L.torq_rotation_create_butterfly(C.byref(h), 4096, 48, p(Tbuf), p(Ri)) == binding.TORQ_EINVAL
+    assert L.torq_rotation_create_butterfly(C.byref(h), 4096, 32, None, p(Ri)) == binding.TORQ_EINVAL
+    bad = np.full((5, 16), np.inf, np.float32)
+    assert L.torq_rotation_create_butterfly(C.byref(h), 4096, 32, p(bad), p(Ri)) == binding.TORQ_EINVAL

@@ -668,3 +668,123 @@ def test_rotate_quantize_fmt_is_rotate_then_quantize(tq, oracle, d, G, fmt):
     c3, s3 = tq.torq_rotate_quantize(rot, x)
     assert torch.equal(c2, c3) and torch.equal(s2, s3)
     rot.close()
+
+
+# ------------------------- butterfly inter-block rotation (Section 5.1, efficient R_inter) ----
+
+def _butterfly_dense(T, G):
+    """The product of the rounds' plane rotations in float64 (round t pairs rows p, p + G / 2^(t+1),
+    pairs counted in increasing p): the matrix the oracle's rotation is given."""
+    R = np.eye(G)
+    h, t = G // 2, 0
+    while h >= 1:
+        lows = [p for p in range(G) if not p & h]
+        th = np.arctan(np.asarray(T[t], np.float64))
+        c, s = np.cos(th), np.sin(th)
+        P, Q = R[lows].copy(), R[[p + h for p in lows]].copy()
+        R[lows] = c[:, None] * P + s[:, None] * Q
+        R[[p + h for p in lows]] = -s[:, None] * P + c[:, None] * Q
+        h //= 2
+        t += 1
+    return R
+
+
+# token-groups: fewer than one workgroup's four waves, ragged, several per wave (2500 > 2048 waves)
+BUTTERFLY_CASES = [(3, 1024, 32), (2500, 1024, 32), (37, 4096, 64), (21, 8192, 128), (64, 4096, 128), (9, 16384, 256),
+                   (5, 8192, 256)]
+
+
+@pytest.mark.parametrize("M,d,G", BUTTERFLY_CASES)
+def test_butterfly_rotate_within_1e3_of_row_rms(tq, oracle, M, d, G):
+    x = synth.activations(M, d, nu=3.0, outliers=max(2, d // 200), outlier_scale=50.0, seed=900 + G + M)
+    rng = np.random.default_rng(G + M)
+    L = G.bit_length() - 1
+    T = rng.uniform(-1.0, 1.0, size=(L, G // 2)).astype(np.float32)     # any angles in [-pi/4, pi/4]
+    _, Ra = synth.rotations(G, seed=79 + G)
+    R = _butterfly_dense(T, G)
+    assert np.abs(R @ R.T - np.eye(G)).max() <= 1e-12
+    want = oracle.rotate(synth.bf16_bits(x), G, R.astype(np.float32), Ra).astype(np.float64)
+    rot = tq.ButterflyRotation(d, G, T, Ra)
+    got = _np(tq.torq_rotate(rot, x.to(DEV))).astype(np.float64)
+    torch.cuda.synchronize()
+    rms = np.sqrt((want ** 2).mean(axis=1, keepdims=True))
+    err = np.abs(got - want) / rms
+    assert err.max() <= 1e-3, (err.max(), np.unravel_index(err.argmax(), err.shape))
+    rot.close()
+
+
+@pytest.mark.parametrize("G", [32, 64, 128, 256])
+def test_butterfly_handle_from_the_oracles_equaliser(tq, oracle, G):
+    # tangents straight from the oracle's butterfly equaliser: the handle applies the oracle's R,
+    # and the rotated sample has equal block energies (the output condition of Section 5.1)
+    M, d = 96, 32 * G * 2
+    x = synth.activations(M, d, nu=3.0, outliers=max(2, G // 8), outlier_scale=50.0, seed=950 + G)
+    xb = synth.bf16_bits(x)
+    Sigma = oracle.block_gram(xb, G)
+    R_o, _, T_o = oracle.equalize_butterfly(Sigma)
+    Ra = np.eye(32, dtype=np.float32)
+    want = oracle.rotate(xb, G, R_o.astype(np.float32), Ra).astype(np.float64)
+    rot = tq.ButterflyRotation(d, G, T_o.astype(np.float32), Ra)
+    got = _np(tq.torq_rotate(rot, x.to(DEV))).astype(np.float64)
+    rms = np.sqrt((want ** 2).mean(axis=1, keepdims=True))
+    assert (np.abs(got - want) / rms).max() <= 1e-3
+    c = np.trace(Sigma) / G
+    energies = (got.reshape(M * d // (32 * G), G, 32) ** 2).sum(axis=2).mean(axis=0)
+    assert np.diag(Sigma).max() / np.diag(Sigma).min() > 20.0
+    assert np.abs(energies - c).max() <= 2e-3 * c
+    rot.close()
+
+
+@pytest.mark.parametrize("M,d,G", [(2100, 1024, 32), (19, 2048, 64), (33, 8192, 128), (6, 8192, 256)])
+def test_butterfly_rotate_quantize_against_oracle(tq, oracle, M, d, G):
+    x = synth.activations(M, d, nu=3.0, outliers=max(2, d // 200), outlier_scale=50.0, seed=970 + G)
+    rng = np.random.default_rng(3 * G)
+    T = rng.uniform(-1.0, 1.0, size=(G.bit_length() - 1, G // 2)).astype(np.float32)
+    _, Ra = synth.rotations(G, seed=80 + G)
+    rot = tq.ButterflyRotation(d, G, T, Ra)
+    xd = x.to(DEV)
+    zg = tq.torq_rotate(rot, xd)
+    # (1) the fused kernel = the stand-alone quantiser on its own rotated values, in every format
+    gs = 0.05
+    for fmt in (tq.TORQ_FMT_MXFP4, tq.TORQ_FMT_MXINT4, tq.TORQ_FMT_NVFP4):
+        c0, s0 = tq.torq_quantize_f32_fmt(zg, fmt, gs)
+        c1, s1 = tq.torq_rotate_quantize_fmt(rot, xd, fmt, gs)
+        assert torch.equal(s0, s1) and torch.equal(c0, c1), fmt
+    got_c, got_s = tq.torq_rotate_quantize(rot, xd)
+    c0, s0 = tq.torq_quantize_f32(zg)
+    torch.cuda.synchronize()
+    assert torch.equal(got_c, c0) and torch.equal(got_s, s0)
+    # (2) and bit for bit the oracle's quantisers on those same fp32 values
+    zc = _np(zg)
+    want_c, want_s = oracle.quantize(zc)
+    assert np.array_equal(_np(got_c), want_c) and np.array_equal(_np(got_s), want_s)
+    # (3) against the oracle's own rotation: differences only within the rotation's error bar of a
+    # rounding boundary (codes) or of a power of two (scales)
+    z = oracle.rotate(synth.bf16_bits(x), G, _butterfly_dense(T, G).astype(np.float32), Ra)
+    want_c, want_s = oracle.quantize(z)
+    got_c, got_s = _np(got_c), _np(got_s)
+    rms = np.sqrt((z.astype(np.float64) ** 2).mean(axis=1, keepdims=True))
+    tol = 1e-3 * rms
+    sdiff = got_s != want_s
+    assert sdiff.mean() <= 0.002
+    unpack = lambda c: np.stack([c & 15, c >> 4], axis=-1).reshape(M, d)
+    gc, wc = unpack(got_c), unpack(want_c)
+    cdiff = (gc != wc) & ~np.repeat(sdiff, 32, axis=1)
+    slack, s = _boundary_slack(z, want_s, tol)
+    near = slack * s <= np.broadcast_to(tol, slack.shape)
+    tiny = np.abs(z) <= np.broadcast_to(tol, z.shape)
+    assert np.all(near[cdiff] | tiny[cdiff])
+    assert cdiff.mean() <= 0.005
+    rot.close()
+
+
+def test_butterfly_identity_and_empty(tq, oracle):
+    # all tangents 0 and R_intra = I: the kernel hands x through exactly
+    M, d, G = 11, 4096, 64
+    x = synth.activations(M, d, seed=33)
+    rot = tq.ButterflyRotation(d, G, np.zeros((6, 32), np.float32), np.eye(32, dtype=np.float32))
+    z = tq.torq_rotate(rot, x.to(DEV))
+    assert torch.equal(z.cpu(), x.to(torch.float32))
+    c, s = tq.torq_rotate_quantize(rot, torch.empty((0, d), dtype=torch.bfloat16, device=DEV))
+    assert c.numel() == 0 and s.numel() == 0
+    rot.close()
