@@ -192,6 +192,9 @@ def main():
         # the kernel moves towards the HBM roofline
         for dd, gg in ((4096, 32), (8192, 32), (8192, 64)):
             print(json.dumps(sweep_line(tq, synth, dd, args.steps, args.warmup, G=gg)), flush=True)
+        # R_inter as a butterfly of plane rotations (Section 5.1's efficient form): no G x G contraction
+        for dd, gg in ((8192, 32), (8192, 64), (8192, 128), (8192, 256), (28672, 128)):
+            print(json.dumps(sweep_line(tq, synth, dd, args.steps, args.warmup, G=gg, butterfly=True)), flush=True)
         # the other block formats of Section 6 through the same kernel
         for ff in (1, 2):
             print(json.dumps(sweep_line(tq, synth, 8192, args.steps, args.warmup, fmt=ff)), flush=True)
@@ -263,8 +266,9 @@ def cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d):
             "gemm_GFLOPps": round(2.0 * gm * gn * d / t_gemm / 1e9, 3)}
 
 
-def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0):
-    """rotate+quantise alone on X [16384, d] (the memory-bound sweep); fmt 1 / 2: MXINT4 / NVFP4 output."""
+def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0, butterfly=False):
+    """rotate+quantise alone on X [16384, d] (the memory-bound sweep); fmt 1 / 2: MXINT4 / NVFP4 output;
+    butterfly: R_inter as log2 G rounds of plane rotations instead of a dense G x G matrix."""
     import torch
     dev = "cuda:0"
     M = 16384
@@ -272,7 +276,12 @@ def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0):
     x = synth.activations(M, d, nu=3.0, outliers=round(0.005 * d), outlier_scale=50.0, seed=synth.SEED_BASE + 5,
                           device=dev)
     Ri, Ra = synth.rotations(G)
-    rot = tq.Rotation(d, G, Ri, Ra)
+    if butterfly:
+        import numpy as np
+        T = np.random.default_rng(synth.SEED_BASE + 6).uniform(-1, 1, (G.bit_length() - 1, G // 2)).astype(np.float32)
+        rot = tq.ButterflyRotation(d, G, T, Ra)
+    else:
+        rot = tq.Rotation(d, G, Ri, Ra)
     codes = torch.empty((M, d // 2), dtype=torch.uint8, device=dev)
     scales = torch.empty((M, d // (16 if fmt == 2 else 32)), dtype=torch.uint8, device=dev)
     gs = 0.01                                          # NVFP4's tensor-wide scale (unused otherwise)
@@ -294,11 +303,12 @@ def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0):
     bytes_per_element = 2.0 + 0.5 + (1.0 / 16 if fmt == 2 else 1.0 / 32)
     gbs = M * d * bytes_per_element / (ms * 1e-3) / 1e9
     rot.close()
-    name = ("", " -> MXINT4", " -> NVFP4")[fmt]
+    name = ("", " -> MXINT4", " -> NVFP4")[fmt] + (", butterfly R_inter" if butterfly else "")
+    mfma_flop = 2 * 64 if butterfly else 2 * 2 * G + 3 * 64      # per element: bf16 passes of the contractions
     return {"metric": "torq_rotate_quantize bandwidth", "value": round(gbs, 1), "unit": "GB/s",
             "config": {"workload": f"sweep: X bf16 [{M}, {d}], G={G}{name}"}, "ms": round(ms, 4),
             "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
-            "mfma_bf16_tflops": round(M * d * (2 * 2 * G + 3 * 64) / (ms * 1e-3) / 1e12, 1)}
+            "mfma_bf16_tflops": round(M * d * mfma_flop / (ms * 1e-3) / 1e12, 1)}
 
 
 def gram_line(tq, x, G, steps, warmup):

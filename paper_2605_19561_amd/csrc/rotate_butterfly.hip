@@ -22,8 +22,11 @@
 //         q' = c (q - t p)  becomes  u_q' = u_q - (t sigma_p / sigma_q) u_p      (t = tan theta),
 //     one FMA per value and round with a per-row coefficient from a host-built table; the final
 //     sigma multiplies once at the end.  Rounds with stride >= 32 pair registers of the same lane,
-//     rounds with stride 16 .. 1 pair lanes (DPP row rotate / quad permute for 8, 2, 1; ds_swizzle
-//     for 16 and 4);
+//     rounds with stride 16 .. 1 pair lanes.  Block row b0 of a tile sits in lane
+//         n = 16 b0[4] ^ 15 b0[3] ^ 7 b0[2] ^ 2 b0[1] ^ b0[0]
+//     so that the partners of strides 8, 4, 2, 1 are the lanes n ^ 15, n ^ 7, n ^ 2, n ^ 1: DPP
+//     row_mirror, row_half_mirror and two quad permutes, each fused into its multiply-add
+//     (v_fmac_f32_dpp, one instruction per value and round); stride 16 is a ds_swizzle;
 //   * step 4 as in rotate_kernel32: a lane holds sixteen consecutive positions of one block.
 #include "torq_device.h"
 #include "torq_internal.h"
@@ -36,23 +39,38 @@ template <int PATTERN>
 __device__ __forceinline__ float swizzle_f32(float v) {
   return __int_as_float(__builtin_amdgcn_ds_swizzle(__float_as_int(v), PATTERN));
 }
-template <int CTRL>
-__device__ __forceinline__ float dpp_f32(float v) {
-  return __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(v), CTRL, 0xF, 0xF, true));
-}
-// the value of lane l ^ S (S < 32; lanes 0..31 and 32..63 separately)
-template <int S>
-__device__ __forceinline__ float lane_xor(float v) {
-  if constexpr (S == 1) return dpp_f32<0xB1>(v);          // quad_perm [1, 0, 3, 2]
-  else if constexpr (S == 2) return dpp_f32<0x4E>(v);     // quad_perm [2, 3, 0, 1]
-  else if constexpr (S == 8) return dpp_f32<0x128>(v);    // row_ror 8: i <- i + 8 mod 16
-  else if constexpr (S == 4) return swizzle_f32<0x101F>(v);   // bit mode: and 0x1f, xor 4
-  else return swizzle_f32<0x401F>(v);                         // xor 16
-}
+
+// v[r] += t * (v[r] of the lane that the DPP control CTRL_ names), r < 16, in place.  The compiler does
+// not fold a DPP move into a fused multiply-add on this target, hence the assembly.  The leading wait
+// covers the DPP read-after-VALU-write and EXEC-write hazards that are not tracked across the
+// boundary of an asm statement; inside it no instruction reads a register the one before wrote.
+#define TORQ_FMAC16_DPP(V_, T_, CTRL_)                                                              \
+  asm volatile("s_nop 4\n"                                                                          \
+      "v_fmac_f32_dpp %0, %0, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                           \
+      "v_fmac_f32_dpp %1, %1, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                           \
+      "v_fmac_f32_dpp %2, %2, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                           \
+      "v_fmac_f32_dpp %3, %3, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                           \
+      "v_fmac_f32_dpp %4, %4, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                           \
+      "v_fmac_f32_dpp %5, %5, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                           \
+      "v_fmac_f32_dpp %6, %6, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                           \
+      "v_fmac_f32_dpp %7, %7, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                           \
+      "v_fmac_f32_dpp %8, %8, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                           \
+      "v_fmac_f32_dpp %9, %9, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                           \
+      "v_fmac_f32_dpp %10, %10, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                         \
+      "v_fmac_f32_dpp %11, %11, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                         \
+      "v_fmac_f32_dpp %12, %12, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                         \
+      "v_fmac_f32_dpp %13, %13, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                         \
+      "v_fmac_f32_dpp %14, %14, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                         \
+      "v_fmac_f32_dpp %15, %15, %16 " CTRL_ " row_mask:0xf bank_mask:0xf\n"                         \
+      : "+v"(V_[0]), "+v"(V_[1]), "+v"(V_[2]), "+v"(V_[3]), "+v"(V_[4]), "+v"(V_[5]), "+v"(V_[6]),  \
+        "+v"(V_[7]), "+v"(V_[8]), "+v"(V_[9]), "+v"(V_[10]), "+v"(V_[11]), "+v"(V_[12]),            \
+        "+v"(V_[13]), "+v"(V_[14]), "+v"(V_[15])                                                    \
+      : "v"(T_))
 
 }  // namespace
 
-// coefficient table, [NC][32] floats, lane b0 reads column b0 (row 32 j + b0 of the butterfly):
+// coefficient table, [NC][32] floats, the lane that holds block row b0 reads column b0 (row 32 j + b0
+// of the butterfly):
 //   round t = 0 .. log2 G - 1, entry t NJ + j:  the row's coefficient of that round (signed: + on the
 //                                               row with the stride bit clear, - on its partner)
 //   entry (log2 G) NJ + j:                      the row's final sigma
@@ -73,7 +91,9 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
 
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int b0 = lane & 31, h = lane >> 5;
+  const int h = lane >> 5;
+  // the block row of the tile that this lane holds (the inverse of the lane map above)
+  const int b0 = ((lane & 24) | ((lane ^ (lane >> 1)) & 4) | ((lane ^ (lane >> 1)) & 2) | ((lane ^ (lane >> 2)) & 1)) & 31;
   char *const my = lds + wave * TG_BYTES;                              // this wave's token-group
 
   float cf[NC];
@@ -155,13 +175,20 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
           }
         }
     }
-#define TORQ_LANE_ROUND(IDX_, S_)                                               \
-  _Pragma("unroll") for (int j = 0; j < NJ; ++j) {                              \
-    const float t = cf[(LJ + (IDX_)) * NJ + j];                               \
-    _Pragma("unroll") for (int r = 0; r < 16; ++r) v[j][r] = fmaf(t, lane_xor<S_>(v[j][r]), v[j][r]); \
-  }
-    TORQ_LANE_ROUND(0, 16) TORQ_LANE_ROUND(1, 8) TORQ_LANE_ROUND(2, 4) TORQ_LANE_ROUND(3, 2) TORQ_LANE_ROUND(4, 1)
-#undef TORQ_LANE_ROUND
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) {                             // stride 16: lane n ^ 16
+      const float t = cf[LJ * NJ + j];
+#pragma unroll
+      for (int r = 0; r < 16; ++r) v[j][r] = fmaf(t, swizzle_f32<0x401F>(v[j][r]), v[j][r]);
+    }
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf[(LJ + 1) * NJ + j], "row_mirror");            // stride 8
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf[(LJ + 2) * NJ + j], "row_half_mirror");       // stride 4
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf[(LJ + 3) * NJ + j], "quad_perm:[2,3,0,1]");   // stride 2
+#pragma unroll
+    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf[(LJ + 4) * NJ + j], "quad_perm:[1,0,3,2]");   // stride 1
 
     // ---- the rows' sigma, then step 4
 #pragma unroll
@@ -200,6 +227,7 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
 }
 
 #undef TORQ_LOAD_TG
+#undef TORQ_FMAC16_DPP
 
 int butterfly_coef_count(int G) {
   const int NJ = G / 32, LJ = NJ == 1 ? 0 : NJ == 2 ? 1 : NJ == 4 ? 2 : 3;
@@ -210,7 +238,8 @@ template <int NJ>
 static hipError_t launch_nj(const torq_rotation *r, const void *x, int64_t TG, int format, float global_scale,
                             uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
   const size_t lds_bytes = 4 * (size_t)NJ * 32 * 64;
-  int64_t grid = (NJ == 8 ? 1 : 2) * 256;                     // resident workgroups of 4 waves
+  // resident workgroups of 4 waves: what the kernel's register count admits per CU
+  int64_t grid = (NJ == 1 ? 6 : NJ == 2 ? 4 : NJ == 4 ? 2 : 1) * 256;
   if (grid * 4 > TG) grid = (TG + 3) / 4;
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
