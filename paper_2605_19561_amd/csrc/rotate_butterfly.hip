@@ -74,10 +74,11 @@ __device__ __forceinline__ float swizzle_f32(float v) {
 //   round t = 0 .. log2 G - 1, entry t NJ + j:  the row's coefficient of that round (signed: + on the
 //                                               row with the stride bit clear, - on its partner)
 //   entry (log2 G) NJ + j:                      the row's final sigma
-// G = 256 needs 128 accumulators, 64 staging registers and 72 coefficients per lane: one workgroup
-// per CU there (512 registers per lane), two otherwise.
+// G <= 64 keeps the lane's coefficients in registers; G >= 128 (32 and 72 of them, next to 64 / 128
+// accumulators and 32 / 64 staging registers) reads them from a copy of the table in LDS where they
+// are used, which lets three (G = 128) and two (G = 256) workgroups share a CU.
 template <int NJ, int FMT>
-__global__ void __launch_bounds__(256, NJ == 8 ? 1 : 2)
+__global__ void __launch_bounds__(256, NJ == 4 ? 3 : 2)
 rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__restrict__ coef,
                         const uint4 *__restrict__ intra_hi_frag, const uint4 *__restrict__ intra_lo_frag,
                         uint2 *__restrict__ codes, uint8_t *__restrict__ scales, float *__restrict__ z_out,
@@ -96,9 +97,18 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
   const int b0 = ((lane & 24) | ((lane ^ (lane >> 1)) & 4) | ((lane ^ (lane >> 1)) & 2) | ((lane ^ (lane >> 2)) & 1)) & 31;
   char *const my = lds + wave * TG_BYTES;                              // this wave's token-group
 
-  float cf[NC];
+  constexpr bool CF_LDS = NJ >= 4;
+  float cf_reg[CF_LDS ? 1 : NC];
+  const float *const cf_lds = reinterpret_cast<const float *>(lds + 4 * TG_BYTES) + b0;
+  if constexpr (CF_LDS) {
+    float *t = reinterpret_cast<float *>(lds + 4 * TG_BYTES);
+    for (int i = threadIdx.x; i < NC * 32; i += 256) t[i] = coef[i];
+    __syncthreads();                                         // before the loop: every wave arrives
+  } else {
 #pragma unroll
-  for (int c = 0; c < NC; ++c) cf[c] = coef[c * 32 + b0];
+    for (int c = 0; c < NC; ++c) cf_reg[c] = coef[c * 32 + b0];
+  }
+#define cf(I_) (CF_LDS ? cf_lds[(I_) * 32] : cf_reg[CF_LDS ? 0 : (I_)])
   bf16x8 Ah[2], Al[2];
 #pragma unroll
   for (int t = 0; t < 2; ++t) {
@@ -166,7 +176,7 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
         if ((j & hj) == 0) {
-          const float tp = cf[m * NJ + j], tq = cf[m * NJ + j + hj];
+          const float tp = cf(m * NJ + j), tq = cf(m * NJ + j + hj);
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const float p = v[j][r], q = v[j + hj][r];
@@ -177,23 +187,23 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
     }
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {                             // stride 16: lane n ^ 16
-      const float t = cf[LJ * NJ + j];
+      const float t = cf(LJ * NJ + j);
 #pragma unroll
       for (int r = 0; r < 16; ++r) v[j][r] = fmaf(t, swizzle_f32<0x401F>(v[j][r]), v[j][r]);
     }
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf[(LJ + 1) * NJ + j], "row_mirror");            // stride 8
+    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf((LJ + 1) * NJ + j), "row_mirror");            // stride 8
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf[(LJ + 2) * NJ + j], "row_half_mirror");       // stride 4
+    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf((LJ + 2) * NJ + j), "row_half_mirror");       // stride 4
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf[(LJ + 3) * NJ + j], "quad_perm:[2,3,0,1]");   // stride 2
+    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf((LJ + 3) * NJ + j), "quad_perm:[2,3,0,1]");   // stride 2
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf[(LJ + 4) * NJ + j], "quad_perm:[1,0,3,2]");   // stride 1
+    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf((LJ + 4) * NJ + j), "quad_perm:[1,0,3,2]");   // stride 1
 
     // ---- the rows' sigma, then step 4
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
-      const float rs = cf[(LJ + 5) * NJ + j];
+      const float rs = cf((LJ + 5) * NJ + j);
       float zz[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) zz[r] = v[j][r] * rs;
@@ -227,6 +237,7 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
 }
 
 #undef TORQ_LOAD_TG
+#undef cf
 #undef TORQ_FMAC16_DPP
 
 int butterfly_coef_count(int G) {
@@ -237,9 +248,9 @@ int butterfly_coef_count(int G) {
 template <int NJ>
 static hipError_t launch_nj(const torq_rotation *r, const void *x, int64_t TG, int format, float global_scale,
                             uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
-  const size_t lds_bytes = 4 * (size_t)NJ * 32 * 64;
-  // resident workgroups of 4 waves: what the kernel's register count admits per CU
-  int64_t grid = (NJ == 1 ? 6 : NJ == 2 ? 4 : NJ == 4 ? 2 : 1) * 256;
+  const size_t lds_bytes = 4 * (size_t)NJ * 32 * 64 + (NJ >= 4 ? (size_t)butterfly_coef_count(32 * NJ) * 32 * 4 : 0);
+  // resident workgroups of 4 waves: what the kernel's register count (and LDS) admits per CU
+  int64_t grid = (NJ == 1 ? 6 : NJ == 2 ? 4 : NJ == 4 ? 3 : 2) * 256;
   if (grid * 4 > TG) grid = (TG + 3) / 4;
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
