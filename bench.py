@@ -184,6 +184,9 @@ def main():
         del src, dst
 
     if args.sweep:
+        # context for the HBM-bound lines below: what the runtime's own device-to-device copy of 1 GiB
+        # (read + write, far beyond the 256 MB Infinity Cache) reaches on this machine
+        print(json.dumps(copy_line(torch, dev, args.steps)), flush=True)
         for dd in (4096, 8192, 14336, 28672):
             print(json.dumps(sweep_line(tq, synth, dd, args.steps, args.warmup)), flush=True)
         # G = d/32: Algorithm 3 as printed (one R_inter over the whole row), a dense contraction
@@ -264,6 +267,24 @@ def cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d):
                       f"[{M}, {N}, {d}] step",
             "rotate_quantize_GBps": round(rows * d * RQ_BYTES_PER_ELEMENT / t_rq / 1e9, 4),
             "gemm_GFLOPps": round(2.0 * gm * gn * d / t_gemm / 1e9, 3)}
+
+
+def copy_line(torch, dev, steps):
+    src = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        dst.copy_(src)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    gbs = 2.0 * (1 << 30) / (ms * 1e-3) / 1e9
+    return {"metric": "device copy bandwidth (runtime's kernel, context)", "value": round(gbs, 1), "unit": "GB/s",
+            "config": {"workload": "1 GiB read + 1 GiB written"}, "ms": round(ms, 4),
+            "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
 
 
 def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0, butterfly=False):

@@ -10,9 +10,11 @@
 // into bf16 hi + lo) and leaves the result in fp32 registers in the layout the butterfly wants.
 //
 // One wave = one token-group (G blocks of 32) at a time; workgroups are persistent.
-//   * global -> registers (16 bytes per lane, coalesced) -> LDS (wave-private, 16-byte chunks of a
-//     64-byte row XOR-swizzled with (row >> 1) & 3), the next token-group's loads in flight while the
-//     current one is computed;
+//   * global -> LDS directly (buffer_load ... lds, 16 bytes per lane; the LDS side is lane-linear, so
+//     the lane picks the global chunk that belongs at its LDS place: 16-byte chunks of a 64-byte row
+//     XOR-swizzled with (row >> 1) & 3).  The wave's LDS region is free as soon as the MFMA operands
+//     of the current token-group have been read, so the next token-group's loads are issued right
+//     there and land while the butterfly and step 4 run: no staging registers, no second buffer;
 //   * Z'^T = R_intra^T X^T per tile of 32 blocks on v_mfma_f32_32x32x16_bf16: B operand = two 8-byte
 //     LDS reads of row b per k-step; afterwards lane (b0 = l % 32, h = l / 32) holds
 //     v[j][r] = Z'[32 j + b0][16 h + r], j < G / 32, r < 16;
@@ -75,10 +77,10 @@ __device__ __forceinline__ float swizzle_f32(float v) {
 //                                               row with the stride bit clear, - on its partner)
 //   entry (log2 G) NJ + j:                      the row's final sigma
 // G <= 64 keeps the lane's coefficients in registers; G >= 128 (32 and 72 of them, next to 64 / 128
-// accumulators and 32 / 64 staging registers) reads them from a copy of the table in LDS where they
-// are used, which lets three (G = 128) and two (G = 256) workgroups share a CU.
+// accumulators) reads them from a copy of the table in LDS where they are used.  Workgroups per CU
+// that the register counts admit: 8, 5, 4, 2 for G = 32, 64, 128, 256.
 template <int NJ, int FMT>
-__global__ void __launch_bounds__(256, NJ == 4 ? 3 : 2)
+__global__ void __launch_bounds__(256, NJ == 1 ? 8 : NJ == 2 ? 5 : NJ == 4 ? 4 : 2)
 rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__restrict__ coef,
                         const uint4 *__restrict__ intra_hi_frag, const uint4 *__restrict__ intra_lo_frag,
                         uint2 *__restrict__ codes, uint8_t *__restrict__ scales, float *__restrict__ z_out,
@@ -116,13 +118,9 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
     Al[t] = __builtin_bit_cast(bf16x8, intra_lo_frag[t * 64 + lane]);
   }
 
-  // chunk c = lane + 64 i of the token-group: row c / 4, 16-byte part c % 4
-  int st_off[CH];
-#pragma unroll
-  for (int i = 0; i < CH; ++i) {
-    const int c = lane + 64 * i, row = c >> 2;
-    st_off[i] = row * 64 + (((c & 3) ^ ((row >> 1) & 3)) * 16);
-  }
+  // LDS place P = 64 i + lane (16-byte units) holds row P / 4, part (P % 4) ^ ((row >> 1) & 3) of the
+  // token-group; (row >> 1) & 3 = (lane >> 3) & 3 for every i
+  const int ld_voff = ((lane & ~3) | ((lane & 3) ^ ((lane >> 3) & 3))) * 16;
   // B operand of k-step t, tile j: the 8-byte pieces at positions 16 t + 4 h and 16 t + 8 + 4 h of
   // row 32 j + b0, i.e. 16-byte part 2 t (+ 1), half h; (row >> 1) & 3 does not depend on j
   int rd_off[2][2];
@@ -132,22 +130,23 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
     for (int u = 0; u < 2; ++u) rd_off[t][u] = b0 * 64 + (((2 * t + u) ^ ((b0 >> 1) & 3)) * 16) + 8 * h;
 
   const int64_t wave_id = (int64_t)blockIdx.x * 4 + wave, nwave = (int64_t)gridDim.x * 4;
-  // (a plain vector type: an array of the HIP struct type assigned under a condition is not
-  // promoted to registers)
-  typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
-  const u32x4 *xv = reinterpret_cast<const u32x4 *>(x);
-  u32x4 stage[CH];
-#define TORQ_LOAD_TG(TG_)                                                                     \
-  _Pragma("unroll") for (int i = 0; i < CH; ++i) stage[i] = xv[(TG_) * (TG_BYTES / 16) + lane + 64 * i];
+  // loads of token-group TG_: CH instructions of 1 KB each; the range of the descriptor is the
+  // token-group itself
+#define TORQ_LOAD_TG(TG_)                                                                           \
+  {                                                                                                 \
+    const __amdgpu_buffer_rsrc_t rs_ = __builtin_amdgcn_make_buffer_rsrc(                           \
+        const_cast<char *>(reinterpret_cast<const char *>(x) + (TG_) * (int64_t)TG_BYTES), 0, TG_BYTES, 0x00020000); \
+    _Pragma("unroll") for (int i = 0; i < CH; ++i)                                                  \
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rs_, (__attribute__((address_space(3))) void *)(my + i * 1024), 16, \
+                                                 ld_voff, i * 1024, 0, 0);                          \
+  }
 
   int64_t tg = wave_id;
-  if (tg < TG) { TORQ_LOAD_TG(tg) }
+  if (tg < TG) TORQ_LOAD_TG(tg)
   for (; tg < TG; tg += nwave) {
-    // the wave is the only user of its LDS region: its own reads of the previous token-group
-    // have returned (their values were consumed), so the stores need no barrier
-#pragma unroll
-    for (int i = 0; i < CH; ++i) *reinterpret_cast<u32x4 *>(my + st_off[i]) = stage[i];
-    if (tg + nwave < TG) { TORQ_LOAD_TG(tg + nwave) }
+    // the loads of this token-group have landed (vmcnt(0); lgkmcnt and expcnt left alone)
+    __builtin_amdgcn_s_waitcnt(0x0F70);
+    asm volatile("" ::: "memory");
 
     // ---- intra-block rotation: Z'^T = R_intra^T X^T, two passes (R_intra hi, lo)
     float v[NJ][16];
@@ -167,6 +166,12 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
 #pragma unroll
       for (int r = 0; r < 16; ++r) v[j][r] = acc[r];
     }
+
+    // every LDS read of this token-group has returned (the MFMAs consumed them) and nothing moves
+    // across this point: the region can be overwritten
+    __builtin_amdgcn_sched_barrier(0);
+    if (tg + nwave < TG) TORQ_LOAD_TG(tg + nwave)
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- inter-block rotation: the butterfly over b = 32 j + b0 (all indices are literals after
     // unrolling: cf stays in registers)
@@ -250,7 +255,7 @@ static hipError_t launch_nj(const torq_rotation *r, const void *x, int64_t TG, i
                             uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
   const size_t lds_bytes = 4 * (size_t)NJ * 32 * 64 + (NJ >= 4 ? (size_t)butterfly_coef_count(32 * NJ) * 32 * 4 : 0);
   // resident workgroups of 4 waves: what the kernel's register count (and LDS) admits per CU
-  int64_t grid = (NJ == 1 ? 6 : NJ == 2 ? 4 : NJ == 4 ? 3 : 2) * 256;
+  int64_t grid = (NJ == 1 ? 8 : NJ == 2 ? 5 : NJ == 4 ? 4 : 2) * 256;
   if (grid * 4 > TG) grid = (TG + 3) / 4;
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
