@@ -203,14 +203,14 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16,
  * leaves a dense G x G matrix to multiply online).  Round t = 0 .. log2(G) - 1 turns the G/2
  * independent pairs of block rows (p, p + G / 2^(t+1)) by the angle that makes each pair's two
  * diagonal entries of Sigma equal; after the last round diag(R Sigma R^T) = tr(Sigma)/G * 1, the
- * same output condition (the equality case of Theorem 4.1).  Online this costs 2 fused multiply-adds
- * per pair and element in fp32 instead of a dense contraction: torq_rotate_quantize on such a handle
- * is bound by HBM at any G.
+ * same output condition (the equality case of Theorem 4.1).  Online this costs one fused
+ * multiply-add per element and round in fp32 (log2(G) + 1 in all) instead of a dense G x G
+ * contraction.
  *
  * torq_equalize_inter_butterfly (HOST, double):
  *   Sigma_host     G*G doubles, symmetric, finite, not modified; G in {32, 64, 128, 256}
- *   R_inter_host   optional, G*G floats out: the dense matrix of the returned tangents, for the
- *                  oracle, for weights prepared elsewhere, or for torq_rotation_create
+ *   R_inter_host   optional, G*G floats out: the dense matrix of the returned tangents, for
+ *                  checking, for weights prepared elsewhere, or for torq_rotation_create
  *   tangents_host  log2(G) * G/2 floats out: tan(theta) of every pair, rounds in order, pairs in
  *                  increasing p; |tan| <= 1
  * torq_rotation_create_butterfly: a handle whose inter-block rotation is that butterfly (any finite
