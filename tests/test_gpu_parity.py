@@ -788,3 +788,34 @@ def test_butterfly_identity_and_empty(tq, oracle):
     c, s = tq.torq_rotate_quantize(rot, torch.empty((0, d), dtype=torch.bfloat16, device=DEV))
     assert c.numel() == 0 and s.numel() == 0
     rot.close()
+
+
+def test_linear_with_a_butterfly_handle(tq, oracle):
+    # the calibrated chain on one sample: Gram (GPU) -> butterfly equaliser (host) -> handle ->
+    # weights and activations through the same rotation -> torq_linear
+    x = synth.workload_activations("tiny")
+    w = synth.workload_weights("tiny")
+    G, d = 128, 4096
+    xd, wd = x.to(DEV), w.to(DEV)
+    Sigma = _np(tq.torq_block_gram(xd, G))
+    R, T = tq.torq_equalize_inter_butterfly(Sigma)
+    Ra = synth.rotations(G)[1]
+    rot = tq.ButterflyRotation(d, G, T, Ra)
+    W_q, W_s = tq.torq_rotate_quantize(rot, wd)
+    out = tq.torq_linear(rot, xd, W_q, W_s)
+    A_q, A_s = tq.torq_rotate_quantize(rot, xd)
+    torch.cuda.synchronize()
+    assert torch.equal(out, tq.mxfp4_gemm(A_q, A_s, W_q, W_s))
+    # the dense handle made from the matrix the equaliser handed back computes the same layer
+    dense = tq.Rotation(d, G, R, Ra)
+    Wd_q, Wd_s = tq.torq_rotate_quantize(dense, wd)
+    out_d = tq.torq_linear(dense, xd, Wd_q, Wd_s)
+    assert _rel_fro(_bits(out), _bits(out_d).astype(np.uint16)) <= 5e-3
+    # against the oracle's whole chain with that matrix
+    oA = oracle.rotate_quantize(synth.bf16_bits(x), G, R, Ra)
+    oW = oracle.rotate_quantize(synth.bf16_bits(w), G, R, Ra)
+    assert _rel_fro(_bits(out), oracle.gemm(oA[0], oA[1], oW[0], oW[1])) <= 5e-3
+    plain = (x.to(torch.float64) @ w.to(torch.float64).T).numpy()
+    assert np.linalg.norm(_np(out.to(torch.float64)) - plain) / np.linalg.norm(plain) < 0.25
+    dense.close()
+    rot.close()
