@@ -141,6 +141,8 @@ def main():
     rq_gbs = rq_bytes / (rq_ms * 1e-3) / 1e9
     # split-bf16 contraction actually executed: 2 passes over R_inter (2G flop each), 3 over R_intra (64)
     rq_mfma_tflops = M * d * (2 * 2 * G + 3 * 64) / (rq_ms * 1e-3) / 1e12
+    # context: what the runtime's own device-to-device copy of 1 GiB reaches on this machine
+    copy_gbs = copy_line(torch, dev, 10)["value"]
 
     result = {
         "metric": "TORQ W4A4 MXFP4 linear layer (rotate + MXFP4 quantise + fp4 GEMM), whole step",
@@ -164,7 +166,8 @@ def main():
                                   "avg_kernel_ms": round(rq_ms, 4),
                                   "mfma_bf16_tflops": round(rq_mfma_tflops, 1),
                                   "mfma_bf16_frac": round(rq_mfma_tflops / BF16_PEAK_TFLOPS, 4),
-                                  "mfma_bf16_sustained_mfma_only": round(sustained[tq.TORQ_DIAG_BF16], 1)},
+                                  "mfma_bf16_sustained_mfma_only": round(sustained[tq.TORQ_DIAG_BF16], 1),
+                                  "runtime_copy_1GiB_GBps": copy_gbs},
     }
 
     if args.library_gemm:

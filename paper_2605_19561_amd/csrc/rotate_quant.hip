@@ -241,8 +241,13 @@ rotate_kernel(const uint4 *__restrict__ x, int64_t TG, int G,
 //           A = R_intra^T lane (m, h), slot jj:        R_intra[that k'][kout(m)],
 //                         kout(m) = 16 ((m/4)%2) + 4 (m/8) + m%4
 //           D             lane (b, h), reg r:          Z[b][16 h + r]
+// Input staging.  G <= 64: global -> registers -> LDS, the next batch's loads in flight during the
+// current batch.  G >= 96: global -> LDS directly (buffer_load ... lds), issued once the wave has
+// read its step-2 operands of the current batch and landing during steps 3 and 4; without the
+// staging registers three waves fit a SIMD up to G = 128 (160 registers), which is worth 5 - 15 %
+// there and a few per cent beyond; at G <= 64 the register path measured faster.
 template <int KS16, int FMT>
-__global__ void __launch_bounds__(64 * (KS16 / 2), 2)   // at least two waves per SIMD
+__global__ void __launch_bounds__(64 * (KS16 / 2), (KS16 >= 6 && KS16 <= 8) ? 3 : 2)   // waves per SIMD
 rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
                 const uint16_t *__restrict__ inter_hi, const uint16_t *__restrict__ inter_lo,
                 const uint4 *__restrict__ intra_hi_frag, const uint4 *__restrict__ intra_lo_frag,
@@ -253,6 +258,7 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
   constexpr int STAGE_BYTES = TB * TG_BYTES;
   constexpr int NTHR = 64 * (KS16 / 2);
   constexpr int CH = TG_BYTES / 16 / NTHR;           // 16-byte chunks per thread per token-group (= 2)
+  constexpr bool DMA = KS16 >= 6;
   extern __shared__ __attribute__((aligned(16))) char lds[];
 
   const int tid = threadIdx.x;
@@ -303,18 +309,48 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
         *reinterpret_cast<uint4 *>(base + j * TG_BYTES + (tid + i * NTHR) * 16) = stage_regs[j][i];
   };
 
+  // the direct form: lane l of wave w fills LDS chunk 64 w + l (+ NTHR i) of a token-group, which is
+  // the chunk of the same index in global memory; a token-group past the end reads as zeros through
+  // an empty descriptor
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  auto dma_batch = [&](int64_t b_, int buf_) {
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+      const int64_t tg = b_ * TB + j;
+      const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(
+          const_cast<char *>(reinterpret_cast<const char *>(x) + (tg < TG ? tg : 0) * (int64_t)TG_BYTES), 0,
+          tg < TG ? TG_BYTES : 0, 0x00020000);
+#pragma unroll
+      for (int i = 0; i < CH; ++i)
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            rs, (__attribute__((address_space(3))) void *)(lds + buf_ * STAGE_BYTES + j * TG_BYTES + (wave_u * 64 + i * NTHR) * 16),
+            16, tid * 16, i * NTHR * 16, 0, 0);
+    }
+  };
+
   int64_t batch = blockIdx.x;
   if (batch < nbatch) {
-    load_batch(batch);
-    store_batch(0);
+    if constexpr (DMA) {
+      dma_batch(batch, 0);
+    } else {
+      load_batch(batch);
+      store_batch(0);
+    }
   }
-  __syncthreads();
+  if constexpr (!DMA) __syncthreads();
 
   int buf = 0;
   for (; batch < nbatch; batch += gridDim.x, buf ^= 1) {
     const int64_t next = batch + gridDim.x;
     const bool have_next = next < nbatch;
-    if (have_next) load_batch(next);
+    if constexpr (DMA) {
+      // this wave's part of the batch has landed (vmcnt(0)), then everybody's; the barrier also says
+      // that every wave is done reading the other buffer
+      __builtin_amdgcn_s_waitcnt(0x0F70);
+      __syncthreads();
+    } else {
+      if (have_next) load_batch(next);
+    }
 
     const char *stage = lds + buf * STAGE_BYTES + tr_off;
     // ---- step 2: Y^T = X^T R_inter^T for both token-groups
@@ -340,6 +376,14 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
 #pragma unroll
       for (int j = 0; j < TB; ++j)
         acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[j], Bl[ks], acc[j], 0, 0, 0);
+    }
+
+    if constexpr (DMA) {
+      // this wave's LDS reads of the batch are done (the MFMAs consumed them); no LDS read follows
+      // in this iteration, so the compiler's rule "LDS reads wait for loads into LDS" costs nothing
+      __builtin_amdgcn_sched_barrier(0);
+      if (have_next) dma_batch(next, buf ^ 1);
+      __builtin_amdgcn_sched_barrier(0);
     }
 
     // ---- step 3: Z^T = R_intra^T Y^T with Y split into bf16 hi + lo; then step 4
@@ -410,8 +454,10 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
       }
     }
 
-    if (have_next) store_batch(buf ^ 1);
-    __syncthreads();
+    if constexpr (!DMA) {
+      if (have_next) store_batch(buf ^ 1);
+      __syncthreads();
+    }
   }
 }
 
@@ -449,9 +495,11 @@ static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG
   const int nw = KS16 / 2;                               // = G / 32
   const int64_t nbatch = (TG + TB - 1) / TB;
   const size_t lds_bytes = 2 * (size_t)TB * KS16 * 16 * 64;
-  // resident workgroups per CU: limited by LDS (160 KiB) and by 8 waves per CU at these register counts
+  // resident workgroups per CU: limited by LDS (160 KiB) and by the waves per SIMD that the register
+  // count admits (three for G = 96 and 128, two otherwise)
+  const int waves_per_cu = (KS16 >= 6 && KS16 <= 8) ? 12 : 8;
   int per_cu = (int)((160 * 1024) / lds_bytes);
-  if (per_cu * nw > 8) per_cu = 8 / nw;
+  if (per_cu * nw > waves_per_cu) per_cu = waves_per_cu / nw;
   if (per_cu < 1) per_cu = 1;
   int64_t grid = (int64_t)per_cu * 256;
   if (grid > nbatch) grid = nbatch;
