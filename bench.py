@@ -120,6 +120,11 @@ def main():
     torch.cuda.synchronize()
     rq_ms = e[0].elapsed_time(e[1]) / args.steps
     gemm_ms = e[2].elapsed_time(e[3]) / args.steps
+
+    # ---- board power and shader clock while each kernel runs alone for a second (the driver's
+    # sensors, read from sysfs; None where the machine does not expose them)
+    gemm_env = sample_board(torch, lambda i: tq.mxfp4_gemm(codes, scales, W_q, W_s, out=out), 1.0)
+    rq_env = sample_board(torch, lambda i: tq.torq_rotate_quantize(rot, x_copies[i % 3], codes=codes, scales=scales), 1.0)
     del x_copies
 
     # ---- what the matrix cores sustain on this part with nothing else running, on this step's own
@@ -159,7 +164,8 @@ def main():
                      "traffic": MEASURED_TRAFFIC.get(f"mxfp4_gemm/{args.workload}"),
                      "avg_kernel_ms": round(gemm_ms, 4),
                      "sustained_mfma_only": round(sustained[tq.TORQ_DIAG_FP4], 1),
-                     "frac_of_sustained": round(gemm_tflops / sustained[tq.TORQ_DIAG_FP4], 4)},
+                     "frac_of_sustained": round(gemm_tflops / sustained[tq.TORQ_DIAG_FP4], 4),
+                     "board": gemm_env},
         "roofline_rotate_quant": {"kernel": "torq_rotate_quantize", "bound": "hbm", "achieved": round(rq_gbs, 1),
                                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(rq_gbs / HBM_PEAK_GBS, 4),
                                   "traffic": MEASURED_TRAFFIC.get(f"torq_rotate_quantize/{args.workload}"),
@@ -167,7 +173,8 @@ def main():
                                   "mfma_bf16_tflops": round(rq_mfma_tflops, 1),
                                   "mfma_bf16_frac": round(rq_mfma_tflops / BF16_PEAK_TFLOPS, 4),
                                   "mfma_bf16_sustained_mfma_only": round(sustained[tq.TORQ_DIAG_BF16], 1),
-                                  "runtime_copy_1GiB_GBps": copy_gbs},
+                                  "runtime_copy_1GiB_GBps": copy_gbs,
+                                  "board": rq_env},
     }
 
     if args.library_gemm:
@@ -270,6 +277,56 @@ def cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d):
                       f"[{M}, {N}, {d}] step",
             "rotate_quantize_GBps": round(rows * d * RQ_BYTES_PER_ELEMENT / t_rq / 1e9, 4),
             "gemm_GFLOPps": round(2.0 * gm * gn * d / t_gemm / 1e9, 3)}
+
+
+def sample_board(torch, launch, seconds):
+    """Median board power (W), its cap and the median shader clock (MHz) while `launch(i)` runs back to
+    back for `seconds`: the amdgpu driver's hwmon power1_input / power1_cap and pp_dpm_sclk."""
+    import glob
+    import threading
+    hw = glob.glob("/sys/class/drm/card*/device/hwmon/hwmon*/power1_input")
+    ck = glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk")
+    if not hw or not ck:
+        return None
+    samples, stop = [], [False]
+
+    def read():
+        try:
+            watts = int(open(hw[0]).read()) / 1e6
+            cur = [l for l in open(ck[0]).read().splitlines() if "*" in l]
+            mhz = int(cur[0].split(":")[1].lower().replace("mhz", "").replace("*", "").strip()) if cur else None
+            return watts, mhz
+        except (OSError, ValueError, IndexError):
+            return None
+
+    def loop():
+        while not stop[0]:
+            r = read()
+            if r:
+                samples.append(r)
+            time.sleep(0.02)
+    t = threading.Thread(target=loop)
+    t0 = time.perf_counter()
+    i = 0
+    t.start()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(16):
+            launch(i)
+            i += 1
+        torch.cuda.synchronize()
+    stop[0] = True
+    t.join()
+    samples = samples[len(samples) // 3:]            # the clock settles within the first third
+    if not samples:
+        return None
+    med = lambda v: sorted(v)[len(v) // 2]
+    try:
+        cap = int(open(hw[0].replace("power1_input", "power1_cap")).read()) / 1e6
+    except (OSError, ValueError):
+        cap = None
+    clocks = [m for _, m in samples if m]
+    return {"power_w": round(med([w for w, _ in samples])), "power_cap_w": cap,
+            "shader_clock_mhz": med(clocks) if clocks else None, "nominal_clock_mhz": 2400}
 
 
 def copy_line(torch, dev, steps):
