@@ -819,3 +819,82 @@ def test_linear_with_a_butterfly_handle(tq, oracle):
     assert np.linalg.norm(_np(out.to(torch.float64)) - plain) / np.linalg.norm(plain) < 0.25
     dense.close()
     rot.close()
+
+
+# ----------------------- torq_linear at decode sizes (a few rows against a weight-streaming GEMM) ----
+
+DECODE_CASES = [(1, 1024, 4096), (5, 4100, 4096), (16, 14336, 4096), (17, 1032, 4096), (33, 2048, 8192),
+                (64, 1040, 8192), (2, 520, 12288)]
+
+
+@pytest.mark.parametrize("M,N,d", DECODE_CASES)
+def test_linear_decode_form_is_rotate_quantize_then_gemm(tq, oracle, M, N, d):
+    # at most 64 rows: bit for bit the two-call chain, also on repeated and interleaved calls with
+    # one workspace
+    G = 128
+    x = synth.activations(M, d, nu=3.0, outliers=max(2, d // 200), outlier_scale=50.0, seed=1200 + M)
+    Ri, Ra = synth.rotations(G, seed=5 + M)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(N + d)
+    W_q = torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=DEV, generator=gen)
+    W_s = torch.randint(118, 128, (N, d // 32), dtype=torch.uint8, device=DEV, generator=gen)
+    xd = x.to(DEV)
+    assert tq.mxfp4_gemm_plan(M, N, d)[0], "this shape is meant to take the weight-streaming kernel"
+    ws = torch.zeros((tq.torq_linear_workspace_bytes_n(M, N, d),), dtype=torch.uint8, device=DEV)
+    A_q, A_s = tq.torq_rotate_quantize(rot, xd)
+    want = tq.mxfp4_gemm(A_q, A_s, W_q, W_s)
+    x2 = (xd.float() * 0.5 + 0.25).to(torch.bfloat16)
+    A2_q, A2_s = tq.torq_rotate_quantize(rot, x2)
+    want2 = tq.mxfp4_gemm(A2_q, A2_s, W_q, W_s)
+    for rep in range(3):
+        out = tq.torq_linear(rot, xd, W_q, W_s, workspace=ws)
+        out2 = tq.torq_linear(rot, x2, W_q, W_s, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out, want) and torch.equal(out2, want2), rep
+    # the activations' codes and scales in the workspace are the rotate+quantise kernel's
+    tq.torq_linear(rot, xd, W_q, W_s, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(ws[:M * d // 2].view(M, d // 2), A_q)
+    off = (M * d // 2 + 255) // 256 * 256
+    assert torch.equal(ws[off:off + M * d // 32].view(M, d // 32), A_s)
+    # and the codes are the oracle's up to the rotation's error bar (rotated values within 1e-3 RMS)
+    z = _np(tq.torq_rotate(rot, xd)).astype(np.float64)
+    zo = oracle.rotate(synth.bf16_bits(x), G, Ri, Ra).astype(np.float64)
+    assert (np.abs(z - zo) / np.sqrt((zo ** 2).mean(axis=1, keepdims=True))).max() <= 1e-3
+    oc, os_ = oracle.quantize(_np(tq.torq_rotate(rot, xd)))
+    assert np.array_equal(_np(A_q), oc) and np.array_equal(_np(A_s), os_)
+    rot.close()
+
+
+def test_linear_decode_form_replays_from_a_hip_graph(tq):
+    M, d, N, G = 1, 4096, 4096, 128
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(3)
+    W_q = torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=DEV, generator=gen)
+    W_s = torch.randint(118, 128, (N, d // 32), dtype=torch.uint8, device=DEV, generator=gen)
+    xs = [synth.activations(M, d, seed=1300 + i).to(DEV) for i in range(3)]
+    ws = torch.empty((tq.torq_linear_workspace_bytes_n(M, N, d),), dtype=torch.uint8, device=DEV)
+    wants = [tq.mxfp4_gemm(*tq.torq_rotate_quantize(rot, x), W_q, W_s) for x in xs]
+    x_in = xs[0].clone()
+    out = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        tq.torq_linear(rot, x_in, W_q, W_s, out=out, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(4):                                   # four calls back to back in one graph
+            tq.torq_linear(rot, x_in, W_q, W_s, out=out, workspace=ws)
+    for rep in range(6):
+        x_in.copy_(xs[rep % 3])
+        out.fill_(1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, wants[rep % 3]), f"replay {rep}"
+    rot.close()
