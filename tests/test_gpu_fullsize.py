@@ -46,6 +46,7 @@ ROT_FULL = [
     ("llama3_70b_up", None),                       # [8192, 8192], G = 128: the benchmark's step
     ("qwen3_32b", None),                           # [4096, 5120], G = 80, per-token log-normal scale
     ("llama3_70b_down", 2048),                     # d = 28672, G = 128 (rows trimmed: generation time)
+    ("llama3_8b_prefill", None),                   # [2048, 4096], G = 128
 ]
 
 
@@ -101,6 +102,12 @@ GEMM_FULL = [
     (2048, 4096, 4096),       # LLaMA3-8B attention projection, prefill: the 256 x 128 tile
     (1000, 8100, 1024),       # 256 x 128 tile with ragged last tiles in both directions
     (1000, 8100, 640),        # the same with a k range that is not a whole number of 512-element pieces
+    (2048, 4096, 14336),      # LLaMA3-8B MLP down, prefill
+    (16, 4096, 14336),        # ... and at decode size
+    (2048, 1024, 4096),       # LLaMA3-8B k/v projection
+    (4096, 25600, 5120),      # Qwen3-32B MLP up / gate
+    (4096, 1024, 5120),       # Qwen3-32B k/v projection
+    (4096, 8192, 5120),       # Qwen3-32B q projection
 ]
 
 
