@@ -1,9 +1,9 @@
 // Rotate + quantise for an inter-block rotation that is a BUTTERFLY of plane rotations
 // (torq_equalize_inter_butterfly: log2 G rounds, round t turning the G/2 independent pairs of block
 // rows (p, p + G / 2^(t+1))), i.e. Algorithm 3's Y = R_inter X without the dense G x G contraction:
-// 2 fused multiply-adds per pair and element instead of 2 G per element on the matrix cores.  With it
-// the kernel is bound by HBM again at any G (Section 5.1's "efficient implementation" of R_inter;
-// Appendix A.7 counts O(B^2 K) for the dense form).
+// one fused multiply-add per element and round (log2 G + 1 in all) instead of 2 G per element, twice,
+// on the matrix cores (Section 5.1 asks for an efficient implementation of R_inter; Appendix A.7
+// counts O(B^2 K) for the dense form).  Up to G = 64 the kernel then moves data as fast as a copy.
 //
 // The two rotations commute (R_inter mixes blocks, R_intra mixes positions), so the kernel applies
 // R_intra FIRST: X is exact in bf16, which makes the intra rotation two MFMA passes (R_intra split
@@ -16,8 +16,8 @@
 //     of the current token-group have been read, so the next token-group's loads are issued right
 //     there and land while the butterfly and step 4 run: no staging registers, no second buffer;
 //   * Z'^T = R_intra^T X^T per tile of 32 blocks on v_mfma_f32_32x32x16_bf16: B operand = two 8-byte
-//     LDS reads of row b per k-step; afterwards lane (b0 = l % 32, h = l / 32) holds
-//     v[j][r] = Z'[32 j + b0][16 h + r], j < G / 32, r < 16;
+//     LDS reads of row b per k-step; afterwards lane (n = l % 32, h = l / 32) holds
+//     v[j][r] = Z'[32 j + b0][16 h + r], j < G / 32, r < 16 (which block row b0 a lane holds: below);
 //   * butterfly over the block index b = 32 j + b0 with the cosines deferred: a row carries
 //     u = (true value) / sigma, sigma = the product of the cosines of the pairs it has been in, and
 //         p' = c (p + t q)  becomes  u_p' = u_p + (t sigma_q / sigma_p) u_q,
@@ -174,7 +174,7 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- inter-block rotation: the butterfly over b = 32 j + b0 (all indices are literals after
-    // unrolling: cf stays in registers)
+    // unrolling)
 #pragma unroll
     for (int m = 0; m < LJ; ++m) {                             // strides 32 hj: pairs of tiles
       const int hj = NJ >> (m + 1);
