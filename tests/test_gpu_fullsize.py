@@ -272,3 +272,36 @@ def test_code_histogram_of_the_benchmark_step(tq, oracle):
     got = _np(tq.torq_code_histogram(codes, d)).astype(np.uint64)
     assert np.array_equal(got, oracle.code_histogram(_np(codes), d))
     rot.close()
+
+
+@pytest.mark.parametrize("name,G", [("llama3_70b_up", 128), ("llama3_70b_up", 256), ("llama3_8b_prefill", 64)])
+def test_butterfly_rotate_quantize_full_size_sampled_rows(tq, oracle, name, G):
+    # the butterfly handle at the benchmark's sizes: tangents from the host equaliser on the Gram of the
+    # activations themselves (GPU), rows sampled for the oracle, which rotates with the dense matrix
+    x = synth.workload_activations(name, device=DEV)
+    M, d = x.shape
+    Sigma = _np(tq.torq_block_gram(x, G))
+    R, T = tq.torq_equalize_inter_butterfly(Sigma)
+    _, Ra = synth.rotations(G)
+    rot = tq.ButterflyRotation(d, G, T, Ra)
+    codes, scales = tq.torq_rotate_quantize(rot, x)
+    z = tq.torq_rotate(rot, x)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(19)
+    rows = np.unique(np.concatenate([[0, 1, M - 2, M - 1], rng.integers(0, M, size=12)]))
+    rows_t = torch.from_numpy(rows).to(DEV)
+    xs, z_ref, want_c, want_s, _ = _check_rows(oracle, tq, rot, x, rows_t, G, R, Ra)
+    zr = z_ref.astype(np.float64)
+    rms = np.sqrt((zr ** 2).mean(axis=1, keepdims=True))
+    assert (np.abs(_np(z[rows_t]).astype(np.float64) - zr) / rms).max() <= 1e-3
+    c2, s2 = tq.torq_quantize_f32(z[rows_t].contiguous())
+    assert torch.equal(c2, codes[rows_t]) and torch.equal(s2, scales[rows_t])
+    oc, os_ = oracle.quantize(_np(z[rows_t]))
+    assert np.array_equal(_np(c2), oc) and np.array_equal(_np(s2), os_)
+    # the whole sample's block energies are equal after the rotation (output condition of Section 5.1)
+    nt = M * d // (32 * G)
+    energies = (z.double().reshape(nt, G, 32) ** 2).sum(dim=2).mean(dim=0).cpu().numpy()
+    c = np.trace(Sigma) / G
+    assert np.diag(Sigma).max() / np.diag(Sigma).min() > 5.0
+    assert np.abs(energies - c).max() <= 2e-3 * c
+    rot.close()
