@@ -898,3 +898,69 @@ def test_linear_decode_form_replays_from_a_hip_graph(tq):
         torch.cuda.synchronize()
         assert torch.equal(out, wants[rep % 3]), f"replay {rep}"
     rot.close()
+
+
+# ------------------------------------------------ seeded random shapes (every kernel family) ----
+
+def _random_gemm_shapes():
+    rng = np.random.default_rng(20260)
+    shapes = []
+    for _ in range(14):
+        M = int(rng.choice([1, 3, 17, 64, 65, 200, 513, 1100]))
+        N = int(rng.integers(1, 3000))
+        d = 128 * int(rng.integers(1, 60))
+        shapes.append((M, N, d))
+    return shapes
+
+
+@pytest.mark.parametrize("M,N,d", _random_gemm_shapes())
+def test_gemm_random_shapes_sampled_outputs(tq, oracle, M, N, d):
+    # whatever kernel the planner picks for the shape (weight streaming, three tile sizes, the k range
+    # cut when scratch is given), sampled outputs against the oracle
+    g = torch.Generator(device=DEV)
+    g.manual_seed(M * 7 + N * 3 + d)
+    A_q = torch.randint(0, 256, (M, d // 2), dtype=torch.uint8, device=DEV, generator=g)
+    W_q = torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=DEV, generator=g)
+    A_s = torch.randint(118, 136, (M, d // 32), dtype=torch.uint8, device=DEV, generator=g)
+    W_s = torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=DEV, generator=g)
+    rng = np.random.default_rng(M + N + d)
+    n_s = min(2048, M * N)
+    ms, ns = rng.integers(0, M, size=n_s), rng.integers(0, N, size=n_s)
+    ms[:4], ns[:4] = [0, M - 1, 0, M - 1], [0, 0, N - 1, N - 1]
+    um, im = np.unique(ms, return_inverse=True)
+    un, inn = np.unique(ns, return_inverse=True)
+    want = oracle.gemm_sampled(_np(A_q)[um], _np(A_s)[um], _np(W_q)[un], _np(W_s)[un], im, inn)
+    for name, out in (("plain", tq.mxfp4_gemm(A_q, A_s, W_q, W_s)), ("scratch", tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s))):
+        torch.cuda.synchronize()
+        got = _np(out[torch.from_numpy(ms).to(DEV), torch.from_numpy(ns).to(DEV)].view(torch.int16)).view(np.uint16)
+        assert _rel_fro(got, want) <= 1e-3, (name, tq.mxfp4_gemm_plan(M, N, d))
+
+
+def _random_rotate_shapes():
+    rng = np.random.default_rng(20261)
+    shapes = []
+    for _ in range(12):
+        G = int(rng.choice([16, 32, 48, 64, 80, 96, 128, 160, 192, 256]))
+        groups = int(rng.integers(1, 4))
+        M = int(rng.choice([1, 2, 7, 31, 64, 65, 130]))
+        shapes.append((M, 32 * G * groups, G))
+    return shapes
+
+
+@pytest.mark.parametrize("M,d,G", _random_rotate_shapes())
+def test_rotate_random_shapes(tq, oracle, M, d, G):
+    x = synth.activations(M, d, nu=3.0, outliers=max(1, d // 300), outlier_scale=50.0, seed=3000 + M + G)
+    Ri, Ra = synth.rotations(G, seed=G + M)
+    want = oracle.rotate(synth.bf16_bits(x), G, Ri, Ra).astype(np.float64)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    xd = x.to(DEV)
+    z = tq.torq_rotate(rot, xd)
+    rms = np.sqrt((want ** 2).mean(axis=1, keepdims=True))
+    assert (np.abs(_np(z).astype(np.float64) - want) / rms).max() <= 1e-3
+    c, s = tq.torq_rotate_quantize(rot, xd)
+    c2, s2 = tq.torq_quantize_f32(z)
+    torch.cuda.synchronize()
+    assert torch.equal(c, c2) and torch.equal(s, s2)
+    oc, os_ = oracle.quantize(_np(z))
+    assert np.array_equal(_np(c), oc) and np.array_equal(_np(s), os_)
+    rot.close()
