@@ -246,14 +246,15 @@ rotate_kernel(const uint4 *__restrict__ x, int64_t TG, int G,
 // read its step-2 operands of the current batch and landing during steps 3 and 4; without the
 // staging registers three waves fit a SIMD up to G = 128 (160 registers), which is worth 5 - 15 %
 // there and a few per cent beyond; at G <= 64 the register path measured faster.
-template <int KS16, int FMT>
+// TB: token-groups per batch, processed together (2: every MFMA has an independent neighbour; 1 for a
+// handful of token-groups, where the shortest path through one token-group counts).
+template <int KS16, int TB, int FMT>
 __global__ void __launch_bounds__(64 * (KS16 / 2), (KS16 >= 6 && KS16 <= 8) ? 3 : 2)   // waves per SIMD
 rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
                 const uint16_t *__restrict__ inter_hi, const uint16_t *__restrict__ inter_lo,
                 const uint4 *__restrict__ intra_hi_frag, const uint4 *__restrict__ intra_lo_frag,
                 uint2 *__restrict__ codes, uint8_t *__restrict__ scales, float *__restrict__ z_out,
                 float global_scale) {
-  constexpr int TB = 2;                              // token-groups per batch, processed together
   constexpr int TG_BYTES = KS16 * 16 * 64;           // one token-group: G rows of 64 bytes
   constexpr int STAGE_BYTES = TB * TG_BYTES;
   constexpr int NTHR = 64 * (KS16 / 2);
@@ -488,10 +489,9 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
   }                                                                                                             \
   return hipGetLastError();
 
-template <int KS16>
+template <int KS16, int TB = 2>
 static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG, int format, float global_scale,
                                uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
-  constexpr int TB = 2;
   const int nw = KS16 / 2;                               // = G / 32
   const int64_t nbatch = (TG + TB - 1) / TB;
   const size_t lds_bytes = 2 * (size_t)TB * KS16 * 16 * 64;
@@ -505,7 +505,7 @@ static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG
   if (grid > nbatch) grid = nbatch;
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
-  TORQ_LAUNCH_FMT(rotate_kernel32, uint2, KS16)
+  TORQ_LAUNCH_FMT(rotate_kernel32, uint2, KS16, TB)
 }
 
 template <int KS, int NT>
@@ -537,6 +537,8 @@ hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, 
                          uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
   const int64_t TG = M * (int64_t)(r->d / 32 / r->G);
   if (TG == 0) return hipSuccess;
+  // a handful of token-groups at G = 128 (decode): one per workgroup
+  if (r->G == 128 && TG <= 128) return launch_cfg32<8, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
   if (r->G % 32 == 0) {
     switch (r->G / 16) {
 #define TORQ_CASE32(K16_) \
