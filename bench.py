@@ -456,26 +456,32 @@ def decode_line(tq, synth, M, N, d):
     out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
     ws = torch.empty((tq.torq_linear_workspace_bytes_n(M, N, d),), dtype=torch.uint8, device=dev)
     calls = 24
-    side = torch.cuda.Stream()
-    side.wait_stream(torch.cuda.current_stream())
-    with torch.cuda.stream(side):
-        for i in range(n_copies):
-            tq.torq_linear(rot, x, W_q[i], W_s[i], out=out, workspace=ws)
-    torch.cuda.current_stream().wait_stream(side)
-    torch.cuda.synchronize()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph, stream=side):
-        for i in range(calls):
-            tq.torq_linear(rot, x, W_q[i % n_copies], W_s[i % n_copies], out=out, workspace=ws)
-    graph.replay()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    reps = 10
-    e0.record()
-    for _ in range(reps):
+
+    def replayed(fn):
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for i in range(n_copies):
+                fn(rot, x, W_q[i], W_s[i], out=out, workspace=ws)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for i in range(calls):
+                fn(rot, x, W_q[i % n_copies], W_s[i % n_copies], out=out, workspace=ws)
         graph.replay()
-    e1.record()
-    torch.cuda.synchronize()
-    us = e0.elapsed_time(e1) * 1e3 / (reps * calls)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 10
+        e0.record()
+        for _ in range(reps):
+            graph.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) * 1e3 / (reps * calls)
+
+    us = replayed(tq.torq_linear)
+    # the one-launch form of the same layer, where it applies (G = 128, at most 64 rows)
+    us_single = round(replayed(tq.torq_linear_single_launch), 2) if (G == 128 and M <= 64) else None
     wbytes = N * d * 0.53125
     rot.close()
     streaming, tile_m, tile_n, pieces = tq.mxfp4_gemm_plan(M, N, d, tq.mxfp4_gemm_workspace_bytes(M, N, d))
@@ -483,7 +489,7 @@ def decode_line(tq, synth, M, N, d):
     return {"metric": "torq_linear, decode", "value": round(us, 2), "unit": "us per call", "higher_is_better": False,
             "config": {"workload": f"decode: X bf16 [{M}, {d}], G={G}, W [{N}, {d}] packed MXFP4 ({wbytes / 1e6:.1f} MB)",
                        "gemm_kernel": kernel},
-            "weight_stream_GBps": round(wbytes / us / 1e3, 1), "frac_hbm_peak": round(wbytes / us / 1e3 / HBM_PEAK_GBS, 4)}
+            "single_launch_us": us_single, "weight_stream_GBps": round(wbytes / us / 1e3, 1), "frac_hbm_peak": round(wbytes / us / 1e3 / HBM_PEAK_GBS, 4)}
 
 
 if __name__ == "__main__":

@@ -173,6 +173,25 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16,
                 int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
                 void *stream);
 
+/* torq_linear for decode sizes in ONE kernel launch (Algorithm 3, steps 1-4 and "Return"): the first
+ * workgroups rotate and quantise one token-group each while the others, one per strip of weight rows,
+ * already have their weight scales and codes on the way and wait for the activations at a counter
+ * in device memory.  Same arguments and workspace as torq_linear, with these limits:
+ *   the handle's G is 128 and its R_inter a dense matrix (torq_rotation_create); 0 <= M <= 64;
+ *   d a multiple of 128 whose scale rows fit the LDS (every d up to 28672 does).
+ * Anything else is TORQ_EINVAL.  The packed activations are left in the workspace as by torq_linear; they
+ * come from the 16-block rotation kernel, so a value that sits within the rotation's error bar of a
+ * rounding boundary may get the neighbouring code of torq_rotate_quantize's; the product is exactly
+ * mxfp4_gemm of those codes.  Every workgroup exits (the wait is bounded; a workgroup that gives up
+ * leaves its outputs unwritten, which cannot happen while the rotating workgroups run).  Calls on one
+ * handle must not overlap in time (they share the handle's counters; stream order is enough).  On
+ * this part the hand-off between workgroups costs what the second launch costs: measured 1-5 us
+ * SLOWER than torq_linear (10.1 against 8.1 us at [1, 4096] -> 4096), which is why torq_linear does
+ * not use it. */
+int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q, const uint8_t *W_s,
+                              void *out_bf16, int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
+                              void *stream);
+
 /* ------------------------------------------------------------------------ */
 /* Calibration of the inter-block rotation (Section 5.1, Algorithm 1).  Not part of the online
  * path: run once on calibration activations to obtain R_inter for torq_rotation_create.

@@ -17,7 +17,7 @@ EXPORTS = [
     "torq_rotation_G", "torq_rotate_quantize", "torq_rotate", "torq_quantize_f32", "mxfp4_gemm",
     "torq_linear_workspace_bytes", "torq_linear", "mxfp4_gemm_workspace_bytes", "mxfp4_gemm_ws", "mxfp4_gemm_plan",
     "torq_rotate_quantize_fmt", "torq_quantize_f32_fmt", "torq_equalize_inter_butterfly",
-    "torq_rotation_create_butterfly",
+    "torq_rotation_create_butterfly", "torq_linear_single_launch",
     "torq_linear_workspace_bytes_n", "torq_block_gram_workspace_bytes", "torq_block_gram",
     "torq_equalize_inter", "torq_code_histogram_workspace_bytes", "torq_code_histogram", "torq_intra_pair_scores",
     "torq_intra_best_angle", "torq_calibrate_intra", "torq_diag_mfma_burn",
@@ -82,6 +82,8 @@ def lib():
         L.torq_linear_workspace_bytes.argtypes = [i64, i32]
         L.torq_linear.restype = i32
         L.torq_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, sz, vp]
+        L.torq_linear_single_launch.restype = i32
+        L.torq_linear_single_launch.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, sz, vp]
         L.torq_block_gram_workspace_bytes.restype = sz
         L.torq_block_gram_workspace_bytes.argtypes = [i32]
         L.torq_block_gram.restype = i32
@@ -292,6 +294,22 @@ def torq_linear_workspace_bytes(M: int, d: int) -> int:
 
 def torq_linear_workspace_bytes_n(M: int, N: int, d: int) -> int:
     return int(lib().torq_linear_workspace_bytes_n(M, N, d))
+
+
+def torq_linear_single_launch(rot: Rotation, x_bf16, W_q, W_s, out=None, workspace=None, stream=None):
+    """torq_linear for at most 64 rows, G = 128, in one kernel launch (see include/torq.h)."""
+    M, d = x_bf16.shape
+    N = W_q.shape[0]
+    assert d == rot.d and W_q.shape == (N, d // 2) and W_s.shape == (N, d // 32)
+    if workspace is None:
+        workspace = torch.empty((max(torq_linear_workspace_bytes(M, d), 1),), dtype=torch.uint8, device=x_bf16.device)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=x_bf16.device)
+    _check(lib().torq_linear_single_launch(rot.handle, _dev(x_bf16, torch.bfloat16, "x"), _dev(W_q, torch.uint8, "W_q"),
+                                           _dev(W_s, torch.uint8, "W_s"), _dev(out, torch.bfloat16, "out"), M, N,
+                                           _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)),
+           "torq_linear_single_launch")
+    return out
 
 
 def torq_linear(rot: Rotation, x_bf16, W_q, W_s, out=None, workspace=None, stream=None):

@@ -21,7 +21,8 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
 # The rotate kernel post-processes its MFMA results with vector ALU code, so its accumulators are
 # kept in ordinary VGPRs (no v_accvgpr_read traffic); the GEMM needs the AGPR half for its tile.
 EXTRA = {"rotate_quant.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
-         "rotate_butterfly.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+         "rotate_butterfly.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+         "mxfp4_gemm_skinny.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
 
 
 def build(verbose: bool = False) -> str:

@@ -96,6 +96,7 @@ int torq_rotation_create(torq_rotation_t **out, int d, int G, const float *R_int
   r->device = dev;
   r->inter_hi = r->inter_lo = r->intra_hi = r->intra_lo = r->intra32_hi = r->intra32_lo = nullptr;
   r->butterfly = nullptr;
+  r->decode_ctr = nullptr;
 
   // R_inter, bf16 hi/lo, [G][KS*32] with zero padding: row b is the B operand
   // "column" b of R_inter^T (Algorithm 3 step 2: Y[b] = sum_b' R_inter[b][b'] X[b']).
@@ -141,6 +142,7 @@ int torq_rotation_create(torq_rotation_t **out, int d, int G, const float *R_int
   if (e == hipSuccess) e = upload(&r->intra_lo, al);
   if (e == hipSuccess) e = upload(&r->intra32_hi, a32h);
   if (e == hipSuccess) e = upload(&r->intra32_lo, a32l);
+  if (e == hipSuccess) e = upload(&r->decode_ctr, std::vector<unsigned>(DECODE_CTR_WORDS, 0u));
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     torq_rotation_destroy(r);
@@ -159,6 +161,7 @@ void torq_rotation_destroy(torq_rotation_t *r) {
   if (r->intra32_hi) (void)hipFree(r->intra32_hi);
   if (r->intra32_lo) (void)hipFree(r->intra32_lo);
   if (r->butterfly) (void)hipFree(r->butterfly);
+  if (r->decode_ctr) (void)hipFree(r->decode_ctr);
   delete r;
 }
 
@@ -406,6 +409,23 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q
   const size_t used = torq_linear_workspace_bytes(M, r->d);
   e = torq::launch_mxfp4_gemm(codes, scales, W_q, W_s, out_bf16, M, N, r->d, static_cast<char *>(workspace) + used,
                               workspace_bytes - used, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q, const uint8_t *W_s,
+                              void *out_bf16, int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
+                              void *stream) {
+  if (!r || M < 0 || N < 0) return TORQ_EINVAL;
+  if (r->G != 128 || r->butterfly || r->d % 128 != 0 || M > 64) return TORQ_EINVAL;
+  if ((int64_t)r->d * 128 >= 0x7FFFFFFF || (M > 0 && !torq::mxfp4_gemm_skinny_fits(M, r->d))) return TORQ_EINVAL;
+  if (M == 0 || N == 0) return TORQ_OK;
+  if (!x_bf16 || !W_q || !W_s || !out_bf16 || !workspace) return TORQ_EINVAL;
+  if (misaligned(x_bf16) || misaligned(W_q) || misaligned(out_bf16) || misaligned(workspace)) return TORQ_EALIGN;
+  if (reinterpret_cast<uintptr_t>(W_s) & 3u) return TORQ_EALIGN;
+  if (workspace_bytes < torq_linear_workspace_bytes(M, r->d)) return TORQ_EWORKSPACE;
+  uint8_t *codes = static_cast<uint8_t *>(workspace);
+  uint8_t *scales = codes + (((size_t)M * (size_t)(r->d / 2) + 255) & ~(size_t)255);
+  hipError_t e = torq::launch_torq_linear_decode(r, x_bf16, codes, scales, W_q, W_s, out_bf16, M, N, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 

@@ -15,6 +15,7 @@
 //
 // The first MFMA operand is the weight strip and the second the activations, so an accumulator
 // lane holds out[m = l % 16][n = n0 + 4 (l / 16) + 0..3]: four consecutive outputs of one row.
+#include "rotate16_body.h"
 #include "torq_device.h"
 #include "torq_internal.h"
 
@@ -36,7 +37,66 @@ constexpr int SKINNY_MIN_GROUPS = 384; // fewer workgroups than this leave CUs w
 // a voffset that the range check of any buffer used here rejects (the load then delivers zeros)
 constexpr int OOB_VOFF = 0x7FFFFFF0;
 
+// what the decode form of torq_linear needs on top of the GEMM's arguments
+struct DecodeArgs {
+  const uint4 *x;
+  int64_t TG;
+  const uint16_t *inter_hi, *inter_lo;
+  const uint4 *intra_hi_frag, *intra_lo_frag;
+  uint8_t *A_q, *A_s;          // written by the first P workgroups, read by the others
+  int P;
+  unsigned *ctr;
+};
+
 }  // namespace
+
+// The end of both kernels: add the waves' partial tiles through LDS and store.
+template <int MT, int NS>
+__device__ __forceinline__ void skinny_reduce_store(f32x4 (&acc)[NS][MT], unsigned char *smem, uint16_t *__restrict__ out,
+                                                    int M, int64_t N, int64_t n0, int wave, int lane) {
+  const int r16 = lane & 15, q = lane >> 4;
+  // ---- add the waves' partial tiles in a fixed order (wave 0 + 1 + ... + 7), round, store
+  __syncthreads();                                 // everybody is done with the scales
+  float *red = reinterpret_cast<float *>(smem);    // [WAVES - 1][NS][MT][4][64]
+  if (wave > 0) {
+#pragma unroll
+    for (int n = 0; n < NS; ++n)
+#pragma unroll
+      for (int t = 0; t < MT; ++t)
+#pragma unroll
+        for (int r = 0; r < 4; ++r) red[((((wave - 1) * NS + n) * MT + t) * 4 + r) * 64 + lane] = acc[n][t][r];
+  }
+  __syncthreads();
+  if (wave == 0) {
+#pragma unroll
+    for (int n = 0; n < NS; ++n) {
+      const int64_t nn = n0 + n * 16 + 4 * q;
+#pragma unroll
+      for (int t = 0; t < MT; ++t) {
+        bf16x4 v;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          float sum = acc[n][t][r];
+#pragma unroll
+          for (int w = 0; w < WAVES - 1; ++w) sum += red[(((w * NS + n) * MT + t) * 4 + r) * 64 + lane];
+          v[r] = (__bf16)sum;
+        }
+        const int m = t * 16 + r16;
+        if (m < M) {
+          uint16_t *dst = out + (int64_t)m * N + nn;
+          if ((N & 3) == 0 && nn + 4 <= N) {
+            *reinterpret_cast<bf16x4 *>(dst) = v;
+          } else {
+            const uint64_t bits = __builtin_bit_cast(uint64_t, v);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+              if (nn + r < N) dst[r] = (uint16_t)(bits >> (16 * r));
+          }
+        }
+      }
+    }
+  }
+}
 
 // MT = number of 16-row activation tiles (M <= 16 MT); NS = 16-row weight strips per workgroup
 // (1 or 2; they share the activation loads); PT = line pairs per wave and trip
@@ -135,58 +195,206 @@ mxfp4_gemm_skinny_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restr
   }
   if (first) __syncthreads();                      // a wave without any pair still meets the others
 
-  // ---- add the waves' partial tiles in a fixed order (wave 0 + 1 + ... + 7), round, store
-  __syncthreads();                                 // everybody is done with the scales
-  float *red = reinterpret_cast<float *>(smem);    // [WAVES - 1][NS][MT][4][64]
-  if (wave > 0) {
-#pragma unroll
-    for (int n = 0; n < NS; ++n)
-#pragma unroll
-      for (int t = 0; t < MT; ++t)
-#pragma unroll
-        for (int r = 0; r < 4; ++r) red[((((wave - 1) * NS + n) * MT + t) * 4 + r) * 64 + lane] = acc[n][t][r];
+  skinny_reduce_store<MT, NS>(acc, smem, out, M, N, n0, wave, lane);
+}
+
+// One lane of a consumer workgroup that is done with ctr[0] (see torq_linear_decode_kernel).
+__device__ __forceinline__ void decode_consumer_done(unsigned *ctr, int gid, int groups) {
+  const int stripes = groups < 64 ? groups : 64;
+  const int s = gid % stripes;
+  const unsigned quota = (unsigned)((groups - s + stripes - 1) / stripes);    // workgroups with gid % stripes == s
+  const unsigned mine = __hip_atomic_fetch_add(&ctr[32 * (1 + s)], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (mine != quota - 1u) return;
+  const unsigned full = __hip_atomic_fetch_add(&ctr[32 * 65], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (full != (unsigned)stripes - 1u) return;
+  __hip_atomic_store(&ctr[0], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (int i = 0; i < stripes; ++i) __hip_atomic_store(&ctr[32 * (1 + i)], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  __hip_atomic_store(&ctr[32 * 65], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  for (int i = 0; i < 64; ++i) __hip_atomic_store(&ctr[32 * (66 + i)], 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// ---------------------------------------------------------------------------------------------
+// torq_linear_single_launch: torq_linear for decode sizes in ONE launch (Algorithm 3, steps 1-4 and
+// "Return").  With a few
+// rows, rotate + quantise is a latency of 4-5 us in front of a GEMM of 4-30 us; here it runs in the
+// first P workgroups of the GEMM's own launch (rotate16_body, one batch of token-groups each) while
+// the others, one per weight strip as in mxfp4_gemm_skinny_kernel, already have their scale bytes and
+// the first trip of their weight codes on the way.  The two meet at counters in device memory
+// (DECODE_CTR_WORDS words, one counter per 128-byte line: read-modify-writes of one address from
+// the whole device take about 80 ns each, one after the other):
+//   ctr[0]                   producers done: each adds 1 once its codes and scales (stored through to
+//                            device-coherent memory) have been acknowledged; the last one raises
+//   ctr[32 (66 + s)], s < 64  "ready", 64 copies: consumer g polls copy g % 64, so that no address is
+//                            polled by more than 1/64 of the workgroups (thousands of polls on one
+//                            address delay the producers' own updates of it);
+//   ctr[32 (1 + s)], s < 64   consumers finished, striped the same way; a complete stripe adds 1 to
+//   ctr[32 * 65]             stripes complete; the workgroup that completes the last one sets every
+//                            counter back to 0, so that the next launch (and every replay of a
+//                            captured one) starts from the same state.
+// The consumers read the activations with device-coherent loads (sc1), so neither side needs a
+// cache write-back or invalidate.
+// Workgroups are dispatched in index order and the producers come first, so a waiting consumer can
+// never keep a producer off the machine; the wait is bounded all the same (a consumer that gives
+// up leaves its outputs unwritten).  Launches that share a counter pair must not overlap.
+template <int MT, int NS, int PT>
+__global__ void __launch_bounds__(64 * WAVES, 4)
+torq_linear_decode_kernel(const uint4 *__restrict__ x, int64_t TG, const uint16_t *__restrict__ inter_hi,
+                          const uint16_t *__restrict__ inter_lo, const uint4 *__restrict__ intra_hi_frag,
+                          const uint4 *__restrict__ intra_lo_frag, uint8_t *__restrict__ A_q,
+                          uint8_t *__restrict__ A_s, const uint8_t *__restrict__ W_q,
+                          const uint8_t *__restrict__ W_s, uint16_t *__restrict__ out, int M, int64_t N, int d,
+                          int P, int groups, unsigned *__restrict__ ctr) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  if ((int)blockIdx.x < P) {
+    rotate16_body<4, 1, FMT_MXFP4, 1, true>(x, TG, 128, inter_hi, inter_lo, intra_hi_frag, intra_lo_frag,
+                                            reinterpret_cast<uint32_t *>(A_q), A_s, nullptr, 1.0f,
+                                            reinterpret_cast<char *>(smem), blockIdx.x, P);
+    __builtin_amdgcn_s_waitcnt(0);                 // this lane's stores have been acknowledged
+    __syncthreads();
+    if (tid == 0) {
+      const unsigned before = __hip_atomic_fetch_add(&ctr[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (before == (unsigned)P - 1u)              // every producer's stores were complete before its own add
+        for (int s = 0; s < 64; ++s) __hip_atomic_store(&ctr[32 * (66 + s)], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    return;
+  }
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r16 = lane & 15, q = lane >> 4;
+  const int row_bytes = d / 2, srow_bytes = d / 32;
+  const int KS = d / 128;
+  const int KP = (KS + 1) / 2;
+  const int64_t n0 = (int64_t)((int)blockIdx.x - P) * 16 * NS;
+  const int rows_w = (N - n0 < 16 * NS) ? (int)(N - n0) : 16 * NS;
+  const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(W_q + n0 * row_bytes, (uint32_t)rows_w * row_bytes);
+  const __amdgpu_buffer_rsrc_t ws_rsrc = make_rsrc(W_s + n0 * srow_bytes, (uint32_t)rows_w * srow_bytes);
+  const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(A_q, (uint32_t)M * row_bytes);
+  const __amdgpu_buffer_rsrc_t as_rsrc = make_rsrc(A_s, (uint32_t)M * srow_bytes);
+  const int c_voff = r16 * row_bytes + q * 16;
+  const int sdw = srow_bytes / 4, pd = sdw + 1;
+  const int w_ins = (16 * NS * pd + 63) / 64, a_ins = (16 * MT * pd + 63) / 64;
+  const int ws_off = r16 * pd * 4 + q;
+  const int as_off = w_ins * 256 + r16 * pd * 4 + q;
+
+  // ---- the weight side goes out first: scale bytes to LDS, the first trip's codes to registers
+  for (int i = wave; i < w_ins; i += WAVES) {
+    const int j = i * 64 + lane;
+    const int row = j / pd, col = j - row * pd;
+    const bool ok = col < sdw && row < 16 * NS;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(ws_rsrc, LDSP(smem + i * 256), 4, ok ? row * srow_bytes + col * 4 : OOB_VOFF, 0, 0, 0);
+  }
+  u32x4 wq[2 * PT][NS], aq[2 * PT][MT];
+  // AUX_: cache policy of the load; 16 = sc1, a device-coherent read
+#define TORQ_LOAD_TRIP(DST_, RSRC_, CNT_, P0_, AUX_)                                             \
+  _Pragma("unroll") for (int u = 0; u < 2 * PT; ++u) {                                           \
+    const int ks = 2 * ((P0_) + (u >> 1) * WAVES) + (u & 1);                                     \
+    const bool in = ks < KS;                                                                     \
+    _Pragma("unroll") for (int n = 0; n < CNT_; ++n)                                             \
+        DST_[u][n] = __builtin_amdgcn_raw_buffer_load_b128(RSRC_, in ? c_voff : OOB_VOFF,        \
+                                                           in ? ks * 64 + n * 16 * row_bytes : 0, AUX_); \
+  }
+  int p0 = wave;
+  if (p0 < KP) { TORQ_LOAD_TRIP(wq, w_rsrc, NS, p0, 0) }
+  __builtin_amdgcn_sched_barrier(0);
+
+  // ---- wait for the activations' codes and scales
+  if (tid == 0) {
+    const unsigned *flag = &ctr[32 * (66 + (((int)blockIdx.x - P) & 63))];
+    unsigned seen = 0;
+    for (int spin = 0; spin < (1 << 18); ++spin) {
+      seen = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (seen) break;
+      __builtin_amdgcn_s_sleep(8);
+    }
+    reinterpret_cast<volatile unsigned *>(smem)[(w_ins + a_ins) * 64] = seen;
   }
   __syncthreads();
-  if (wave == 0) {
+  const bool ready = reinterpret_cast<volatile unsigned *>(smem)[(w_ins + a_ins) * 64] != 0;
+  __builtin_amdgcn_sched_barrier(0);
+  asm volatile("" ::: "memory");                   // nothing below is moved above the wait
+  if (!ready) {                                    // uniform over the workgroup
+    if (tid == 0) decode_consumer_done(ctr, (int)blockIdx.x - P, groups);
+    return;
+  }
+
+  for (int i = w_ins + wave; i < w_ins + a_ins; i += WAVES) {
+    const int j = (i - w_ins) * 64 + lane;
+    const int row = j / pd, col = j - row * pd;
+    const bool ok = col < sdw && row < 16 * MT;
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(as_rsrc, LDSP(smem + i * 256), 4, ok ? row * srow_bytes + col * 4 : OOB_VOFF, 0, 0, 16);
+  }
+
+  f32x4 acc[NS][MT];
 #pragma unroll
-    for (int n = 0; n < NS; ++n) {
-      const int64_t nn = n0 + n * 16 + 4 * q;
+  for (int n = 0; n < NS; ++n)
 #pragma unroll
-      for (int t = 0; t < MT; ++t) {
-        bf16x4 v;
+    for (int t = 0; t < MT; ++t) acc[n][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  bool first = true;
+  for (; p0 < KP; p0 += PT * WAVES) {
+    if (!first) { TORQ_LOAD_TRIP(wq, w_rsrc, NS, p0, 0) }
+    TORQ_LOAD_TRIP(aq, a_rsrc, MT, p0, 16)
+    __builtin_amdgcn_sched_barrier(0);
+    if (first) {
+      __syncthreads();                             // the scales are in LDS
+      first = false;
+    }
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          float sum = acc[n][t][r];
+    for (int u = 0; u < 2 * PT; ++u) {
+      const int ks = 2 * (p0 + (u >> 1) * WAVES) + (u & 1);
+      const int sb = (ks < KS ? ks : 0) * 4;
+      int asc[MT];
 #pragma unroll
-          for (int w = 0; w < WAVES - 1; ++w) sum += red[(((w * NS + n) * MT + t) * 4 + r) * 64 + lane];
-          v[r] = (__bf16)sum;
-        }
-        const int m = t * 16 + r16;
-        if (m < M) {
-          uint16_t *dst = out + (int64_t)m * N + nn;
-          if ((N & 3) == 0 && nn + 4 <= N) {
-            *reinterpret_cast<bf16x4 *>(dst) = v;
-          } else {
-            const uint64_t bits = __builtin_bit_cast(uint64_t, v);
+      for (int t = 0; t < MT; ++t) asc[t] = smem[as_off + t * 16 * pd * 4 + sb];
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-              if (nn + r < N) dst[r] = (uint16_t)(bits >> (16 * r));
-          }
-        }
+      for (int n = 0; n < NS; ++n) {
+        const int wsc = smem[ws_off + n * 16 * pd * 4 + sb];
+#pragma unroll
+        for (int t = 0; t < MT; ++t)
+          acc[n][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+              i32x8{(int)wq[u][n][0], (int)wq[u][n][1], (int)wq[u][n][2], (int)wq[u][n][3], 0, 0, 0, 0},
+              i32x8{(int)aq[u][t][0], (int)aq[u][t][1], (int)aq[u][t][2], (int)aq[u][t][3], 0, 0, 0, 0},
+              acc[n][t], 4, 4, 0, wsc, 0, asc[t]);
       }
     }
   }
+#undef TORQ_LOAD_TRIP
+  if (first) __syncthreads();                      // a wave without any pair still meets the others
+
+  skinny_reduce_store<MT, NS>(acc, smem, out, M, N, n0, wave, lane);
+  if (tid == 0) decode_consumer_done(ctr, (int)blockIdx.x - P, groups);
 }
 
 template <int MT, int NS, int PT>
 static hipError_t launch_cfg(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
-                             void *out, int64_t M, int64_t N, int d, hipStream_t stream) {
+                             void *out, int64_t M, int64_t N, int d, hipStream_t stream, const DecodeArgs *fused) {
   const int64_t groups = (N + 16 * NS - 1) / (16 * NS);
-  if (groups > 0x7FFFFFFF) return hipErrorInvalidValue;
+  if (groups > 0x7FFFFFF0) return hipErrorInvalidValue;
   const int pd = d / 128 + 1;                      // padded dwords per scale row
   const size_t scale_bytes = (size_t)((16 * NS * pd + 63) / 64 + (16 * MT * pd + 63) / 64) * 256;
   const size_t red_bytes = (size_t)(WAVES - 1) * NS * MT * 4 * 64 * sizeof(float);
-  const size_t lds_bytes = scale_bytes > red_bytes ? scale_bytes : red_bytes;
+  size_t lds_bytes = scale_bytes > red_bytes ? scale_bytes : red_bytes;
+  if (fused) {
+    // + the "ready" word behind the scales; at least the rotation's two staging buffers
+    lds_bytes = lds_bytes > scale_bytes + 16 ? lds_bytes : scale_bytes + 16;
+    const size_t rot_bytes = 2 * (size_t)RotCfg<4>::TG_LDS_BYTES;
+    lds_bytes = lds_bytes > rot_bytes ? lds_bytes : rot_bytes;
+    if (lds_bytes > SKINNY_MAX_LDS) return hipErrorInvalidValue;
+    if (lds_bytes > 64 * 1024) {
+      static bool raised_fused = false;
+      if (!raised_fused) {
+        hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(torq_linear_decode_kernel<MT, NS, PT>),
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)SKINNY_MAX_LDS);
+        if (e != hipSuccess) return e;
+        raised_fused = true;
+      }
+    }
+    hipLaunchKernelGGL((torq_linear_decode_kernel<MT, NS, PT>), dim3((unsigned)(groups + fused->P)), dim3(64 * WAVES),
+                       lds_bytes, stream, fused->x, fused->TG, fused->inter_hi, fused->inter_lo, fused->intra_hi_frag,
+                       fused->intra_lo_frag, fused->A_q, fused->A_s, W_q, W_s, reinterpret_cast<uint16_t *>(out), (int)M,
+                       N, d, fused->P, (int)groups, fused->ctr);
+    return hipGetLastError();
+  }
   if (lds_bytes > SKINNY_MAX_LDS) return hipErrorInvalidValue;
   if (lds_bytes > 64 * 1024) {
     // raise the dynamic LDS limit once per process and kernel variant (the call is slow)
@@ -205,25 +413,25 @@ static hipError_t launch_cfg(const uint8_t *A_q, const uint8_t *A_s, const uint8
 
 template <int MT, int NS>
 static hipError_t launch_mt_ns(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
-                               void *out, int64_t M, int64_t N, int d, hipStream_t stream) {
+                               void *out, int64_t M, int64_t N, int d, hipStream_t stream, const DecodeArgs *fused) {
   // trip depth: as deep as the k range of a wave goes, at most 4 line pairs (8 k-steps) in flight
   // (2 when the operand registers of a trip would not leave room for several workgroups per CU)
   const int pairs_per_wave = ((d / 128 + 1) / 2 + WAVES - 1) / WAVES;
-  if (pairs_per_wave <= 1) return launch_cfg<MT, NS, 1>(A_q, A_s, W_q, W_s, out, M, N, d, stream);
-  if (pairs_per_wave <= 2) return launch_cfg<MT, NS, 2>(A_q, A_s, W_q, W_s, out, M, N, d, stream);
-  return launch_cfg<MT, NS, (MT + NS <= 3 ? 4 : 2)>(A_q, A_s, W_q, W_s, out, M, N, d, stream);
+  if (pairs_per_wave <= 1) return launch_cfg<MT, NS, 1>(A_q, A_s, W_q, W_s, out, M, N, d, stream, fused);
+  if (pairs_per_wave <= 2) return launch_cfg<MT, NS, 2>(A_q, A_s, W_q, W_s, out, M, N, d, stream, fused);
+  return launch_cfg<MT, NS, (MT + NS <= 3 ? 4 : 2)>(A_q, A_s, W_q, W_s, out, M, N, d, stream, fused);
 }
 
 template <int MT>
 static hipError_t launch_mt(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
-                            void *out, int64_t M, int64_t N, int d, hipStream_t stream) {
+                            void *out, int64_t M, int64_t N, int d, hipStream_t stream, const DecodeArgs *fused) {
   // Two strips per workgroup share the activation loads.  That pays when the activations are
   // real traffic (not a row or two) and there are still enough workgroups to keep every CU
   // streaming; deeper sharing costs more in registers (fewer loads in flight) than it saves.
   const int64_t strips = (N + 15) / 16;
   if (MT <= 2 && M >= 8 && strips >= 2 * SKINNY_MIN_GROUPS)
-    return launch_mt_ns<MT, (MT <= 2 ? 2 : 1)>(A_q, A_s, W_q, W_s, out, M, N, d, stream);
-  return launch_mt_ns<MT, 1>(A_q, A_s, W_q, W_s, out, M, N, d, stream);
+    return launch_mt_ns<MT, (MT <= 2 ? 2 : 1)>(A_q, A_s, W_q, W_s, out, M, N, d, stream, fused);
+  return launch_mt_ns<MT, 1>(A_q, A_s, W_q, W_s, out, M, N, d, stream, fused);
 }
 
 // Whether the scale rows of (up to two) strips and of the activations fit the LDS.
@@ -236,16 +444,40 @@ bool mxfp4_gemm_skinny_fits(int64_t M, int d) {
 
 // 1 <= M <= 64; d a multiple of 128 with 64 rows of d / 2 bytes addressable in 32 bits (the caller
 // checks both) and mxfp4_gemm_skinny_fits(M, d).
+static hipError_t launch_by_rows(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                                 void *out, int64_t M, int64_t N, int d, hipStream_t stream, const DecodeArgs *fused) {
+  switch ((M + 15) / 16) {
+    case 1: return launch_mt<1>(A_q, A_s, W_q, W_s, out, M, N, d, stream, fused);
+    case 2: return launch_mt<2>(A_q, A_s, W_q, W_s, out, M, N, d, stream, fused);
+    case 3: return launch_mt<3>(A_q, A_s, W_q, W_s, out, M, N, d, stream, fused);
+    case 4: return launch_mt<4>(A_q, A_s, W_q, W_s, out, M, N, d, stream, fused);
+    default: return hipErrorInvalidValue;
+  }
+}
+
 hipError_t launch_mxfp4_gemm_skinny(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                                     const uint8_t *W_s, void *out, int64_t M, int64_t N, int d,
                                     hipStream_t stream) {
-  switch ((M + 15) / 16) {
-    case 1: return launch_mt<1>(A_q, A_s, W_q, W_s, out, M, N, d, stream);
-    case 2: return launch_mt<2>(A_q, A_s, W_q, W_s, out, M, N, d, stream);
-    case 3: return launch_mt<3>(A_q, A_s, W_q, W_s, out, M, N, d, stream);
-    case 4: return launch_mt<4>(A_q, A_s, W_q, W_s, out, M, N, d, stream);
-    default: return hipErrorInvalidValue;
-  }
+  return launch_by_rows(A_q, A_s, W_q, W_s, out, M, N, d, stream, nullptr);
+}
+
+// torq_linear in one launch (torq_linear_single_launch); the caller has checked G = 128, a dense R_inter,
+// 1 <= M <= 64, mxfp4_gemm_skinny_fits(M, r->d) and N > 0.  A_q / A_s: the workspace's code and scale areas.
+hipError_t launch_torq_linear_decode(const torq_rotation *r, const void *x_bf16, uint8_t *A_q, uint8_t *A_s,
+                                     const uint8_t *W_q, const uint8_t *W_s, void *out, int64_t M, int64_t N,
+                                     hipStream_t stream) {
+  DecodeArgs fz;
+  fz.x = reinterpret_cast<const uint4 *>(x_bf16);
+  fz.TG = M * (int64_t)(r->d / 32 / r->G);
+  fz.inter_hi = r->inter_hi;
+  fz.inter_lo = r->inter_lo;
+  fz.intra_hi_frag = reinterpret_cast<const uint4 *>(r->intra_hi);
+  fz.intra_lo_frag = reinterpret_cast<const uint4 *>(r->intra_lo);
+  fz.A_q = A_q;
+  fz.A_s = A_s;
+  fz.P = (int)fz.TG;                               // one token-group per rotating workgroup
+  fz.ctr = r->decode_ctr;
+  return launch_by_rows(A_q, A_s, W_q, W_s, out, M, N, r->d, stream, &fz);
 }
 
 }  // namespace torq

@@ -20,7 +20,11 @@ struct torq_rotation {
   // optional: R_inter as a butterfly of plane rotations (rotate_butterfly.hip), the per-lane
   // coefficient table [butterfly_coef_count(G)][32]; nullptr for a dense R_inter
   float *butterfly;
+  // DECODE_CTR_WORDS counters (zero between launches) on which torq_linear_single_launch synchronises
+  // its rotating and its multiplying workgroups (mxfp4_gemm_skinny.hip)
+  unsigned *decode_ctr;
 };
+constexpr int DECODE_CTR_WORDS = 32 * 130;
 
 namespace torq {
 
@@ -56,6 +60,12 @@ bool mxfp4_gemm_skinny_fits(int64_t M, int d);
 hipError_t launch_mxfp4_gemm_skinny(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                                     const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, int d,
                                     hipStream_t stream);
+// torq_linear for at most 64 rows in one launch: rotate + quantise (the 16-block body, G = 128) in the
+// first workgroups of the weight-streaming GEMM.  Preconditions: r->G == 128, dense R_inter,
+// 1 <= M <= 64, mxfp4_gemm_skinny_fits(M, r->d); A_q / A_s are the workspace's code and scale areas.
+hipError_t launch_torq_linear_decode(const torq_rotation *r, const void *x_bf16, uint8_t *A_q, uint8_t *A_s,
+                                     const uint8_t *W_q, const uint8_t *W_s, void *out, int64_t M, int64_t N,
+                                     hipStream_t stream);
 
 // Block Gram matrix of the runs of G blocks (block_gram.hip): TG token-groups of G * 32 bf16 each.
 size_t block_gram_workspace_bytes(int G);

@@ -964,3 +964,100 @@ def test_rotate_random_shapes(tq, oracle, M, d, G):
     oc, os_ = oracle.quantize(_np(z))
     assert np.array_equal(_np(c), oc) and np.array_equal(_np(s), os_)
     rot.close()
+
+
+# ------------------------------------ torq_linear_single_launch (rotate + quantise inside the GEMM's launch) ----
+
+@pytest.mark.parametrize("M,N,d", DECODE_CASES)
+def test_linear_single_launch_against_chain_and_oracle(tq, oracle, M, N, d):
+    G = 128
+    x = synth.activations(M, d, nu=3.0, outliers=max(2, d // 200), outlier_scale=50.0, seed=1400 + M)
+    Ri, Ra = synth.rotations(G, seed=9 + M)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(N + 2 * d)
+    W_q = torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=DEV, generator=gen)
+    W_s = torch.randint(118, 128, (N, d // 32), dtype=torch.uint8, device=DEV, generator=gen)
+    xd = x.to(DEV)
+    x2 = (xd.float() * 0.5 + 0.25).to(torch.bfloat16)
+    ws = torch.zeros((tq.torq_linear_workspace_bytes(M, d),), dtype=torch.uint8, device=DEV)
+    off = (M * d // 2 + 255) // 256 * 256
+    outs = []
+    for rep in range(3):                              # repeated and interleaved calls: the counters return to zero
+        for xin in (xd, x2):
+            out = tq.torq_linear_single_launch(rot, xin, W_q, W_s, workspace=ws)
+            torch.cuda.synchronize()
+            A_q = ws[:M * d // 2].view(M, d // 2).clone()
+            A_s = ws[off:off + M * d // 32].view(M, d // 32).clone()
+            # (1) the product is the GEMM of the codes the launch left in the workspace, bit for bit
+            assert torch.equal(out, tq.mxfp4_gemm(A_q, A_s, W_q, W_s)), rep
+            outs.append((out.clone(), A_q, A_s))
+    assert all(torch.equal(outs[0][k], outs[i][k]) for i in (2, 4) for k in range(3))      # deterministic
+    out, A_q, A_s = outs[0]
+    # (2) the codes against the oracle's rotate + quantise: differences only within the rotation's error
+    # bar of a rounding boundary (codes) or of a power of two (scales)
+    z = oracle.rotate(synth.bf16_bits(x), G, Ri, Ra)
+    want_c, want_s = oracle.quantize(z)
+    got_c, got_s = _np(A_q), _np(A_s)
+    rms = np.sqrt((z.astype(np.float64) ** 2).mean(axis=1, keepdims=True))
+    tol = 1e-3 * rms
+    sdiff = got_s != want_s
+    assert sdiff.mean() <= 0.004
+    unpack = lambda c: np.stack([c & 15, c >> 4], axis=-1).reshape(M, d)
+    gc, wc = unpack(got_c), unpack(want_c)
+    cdiff = (gc != wc) & ~np.repeat(sdiff, 32, axis=1)
+    slack, s = _boundary_slack(z, want_s, tol)
+    near = (slack * s <= np.broadcast_to(tol, slack.shape)) | (np.abs(z) <= np.broadcast_to(tol, z.shape))
+    assert np.all(near[cdiff]) and cdiff.mean() <= 0.005
+    # (3) the layer against the oracle's whole chain, and against torq_linear
+    ref = oracle.gemm(want_c, want_s, _np(W_q), _np(W_s))
+    assert _rel_fro(_bits(out), ref) <= 5e-3
+    assert _rel_fro(_bits(out), _bits(tq.torq_linear(rot, xd, W_q, W_s))) <= 5e-3
+    rot.close()
+
+
+def test_linear_single_launch_replays_from_a_hip_graph_and_rejects_what_it_cannot_do(tq):
+    M, d, N, G = 2, 4096, 4096, 128
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(5)
+    W_q = torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=DEV, generator=gen)
+    W_s = torch.randint(118, 128, (N, d // 32), dtype=torch.uint8, device=DEV, generator=gen)
+    xs = [synth.activations(M, d, seed=1500 + i).to(DEV) for i in range(3)]
+    ws = torch.empty((tq.torq_linear_workspace_bytes(M, d),), dtype=torch.uint8, device=DEV)
+    wants = [tq.torq_linear_single_launch(rot, x, W_q, W_s, workspace=ws).clone() for x in xs]
+    x_in = xs[0].clone()
+    out = torch.zeros((M, N), dtype=torch.bfloat16, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        tq.torq_linear_single_launch(rot, x_in, W_q, W_s, out=out, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(4):
+            tq.torq_linear_single_launch(rot, x_in, W_q, W_s, out=out, workspace=ws)
+    for rep in range(6):
+        x_in.copy_(xs[rep % 3])
+        out.fill_(1.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, wants[rep % 3]), f"replay {rep}"
+    # what it does not cover is an error, not a silent detour
+    big = torch.zeros((65, d), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(tq.TorqError) as ei:
+        tq.torq_linear_single_launch(rot, big, W_q, W_s)
+    assert ei.value.status == tq.TORQ_EINVAL
+    rot64 = tq.Rotation(d, 64, *synth.rotations(64))
+    brot = tq.ButterflyRotation(d, G, np.zeros((7, 64), np.float32), Ra)
+    for bad in (rot64, brot):
+        with pytest.raises(tq.TorqError) as ei:
+            tq.torq_linear_single_launch(bad, xs[0], W_q, W_s)
+        assert ei.value.status == tq.TORQ_EINVAL
+        bad.close()
+    empty = tq.torq_linear_single_launch(rot, torch.zeros((0, d), dtype=torch.bfloat16, device=DEV), W_q, W_s)
+    assert empty.shape == (0, N)
+    rot.close()
