@@ -220,6 +220,11 @@ def main():
         # packed codes, and of a set eight times as long; HBM bound at half a byte per element
         print(json.dumps(hist_line(tq, codes, d, args.steps, args.warmup)), flush=True)
         print(json.dumps(hist_line(tq, torch.cat([codes] * 8, dim=0), d, args.steps, args.warmup)), flush=True)
+        # the W4A4 GEMM alone on the other layer shapes of the LLaMA3-8B / Qwen3-32B / LLaMA3-70B configurations
+        for (mm, nn, dd) in ((8192, 8192, 28672), (8192, 8192, 8192), (2048, 14336, 4096), (2048, 4096, 14336),
+                             (2048, 4096, 4096), (2048, 1024, 4096), (4096, 25600, 5120), (4096, 5120, 25600),
+                             (4096, 8192, 5120), (4096, 5120, 5120), (4096, 1024, 5120)):
+            print(json.dumps(gemm_line(tq, mm, nn, dd, args.steps, args.warmup)), flush=True)
         # decode-sized linear layers (few activation rows: weight streaming, HBM bound), timed as
         # replays of a HIP graph of 20 calls so that Python's launch overhead is not in the figure
         for (mm, nn, dd) in ((1, 14336, 4096), (16, 14336, 4096), (16, 4096, 14336), (16, 28672, 8192),
@@ -390,6 +395,35 @@ def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0, butterfly=False):
             "config": {"workload": f"sweep: X bf16 [{M}, {d}], G={G}{name}"}, "ms": round(ms, 4),
             "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
             "mfma_bf16_tflops": round(M * d * mfma_flop / (ms * 1e-3) / 1e12, 1)}
+
+
+def gemm_line(tq, M, N, d, steps, warmup):
+    """mxfp4_gemm alone on random codes and scale bytes of one layer shape (with the workspace the planner asks for)."""
+    import torch
+    dev = "cuda:0"
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(M + N + d)
+    A_q = torch.randint(0, 256, (M, d // 2), dtype=torch.uint8, device=dev, generator=gen)
+    W_q = torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=dev, generator=gen)
+    A_s = torch.randint(118, 136, (M, d // 32), dtype=torch.uint8, device=dev, generator=gen)
+    W_s = torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=dev, generator=gen)
+    out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+    ws = torch.empty((max(tq.mxfp4_gemm_workspace_bytes(M, N, d), 16),), dtype=torch.uint8, device=dev)
+    for _ in range(warmup):
+        tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=out, workspace=ws)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=out, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    tf = 2.0 * M * N * d / (ms * 1e-3) / 1e12
+    streaming, tile_m, tile_n, pieces = tq.mxfp4_gemm_plan(M, N, d, ws.numel())
+    kernel = "weight-streaming" if streaming else f"tiled {tile_m}x{tile_n}" + (f", k cut in {pieces}" if pieces > 1 else "")
+    return {"metric": "mxfp4_gemm", "value": round(tf, 1), "unit": "TFLOP/s",
+            "config": {"workload": f"A [{M}, {d}] x W [{N}, {d}] packed MXFP4 -> bf16 [{M}, {N}]", "gemm_kernel": kernel},
+            "ms": round(ms, 4), "frac_fp4_peak": round(tf / 10100.0, 4)}
 
 
 def gram_line(tq, x, G, steps, warmup):
