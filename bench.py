@@ -42,7 +42,7 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=50)
-    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="llama3_70b_up")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -337,8 +337,7 @@ def sample_board(torch, launch, seconds):
 def copy_line(torch, dev, steps):
     src = torch.empty((1 << 30,), dtype=torch.uint8, device=dev).random_(0, 255)
     dst = torch.empty_like(src)
-    for _ in range(3):
-        dst.copy_(src)
+    settle(torch, lambda: dst.copy_(src), 3)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(steps):
@@ -350,6 +349,21 @@ def copy_line(torch, dev, steps):
     return {"metric": "device copy bandwidth (runtime's kernel, context)", "value": round(gbs, 1), "unit": "GB/s",
             "config": {"workload": "1 GiB read + 1 GiB written"}, "ms": round(ms, 4),
             "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+
+
+def settle(torch, call, warmup, seconds=0.04):
+    """Untimed launches in front of a measurement: `warmup` of them, then more until `seconds` have passed.
+    After a pause (input generation is one for the part's power management) the shader clock takes some
+    tens of milliseconds of sustained work to reach the level it then keeps: the first few hundred launches
+    of a 50 us kernel run up to 20 % slower than the ones that follow."""
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(8):
+            call()
+        torch.cuda.synchronize()
 
 
 def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0, butterfly=False):
@@ -377,8 +391,7 @@ def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0, butterfly=False):
             tq.torq_rotate_quantize(rot, x, codes=codes, scales=scales)
         else:
             tq.torq_rotate_quantize_fmt(rot, x, fmt, gs, codes=codes, scales=scales)
-    for _ in range(warmup):
-        call()
+    settle(torch, call, warmup)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(steps):
@@ -409,8 +422,7 @@ def gemm_line(tq, M, N, d, steps, warmup):
     W_s = torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=dev, generator=gen)
     out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
     ws = torch.empty((max(tq.mxfp4_gemm_workspace_bytes(M, N, d), 16),), dtype=torch.uint8, device=dev)
-    for _ in range(warmup):
-        tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=out, workspace=ws)
+    settle(torch, lambda: tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=out, workspace=ws), warmup)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(steps):
@@ -433,8 +445,7 @@ def gram_line(tq, x, G, steps, warmup):
     xs = [x, x.clone(), x.clone()]                   # 3 x 134 MB: more than the Infinity Cache holds
     Sigma = torch.empty((G, G), dtype=torch.float64, device=x.device)
     ws = torch.empty((tq.torq_block_gram_workspace_bytes(G),), dtype=torch.uint8, device=x.device)
-    for i in range(warmup):
-        tq.torq_block_gram(xs[i % 3], G, Sigma=Sigma, workspace=ws)
+    settle(torch, lambda: tq.torq_block_gram(xs[0], G, Sigma=Sigma, workspace=ws), warmup)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for i in range(steps):
@@ -456,8 +467,7 @@ def hist_line(tq, codes, d, steps, warmup):
     cs = [codes] + [codes.clone() for _ in range(copies - 1)]
     counts = torch.empty((32, 8), dtype=torch.int64, device=codes.device)
     ws = torch.empty((tq.torq_code_histogram_workspace_bytes(),), dtype=torch.uint8, device=codes.device)
-    for i in range(warmup):
-        tq.torq_code_histogram(cs[i % copies], d, counts=counts, workspace=ws)
+    settle(torch, lambda: tq.torq_code_histogram(cs[0], d, counts=counts, workspace=ws), warmup)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for i in range(steps):
@@ -503,7 +513,7 @@ def decode_line(tq, synth, M, N, d):
         with torch.cuda.graph(graph, stream=side):
             for i in range(calls):
                 fn(rot, x, W_q[i % n_copies], W_s[i % n_copies], out=out, workspace=ws)
-        graph.replay()
+        settle(torch, graph.replay, 1)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         reps = 10
         e0.record()
