@@ -45,6 +45,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=30)
     ap.add_argument("--workload", default="llama3_70b_up")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-board-sample", action="store_true",
+                    help="skip the two one-second runs that sample board power and shader clock (for kernel "
+                         "traces: they add some 20000 launches to the per-kernel averages)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that a rocprofv3 --pmc run of this "
                          "command carries its own scale for FETCH_SIZE / WRITE_SIZE")
@@ -123,8 +126,10 @@ def main():
 
     # ---- board power and shader clock while each kernel runs alone for a second (the driver's
     # sensors, read from sysfs; None where the machine does not expose them)
-    gemm_env = sample_board(torch, lambda i: tq.mxfp4_gemm(codes, scales, W_q, W_s, out=out), 1.0)
-    rq_env = sample_board(torch, lambda i: tq.torq_rotate_quantize(rot, x_copies[i % 3], codes=codes, scales=scales), 1.0)
+    gemm_env = rq_env = None
+    if not args.no_board_sample:
+        gemm_env = sample_board(torch, lambda i: tq.mxfp4_gemm(codes, scales, W_q, W_s, out=out), 1.0)
+        rq_env = sample_board(torch, lambda i: tq.torq_rotate_quantize(rot, x_copies[i % 3], codes=codes, scales=scales), 1.0)
     del x_copies
 
     # ---- what the matrix cores sustain on this part with nothing else running, on this step's own
