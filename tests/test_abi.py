@@ -134,3 +134,12 @@ def test_format_entry_points_reject_unknown_formats_and_bad_scales():
     assert L.torq_quantize_f32_fmt(good, 0, 64, 1, f(0.0), None, None, None) == binding.TORQ_OK          # empty; scale unused
     assert L.torq_quantize_f32_fmt(C.c_void_p(0x1004), 4, 64, 1, f(1.0), good, good, None) == binding.TORQ_EALIGN
     assert L.torq_rotate_quantize_fmt(None, good, 4, 1, f(1.0), good, good, None) == binding.TORQ_EINVAL
+
+
+def test_bench_refuses_more_than_one_gpu():
+    # the build is for one GPU: asking bench.py for more ends with a message before anything is imported
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert p.returncode != 0 and "ONE GPU" in (p.stdout + p.stderr)
