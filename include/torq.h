@@ -185,9 +185,10 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16,
  * mxfp4_gemm of those codes.  Every workgroup exits (the wait is bounded; a workgroup that gives up
  * leaves its outputs unwritten, which cannot happen while the rotating workgroups run).  Calls on one
  * handle must not overlap in time (they share the handle's counters; stream order is enough).  On
- * this part the hand-off between workgroups costs what the second launch costs: measured 1-5 us
- * SLOWER than torq_linear (10.1 against 8.1 us at [1, 4096] -> 4096), which is why torq_linear does
- * not use it. */
+ * this part the hand-off between workgroups costs what the second launch costs: measured against
+ * torq_linear 14.4 against 11.7 us at [1, 4096] -> 14336, 13.1 against 13.5 us at [16, 4096] -> 14336,
+ * 36.5 against 34.3 us at [16, 8192] -> 28672 and 85 against 37 us at [64, 8192] -> 28672 (where
+ * torq_linear takes a tiled GEMM kernel), which is why torq_linear does not use it. */
 int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q, const uint8_t *W_s,
                               void *out_bf16, int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
                               void *stream);
