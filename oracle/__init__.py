@@ -66,6 +66,8 @@ def lib():
         L.torq_o_gemm_sampled.argtypes = [vp, vp, vp, vp, i32, i64, vp, vp, vp, vp]
         L.torq_o_block_gram.restype = None
         L.torq_o_block_gram.argtypes = [vp, i64, i32, i32, vp]
+        L.torq_o_block_gram_positions.restype = None
+        L.torq_o_block_gram_positions.argtypes = [vp, i64, i32, i32, vp]
         L.torq_o_equalize.restype = i32
         L.torq_o_equalize.argtypes = [vp, i32, f64, vp]
         u64p = C.POINTER(C.c_uint64)
@@ -295,6 +297,17 @@ def block_gram(x_bf16, G):
     assert d % 32 == 0 and (d // 32) % G == 0
     S = np.empty((G, G), np.float64)
     lib().torq_o_block_gram(_p(x), M, d, G, _p(S))
+    return S
+
+
+def block_gram_positions(x_bf16, G):
+    """x_bf16: uint16 [M, d] -> float64 [32, G, G]: the Gram matrix of the runs of G blocks kept apart by
+    the position inside a block (Sigma_k of Theorem 4.1); sums over axis 0 to block_gram."""
+    x = _arr(x_bf16, np.uint16)
+    M, d = x.shape
+    assert d % 32 == 0 and (d // 32) % G == 0
+    S = np.empty((32, G, G), np.float64)
+    lib().torq_o_block_gram_positions(_p(x), M, d, G, _p(S))
     return S
 
 

@@ -437,6 +437,32 @@ void torq_o_block_gram(const uint16_t *x_bf16, int64_t M, int d, int G, double *
         for (int i = 0; i < G * G; ++i) Sigma[i] /= (double)groups;
 }
 
+/* The same statistic kept apart by the position k inside a block: the covariance matrices
+ * Sigma_k of Theorem 4.1 (one per position, B x B each; the calibration cost analysis counts
+ * "covariance matrices for all K positions"):
+ *
+ *   Sigma_pos[k][b][b'] = mean over the runs of G blocks of  X[b][k] X[b'][k]
+ *
+ * so that the sum over k is torq_o_block_gram's Sigma. */
+void torq_o_block_gram_positions(const uint16_t *x_bf16, int64_t M, int d, int G, double *Sigma_pos)
+{
+    const int B = d / BLK;
+    const int64_t groups = M * (int64_t)(B / G);
+    for (int64_t i = 0; i < (int64_t)BLK * G * G; ++i) Sigma_pos[i] = 0.0;
+    for (int64_t m = 0; m < M; ++m)
+        for (int g0 = 0; g0 < B; g0 += G) {
+            const uint16_t *Xg = x_bf16 + m * (int64_t)d + (int64_t)g0 * BLK;
+            for (int k = 0; k < BLK; ++k)
+                for (int b = 0; b < G; ++b)
+                    for (int bp = 0; bp < G; ++bp)
+                        Sigma_pos[((int64_t)k * G + b) * G + bp] +=
+                            (double)torq_o_bf16_to_f32(Xg[b * BLK + k]) *
+                            (double)torq_o_bf16_to_f32(Xg[bp * BLK + k]);
+        }
+    if (groups > 0)
+        for (int64_t i = 0; i < (int64_t)BLK * G * G; ++i) Sigma_pos[i] /= (double)groups;
+}
+
 /* Algorithm 1 (Section 5.1): plane rotations until diag(R Sigma R^T) = c 1,
  * c = tr(Sigma) / B.  Each step takes the block i furthest above c and the
  * block j furthest below it (opposite deviation signs, as the algorithm asks)

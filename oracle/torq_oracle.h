@@ -119,6 +119,8 @@ void torq_o_gemm_sampled(const uint8_t *A_q, const uint8_t *A_s,
  * run of G consecutive 32-element blocks of one row (every row of [M, d] holds d/32/G of them).
  * Sigma is G x G, row-major, double.  Its diagonal holds the mean block energies. */
 void torq_o_block_gram(const uint16_t *x_bf16, int64_t M, int d, int G, double *Sigma);
+/* Section 4.2, Theorem 4.1: the per-position covariance matrices Sigma_k, [32][G][G]; their sum is Sigma. */
+void torq_o_block_gram_positions(const uint16_t *x_bf16, int64_t M, int d, int G, double *Sigma_pos);
 
 /* Algorithm 1 with the equalising angle (the printed Jacobi angle separates
  * the two diagonal entries instead of moving one onto the target).  Sigma is

@@ -54,6 +54,11 @@ MUTATIONS = [
      "const uint16_t *X = x_bf16 + m * (int64_t)d;"),
     ("gram_sum_not_mean", "for (int i = 0; i < G * G; ++i) Sigma[i] /= (double)groups;",
      "for (int i = 0; i < G * G; ++i) Sigma[i] /= (double)M;"),
+    ("gram_pos_wrong_position", "(double)torq_o_bf16_to_f32(Xg[bp * BLK + k]);", "(double)torq_o_bf16_to_f32(Xg[bp * BLK + (k ^ 1)]);"),
+    ("gram_pos_layout", "Sigma_pos[((int64_t)k * G + b) * G + bp] +=", "Sigma_pos[((int64_t)b * BLK + k) * G + bp] +="),
+    ("gram_pos_sum_not_mean", "Sigma_pos[i] /= (double)groups;", "Sigma_pos[i] /= (double)M;"),
+    ("gram_pos_ignores_later_runs", "const uint16_t *Xg = x_bf16 + m * (int64_t)d + (int64_t)g0 * BLK;",
+     "const uint16_t *Xg = x_bf16 + m * (int64_t)d;"),
     ("gram_wrong_partner", "(double)torq_o_bf16_to_f32(X[bp * BLK + k]);", "(double)torq_o_bf16_to_f32(X[bp * BLK + (k ^ 1)]);"),
     ("equalize_other_root", "const double t = -(a - c) / (g + (g >= 0.0 ? D : -D));", "const double t = -(a - c) / (g - (g >= 0.0 ? D : -D) + 1e-300);"),
     ("equalize_jacobi_angle", "const double t = -(a - c) / (g + (g >= 0.0 ? D : -D));",

@@ -234,6 +234,39 @@ def test_block_gram_closed_forms(oracle):
     assert S[3, 3] == e and S[4, 4] == e and S[3, 4] == -e and S[4, 3] == -e and np.count_nonzero(S) == 4
 
 
+def test_block_gram_positions_against_its_definition_and_closed_forms(oracle):
+    # Sigma_k of Theorem 4.1, one matrix per position inside a block: numpy's einsum on the widened values,
+    # the sum over k (the block Gram, pinned above), and inputs whose answer can be written down
+    M, d, G = 24, 3072, 32
+    x = synth.activations(M, d, nu=3.0, outliers=12, outlier_scale=50.0, seed=43)
+    xb = synth.bf16_bits(x)
+    P = oracle.block_gram_positions(xb, G)
+    X = x.to(torch.float64).numpy().reshape(M * (d // 32 // G), G, 32)
+    want = np.einsum("tbk,tck->kbc", X, X) / X.shape[0]
+    assert P.shape == (32, G, G) and np.abs(P - want).max() <= 1e-12 * np.abs(want).max()
+    assert np.abs(P.sum(axis=0) - oracle.block_gram(xb, G)).max() <= 1e-12 * np.abs(want).max()
+    assert all(np.array_equal(P[k], P[k].T) for k in range(32))
+    # position k of block b varies over the rows as a known sequence: x[m][32 b + k] = (b + 1) * s_k(m)
+    # with s_k(m) = 1 if m % 32 == k else 0: Sigma_k[b][b'] = (b + 1)(b' + 1) / 32 for every k
+    G2 = 16
+    x2 = torch.zeros((32, 32 * G2), dtype=torch.float32)
+    for m in range(32):
+        for b in range(G2):
+            x2[m, 32 * b + m] = b + 1.0
+    P2 = oracle.block_gram_positions(synth.bf16_bits(x2.to(torch.bfloat16)), G2)
+    outer = np.outer(np.arange(1, G2 + 1), np.arange(1, G2 + 1)) / 32.0
+    assert all(np.array_equal(P2[k], outer) for k in range(32))
+    # only position 5 is ever non-zero: every other matrix is zero, and an antisymmetric pair of blocks
+    # gives a negative off-diagonal entry (the order of the two factors and their signs)
+    x3 = torch.zeros((2, 32 * G2), dtype=torch.float32)
+    x3[0, 32 * 3 + 5], x3[0, 32 * 9 + 5] = 2.0, -3.0
+    x3[1, 32 * 3 + 5] = 1.0
+    P3 = oracle.block_gram_positions(synth.bf16_bits(x3.to(torch.bfloat16)), G2)
+    assert np.count_nonzero(P3[np.arange(32) != 5]) == 0
+    assert P3[5, 3, 3] == 2.5 and P3[5, 9, 9] == 4.5 and P3[5, 3, 9] == -3.0 and P3[5, 9, 3] == -3.0
+    assert np.count_nonzero(P3[5]) == 4
+
+
 def test_rotating_with_the_equalizer_of_the_sample_gram_equalizes_block_energies(oracle):
     # Sections 4.2 / 5.1 end to end on the oracle: Gram of a sample -> Algorithm 1 -> rotate that
     # sample -> Gram of the result has a constant diagonal (and is R Sigma R^T)
