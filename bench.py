@@ -459,9 +459,18 @@ def gram_line(tq, x, G, steps, warmup):
     torch.cuda.synchronize()
     ms = e0.elapsed_time(e1) / steps
     gbs = M * d * 2.0 / (ms * 1e-3) / 1e9
+    # the per-position matrices Sigma_k: 32 passes of the same kernel over x
+    Sp = torch.empty((32, G, G), dtype=torch.float64, device=x.device)
+    tq.torq_block_gram_positions(xs[0], G, Sigma_pos=Sp, workspace=ws)
+    e0.record()
+    for i in range(3):
+        tq.torq_block_gram_positions(xs[i % 3], G, Sigma_pos=Sp, workspace=ws)
+    e1.record()
+    torch.cuda.synchronize()
+    pos_ms = e0.elapsed_time(e1) / 3
     return {"metric": "torq_block_gram bandwidth", "value": round(gbs, 1), "unit": "GB/s",
             "config": {"workload": f"calibration statistic: X bf16 [{M}, {d}], G={G}"}, "ms": round(ms, 4),
-            "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
+            "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4), "positions_ms": round(pos_ms, 3)}
 
 
 def hist_line(tq, codes, d, steps, warmup):

@@ -208,6 +208,16 @@ int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, cons
  * M = 0 is TORQ_EINVAL (a mean over nothing).  Sums are fp32 inside a workgroup and double across
  * workgroups, in a fixed order: the result is deterministic.
  *
+ * torq_block_gram_positions: the same statistic kept apart by the position k inside a block, the
+ * covariance matrices Sigma_k of Theorem 4.1 (Section 4.2; the calibration cost analysis of the
+ * appendix counts "covariance matrices for all K positions"),
+ *   Sigma_pos[k][b][b'] = mean over token-groups of X[b][k] X[b'][k],   k < 32,
+ * whose sum over k is Sigma.  Arguments as torq_block_gram, with
+ *   Sigma_pos  device, 32*G*G doubles, [k][b][b'], overwritten
+ * One pass over x per position (32 launches of the same kernel on the stream).  Each matrix can be
+ * handed to torq_equalize_inter; the online path of Algorithm 3 applies ONE R_inter to all
+ * positions, so a per-position rotation is not something torq_rotation_create takes.
+ *
  * torq_equalize_inter: Algorithm 1 on the HOST, in double.  Plane rotations of the pair (block
  * furthest above the mean energy c = tr(Sigma)/G, block furthest below it) until every diagonal
  * entry of R Sigma R^T is within eps of c; at most G-1 of them.  The rotation angle is the one that
@@ -242,6 +252,8 @@ int torq_rotation_create_butterfly(torq_rotation_t **out, int d, int G, const fl
 size_t torq_block_gram_workspace_bytes(int G);
 int torq_block_gram(const void *x_bf16, int64_t M, int d, int G, double *Sigma,
                     void *workspace, size_t workspace_bytes, void *stream);
+int torq_block_gram_positions(const void *x_bf16, int64_t M, int d, int G, double *Sigma_pos,
+                              void *workspace, size_t workspace_bytes, void *stream);
 int torq_equalize_inter(const double *Sigma_host, int G, double eps, float *R_inter_host, int *steps);
 
 /* ------------------------------------------------------------------------ */

@@ -18,7 +18,7 @@ EXPORTS = [
     "torq_linear_workspace_bytes", "torq_linear", "mxfp4_gemm_workspace_bytes", "mxfp4_gemm_ws", "mxfp4_gemm_plan",
     "torq_rotate_quantize_fmt", "torq_quantize_f32_fmt", "torq_equalize_inter_butterfly",
     "torq_rotation_create_butterfly", "torq_linear_single_launch",
-    "torq_linear_workspace_bytes_n", "torq_block_gram_workspace_bytes", "torq_block_gram",
+    "torq_linear_workspace_bytes_n", "torq_block_gram_workspace_bytes", "torq_block_gram", "torq_block_gram_positions",
     "torq_equalize_inter", "torq_code_histogram_workspace_bytes", "torq_code_histogram", "torq_intra_pair_scores",
     "torq_intra_best_angle", "torq_calibrate_intra", "torq_diag_mfma_burn",
 ]
@@ -88,6 +88,8 @@ def lib():
         L.torq_block_gram_workspace_bytes.argtypes = [i32]
         L.torq_block_gram.restype = i32
         L.torq_block_gram.argtypes = [vp, i64, i32, i32, vp, vp, sz, vp]
+        L.torq_block_gram_positions.restype = i32
+        L.torq_block_gram_positions.argtypes = [vp, i64, i32, i32, vp, vp, sz, vp]
         L.torq_equalize_inter.restype = i32
         L.torq_equalize_inter.argtypes = [vp, i32, C.c_double, vp, C.POINTER(i32)]
         L.torq_code_histogram_workspace_bytes.restype = sz
@@ -363,6 +365,21 @@ def torq_block_gram(x_bf16: torch.Tensor, G: int, Sigma=None, workspace=None, st
                                  _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)),
            "torq_block_gram")
     return Sigma
+
+
+def torq_block_gram_positions(x_bf16: torch.Tensor, G: int, Sigma_pos=None, workspace=None, stream=None):
+    """Sigma_pos [32, G, G] float64 on the device: the Gram matrix kept apart by the position inside a block."""
+    M, d = x_bf16.shape
+    if Sigma_pos is None:
+        Sigma_pos = torch.empty((32, G, G), dtype=torch.float64, device=x_bf16.device)
+    if workspace is None:
+        workspace = torch.empty((max(torq_block_gram_workspace_bytes(G), 16),), dtype=torch.uint8,
+                                device=x_bf16.device)
+    _check(lib().torq_block_gram_positions(_dev(x_bf16, torch.bfloat16, "x"), M, d, G,
+                                           _dev(Sigma_pos, torch.float64, "Sigma_pos"),
+                                           _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                           _stream(stream)), "torq_block_gram_positions")
+    return Sigma_pos
 
 
 def torq_equalize_inter(Sigma, eps: float = 0.0):

@@ -448,8 +448,24 @@ int torq_block_gram(const void *x_bf16, int64_t M, int d, int G, double *Sigma, 
   if (misaligned(x_bf16) || misaligned(workspace) || (reinterpret_cast<uintptr_t>(Sigma) & 7u)) return TORQ_EALIGN;
   if (workspace_bytes < torq::block_gram_workspace_bytes(G)) return TORQ_EWORKSPACE;
   const int64_t TG = M * (int64_t)(d / TORQ_BLOCK / G);
-  hipError_t e = torq::launch_block_gram(x_bf16, TG, G, Sigma, workspace, (hipStream_t)stream);
+  hipError_t e = torq::launch_block_gram(x_bf16, TG, G, -1, Sigma, workspace, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+int torq_block_gram_positions(const void *x_bf16, int64_t M, int d, int G, double *Sigma_pos, void *workspace,
+                              size_t workspace_bytes, void *stream) {
+  if (M <= 0 || d <= 0 || d % TORQ_BLOCK != 0) return TORQ_EINVAL;
+  if (G <= 0 || G % 16 != 0 || G > TORQ_MAX_G || (d / TORQ_BLOCK) % G != 0) return TORQ_EINVAL;
+  if (!x_bf16 || !Sigma_pos || !workspace) return TORQ_EINVAL;
+  if (misaligned(x_bf16) || misaligned(workspace) || (reinterpret_cast<uintptr_t>(Sigma_pos) & 7u)) return TORQ_EALIGN;
+  if (workspace_bytes < torq::block_gram_workspace_bytes(G)) return TORQ_EWORKSPACE;
+  const int64_t TG = M * (int64_t)(d / TORQ_BLOCK / G);
+  // one pass per position: the partial sums in the workspace are reused in stream order
+  for (int k = 0; k < TORQ_BLOCK; ++k) {
+    hipError_t e = torq::launch_block_gram(x_bf16, TG, G, k, Sigma_pos + (size_t)k * G * G, workspace, (hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e);
+  }
+  return TORQ_OK;
 }
 
 // Algorithm 1 (Section 5.1) with the equalising angle.  One step takes the block p furthest above

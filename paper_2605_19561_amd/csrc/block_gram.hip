@@ -28,7 +28,7 @@ constexpr int GRAM_GROUPS_PER_TRIP = 2;
 
 template <int NT>
 __global__ void __launch_bounds__(64 * ((NT + 1) / 2))
-block_gram_kernel(const uint4 *__restrict__ x, int64_t TG, float *__restrict__ partial) {
+block_gram_kernel(const uint4 *__restrict__ x, int64_t TG, int position, float *__restrict__ partial) {
   constexpr int G = 16 * NT;
   constexpr int NTHR = 64 * ((NT + 1) / 2);
   constexpr int CHUNKS = 4 * G;                          // 16-byte chunks of one token-group
@@ -59,6 +59,17 @@ block_gram_kernel(const uint4 *__restrict__ x, int64_t TG, float *__restrict__ p
     st_off[i] = r * 64 + (((c & 3) ^ ((r >> 2) & 3)) * 16);
   }
 
+  // Which bits of this thread's chunks count: all of them for Sigma (position < 0); for Sigma_k only
+  // element `position` of every block, i.e. one half of word (position / 2) % 4 of chunk position / 8.
+  uint32_t keep[CH][4];
+#pragma unroll
+  for (int i = 0; i < CH; ++i)
+#pragma unroll
+    for (int w = 0; w < 4; ++w)
+      keep[i][w] = position < 0 ? 0xFFFFFFFFu
+                 : ((((tid + i * NTHR) & 3) == ((position >> 3) & 3) && w == ((position >> 1) & 3))
+                        ? ((position & 1) ? 0xFFFF0000u : 0x0000FFFFu) : 0u);
+
   // a trip = U token-groups; trips are dealt to the workgroups round robin
   const int64_t ntrip = (TG + U - 1) / U;
   uint4 regs[U][CH];
@@ -70,6 +81,10 @@ block_gram_kernel(const uint4 *__restrict__ x, int64_t TG, float *__restrict__ p
       for (int i = 0; i < CH; ++i) {
         const int c = tid + i * NTHR;
         regs[u][i] = (tg < TG && c < CHUNKS) ? x[tg * CHUNKS + c] : make_uint4(0, 0, 0, 0);
+        regs[u][i].x &= keep[i][0];
+        regs[u][i].y &= keep[i][1];
+        regs[u][i].z &= keep[i][2];
+        regs[u][i].w &= keep[i][3];
       }
     }
   };
@@ -160,7 +175,7 @@ size_t block_gram_workspace_bytes(int G) {
 }
 
 template <int NT>
-static hipError_t launch_nt(const void *x, int64_t TG, double *Sigma, void *workspace, hipStream_t stream) {
+static hipError_t launch_nt(const void *x, int64_t TG, int position, double *Sigma, void *workspace, hipStream_t stream) {
   constexpr int G = 16 * NT;
   float *partial = static_cast<float *>(workspace);
   double *slices = reinterpret_cast<double *>(static_cast<char *>(workspace) + (size_t)GRAM_MAX_WG * G * G * sizeof(float));
@@ -168,7 +183,7 @@ static hipError_t launch_nt(const void *x, int64_t TG, double *Sigma, void *work
   const int n_wg = (int)(ntrip < GRAM_MAX_WG ? ntrip : GRAM_MAX_WG);
   const size_t lds_bytes = 2 * (size_t)GRAM_GROUPS_PER_TRIP * G * 64;
   hipLaunchKernelGGL((block_gram_kernel<NT>), dim3(n_wg), dim3(64 * ((NT + 1) / 2)), lds_bytes, stream,
-                     reinterpret_cast<const uint4 *>(x), TG, partial);
+                     reinterpret_cast<const uint4 *>(x), TG, position, partial);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
   hipLaunchKernelGGL(block_gram_reduce1_kernel, dim3((G * G + 255) / 256, GRAM_SLICES), dim3(256), 0, stream, partial,
@@ -181,11 +196,13 @@ static hipError_t launch_nt(const void *x, int64_t TG, double *Sigma, void *work
 }
 
 // G a multiple of 16 in [16, 256], TG > 0 token-groups, workspace of block_gram_workspace_bytes(G)
-hipError_t launch_block_gram(const void *x_bf16, int64_t TG, int G, double *Sigma, void *workspace,
+// position: -1 for Sigma, 0 .. 31 for the per-position matrix Sigma_k (every other element of a block
+// counts as zero)
+hipError_t launch_block_gram(const void *x_bf16, int64_t TG, int G, int position, double *Sigma, void *workspace,
                              hipStream_t stream) {
   switch (G / 16) {
 #define TORQ_GRAM_CASE(NT_) \
-  case NT_: return launch_nt<NT_>(x_bf16, TG, Sigma, workspace, stream);
+  case NT_: return launch_nt<NT_>(x_bf16, TG, position, Sigma, workspace, stream);
     TORQ_GRAM_CASE(1) TORQ_GRAM_CASE(2) TORQ_GRAM_CASE(3) TORQ_GRAM_CASE(4)
     TORQ_GRAM_CASE(5) TORQ_GRAM_CASE(6) TORQ_GRAM_CASE(7) TORQ_GRAM_CASE(8)
     TORQ_GRAM_CASE(9) TORQ_GRAM_CASE(10) TORQ_GRAM_CASE(11) TORQ_GRAM_CASE(12)

@@ -69,7 +69,7 @@ hipError_t launch_torq_linear_decode(const torq_rotation *r, const void *x_bf16,
 
 // Block Gram matrix of the runs of G blocks (block_gram.hip): TG token-groups of G * 32 bf16 each.
 size_t block_gram_workspace_bytes(int G);
-hipError_t launch_block_gram(const void *x_bf16, int64_t TG, int G, double *Sigma, void *workspace,
+hipError_t launch_block_gram(const void *x_bf16, int64_t TG, int G, int position, double *Sigma, void *workspace,
                              hipStream_t stream);
 
 // Codeword histogram per in-block position (code_histogram.hip): nblk blocks of 16 code bytes.

@@ -56,6 +56,12 @@ def test_equalize_inter_trivial_and_invalid_inputs():
     assert L.torq_block_gram(good, 4, 4096, 48, good, good, 1 << 30, None) == binding.TORQ_EINVAL   # 128 % 48
     assert L.torq_block_gram(good, 4, 4096, 128, good, good, 16, None) == binding.TORQ_EWORKSPACE
     assert L.torq_block_gram(C.c_void_p(0x1004), 4, 4096, 128, good, good, 1 << 30, None) == binding.TORQ_EALIGN
+    for fn in (L.torq_block_gram_positions,):
+        assert fn(good, 0, 4096, 128, good, good, 1 << 30, None) == binding.TORQ_EINVAL
+        assert fn(good, 4, 4096, 48, good, good, 1 << 30, None) == binding.TORQ_EINVAL
+        assert fn(good, 4, 4096, 128, None, good, 1 << 30, None) == binding.TORQ_EINVAL
+        assert fn(good, 4, 4096, 128, good, good, 16, None) == binding.TORQ_EWORKSPACE
+        assert fn(good, 4, 4096, 128, C.c_void_p(0x1004), good, 1 << 30, None) == binding.TORQ_EALIGN
 
 
 # ---- the butterfly equaliser (Section 5.1's output condition, reached in log2 G rounds) ------------

@@ -473,6 +473,24 @@ def test_block_gram_against_oracle(tq, oracle, M, d, G):
     assert np.array_equal(_np(tq.torq_block_gram(x.to(DEV), G)), got)
 
 
+@pytest.mark.parametrize("M,d,G", [(5, 4096, 128), (33, 2048, 16), (7, 5120, 80), (3, 8192, 256), (64, 3072, 48)])
+def test_block_gram_positions_against_oracle(tq, oracle, M, d, G):
+    # Sigma_k of Theorem 4.1: one matrix per position inside a block
+    x = synth.activations(M, d, nu=3.0, outliers=max(2, d // 200), outlier_scale=50.0, seed=350 + G + M)
+    want = oracle.block_gram_positions(synth.bf16_bits(x), G)
+    xd = x.to(DEV)
+    got = _np(tq.torq_block_gram_positions(xd, G))
+    torch.cuda.synchronize()
+    assert got.shape == (32, G, G)
+    for k in range(32):
+        assert np.abs(got[k] - want[k]).max() <= 1e-5 * np.abs(want[k]).max(), k
+        assert np.array_equal(got[k], got[k].T)
+    # the positions add up to the block Gram matrix (the two kernels' fp32 sums differ in order only)
+    S = _np(tq.torq_block_gram(xd, G))
+    assert np.abs(got.sum(axis=0) - S).max() <= 1e-5 * np.abs(S).max()
+    assert np.array_equal(_np(tq.torq_block_gram_positions(xd, G)), got)          # deterministic
+
+
 def test_calibrated_rotation_equalizes_block_energies_on_the_gpu(tq, oracle):
     # Gram of a sample (GPU) -> Algorithm 1 (host) -> rotation handle -> rotate the sample (GPU):
     # the rotated sample's block energies are all tr(Sigma) / G (Theorem 4.1's equality condition)
