@@ -183,7 +183,7 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16,
  * come from the 16-block rotation kernel, so a value that sits within the rotation's error bar of a
  * rounding boundary may get the neighbouring code of torq_rotate_quantize's; the product is exactly
  * mxfp4_gemm of those codes.  Every workgroup exits (the wait is bounded; a workgroup that gives up
- * leaves its outputs unwritten, which cannot happen while the rotating workgroups run).  Calls on one
+ * writes NaN to its outputs, which cannot happen while the rotating workgroups run).  Calls on one
  * handle must not overlap in time (they share the handle's counters; stream order is enough).  On
  * this part the hand-off between workgroups costs what the second launch costs: measured against
  * torq_linear 14.4 against 11.7 us at [1, 4096] -> 14336, 13.1 against 13.5 us at [16, 4096] -> 14336,

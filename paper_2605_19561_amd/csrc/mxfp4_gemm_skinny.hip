@@ -235,7 +235,7 @@ __device__ __forceinline__ void decode_consumer_done(unsigned *ctr, int gid, int
 // cache write-back or invalidate.
 // Workgroups are dispatched in index order and the producers come first, so a waiting consumer can
 // never keep a producer off the machine; the wait is bounded all the same (a consumer that gives
-// up leaves its outputs unwritten).  Launches that share a counter pair must not overlap.
+// up writes NaN to its outputs).  Launches that share a counter pair must not overlap.
 template <int MT, int NS, int PT>
 __global__ void __launch_bounds__(64 * WAVES, 4)
 torq_linear_decode_kernel(const uint4 *__restrict__ x, int64_t TG, const uint16_t *__restrict__ inter_hi,
@@ -313,6 +313,12 @@ torq_linear_decode_kernel(const uint4 *__restrict__ x, int64_t TG, const uint16_
   __builtin_amdgcn_sched_barrier(0);
   asm volatile("" ::: "memory");                   // nothing below is moved above the wait
   if (!ready) {                                    // uniform over the workgroup
+    // gave up: mark this strip's outputs as NaN rather than leave what the buffer held
+    for (int e = tid; e < M * 16 * NS; e += 64 * WAVES) {
+      const int m = e / (16 * NS);
+      const int64_t n = n0 + e % (16 * NS);
+      if (n < N) out[(int64_t)m * N + n] = 0x7FC0;
+    }
     if (tid == 0) decode_consumer_done(ctr, (int)blockIdx.x - P, groups);
     return;
   }
