@@ -204,6 +204,10 @@ def main():
         print(json.dumps(copy_line(torch, dev, args.steps)), flush=True)
         for dd in (4096, 8192, 14336, 28672):
             print(json.dumps(sweep_line(tq, synth, dd, args.steps, args.warmup)), flush=True)
+        # the Qwen3-32B widths (d/32 = 160 and 800: G = 80, the 16x16x32 MFMA kernel; and G = 160 at d = 5120)
+        for dd in (5120, 25600):
+            print(json.dumps(sweep_line(tq, synth, dd, args.steps, args.warmup)), flush=True)
+        print(json.dumps(sweep_line(tq, synth, 5120, args.steps, args.warmup, G=160)), flush=True)
         # G = d/32: Algorithm 3 as printed (one R_inter over the whole row), a dense contraction
         print(json.dumps(sweep_line(tq, synth, 8192, args.steps, args.warmup, G=256)), flush=True)
         # smaller inter-block rotations (Appendix A.7 counts with B = 32): less contraction per byte,

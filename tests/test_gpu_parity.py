@@ -91,7 +91,9 @@ ROT_CASES = [
     (10, 8192, 128, 2.5, 82, 100.0),     # LLaMA3-70B hidden size, two groups per row
     (3, 4608, 144, 3.0, 8, 50.0),
     (5, 5120, 160, 3.0, 26, 50.0),
+    (3, 5632, 176, 3.0, 8, 50.0),
     (4, 6656, 208, 3.0, 8, 50.0),
+    (2, 7680, 240, 3.0, 8, 50.0),
     (6, 8192, 256, 2.5, 82, 100.0),      # G = B for d = 8192
 ]
 
