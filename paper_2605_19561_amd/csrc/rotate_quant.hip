@@ -376,8 +376,9 @@ hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, 
                          uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
   const int64_t TG = M * (int64_t)(r->d / 32 / r->G);
   if (TG == 0) return hipSuccess;
-  // a handful of token-groups at G = 128 (decode): one per workgroup
+  // a handful of token-groups at G = 128 or 112 (decode): one per workgroup
   if (r->G == 128 && TG <= 128) return launch_cfg32<8, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
+  if (r->G == 112 && TG <= 128) return launch_cfg32<7, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
   // G a multiple of 32, or 16 * odd from 112 up: the 32x32x16 kernel (with a half-empty last tile).
   // Measured on X [16384, d]: G = 112 gains 9 % over the 16x16x32 kernel, G = 80 (three waves, one of
   // them half idle) loses 3 - 4 %.
