@@ -48,9 +48,9 @@ rotate_kernel(const uint4 *__restrict__ x, int64_t TG, int G,
 
 // ---------------------------------------------------------------------------
 // Variant on v_mfma_f32_32x32x16_bf16 (which sustains a higher rate than the 16x16x32 form): every G
-// that is a multiple of 32, and G = 16 * odd from 112 up (112 is the LLaMA3-8B down-projection
-// width), where the last wave's tile is half empty; the 16x16x32 kernel above keeps G = 16, 48 and
-// 80 (the Qwen3-32B widths).  Same formulation; wave w owns the 32 output blocks b = 32 w .. 32 w + 31
+// that is a multiple of 32, and G = 16 * odd from 80 up (80 and 112 are the Qwen3-32B and LLaMA3-8B
+// down-projection widths), where the last wave's tile is half empty; the 16x16x32 kernel above
+// keeps G = 16 and 48.  Same formulation; wave w owns the 32 output blocks b = 32 w .. 32 w + 31
 // and there are ceil(G/32) waves.  Two token-groups are processed together so that every MFMA has an
 // independent neighbour.  After step 3 a lane holds sixteen consecutive k of one block: two
 // lanes per block, one cross-lane step for the amax, 8 bytes of codes per lane.
@@ -63,15 +63,16 @@ rotate_kernel(const uint4 *__restrict__ x, int64_t TG, int G,
 //           A = R_intra^T lane (m, h), slot jj:        R_intra[that k'][kout(m)],
 //                         kout(m) = 16 ((m/4)%2) + 4 (m/8) + m%4
 //           D             lane (b, h), reg r:          Z[b][16 h + r]
-// Input staging.  G <= 64: global -> registers -> LDS, the next batch's loads in flight during the
+// Input staging.  G <= 80: global -> registers -> LDS, the next batch's loads in flight during the
 // current batch.  G >= 96: global -> LDS directly (buffer_load ... lds), issued once the wave has
 // read its step-2 operands of the current batch and landing during steps 3 and 4; without the
 // staging registers three waves fit a SIMD up to G = 128 (160 registers), which is worth 5 - 15 %
-// there and a few per cent beyond; at G <= 64 the register path measured faster.
+// there and a few per cent beyond; at G <= 80 the register path measured faster (and fits three
+// waves per SIMD from G = 64 up as it is).
 // TB: token-groups per batch, processed together (2: every MFMA has an independent neighbour; 1 for a
 // handful of token-groups, where the shortest path through one token-group counts).
 template <int KS16, int TB, int FMT>
-__global__ void __launch_bounds__(64 * ((KS16 + 1) / 2), (KS16 >= 6 && KS16 <= 8) ? 3 : 2)   // waves per SIMD
+__global__ void __launch_bounds__(64 * ((KS16 + 1) / 2), (KS16 >= 4 && KS16 <= 8) ? 3 : 2)   // waves per SIMD
 rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
                 const uint16_t *__restrict__ inter_hi, const uint16_t *__restrict__ inter_lo,
                 const uint4 *__restrict__ intra_hi_frag, const uint4 *__restrict__ intra_lo_frag,
@@ -335,8 +336,8 @@ static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG
   const size_t tg_stride = (size_t)((KS16 * 64 + 64 * nw - 1) / (64 * nw)) * (64 * nw) * 16;
   const size_t lds_bytes = 2 * (size_t)TB * tg_stride;
   // resident workgroups per CU: limited by LDS (160 KiB) and by the waves per SIMD that the register
-  // count admits (three for G = 96 and 128, two otherwise)
-  const int waves_per_cu = (KS16 >= 6 && KS16 <= 8) ? 12 : 8;
+  // count admits (three for G = 64 ... 128, two otherwise)
+  const int waves_per_cu = (KS16 >= 4 && KS16 <= 8) ? 12 : 8;
   int per_cu = (int)((160 * 1024) / lds_bytes);
   if (per_cu * nw > waves_per_cu) per_cu = waves_per_cu / nw;
   if (per_cu < 1) per_cu = 1;
@@ -379,24 +380,24 @@ hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, 
   // a handful of token-groups at G = 128 or 112 (decode): one per workgroup
   if (r->G == 128 && TG <= 128) return launch_cfg32<8, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
   if (r->G == 112 && TG <= 128) return launch_cfg32<7, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
-  // G a multiple of 32, or 16 * odd from 112 up: the 32x32x16 kernel (with a half-empty last tile).
-  // Measured on X [16384, d]: G = 112 gains 9 % over the 16x16x32 kernel, G = 80 (three waves, one of
-  // them half idle) loses 3 - 4 %.
-  if (r->G % 32 == 0 || r->G >= 112) {
+  // G a multiple of 32, or 16 * odd from 80 up: the 32x32x16 kernel (with a half-empty last tile).
+  // Measured on X [16384, d] against the 16x16x32 kernel: G = 112 gains 7 - 9 %, G = 80 3 - 7 % (at
+  // three waves per SIMD; at two it lost 3 - 4 %).
+  if (r->G % 32 == 0 || r->G >= 80) {
     switch (r->G / 16) {
 #define TORQ_CASE32(K16_) \
   case K16_: return launch_cfg32<K16_>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
-      TORQ_CASE32(2) TORQ_CASE32(4) TORQ_CASE32(6) TORQ_CASE32(7) TORQ_CASE32(8)
+      TORQ_CASE32(2) TORQ_CASE32(4) TORQ_CASE32(5) TORQ_CASE32(6) TORQ_CASE32(7) TORQ_CASE32(8)
       TORQ_CASE32(9) TORQ_CASE32(10) TORQ_CASE32(11) TORQ_CASE32(12) TORQ_CASE32(13) TORQ_CASE32(14)
       TORQ_CASE32(15) TORQ_CASE32(16)
 #undef TORQ_CASE32
     }
   }
-  // G = 16, 48 and 80: the 16x16x32 kernel, one tile of 16 blocks per wave
+  // G = 16 and 48: the 16x16x32 kernel, one tile of 16 blocks per wave
   switch (r->KS) {
 #define TORQ_CASE(KS_) \
   case KS_: return launch_cfg<KS_, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
-    TORQ_CASE(1) TORQ_CASE(2) TORQ_CASE(3)
+    TORQ_CASE(1) TORQ_CASE(2)
 #undef TORQ_CASE
   }
   return hipErrorInvalidValue;
