@@ -113,6 +113,9 @@ WORKLOADS = {
     "qwen3_32b": dict(M=4096, d=5120, nu=3.0, outliers=26, outlier_scale=50.0, token_lognormal=True, N=25600, wstd=0.02),
     "llama3_70b_up": dict(M=8192, d=8192, nu=2.5, outliers=82, outlier_scale=100.0, token_lognormal=False, N=28672, wstd=0.01),
     "llama3_70b_down": dict(M=8192, d=28672, nu=2.5, outliers=287, outlier_scale=100.0, token_lognormal=False, N=8192, wstd=0.01),
+    # the down-projection inputs of the two smaller configurations (appended: a workload's seed is its position)
+    "llama3_8b_down": dict(M=2048, d=14336, nu=3.0, outliers=72, outlier_scale=50.0, token_lognormal=False, N=4096, wstd=0.02),
+    "qwen3_32b_down": dict(M=4096, d=25600, nu=3.0, outliers=128, outlier_scale=50.0, token_lognormal=True, N=5120, wstd=0.02),
 }
 
 

@@ -47,6 +47,8 @@ ROT_FULL = [
     ("qwen3_32b", None),                           # [4096, 5120], G = 80, per-token log-normal scale
     ("llama3_70b_down", 2048),                     # d = 28672, G = 128 (rows trimmed: generation time)
     ("llama3_8b_prefill", None),                   # [2048, 4096], G = 128
+    ("llama3_8b_down", None),                      # [2048, 14336], G = 112: half-empty last tile of the 32x32 kernel
+    ("qwen3_32b_down", 2048),                      # d = 25600, G = 80, ten groups per row (rows trimmed)
 ]
 
 
