@@ -20,7 +20,8 @@
  *
  * Parity status of the pieces:
  *   - bf16 conversion, E8M0 scale, e2m1 rounding, nibble packing, rotation,
- *     reference GEMM, variance equaliser, block Gram matrix, code histogram,
+ *     reference GEMM, variance equaliser (greedy and butterfly), block Gram matrix (whole and per
+ *     position), MXINT4 / NVFP4 quantisers, code histogram,
  *     occupancy loss, pair scores, exact angle solver and the Algorithm 2 loop:
  *     pinned by tests/test_oracle_*.py.  Algorithm 2 leaves its loop control
  *     open (what the loss change is measured between, which rotation is
