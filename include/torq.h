@@ -37,9 +37,10 @@ enum {
     TORQ_EWORKSPACE  = -3,  /* workspace smaller than torq_linear_workspace_bytes() */
     TORQ_EHIP        = -4,  /* the HIP runtime reported an error (allocation, copy or launch) */
     TORQ_ENODEVICE   = -5,  /* no gfx950 device is current */
-    TORQ_ECONVERGE   = -6   /* torq_equalize_inter: no pair of blocks with deviations of opposite sign is
+    TORQ_ECONVERGE   = -6,  /* torq_equalize_inter: no pair of blocks with deviations of opposite sign is
                                left although the tolerance is not met (Sigma not symmetric, or eps below
                                what double precision can reach) */
+    TORQ_ETOOBIG     = -7   /* torq_linear_static: the packed activations do not fit TORQ_STATIC_SCRATCH_BYTES */
 };
 
 #define TORQ_BLOCK 32       /* elements per microscaling block (the paper's K) */
@@ -172,6 +173,24 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16,
                 const uint8_t *W_q, const uint8_t *W_s, void *out_bf16,
                 int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
                 void *stream);
+
+/* torq_linear for callers that cannot allocate device memory or hand over a workspace: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same operands, same
+ * kernels and the same result, bit for bit, as torq_linear with a workspace of exactly
+ * torq_linear_workspace_bytes(M, d) bytes (so the GEMM inside never cuts its k range); the packed
+ * activations pass through an array of TORQ_STATIC_SCRATCH_BYTES bytes that is part of the library's
+ * device image (every GPU the library runs on holds its own copy until the process ends).  The call
+ * allocates nothing and frees nothing.
+ *   torq_linear_workspace_bytes(M, d) must not exceed TORQ_STATIC_SCRATCH_BYTES (e.g. 64 rows of
+ *   d = 28672, 1900 rows of d = 4096), else TORQ_ETOOBIG and nothing is launched.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (different
+ * streams, different threads) race on it -- order them on one stream.  The array keeps the packed
+ * activations of the last call; nothing in it has to start at zero, every call overwrites the part
+ * it reads.  The first call on a device looks the array's address up (no allocation; not a call to
+ * make for the first time under stream capture). */
+#define TORQ_STATIC_SCRATCH_BYTES ((size_t)4 << 20)
+int torq_linear_static(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q, const uint8_t *W_s,
+                       void *out_bf16, int64_t M, int64_t N, void *stream);
 
 /* torq_linear for decode sizes in ONE kernel launch (Algorithm 3, steps 1-4 and "Return"): the first
  * workgroups rotate and quantise one token-group each while the others, one per strip of weight rows,

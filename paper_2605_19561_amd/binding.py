@@ -20,10 +20,12 @@ EXPORTS = [
     "torq_rotation_create_butterfly", "torq_linear_single_launch",
     "torq_linear_workspace_bytes_n", "torq_block_gram_workspace_bytes", "torq_block_gram", "torq_block_gram_positions",
     "torq_equalize_inter", "torq_code_histogram_workspace_bytes", "torq_code_histogram", "torq_intra_pair_scores",
-    "torq_intra_best_angle", "torq_calibrate_intra", "torq_diag_mfma_burn",
+    "torq_intra_best_angle", "torq_calibrate_intra", "torq_diag_mfma_burn", "torq_linear_static",
 ]
 
 TORQ_OK, TORQ_EINVAL, TORQ_EALIGN, TORQ_EWORKSPACE, TORQ_EHIP, TORQ_ENODEVICE, TORQ_ECONVERGE = 0, -1, -2, -3, -4, -5, -6
+TORQ_ETOOBIG = -7
+TORQ_STATIC_SCRATCH_BYTES = 4 << 20
 
 _lib = None
 
@@ -82,6 +84,8 @@ def lib():
         L.torq_linear_workspace_bytes.argtypes = [i64, i32]
         L.torq_linear.restype = i32
         L.torq_linear.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, sz, vp]
+        L.torq_linear_static.restype = i32
+        L.torq_linear_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp]
         L.torq_linear_single_launch.restype = i32
         L.torq_linear_single_launch.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, sz, vp]
         L.torq_block_gram_workspace_bytes.restype = sz
@@ -327,6 +331,17 @@ def torq_linear(rot: Rotation, x_bf16, W_q, W_s, out=None, workspace=None, strea
                              _dev(W_s, torch.uint8, "W_s"), _dev(out, torch.bfloat16, "out"), M, N,
                              _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)),
            "torq_linear")
+    return out
+
+
+def torq_linear_static(rot: Rotation, x_bf16, W_q, W_s, out, stream=None):
+    """torq_linear through the library's built-in scratch: the caller passes inputs and the output only."""
+    M, d = x_bf16.shape
+    N = W_q.shape[0]
+    assert d == rot.d and W_q.shape == (N, d // 2) and W_s.shape == (N, d // 32) and out.shape == (M, N)
+    _check(lib().torq_linear_static(rot.handle, _dev(x_bf16, torch.bfloat16, "x"), _dev(W_q, torch.uint8, "W_q"),
+                                    _dev(W_s, torch.uint8, "W_s"), _dev(out, torch.bfloat16, "out"), M, N,
+                                    _stream(stream)), "torq_linear_static")
     return out
 
 

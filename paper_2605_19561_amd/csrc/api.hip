@@ -1,15 +1,49 @@
 // C-ABI entry points of libtorq: argument validation, the rotation handle, and
 // dispatch to the kernel launchers.  The online path computes nothing on the host; the calibration
 // entry points that are documented as host routines do.
+#include <atomic>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
 #include "torq_internal.h"
 
+// Scratch of torq_linear_static: the packed activations between its two kernels.  One copy per GPU
+// the library runs on, held until the process ends.  In host code this name is only a handle for
+// hipGetSymbolAddress; kernels get the address that call returns for the current device.
+static __device__ __align__(256) unsigned char scratch[TORQ_STATIC_SCRATCH_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+std::atomic<unsigned char *> g_scratch_ptr[MAX_DEVICES];
+std::mutex g_scratch_mutex;
+
+// Device address of `scratch` on the current device, looked up once per device.
+hipError_t scratch_of_current_device(unsigned char **out) {
+  int dev = -1;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= MAX_DEVICES) return hipErrorInvalidDevice;
+  unsigned char *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    p = g_scratch_ptr[dev].load(std::memory_order_relaxed);
+    if (!p) {
+      void *sym = nullptr;
+      e = hipGetSymbolAddress(&sym, HIP_SYMBOL(scratch));
+      if (e != hipSuccess) return e;
+      if (!sym) return hipErrorInvalidSymbol;
+      p = static_cast<unsigned char *>(sym);
+      g_scratch_ptr[dev].store(p, std::memory_order_release);
+    }
+  }
+  *out = p;
+  return hipSuccess;
+}
 
 inline bool misaligned(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) != 0; }
 
@@ -67,6 +101,7 @@ const char *torq_status_string(int status) {
     case TORQ_EHIP: return g_hip_msg[0] ? g_hip_msg : "HIP runtime error";
     case TORQ_ENODEVICE: return "no gfx950 device is current";
     case TORQ_ECONVERGE: return "variance equalisation did not converge (Sigma not symmetric, or eps too small)";
+    case TORQ_ETOOBIG: return "packed activations exceed the library's built-in scratch (TORQ_STATIC_SCRATCH_BYTES); use torq_linear with a workspace";
     default: return "unknown status";
   }
 }
@@ -409,6 +444,28 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q
   const size_t used = torq_linear_workspace_bytes(M, r->d);
   e = torq::launch_mxfp4_gemm(codes, scales, W_q, W_s, out_bf16, M, N, r->d, static_cast<char *>(workspace) + used,
                               workspace_bytes - used, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+int torq_linear_static(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q, const uint8_t *W_s,
+                       void *out_bf16, int64_t M, int64_t N, void *stream) {
+  if (!r || M < 0 || N < 0) return TORQ_EINVAL;
+  if (r->d % 128 != 0) return TORQ_EINVAL;
+  if (M == 0 || N == 0) return TORQ_OK;
+  if (!x_bf16 || !W_q || !W_s || !out_bf16) return TORQ_EINVAL;
+  if (misaligned(x_bf16) || misaligned(W_q) || misaligned(out_bf16)) return TORQ_EALIGN;
+  if (reinterpret_cast<uintptr_t>(W_s) & 3u) return TORQ_EALIGN;
+  // M * d / 2 cannot overflow: both factors are checked against the limit first
+  if (M > (int64_t)TORQ_STATIC_SCRATCH_BYTES || torq_linear_workspace_bytes(M, r->d) > TORQ_STATIC_SCRATCH_BYTES)
+    return TORQ_ETOOBIG;
+  unsigned char *ws = nullptr;
+  hipError_t e = scratch_of_current_device(&ws);
+  if (e != hipSuccess) return hip_fail(e);
+  uint8_t *codes = ws;
+  uint8_t *scales = codes + (((size_t)M * (size_t)(r->d / 2) + 255) & ~(size_t)255);
+  e = rotate_any(r, x_bf16, M, TORQ_FMT_MXFP4, 1.0f, codes, scales, nullptr, (hipStream_t)stream);
+  if (e != hipSuccess) return hip_fail(e);
+  e = torq::launch_mxfp4_gemm(codes, scales, W_q, W_s, out_bf16, M, N, r->d, nullptr, 0, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 

@@ -28,7 +28,7 @@ def test_header_and_library_agree():
 
 
 def test_status_strings():
-    for s in (0, -1, -2, -3, -4, -5, -99):
+    for s in (0, -1, -2, -3, -4, -5, -6, -7, -99):
         assert isinstance(binding.status_string(s), str) and binding.status_string(s)
 
 
@@ -68,6 +68,7 @@ def test_compute_calls_reject_bad_arguments_without_launching():
     assert L.torq_rotate_quantize(None, good, 4, good, good, None) == binding.TORQ_EINVAL
     assert L.torq_rotate(None, good, 4, good, None) == binding.TORQ_EINVAL
     assert L.torq_linear(None, good, good, good, good, 4, 4, good, 1 << 20, None) == binding.TORQ_EINVAL
+    assert L.torq_linear_static(None, good, good, good, good, 4, 4, None) == binding.TORQ_EINVAL
     assert L.torq_rotation_d(None) == binding.TORQ_EINVAL
     odd2 = C.c_void_p(0x1002)
     assert L.torq_diag_mfma_burn(7, good, 4096, 4, good, None) == binding.TORQ_EINVAL          # unknown kind
