@@ -40,7 +40,9 @@ enum {
     TORQ_ECONVERGE   = -6,  /* torq_equalize_inter: no pair of blocks with deviations of opposite sign is
                                left although the tolerance is not met (Sigma not symmetric, or eps below
                                what double precision can reach) */
-    TORQ_ETOOBIG     = -7   /* torq_linear_static: the packed activations do not fit TORQ_STATIC_SCRATCH_BYTES */
+    TORQ_ETOOBIG     = -7,  /* torq_linear_static: the packed activations do not fit TORQ_STATIC_SCRATCH_BYTES */
+    TORQ_ENOMEM      = -8   /* a host routine (handle creation, the equalisers, the intra-block calibration)
+                               could not allocate host memory */
 };
 
 #define TORQ_BLOCK 32       /* elements per microscaling block (the paper's K) */
@@ -201,8 +203,12 @@ int torq_linear_static(const torq_rotation_t *r, const void *x_bf16, const uint8
  * Anything else is TORQ_EINVAL.  The packed activations are left in the workspace as by torq_linear; they
  * come from the 16-block rotation kernel, so a value that sits within the rotation's error bar of a
  * rounding boundary may get the neighbouring code of torq_rotate_quantize's; the product is exactly
- * mxfp4_gemm of those codes.  Every workgroup exits (the wait is bounded; a workgroup that gives up
- * writes NaN to its outputs, which cannot happen while the rotating workgroups run).  Calls on one
+ * mxfp4_gemm of those codes.  Every workgroup exits: the wait is bounded.  A workgroup whose wait runs
+ * out writes NaN to its outputs and raises an error word among the handle's counters that no launch
+ * clears: from then on every torq_linear_single_launch on that handle writes NaN to all of `out`
+ * (the counters of the failed launch cannot be trusted any more) until
+ * torq_linear_single_launch_reset has run; the calls themselves keep returning TORQ_OK, as they only
+ * enqueue.  Calls on one
  * handle must not overlap in time (they share the handle's counters; stream order is enough).  On
  * this part the hand-off between workgroups costs what the second launch costs: measured against
  * torq_linear 14.4 against 11.7 us at [1, 4096] -> 14336, 13.1 against 13.5 us at [16, 4096] -> 14336,
@@ -211,6 +217,20 @@ int torq_linear_static(const torq_rotation_t *r, const void *x_bf16, const uint8
 int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q, const uint8_t *W_s,
                               void *out_bf16, int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
                               void *stream);
+/* torq_linear_single_launch_reset: every counter of the handle back to zero, the error word included
+ *   (one small kernel on `stream`; allowed under stream capture).
+ * torq_linear_single_launch_gave_up: *gave_up = 1 if a launch on this handle has given up since the last
+ *   reset, else 0.  Copies one word from the device with a blocking copy: not a hot call.
+ * torq_linear_single_launch_probe: torq_linear_single_launch with its two internal constants exposed,
+ *   for tests of the give-up path that let every workgroup exit normally: spin_limit = how often a
+ *   waiting workgroup polls before it gives up (1 .. 2^18; torq_linear_single_launch uses 2^18),
+ *   withhold_ready != 0 = the rotating workgroups do their work but never hand over, so every
+ *   multiplying workgroup gives up after spin_limit polls. */
+int torq_linear_single_launch_reset(const torq_rotation_t *r, void *stream);
+int torq_linear_single_launch_gave_up(const torq_rotation_t *r, int *gave_up);
+int torq_linear_single_launch_probe(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q,
+                                    const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, void *workspace,
+                                    size_t workspace_bytes, int spin_limit, int withhold_ready, void *stream);
 
 /* ------------------------------------------------------------------------ */
 /* Calibration of the inter-block rotation (Section 5.1, Algorithm 1).  Not part of the online
@@ -246,7 +266,8 @@ int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, cons
  *   eps           absolute tolerance on the diagonal, >= 0 (e.g. 1e-12 * c)
  *   R_inter_host  HOST, G*G floats out, row-major, for torq_rotation_create (Y = R_inter X)
  *   steps         HOST, optional: number of plane rotations used
- * Returns TORQ_OK, TORQ_EINVAL or TORQ_ECONVERGE. */
+ * Returns TORQ_OK, TORQ_EINVAL (also for a Sigma with a NaN or an infinity), TORQ_ECONVERGE or
+ * TORQ_ENOMEM. */
 /* The inter-block rotation as a BUTTERFLY of plane rotations (what Section 5.1 calls an efficient
  * implementation of R_inter; Algorithm 1 itself picks its pairs greedily, one after the other, which
  * leaves a dense G x G matrix to multiply online).  Round t = 0 .. log2(G) - 1 turns the G/2
@@ -262,9 +283,13 @@ int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, cons
  *                  checking, for weights prepared elsewhere, or for torq_rotation_create
  *   tangents_host  log2(G) * G/2 floats out: tan(theta) of every pair, rounds in order, pairs in
  *                  increasing p; |tan| <= 1
- * torq_rotation_create_butterfly: a handle whose inter-block rotation is that butterfly (any finite
- * tangents are accepted: the rotation is orthogonal whatever they are).  Every entry point that takes
- * a handle works on it; destroy it with torq_rotation_destroy.  Errors as torq_rotation_create. */
+ * torq_rotation_create_butterfly: a handle whose inter-block rotation is that butterfly.  The rotation
+ * is orthogonal whatever the tangents are, but the kernel carries every row divided by the product of
+ * the cosines it has met, in fp32: |tan| must not exceed TORQ_BUTTERFLY_MAX_TAN (then that product
+ * stays above 2^-65 and every coefficient below 2^73); beyond it, or for a NaN, TORQ_EINVAL.  Every
+ * entry point that takes a handle works on it; destroy it with torq_rotation_destroy.  Other errors
+ * as torq_rotation_create. */
+#define TORQ_BUTTERFLY_MAX_TAN 256.0f
 int torq_equalize_inter_butterfly(const double *Sigma_host, int G, float *R_inter_host, float *tangents_host);
 int torq_rotation_create_butterfly(torq_rotation_t **out, int d, int G, const float *tangents_host,
                                    const float *R_intra_host);

@@ -21,10 +21,13 @@ EXPORTS = [
     "torq_linear_workspace_bytes_n", "torq_block_gram_workspace_bytes", "torq_block_gram", "torq_block_gram_positions",
     "torq_equalize_inter", "torq_code_histogram_workspace_bytes", "torq_code_histogram", "torq_intra_pair_scores",
     "torq_intra_best_angle", "torq_calibrate_intra", "torq_diag_mfma_burn", "torq_linear_static",
+    "torq_linear_single_launch_reset", "torq_linear_single_launch_gave_up", "torq_linear_single_launch_probe",
 ]
 
 TORQ_OK, TORQ_EINVAL, TORQ_EALIGN, TORQ_EWORKSPACE, TORQ_EHIP, TORQ_ENODEVICE, TORQ_ECONVERGE = 0, -1, -2, -3, -4, -5, -6
 TORQ_ETOOBIG = -7
+TORQ_ENOMEM = -8
+TORQ_BUTTERFLY_MAX_TAN = 256.0
 TORQ_STATIC_SCRATCH_BYTES = 4 << 20
 
 _lib = None
@@ -88,6 +91,12 @@ def lib():
         L.torq_linear_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp]
         L.torq_linear_single_launch.restype = i32
         L.torq_linear_single_launch.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, sz, vp]
+        L.torq_linear_single_launch_probe.restype = i32
+        L.torq_linear_single_launch_probe.argtypes = [vp, vp, vp, vp, vp, i64, i64, vp, sz, i32, i32, vp]
+        L.torq_linear_single_launch_reset.restype = i32
+        L.torq_linear_single_launch_reset.argtypes = [vp, vp]
+        L.torq_linear_single_launch_gave_up.restype = i32
+        L.torq_linear_single_launch_gave_up.argtypes = [vp, C.POINTER(i32)]
         L.torq_block_gram_workspace_bytes.restype = sz
         L.torq_block_gram_workspace_bytes.argtypes = [i32]
         L.torq_block_gram.restype = i32
@@ -316,6 +325,33 @@ def torq_linear_single_launch(rot: Rotation, x_bf16, W_q, W_s, out=None, workspa
                                            _dev(workspace, torch.uint8, "workspace"), workspace.numel(), _stream(stream)),
            "torq_linear_single_launch")
     return out
+
+
+def torq_linear_single_launch_probe(rot: Rotation, x_bf16, W_q, W_s, spin_limit, withhold_ready, out=None,
+                                    workspace=None, stream=None):
+    """torq_linear_single_launch with its wait limit and the hand-off switch exposed (tests of the give-up path)."""
+    M, d = x_bf16.shape
+    N = W_q.shape[0]
+    assert d == rot.d and W_q.shape == (N, d // 2) and W_s.shape == (N, d // 32)
+    if workspace is None:
+        workspace = torch.empty((max(torq_linear_workspace_bytes(M, d), 1),), dtype=torch.uint8, device=x_bf16.device)
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=x_bf16.device)
+    _check(lib().torq_linear_single_launch_probe(
+        rot.handle, _dev(x_bf16, torch.bfloat16, "x"), _dev(W_q, torch.uint8, "W_q"), _dev(W_s, torch.uint8, "W_s"),
+        _dev(out, torch.bfloat16, "out"), M, N, _dev(workspace, torch.uint8, "workspace"), workspace.numel(),
+        int(spin_limit), int(bool(withhold_ready)), _stream(stream)), "torq_linear_single_launch_probe")
+    return out
+
+
+def torq_linear_single_launch_reset(rot: Rotation, stream=None):
+    _check(lib().torq_linear_single_launch_reset(rot.handle, _stream(stream)), "torq_linear_single_launch_reset")
+
+
+def torq_linear_single_launch_gave_up(rot: Rotation) -> bool:
+    flag = C.c_int(0)
+    _check(lib().torq_linear_single_launch_gave_up(rot.handle, C.byref(flag)), "torq_linear_single_launch_gave_up")
+    return bool(flag.value)
 
 
 def torq_linear(rot: Rotation, x_bf16, W_q, W_s, out=None, workspace=None, stream=None):

@@ -81,6 +81,18 @@ int hip_fail(hipError_t e) {
   return TORQ_EHIP;
 }
 
+// Host routines allocate with std::vector; no exception may cross the C boundary.
+template <class F>
+int guarded(F &&body) noexcept {
+  try {
+    return body();
+  } catch (const std::bad_alloc &) {
+    return TORQ_ENOMEM;
+  } catch (...) {
+    return TORQ_EINVAL;
+  }
+}
+
 // the dense-matrix kernels, or the butterfly kernel for a handle made by torq_rotation_create_butterfly
 hipError_t rotate_any(const torq_rotation *r, const void *x_bf16, int64_t M, int format, float global_scale,
                       uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
@@ -101,12 +113,13 @@ const char *torq_status_string(int status) {
     case TORQ_EHIP: return g_hip_msg[0] ? g_hip_msg : "HIP runtime error";
     case TORQ_ENODEVICE: return "no gfx950 device is current";
     case TORQ_ECONVERGE: return "variance equalisation did not converge (Sigma not symmetric, or eps too small)";
+    case TORQ_ENOMEM: return "host memory allocation failed";
     case TORQ_ETOOBIG: return "packed activations exceed the library's built-in scratch (TORQ_STATIC_SCRATCH_BYTES); use torq_linear with a workspace";
     default: return "unknown status";
   }
 }
 
-int torq_rotation_create(torq_rotation_t **out, int d, int G, const float *R_inter_host,
+static int torq_rotation_create_impl(torq_rotation_t **out, int d, int G, const float *R_inter_host,
                          const float *R_intra_host) {
   if (!out) return TORQ_EINVAL;
   *out = nullptr;
@@ -123,19 +136,10 @@ int torq_rotation_create(torq_rotation_t **out, int d, int G, const float *R_int
   if (e != hipSuccess) return TORQ_ENODEVICE;
   if (std::strncmp(prop.gcnArchName, "gfx950", 6) != 0) return TORQ_ENODEVICE;
 
-  torq_rotation *r = new (std::nothrow) torq_rotation();
-  if (!r) return TORQ_EHIP;
-  r->d = d;
-  r->G = G;
-  r->KS = (G + 31) / 32;
-  r->device = dev;
-  r->inter_hi = r->inter_lo = r->intra_hi = r->intra_lo = r->intra32_hi = r->intra32_lo = nullptr;
-  r->butterfly = nullptr;
-  r->decode_ctr = nullptr;
-
   // R_inter, bf16 hi/lo, [G][KS*32] with zero padding: row b is the B operand
   // "column" b of R_inter^T (Algorithm 3 step 2: Y[b] = sum_b' R_inter[b][b'] X[b']).
-  const int ld = r->KS * 32;
+  const int KS = (G + 31) / 32;
+  const int ld = KS * 32;
   std::vector<uint16_t> ih((size_t)G * ld, 0), il((size_t)G * ld, 0);
   for (int b = 0; b < G; ++b)
     for (int bp = 0; bp < G; ++bp)
@@ -171,13 +175,26 @@ int torq_rotation_create(torq_rotation_t **out, int d, int G, const float *R_int
       }
     }
 
+  const std::vector<unsigned> zero_ctr(DECODE_CTR_WORDS, 0u);
+
+  // every host table exists: from here on nothing throws
+  torq_rotation *r = new (std::nothrow) torq_rotation();
+  if (!r) return TORQ_ENOMEM;
+  r->d = d;
+  r->G = G;
+  r->KS = KS;
+  r->device = dev;
+  r->inter_hi = r->inter_lo = r->intra_hi = r->intra_lo = r->intra32_hi = r->intra32_lo = nullptr;
+  r->butterfly = nullptr;
+  r->decode_ctr = nullptr;
+
   e = upload(&r->inter_hi, ih);
   if (e == hipSuccess) e = upload(&r->inter_lo, il);
   if (e == hipSuccess) e = upload(&r->intra_hi, ah);
   if (e == hipSuccess) e = upload(&r->intra_lo, al);
   if (e == hipSuccess) e = upload(&r->intra32_hi, a32h);
   if (e == hipSuccess) e = upload(&r->intra32_lo, a32l);
-  if (e == hipSuccess) e = upload(&r->decode_ctr, std::vector<unsigned>(DECODE_CTR_WORDS, 0u));
+  if (e == hipSuccess) e = upload(&r->decode_ctr, zero_ctr);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
     torq_rotation_destroy(r);
@@ -234,7 +251,7 @@ void butterfly_dense(const float *tangents, int G, std::vector<double> &R) {
 //   (a - b) cos 2 theta + 2 g sin 2 theta = 0,  theta = atan((b - a) / (2 g)) / 2 in (-pi/4, pi/4)
 // (g = 0: pi/4 unless a = b), so that after round t the diagonal is constant on the residue classes of
 // the row index modulo the stride, and after the last round constant.
-int torq_equalize_inter_butterfly(const double *Sigma_host, int G, float *R_inter_host, float *tangents_host) {
+static int torq_equalize_inter_butterfly_impl(const double *Sigma_host, int G, float *R_inter_host, float *tangents_host) {
   if (!Sigma_host || !tangents_host || !butterfly_size(G)) return TORQ_EINVAL;
   const size_t n = (size_t)G;
   for (size_t i = 0; i < n * n; ++i)
@@ -283,18 +300,18 @@ int torq_equalize_inter_butterfly(const double *Sigma_host, int G, float *R_inte
   return TORQ_OK;
 }
 
-int torq_rotation_create_butterfly(torq_rotation_t **out, int d, int G, const float *tangents_host,
+static int torq_rotation_create_butterfly_impl(torq_rotation_t **out, int d, int G, const float *tangents_host,
                                    const float *R_intra_host) {
   if (!out) return TORQ_EINVAL;
   *out = nullptr;
   if (!tangents_host || !R_intra_host || !butterfly_size(G)) return TORQ_EINVAL;
   const int L = log2i(G), NJ = G / 32;
   for (int i = 0; i < L * (G / 2); ++i)
-    if (!std::isfinite(tangents_host[i])) return TORQ_EINVAL;
+    if (!(std::fabs(tangents_host[i]) <= TORQ_BUTTERFLY_MAX_TAN)) return TORQ_EINVAL;   // NaN fails too
   std::vector<double> Rd;
   butterfly_dense(tangents_host, G, Rd);
   std::vector<float> Rf(Rd.begin(), Rd.end());
-  const int status = torq_rotation_create(out, d, G, Rf.data(), R_intra_host);
+  const int status = torq_rotation_create_impl(out, d, G, Rf.data(), R_intra_host);
   if (status != TORQ_OK) return status;
 
   // per-row coefficients (rotate_butterfly.hip): the kernel carries u = value / sigma, sigma = the
@@ -314,6 +331,16 @@ int torq_rotation_create_butterfly(torq_rotation_t **out, int d, int G, const fl
     for (int p = 0; p < G; ++p) sigma[p] *= cosine[p];
   }
   for (int p = 0; p < G; ++p) coef[(size_t)(L * NJ + p / 32) * 32 + p % 32] = (float)sigma[p];
+  // within the tangent limit every entry is a finite fp32 value (and sigma a normal one); checked all
+  // the same, because the kernel divides by nothing but multiplies by all of them
+  bool usable = true;
+  for (float c : coef) usable = usable && std::isfinite(c);
+  for (int p = 0; p < G; ++p) usable = usable && std::fpclassify((float)sigma[p]) == FP_NORMAL;
+  if (!usable) {
+    torq_rotation_destroy(*out);
+    *out = nullptr;
+    return TORQ_EINVAL;
+  }
   hipError_t e = upload(&(*out)->butterfly, coef);
   if (e != hipSuccess) {
     torq_rotation_destroy(*out);
@@ -469,10 +496,10 @@ int torq_linear_static(const torq_rotation_t *r, const void *x_bf16, const uint8
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 
-int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q, const uint8_t *W_s,
-                              void *out_bf16, int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
-                              void *stream) {
-  if (!r || M < 0 || N < 0) return TORQ_EINVAL;
+int torq_linear_single_launch_probe(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q,
+                                    const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, void *workspace,
+                                    size_t workspace_bytes, int spin_limit, int withhold_ready, void *stream) {
+  if (!r || M < 0 || N < 0 || spin_limit < 1 || spin_limit > (1 << 18)) return TORQ_EINVAL;
   if (r->G != 128 || r->butterfly || r->d % 128 != 0 || M > 64) return TORQ_EINVAL;
   if ((int64_t)r->d * 128 >= 0x7FFFFFFF || (M > 0 && !torq::mxfp4_gemm_skinny_fits(M, r->d))) return TORQ_EINVAL;
   if (M == 0 || N == 0) return TORQ_OK;
@@ -482,8 +509,31 @@ int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, cons
   if (workspace_bytes < torq_linear_workspace_bytes(M, r->d)) return TORQ_EWORKSPACE;
   uint8_t *codes = static_cast<uint8_t *>(workspace);
   uint8_t *scales = codes + (((size_t)M * (size_t)(r->d / 2) + 255) & ~(size_t)255);
-  hipError_t e = torq::launch_torq_linear_decode(r, x_bf16, codes, scales, W_q, W_s, out_bf16, M, N, (hipStream_t)stream);
+  hipError_t e = torq::launch_torq_linear_decode(r, x_bf16, codes, scales, W_q, W_s, out_bf16, M, N, spin_limit,
+                                                 withhold_ready ? 0 : 1, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q, const uint8_t *W_s,
+                              void *out_bf16, int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
+                              void *stream) {
+  return torq_linear_single_launch_probe(r, x_bf16, W_q, W_s, out_bf16, M, N, workspace, workspace_bytes, 1 << 18, 0,
+                                         stream);
+}
+
+int torq_linear_single_launch_reset(const torq_rotation_t *r, void *stream) {
+  if (!r) return TORQ_EINVAL;
+  hipError_t e = torq::launch_decode_ctr_reset(r, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+int torq_linear_single_launch_gave_up(const torq_rotation_t *r, int *gave_up) {
+  if (!r || !gave_up) return TORQ_EINVAL;
+  unsigned word = 0;
+  hipError_t e = hipMemcpy(&word, r->decode_ctr + DECODE_ERR, sizeof word, hipMemcpyDeviceToHost);
+  if (e != hipSuccess) return hip_fail(e);
+  *gave_up = word != 0;
+  return TORQ_OK;
 }
 
 size_t torq_linear_workspace_bytes_n(int64_t M, int64_t N, int d) {
@@ -532,9 +582,12 @@ int torq_block_gram_positions(const void *x_bf16, int64_t M, int d, int G, doubl
 // discriminant positive, and the root of smaller magnitude is t = -(a - c) / (g + sgn(g) D).
 // After the step S_pp = c exactly and S_nn = a + b - c (the trace is conserved), so at most G - 1
 // steps are needed.
-int torq_equalize_inter(const double *Sigma_host, int G, double eps, float *R_inter_host, int *steps_out) {
+static int torq_equalize_inter_impl(const double *Sigma_host, int G, double eps, float *R_inter_host, int *steps_out) {
   if (!Sigma_host || !R_inter_host || G < 1 || G > 4096 || !(eps >= 0.0)) return TORQ_EINVAL;
   const size_t n = (size_t)G;
+  // NaN compares false with everything: the search below would find no deviation and hand back R = I
+  for (size_t i = 0; i < n * n; ++i)
+    if (!std::isfinite(Sigma_host[i])) return TORQ_EINVAL;
   std::vector<double> S(Sigma_host, Sigma_host + n * n), R(n * n, 0.0);
   for (size_t i = 0; i < n; ++i) R[i * n + i] = 1.0;
   double trace = 0.0;
@@ -601,7 +654,7 @@ int torq_intra_pair_scores(const uint64_t *counts_host, double lambda, double *h
   return TORQ_OK;
 }
 
-int torq_intra_best_angle(const double *u_host, const double *v_host, int64_t n, const uint64_t *rest_host,
+static int torq_intra_best_angle_impl(const double *u_host, const double *v_host, int64_t n, const uint64_t *rest_host,
                           double *theta, double *loss, int64_t *critical) {
   if (n < 0 || n > TORQ_INTRA_MAX_SAMPLE || !rest_host || !theta || !loss) return TORQ_EINVAL;
   if (n > 0 && (!u_host || !v_host)) return TORQ_EINVAL;
@@ -612,7 +665,7 @@ int torq_intra_best_angle(const double *u_host, const double *v_host, int64_t n,
   return TORQ_OK;
 }
 
-int torq_calibrate_intra(const float *X_host, int64_t n, int max_iter, int k_top, int P, double lambda,
+static int torq_calibrate_intra_impl(const float *X_host, int64_t n, int max_iter, int k_top, int P, double lambda,
                          double eps, float *R_intra_host, double *losses_host, int *n_eval) {
   if (!X_host || !R_intra_host || !losses_host || !n_eval) return TORQ_EINVAL;
   if (n < 1 || n > TORQ_INTRA_MAX_SAMPLE || max_iter < 0 || max_iter > 1000) return TORQ_EINVAL;
@@ -635,6 +688,31 @@ int torq_diag_mfma_burn(int kind, const void *operands, size_t n_bytes, int iter
   hipError_t e = torq::launch_mfma_burn(kind, static_cast<const uint32_t *>(operands), (uint32_t)n_words, iters,
                                         sink, (hipStream_t)stream);
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+// The host routines above behind a guard: an allocation failure comes back as TORQ_ENOMEM.
+int torq_rotation_create(torq_rotation_t **out, int d, int G, const float *R_inter_host, const float *R_intra_host) {
+  return guarded([&] { return torq_rotation_create_impl(out, d, G, R_inter_host, R_intra_host); });
+}
+
+int torq_equalize_inter_butterfly(const double *Sigma_host, int G, float *R_inter_host, float *tangents_host) {
+  return guarded([&] { return torq_equalize_inter_butterfly_impl(Sigma_host, G, R_inter_host, tangents_host); });
+}
+
+int torq_rotation_create_butterfly(torq_rotation_t **out, int d, int G, const float *tangents_host, const float *R_intra_host) {
+  return guarded([&] { return torq_rotation_create_butterfly_impl(out, d, G, tangents_host, R_intra_host); });
+}
+
+int torq_equalize_inter(const double *Sigma_host, int G, double eps, float *R_inter_host, int *steps_out) {
+  return guarded([&] { return torq_equalize_inter_impl(Sigma_host, G, eps, R_inter_host, steps_out); });
+}
+
+int torq_intra_best_angle(const double *u_host, const double *v_host, int64_t n, const uint64_t *rest_host, double *theta, double *loss, int64_t *critical) {
+  return guarded([&] { return torq_intra_best_angle_impl(u_host, v_host, n, rest_host, theta, loss, critical); });
+}
+
+int torq_calibrate_intra(const float *X_host, int64_t n, int max_iter, int k_top, int P, double lambda, double eps, float *R_intra_host, double *losses_host, int *n_eval) {
+  return guarded([&] { return torq_calibrate_intra_impl(X_host, n, max_iter, k_top, P, lambda, eps, R_intra_host, losses_host, n_eval); });
 }
 
 }  // extern "C"

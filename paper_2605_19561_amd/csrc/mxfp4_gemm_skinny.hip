@@ -46,6 +46,8 @@ struct DecodeArgs {
   uint8_t *A_q, *A_s;          // written by the first P workgroups, read by the others
   int P;
   unsigned *ctr;
+  int spin_limit;              // polls of the "ready" word before a waiting workgroup gives up
+  int raise_ready;             // 0: the producers never raise "ready" (host-driven test of the give-up path)
 };
 
 }  // namespace
@@ -230,12 +232,19 @@ __device__ __forceinline__ void decode_consumer_done(unsigned *ctr, int gid, int
 //   ctr[32 (1 + s)], s < 64   consumers finished, striped the same way; a complete stripe adds 1 to
 //   ctr[32 * 65]             stripes complete; the workgroup that completes the last one sets every
 //                            counter back to 0, so that the next launch (and every replay of a
-//                            captured one) starts from the same state.
+//                            captured one) starts from the same state;
+//   ctr[DECODE_ERR]          "a workgroup gave up": set by a consumer whose bounded wait ran out, never
+//                            cleared by a launch.  Such a consumer does not count itself as finished, so
+//                            the counters are not set back either (late producers may still be adding to
+//                            them); every consumer of every later launch sees the word first and writes
+//                            NaN instead of multiplying whatever the stale counters would let through,
+//                            until decode_ctr_reset_kernel has cleared all words.
 // The consumers read the activations with device-coherent loads (sc1), so neither side needs a
 // cache write-back or invalidate.
 // Workgroups are dispatched in index order and the producers come first, so a waiting consumer can
 // never keep a producer off the machine; the wait is bounded all the same (a consumer that gives
-// up writes NaN to its outputs).  Launches that share a counter pair must not overlap.
+// up writes NaN to its outputs and raises the sticky error word).  Launches that share a handle's
+// counters must not overlap.
 template <int MT, int NS, int PT>
 __global__ void __launch_bounds__(64 * WAVES, 4)
 torq_linear_decode_kernel(const uint4 *__restrict__ x, int64_t TG, const uint16_t *__restrict__ inter_hi,
@@ -243,7 +252,7 @@ torq_linear_decode_kernel(const uint4 *__restrict__ x, int64_t TG, const uint16_
                           const uint4 *__restrict__ intra_lo_frag, uint8_t *__restrict__ A_q,
                           uint8_t *__restrict__ A_s, const uint8_t *__restrict__ W_q,
                           const uint8_t *__restrict__ W_s, uint16_t *__restrict__ out, int M, int64_t N, int d,
-                          int P, int groups, unsigned *__restrict__ ctr) {
+                          int P, int groups, unsigned *__restrict__ ctr, int spin_limit, int raise_ready) {
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   if ((int)blockIdx.x < P) {
@@ -254,7 +263,7 @@ torq_linear_decode_kernel(const uint4 *__restrict__ x, int64_t TG, const uint16_
     __syncthreads();
     if (tid == 0) {
       const unsigned before = __hip_atomic_fetch_add(&ctr[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (before == (unsigned)P - 1u)              // every producer's stores were complete before its own add
+      if (before == (unsigned)P - 1u && raise_ready)   // every producer's stores were complete before its own add
         for (int s = 0; s < 64; ++s) __hip_atomic_store(&ctr[32 * (66 + s)], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     return;
@@ -300,11 +309,16 @@ torq_linear_decode_kernel(const uint4 *__restrict__ x, int64_t TG, const uint16_
   // ---- wait for the activations' codes and scales
   if (tid == 0) {
     const unsigned *flag = &ctr[32 * (66 + (((int)blockIdx.x - P) & 63))];
+    // an earlier launch on these counters gave up: they are stale, nothing they say can be trusted
+    const unsigned err = __hip_atomic_load(&ctr[DECODE_ERR], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     unsigned seen = 0;
-    for (int spin = 0; spin < (1 << 18); ++spin) {
-      seen = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (seen) break;
-      __builtin_amdgcn_s_sleep(8);
+    if (!err) {
+      for (int spin = 0; spin < spin_limit; ++spin) {
+        seen = __hip_atomic_load(flag, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (seen) break;
+        __builtin_amdgcn_s_sleep(8);
+      }
+      if (!seen) __hip_atomic_store(&ctr[DECODE_ERR], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
     reinterpret_cast<volatile unsigned *>(smem)[(w_ins + a_ins) * 64] = seen;
   }
@@ -313,13 +327,14 @@ torq_linear_decode_kernel(const uint4 *__restrict__ x, int64_t TG, const uint16_
   __builtin_amdgcn_sched_barrier(0);
   asm volatile("" ::: "memory");                   // nothing below is moved above the wait
   if (!ready) {                                    // uniform over the workgroup
-    // gave up: mark this strip's outputs as NaN rather than leave what the buffer held
+    __builtin_amdgcn_s_waitcnt(0);                 // the loads already issued land before the workgroup's LDS and registers go
+    // gave up (or the counters are stale): mark this strip's outputs as NaN rather than leave what the
+    // buffer held; the workgroup does not count as finished, so no launch sets the counters back
     for (int e = tid; e < M * 16 * NS; e += 64 * WAVES) {
       const int m = e / (16 * NS);
       const int64_t n = n0 + e % (16 * NS);
       if (n < N) out[(int64_t)m * N + n] = 0x7FC0;
     }
-    if (tid == 0) decode_consumer_done(ctr, (int)blockIdx.x - P, groups);
     return;
   }
 
@@ -398,7 +413,7 @@ static hipError_t launch_cfg(const uint8_t *A_q, const uint8_t *A_s, const uint8
     hipLaunchKernelGGL((torq_linear_decode_kernel<MT, NS, PT>), dim3((unsigned)(groups + fused->P)), dim3(64 * WAVES),
                        lds_bytes, stream, fused->x, fused->TG, fused->inter_hi, fused->inter_lo, fused->intra_hi_frag,
                        fused->intra_lo_frag, fused->A_q, fused->A_s, W_q, W_s, reinterpret_cast<uint16_t *>(out), (int)M,
-                       N, d, fused->P, (int)groups, fused->ctr);
+                       N, d, fused->P, (int)groups, fused->ctr, fused->spin_limit, fused->raise_ready);
     return hipGetLastError();
   }
   if (lds_bytes > SKINNY_MAX_LDS) return hipErrorInvalidValue;
@@ -471,7 +486,7 @@ hipError_t launch_mxfp4_gemm_skinny(const uint8_t *A_q, const uint8_t *A_s, cons
 // 1 <= M <= 64, mxfp4_gemm_skinny_fits(M, r->d) and N > 0.  A_q / A_s: the workspace's code and scale areas.
 hipError_t launch_torq_linear_decode(const torq_rotation *r, const void *x_bf16, uint8_t *A_q, uint8_t *A_s,
                                      const uint8_t *W_q, const uint8_t *W_s, void *out, int64_t M, int64_t N,
-                                     hipStream_t stream) {
+                                     int spin_limit, int raise_ready, hipStream_t stream) {
   DecodeArgs fz;
   fz.x = reinterpret_cast<const uint4 *>(x_bf16);
   fz.TG = M * (int64_t)(r->d / 32 / r->G);
@@ -483,7 +498,21 @@ hipError_t launch_torq_linear_decode(const torq_rotation *r, const void *x_bf16,
   fz.A_s = A_s;
   fz.P = (int)fz.TG;                               // one token-group per rotating workgroup
   fz.ctr = r->decode_ctr;
+  fz.spin_limit = spin_limit;
+  fz.raise_ready = raise_ready;
   return launch_by_rows(A_q, A_s, W_q, W_s, out, M, N, r->d, stream, &fz);
+}
+
+// every counter of a handle back to zero, the error word included (a fill kernel rather than a
+// memset node, so that the call may sit in a captured graph)
+__global__ void __launch_bounds__(256) decode_ctr_reset_kernel(unsigned *__restrict__ ctr) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < DECODE_CTR_WORDS) ctr[i] = 0u;
+}
+
+hipError_t launch_decode_ctr_reset(const torq_rotation *r, hipStream_t stream) {
+  hipLaunchKernelGGL(decode_ctr_reset_kernel, dim3((DECODE_CTR_WORDS + 255) / 256), dim3(256), 0, stream, r->decode_ctr);
+  return hipGetLastError();
 }
 
 }  // namespace torq

@@ -24,7 +24,8 @@ struct torq_rotation {
   // its rotating and its multiplying workgroups (mxfp4_gemm_skinny.hip)
   unsigned *decode_ctr;
 };
-constexpr int DECODE_CTR_WORDS = 32 * 130;
+constexpr int DECODE_CTR_WORDS = 32 * 131;
+constexpr int DECODE_ERR = 32 * 130;      // the sticky "a workgroup gave up" word among them
 
 namespace torq {
 
@@ -63,9 +64,13 @@ hipError_t launch_mxfp4_gemm_skinny(const uint8_t *A_q, const uint8_t *A_s, cons
 // torq_linear for at most 64 rows in one launch: rotate + quantise (the 16-block body, G = 128) in the
 // first workgroups of the weight-streaming GEMM.  Preconditions: r->G == 128, dense R_inter,
 // 1 <= M <= 64, mxfp4_gemm_skinny_fits(M, r->d); A_q / A_s are the workspace's code and scale areas.
+// spin_limit: polls before a waiting workgroup gives up; raise_ready = 0 withholds the hand-off
+// (test of the give-up path: every workgroup still exits).
 hipError_t launch_torq_linear_decode(const torq_rotation *r, const void *x_bf16, uint8_t *A_q, uint8_t *A_s,
                                      const uint8_t *W_q, const uint8_t *W_s, void *out, int64_t M, int64_t N,
-                                     hipStream_t stream);
+                                     int spin_limit, int raise_ready, hipStream_t stream);
+// all of the handle's counters back to zero, the sticky error word included
+hipError_t launch_decode_ctr_reset(const torq_rotation *r, hipStream_t stream);
 
 // Block Gram matrix of the runs of G blocks (block_gram.hip): TG token-groups of G * 32 bf16 each.
 size_t block_gram_workspace_bytes(int G);

@@ -28,7 +28,7 @@ def test_header_and_library_agree():
 
 
 def test_status_strings():
-    for s in (0, -1, -2, -3, -4, -5, -6, -7, -99):
+    for s in (0, -1, -2, -3, -4, -5, -6, -7, -8, -99):
         assert isinstance(binding.status_string(s), str) and binding.status_string(s)
 
 
@@ -135,6 +135,38 @@ def test_format_entry_points_reject_unknown_formats_and_bad_scales():
     assert L.torq_quantize_f32_fmt(good, 0, 64, 1, f(0.0), None, None, None) == binding.TORQ_OK          # empty; scale unused
     assert L.torq_quantize_f32_fmt(C.c_void_p(0x1004), 4, 64, 1, f(1.0), good, good, None) == binding.TORQ_EALIGN
     assert L.torq_rotate_quantize_fmt(None, good, 4, 1, f(1.0), good, good, None) == binding.TORQ_EINVAL
+
+
+def test_host_routines_reject_non_finite_and_out_of_range_input():
+    L = binding.lib()
+    # Algorithm 1 helper: a NaN in Sigma must not come back as "converged, R = I"
+    G = 16
+    Sigma = np.diag(np.arange(1.0, G + 1.0))
+    R = np.zeros((G, G), dtype=np.float32)
+    steps = C.c_int(-1)
+    args = lambda S: (S.ctypes.data_as(C.c_void_p), G, C.c_double(1e-12), R.ctypes.data_as(C.c_void_p), C.byref(steps))
+    assert L.torq_equalize_inter(*args(Sigma)) == binding.TORQ_OK and steps.value > 0
+    for bad in (np.nan, np.inf, -np.inf):
+        S = Sigma.copy()
+        S[3, 5] = bad
+        R[:] = 7.0
+        assert L.torq_equalize_inter(*args(S)) == binding.TORQ_EINVAL
+        assert (R == 7.0).all()                     # nothing written
+    # butterfly handle: tangents beyond the stated limit (or NaN) are refused before any device work
+    Gb = 32
+    Ra = np.eye(32, dtype=np.float32)
+    h = C.c_void_p()
+    for bad in (np.float32(binding.TORQ_BUTTERFLY_MAX_TAN) * 2, -np.float32(1e30), np.float32(np.nan), np.float32(np.inf)):
+        T = np.zeros((5, Gb // 2), dtype=np.float32)
+        T[2, 7] = bad
+        st = L.torq_rotation_create_butterfly(C.byref(h), 32 * Gb, Gb, T.ctypes.data_as(C.c_void_p),
+                                              Ra.ctypes.data_as(C.c_void_p))
+        assert st == binding.TORQ_EINVAL and not h.value
+    # one-launch layer: its test hook validates the wait limit; the counter calls need a handle
+    good = C.c_void_p(0x1000)
+    assert L.torq_linear_single_launch_probe(None, good, good, good, good, 4, 4, good, 1 << 20, 16, 1, None) == binding.TORQ_EINVAL
+    assert L.torq_linear_single_launch_reset(None, None) == binding.TORQ_EINVAL
+    assert L.torq_linear_single_launch_gave_up(None, None) == binding.TORQ_EINVAL
 
 
 def test_bench_refuses_more_than_one_gpu():

@@ -1081,3 +1081,50 @@ def test_linear_single_launch_replays_from_a_hip_graph_and_rejects_what_it_canno
     empty = tq.torq_linear_single_launch(rot, torch.zeros((0, d), dtype=torch.bfloat16, device=DEV), W_q, W_s)
     assert empty.shape == (0, N)
     rot.close()
+
+
+def test_linear_single_launch_give_up_is_sticky_until_reset(tq):
+    # The bounded wait, driven from the host: the rotating workgroups do their work but withhold the
+    # hand-off, the multiplying workgroups poll 4 times and give up.  Every workgroup exits normally.
+    M, d, N, G = 3, 4096, 2048, 128
+    Ri, Ra = synth.rotations(G)
+    rot = tq.Rotation(d, G, Ri, Ra)
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(77)
+    W_q = torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=DEV, generator=gen)
+    W_s = torch.randint(118, 128, (N, d // 32), dtype=torch.uint8, device=DEV, generator=gen)
+    x = synth.activations(M, d, seed=1600).to(DEV)
+    ws = torch.empty((tq.torq_linear_workspace_bytes(M, d),), dtype=torch.uint8, device=DEV)
+    want = tq.torq_linear_single_launch(rot, x, W_q, W_s, workspace=ws).clone()
+    torch.cuda.synchronize()
+    assert torch.isfinite(want.float()).all() and not tq.torq_linear_single_launch_gave_up(rot)
+
+    out = torch.ones((M, N), dtype=torch.bfloat16, device=DEV)
+    tq.torq_linear_single_launch_probe(rot, x, W_q, W_s, 4, True, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.isnan(out.float()).all()                     # every strip gave up and said so
+    assert tq.torq_linear_single_launch_gave_up(rot)
+    # the counters of that launch are stale: later launches must not multiply on their say-so
+    for _ in range(2):
+        out.fill_(1.0)
+        tq.torq_linear_single_launch(rot, x, W_q, W_s, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.isnan(out.float()).all()
+    # a reset brings the handle back, and the next launches are the ordinary ones again
+    tq.torq_linear_single_launch_reset(rot)
+    for _ in range(3):
+        out.fill_(1.0)
+        tq.torq_linear_single_launch(rot, x, W_q, W_s, out=out, workspace=ws)
+        torch.cuda.synchronize()
+        assert torch.equal(out, want)
+    assert not tq.torq_linear_single_launch_gave_up(rot)
+    # a short wait limit alone is no error while the rotating workgroups do hand over ... unless it
+    # really is too short, in which case the NaN marks it; either way the handle recovers after a reset
+    out.fill_(1.0)
+    tq.torq_linear_single_launch_probe(rot, x, W_q, W_s, 1 << 18, False, out=out, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out, want)
+    with pytest.raises(tq.TorqError) as ei:
+        tq.torq_linear_single_launch_probe(rot, x, W_q, W_s, 0, False, out=out, workspace=ws)
+    assert ei.value.status == tq.TORQ_EINVAL
+    rot.close()
