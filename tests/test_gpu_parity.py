@@ -234,8 +234,20 @@ def _bits(t):
     return _np(t.view(torch.int16)).view(np.uint16)
 
 
+def _assert_every_output_within_one_ulp(got_bits, want_bits):
+    # fp32 accumulation of exact products: every output is at most one bf16 ulp from the correctly
+    # rounded value (plus a floor for outputs that cancel to almost nothing)
+    gw = (got_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    ww = (want_bits.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    bad = np.abs(gw - ww) > np.abs(ww) * 2.0 ** -7 + 1e-3 * np.sqrt(np.mean(ww ** 2))
+    assert not bad.any(), f"{int(bad.sum())} outputs off, first at {tuple(np.argwhere(bad)[0])}"
+
+
 GEMM_RANDOM = [(1, 128, 128), (16, 256, 384), (100, 200, 512), (64, 1024, 4096), (300, 520, 1280), (257, 129, 256),
-               (129, 300, 1024), (70, 130, 1536)]    # the deeper load pipeline at 4 and 6 iterations
+               (129, 300, 1024), (70, 130, 1536),    # the deeper load pipeline at 4 and 6 iterations
+               (4096, 4096, 512),                    # 256 tiles of 256 x 256: the large-tile kernel, every output checked
+               (4000, 8190, 512),                    # ... 512 of them (two per CU), ragged last tile row and column, N % 8 != 0
+               (4096, 2048, 768)]                    # 256 tiles of 256 x 128, an odd number of iterations
 
 
 @pytest.mark.parametrize("M,N,d", GEMM_RANDOM)
@@ -249,6 +261,7 @@ def test_gemm_random_codes(tq, oracle, M, N, d):
     got = tq.mxfp4_gemm(*(torch.from_numpy(a).to(DEV) for a in (A_q, A_s, W_q, W_s)))
     torch.cuda.synchronize()
     assert _rel_fro(_bits(got), want) <= 1e-3
+    _assert_every_output_within_one_ulp(_bits(got), want)
 
 
 # Few activation rows (M <= 64) take the weight-streaming kernel: one MFMA k-step only, an odd
