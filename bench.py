@@ -28,14 +28,14 @@ FP4_PEAK_TFLOPS = 10100.0      # MI355X dense fp4 MFMA, published
 BF16_PEAK_TFLOPS = 2500.0      # MI355X dense bf16 MFMA, published
 RQ_BYTES_PER_ELEMENT = 2.0 + 0.5 + 1.0 / 32.0   # bf16 in, packed nibble + 1/32 scale byte out
 
-# HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE), scaled by a plain
-# copy kernel of known size (bytes per launch); see the profiles/ summaries named below.
-MEASURED_TRAFFIC = {
-    # profiles/mxfp4_gemm_llama3_70b_up.md: 1.633e9 B read + 4.734e8 B written per launch
-    "mxfp4_gemm/llama3_70b_up": 2.106e9,
-    # profiles/torq_rotate_quantize_llama3_70b_up.md: 1.348e8 B read + 3.566e7 B written per launch
-    "torq_rotate_quantize/llama3_70b_up": 1.705e8,
-}
+
+
+def measured_traffic(key):
+    """HBM bytes per launch of the headline kernels, from profiles/traffic.json (written by
+    `python -m paper_2605_19561_amd.traffic` out of two rocprofv3 --pmc runs of this program), and whether
+    the kernel sources have changed since those runs."""
+    from paper_2605_19561_amd import traffic
+    return traffic.lookup(key)
 
 
 def main():
@@ -49,11 +49,14 @@ def main():
                     help="skip the two one-second runs that sample board power and shader clock (for kernel "
                          "traces: they add some 20000 launches to the per-kernel averages)")
     ap.add_argument("--calibrate-copy", action="store_true",
-                    help="also run a plain 1 GiB device copy (known traffic) so that a rocprofv3 --pmc run of this "
-                         "command carries its own scale for FETCH_SIZE / WRITE_SIZE")
-    ap.add_argument("--library-gemm", action="store_true",
-                    help="also time the vendor library's block-scaled fp4 GEMM (torch._scaled_mm -> hipBLASLt) on "
-                         "the same operands, for context; its first call takes about half a minute")
+                    help="also run the library's plain copy kernel on 1 GiB (known traffic) so that a rocprofv3 --pmc "
+                         "run of this command carries its own scale for FETCH_SIZE / WRITE_SIZE")
+    ap.add_argument("--headline-only", action="store_true",
+                    help="leave out the `configs` array (the other shapes of the benchmark configurations): for "
+                         "kernel traces and counter runs of the headline step")
+    ap.add_argument("--ablate", action="store_true",
+                    help="also print, for the two headline kernels, the launch time with parts of their work left out "
+                         "(torq_diag_gemm_ablation / torq_diag_rotate_ablation): what each part costs on this machine")
     ap.add_argument("--sweep", action="store_true",
                     help="also print one line per rotate+quantise bandwidth-sweep shape ([16384, d])")
     args = ap.parse_args()
@@ -90,9 +93,9 @@ def main():
     def step():
         tq.torq_linear(rot, x, W_q, W_s, out=out, workspace=workspace)
 
-    for _ in range(args.warmup):
-        step()
-    torch.cuda.synchronize()
+    # W untimed steps, then more of them until 40 ms have passed: after the pause that input generation
+    # is, the shader clock needs that long under load to reach the level it then keeps
+    settle(torch, step, args.warmup)
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
@@ -105,17 +108,22 @@ def main():
     # ---- per-kernel durations: HIP events on the stream the kernels run on (torch's current
     # stream, which is the one handed to the library).  Each kernel is launched `steps` times back
     # to back between two events, so launch gaps are not attributed to it.  rotate+quantise moves
-    # only 170 MB per launch, which would fit the 256 MB Infinity Cache: it cycles over three copies
-    # of the input so that every launch reads from HBM.
+    # only 170 MB per launch, which would fit the 256 MB Infinity Cache: it cycles over five copies
+    # of the input (670 MB) so that every launch reads from HBM.
     x_copies = [x, x.clone(), x.clone()]
     e = [torch.cuda.Event(enable_timing=True) for _ in range(4)]
-    for i in range(3):
-        tq.torq_rotate_quantize(rot, x_copies[i], codes=codes, scales=scales)
+    x_copies += [x.clone() for _ in range(2)]          # five copies, 670 MB: far beyond the Infinity Cache
+    counter = [0]
+
+    def rq_call():
+        tq.torq_rotate_quantize(rot, x_copies[counter[0] % len(x_copies)], codes=codes, scales=scales)
+        counter[0] += 1
+    settle(torch, rq_call, 3)
     e[0].record()
     for i in range(args.steps):
-        tq.torq_rotate_quantize(rot, x_copies[i % 3], codes=codes, scales=scales)
+        tq.torq_rotate_quantize(rot, x_copies[i % len(x_copies)], codes=codes, scales=scales)
     e[1].record()
-    tq.mxfp4_gemm(codes, scales, W_q, W_s, out=out)
+    settle(torch, lambda: tq.mxfp4_gemm(codes, scales, W_q, W_s, out=out), 1)
     e[2].record()
     for i in range(args.steps):
         tq.mxfp4_gemm(codes, scales, W_q, W_s, out=out)
@@ -129,8 +137,7 @@ def main():
     gemm_env = rq_env = None
     if not args.no_board_sample:
         gemm_env = sample_board(torch, lambda i: tq.mxfp4_gemm(codes, scales, W_q, W_s, out=out), 1.0)
-        rq_env = sample_board(torch, lambda i: tq.torq_rotate_quantize(rot, x_copies[i % 3], codes=codes, scales=scales), 1.0)
-    del x_copies
+        rq_env = sample_board(torch, lambda i: tq.torq_rotate_quantize(rot, x_copies[i % len(x_copies)], codes=codes, scales=scales), 1.0)
 
     # ---- what the matrix cores sustain on this part with nothing else running, on this step's own
     # operands (the weights' packed codes; the bf16 activations): the part lowers its clock under
@@ -154,26 +161,31 @@ def main():
     # context: what the runtime's own device-to-device copy of 1 GiB reaches on this machine
     copy_gbs = copy_line(torch, dev, 10)["value"]
 
+    gemm_traffic, gemm_stale = measured_traffic(f"mxfp4_gemm/{args.workload}")
+    rq_traffic, rq_stale = measured_traffic(f"torq_rotate_quantize/{args.workload}")
     result = {
         "metric": "TORQ W4A4 MXFP4 linear layer (rotate + MXFP4 quantise + fp4 GEMM), whole step",
         "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "fp4 (e2m1 x E8M0) with fp32 accumulation; rotation in split bf16",
         "data": "synthetic",
+        "timing": "timed steps start after the warm-up steps and 40 ms more of them (clock settled); per-kernel times "
+                  "from HIP events around back-to-back launches; HBM-bound kernels cycle over input copies of more than "
+                  "600 MB in all, so the 256 MB Infinity Cache serves none of them",
         "config": {"workload": f"{args.workload}: X bf16 [{M}, {d}] Student-t(nu={wl['nu']}) with "
                                f"{wl['outliers']} outlier channels x{wl['outlier_scale']:g}, G={G}, "
                                f"W [{N}, {d}] ~ N(0, {wl['wstd']}^2) rotated+quantised offline, out bf16 [{M}, {N}]",
                    "M": M, "N": N, "d": d, "G": G},
         "roofline": {"kernel": "mxfp4_gemm", "bound": "mfma", "achieved": round(gemm_tflops, 1),
                      "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(gemm_tflops / FP4_PEAK_TFLOPS, 4),
-                     "traffic": MEASURED_TRAFFIC.get(f"mxfp4_gemm/{args.workload}"),
+                     "traffic": gemm_traffic, "traffic_stale": gemm_stale,
                      "avg_kernel_ms": round(gemm_ms, 4),
                      "sustained_mfma_only": round(sustained[tq.TORQ_DIAG_FP4], 1),
                      "frac_of_sustained": round(gemm_tflops / sustained[tq.TORQ_DIAG_FP4], 4),
                      "board": gemm_env},
         "roofline_rotate_quant": {"kernel": "torq_rotate_quantize", "bound": "hbm", "achieved": round(rq_gbs, 1),
                                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(rq_gbs / HBM_PEAK_GBS, 4),
-                                  "traffic": MEASURED_TRAFFIC.get(f"torq_rotate_quantize/{args.workload}"),
+                                  "traffic": rq_traffic, "traffic_stale": rq_stale,
                                   "avg_kernel_ms": round(rq_ms, 4),
                                   "mfma_bf16_tflops": round(rq_mfma_tflops, 1),
                                   "mfma_bf16_frac": round(rq_mfma_tflops / BF16_PEAK_TFLOPS, 4),
@@ -182,8 +194,9 @@ def main():
                                   "board": rq_env},
     }
 
-    if args.library_gemm:
-        result["roofline"]["library_gemm"] = library_gemm(torch, codes, scales, W_q, W_s, M, N, d, args.steps)
+    if not args.headline_only:
+        del x_copies[1:]
+        result["configs"] = config_lines(tq, synth, torch, args.steps, args.warmup, result)
 
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d)
@@ -194,9 +207,12 @@ def main():
         src = torch.full((1 << 30,), 7, dtype=torch.uint8, device=dev)
         dst = torch.empty_like(src)
         for _ in range(3):
-            dst.copy_(src)
+            tq.torq_diag_copy(src, dst)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.ablate:
+        print(json.dumps(ablation_lines(tq, torch, rot, x, codes, scales, W_q, W_s, out, args.steps)), flush=True)
 
     if args.sweep:
         # context for the HBM-bound lines below: what the runtime's own device-to-device copy of 1 GiB
@@ -240,29 +256,6 @@ def main():
                              (64, 28672, 8192), (128, 8192, 28672), (256, 4096, 14336)):
             print(json.dumps(decode_line(tq, synth, mm, nn, dd)), flush=True)
     rot.close()
-
-
-def library_gemm(torch, A_q, A_s, W_q, W_s, M, N, d, steps):
-    """The same product through the vendor library (hipBLASLt behind torch._scaled_mm), same packed
-    operands and scale bytes.  Context only: nothing in the measured path calls it."""
-    try:
-        a = A_q.view(torch.float4_e2m1fn_x2)
-        b = W_q.view(torch.float4_e2m1fn_x2)
-        sa, sb = A_s.view(torch.float8_e8m0fnu), W_s.view(torch.float8_e8m0fnu)
-        f = lambda: torch._scaled_mm(a, b.t(), scale_a=sa, scale_b=sb, out_dtype=torch.bfloat16)
-        for _ in range(3):
-            f()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(steps):
-            f()
-        e1.record()
-        torch.cuda.synchronize()
-        ms = e0.elapsed_time(e1) / steps
-        return {"what": "torch._scaled_mm (hipBLASLt), same operands", "avg_kernel_ms": round(ms, 4),
-                "achieved": round(2.0 * M * N * d / (ms * 1e-3) / 1e12, 1), "unit": "TFLOP/s"}
-    except Exception as ex:  # not every build of the library has this path
-        return {"what": "torch._scaled_mm (hipBLASLt)", "error": repr(ex)[:200]}
 
 
 def cpu_baseline(x, W_q, W_s, Ri, Ra, G, M, N, d):
@@ -375,15 +368,19 @@ def settle(torch, call, warmup, seconds=0.04):
         torch.cuda.synchronize()
 
 
-def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0, butterfly=False):
-    """rotate+quantise alone on X [16384, d] (the memory-bound sweep); fmt 1 / 2: MXINT4 / NVFP4 output;
-    butterfly: R_inter as log2 G rounds of plane rotations instead of a dense G x G matrix."""
+def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0, butterfly=False, M=16384, recipe=None):
+    """rotate+quantise alone on X [M, d] (the memory-bound sweep); fmt 1 / 2: MXINT4 / NVFP4 output;
+    butterfly: R_inter as log2 G rounds of plane rotations instead of a dense G x G matrix.  The launches
+    cycle over copies of X of at least 600 MB in all (at least three), so that no launch finds its input
+    in the 256 MB Infinity Cache."""
     import torch
     dev = "cuda:0"
-    M = 16384
     G = G or synth.default_G(d)
-    x = synth.activations(M, d, nu=3.0, outliers=round(0.005 * d), outlier_scale=50.0, seed=synth.SEED_BASE + 5,
-                          device=dev)
+    r = dict(nu=3.0, outliers=round(0.005 * d), outlier_scale=50.0, seed=synth.SEED_BASE + 5)
+    r.update(recipe or {})
+    x = synth.activations(M, d, device=dev, **r)
+    n_copies = max(3, int(600e6 // (x.numel() * 2)) + 1)
+    xs = [x] + [x.clone() for _ in range(n_copies - 1)]
     Ri, Ra = synth.rotations(G)
     if butterfly:
         import numpy as np
@@ -394,12 +391,15 @@ def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0, butterfly=False):
     codes = torch.empty((M, d // 2), dtype=torch.uint8, device=dev)
     scales = torch.empty((M, d // (16 if fmt == 2 else 32)), dtype=torch.uint8, device=dev)
     gs = 0.01                                          # NVFP4's tensor-wide scale (unused otherwise)
+    turn = [0]
 
     def call():
+        xi = xs[turn[0] % n_copies]
+        turn[0] += 1
         if fmt == 0:
-            tq.torq_rotate_quantize(rot, x, codes=codes, scales=scales)
+            tq.torq_rotate_quantize(rot, xi, codes=codes, scales=scales)
         else:
-            tq.torq_rotate_quantize_fmt(rot, x, fmt, gs, codes=codes, scales=scales)
+            tq.torq_rotate_quantize_fmt(rot, xi, fmt, gs, codes=codes, scales=scales)
     settle(torch, call, warmup)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
@@ -414,9 +414,109 @@ def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0, butterfly=False):
     name = ("", " -> MXINT4", " -> NVFP4")[fmt] + (", butterfly R_inter" if butterfly else "")
     mfma_flop = 2 * 64 if butterfly else 2 * 2 * G + 3 * 64      # per element: bf16 passes of the contractions
     return {"metric": "torq_rotate_quantize bandwidth", "value": round(gbs, 1), "unit": "GB/s",
-            "config": {"workload": f"sweep: X bf16 [{M}, {d}], G={G}{name}"}, "ms": round(ms, 4),
+            "config": {"workload": f"sweep: X bf16 [{M}, {d}], G={G}{name}", "input_copies": n_copies}, "ms": round(ms, 4),
             "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
             "mfma_bf16_tflops": round(M * d * mfma_flop / (ms * 1e-3) / 1e12, 1)}
+
+
+def config_lines(tq, synth, torch, steps, warmup, headline):
+    """The other shapes of the benchmark configurations, one compact entry each: the rotate+quantise kernel
+    against the HBM peak, the GEMM against the fp4 MFMA peak (prefill) and torq_linear per call with the
+    rate at which the weights stream (decode).  `config` is the number of the configuration in the task's
+    list: 1 tiny, 2 LLaMA3-8B, 3 Qwen3-32B, 4 LLaMA3-70B, 5 the rotate+quantise bandwidth sweep."""
+    out = []
+
+    def rq(cfg, M, d, recipe, G=None, butterfly=False):
+        r = sweep_line(tq, synth, d, steps, warmup, M=M, recipe=recipe, G=G, butterfly=butterfly)
+        G_ = G or synth.default_G(d)
+        out.append({"config": cfg, "kernel": "torq_rotate_quantize" + (" (butterfly R_inter)" if butterfly else ""),
+                    "shape": f"X[{M},{d}] G={G_}", "us": round(r["ms"] * 1e3, 2), "value": r["value"], "unit": "GB/s",
+                    "bound": "hbm", "frac": r["frac_hbm_peak"], "input_copies": r["config"]["input_copies"]})
+
+    def gemm(cfg, M, N, d):
+        r = gemm_line(tq, M, N, d, steps, warmup)
+        out.append({"config": cfg, "kernel": "mxfp4_gemm (" + r["config"]["gemm_kernel"] + ")", "shape": f"[{M},{N},{d}]",
+                    "us": round(r["ms"] * 1e3, 2), "value": r["value"], "unit": "TFLOP/s", "bound": "mfma",
+                    "frac": r["frac_fp4_peak"]})
+
+    def decode(cfg, M, N, d):
+        r = decode_line(tq, synth, M, N, d, single_launch=False)
+        out.append({"config": cfg, "kernel": "torq_linear (" + r["config"]["gemm_kernel"] + ")", "shape": f"X[{M},{d}] -> {N}",
+                    "us": r["value"], "value": r["weight_stream_GBps"], "unit": "GB/s of weights", "bound": "hbm",
+                    "frac": r["frac_hbm_peak"]})
+
+    t3 = dict(nu=3.0, outlier_scale=50.0)
+    # 5: the bandwidth sweep
+    for d in (4096, 8192, 14336, 28672):
+        rq(5, 16384, d, dict(t3, outliers=round(0.005 * d)))
+    # 4: LLaMA3-70B; up / gate is the headline step above, here the down projection's two kernels
+    out.append({"config": 4, "kernel": "torq_rotate_quantize", "shape": "X[8192,8192] G=128", "us": round(headline["roofline_rotate_quant"]["avg_kernel_ms"] * 1e3, 2),
+                "value": headline["roofline_rotate_quant"]["achieved"], "unit": "GB/s", "bound": "hbm",
+                "frac": headline["roofline_rotate_quant"]["frac"], "input_copies": 5})
+    out.append({"config": 4, "kernel": "mxfp4_gemm (tiled 256x256)", "shape": "[8192,28672,8192]", "us": round(headline["roofline"]["avg_kernel_ms"] * 1e3, 2),
+                "value": headline["roofline"]["achieved"], "unit": "TFLOP/s", "bound": "mfma", "frac": headline["roofline"]["frac"]})
+    rq(4, 8192, 28672, dict(nu=2.5, outliers=round(0.01 * 28672), outlier_scale=100.0))
+    gemm(4, 8192, 8192, 28672)
+    # 3: Qwen3-32B (G = 80), per-token log-normal scale
+    for d in (5120, 25600):
+        rq(3, 4096, d, dict(t3, outliers=round(0.005 * d), token_lognormal=True))
+    for N, d in ((25600, 5120), (5120, 25600), (8192, 5120), (5120, 5120), (1024, 5120)):
+        gemm(3, 4096, N, d)
+    # 2: LLaMA3-8B, prefill (M = 2048) and decode (M = 1, 16)
+    for d in (4096, 14336):
+        rq(2, 2048, d, dict(t3, outliers=round(0.005 * d)))
+    for N, d in ((14336, 4096), (4096, 4096), (1024, 4096), (4096, 14336)):
+        gemm(2, 2048, N, d)
+    for M in (1, 16):
+        for N, d in ((14336, 4096), (4096, 4096), (1024, 4096), (4096, 14336)):
+            decode(2, M, N, d)
+    # 1: the tiny layer
+    decode(1, 64, 1024, 4096)
+    # the calibrated alternative of Section 5.1 at the headline width: R_inter as a butterfly
+    rq(4, 8192, 8192, dict(nu=2.5, outliers=82, outlier_scale=100.0), G=128, butterfly=True)
+    return out
+
+
+def ablation_lines(tq, torch, rot, x, codes, scales, W_q, W_s, out, steps):
+    """Launch times of the two headline kernels with parts of their work left out (diagnostic builds of the
+    same kernels; their outputs are meaningless and go to scratch copies).  Both kernels run at the board's
+    power limit, so the cost of a part is the time the launch shortens by without it."""
+    M, d = x.shape
+    xs = [x.clone() for _ in range(5)]
+    c2, s2, o2 = torch.empty_like(codes), torch.empty_like(scales), torch.empty_like(out)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(call, reps):
+        turn = [0]
+
+        def f():
+            call(turn[0])
+            turn[0] += 1
+        settle(torch, f, 3)
+        e0.record()
+        for _ in range(reps):
+            f()
+        e1.record()
+        torch.cuda.synchronize()
+        return round(e0.elapsed_time(e1) * 1e3 / reps, 2)
+
+    gemm_names = {0: "product kernel", 1: "no buffer loads in the k loop", 3: "... and no LDS stores",
+                  7: "... and no fragment reads (MFMAs + barrier)", 15: "... and no barrier (MFMAs only)",
+                  4: "no fragment reads only"}
+    rot_names = {0: "product kernel (704 MFMA flop per element)", 6: "no vector-ALU split, no step-4 arithmetic",
+                 2: "no vector-ALU split only", 4: "no step-4 arithmetic only", 8: "one R_intra pass (576 flop)",
+                 1: "no R_inter low pass (448 flop)", 9: "high parts only (320 flop)", 15: "high parts only, no vector ALU"}
+    res = {"metric": "launch time with parts of the kernel's work left out", "unit": "us", "gemm": [], "rotate_quantize": []}
+    for rnd in range(2):                               # twice: the second pass is the one on a warm board
+        g, r = [], []
+        for skip, name in gemm_names.items():
+            g.append({"skip": skip, "what": name,
+                      "us": timed(lambda i: tq.torq_diag_gemm_ablation(codes, scales, W_q, W_s, o2, skip), steps)})
+        for skip, name in rot_names.items():
+            r.append({"skip": skip, "what": name,
+                      "us": timed(lambda i: tq.torq_diag_rotate_ablation(rot, xs[i % 5], c2, s2, skip), 4 * steps)})
+        res["gemm"], res["rotate_quantize"] = g, r
+    return res
 
 
 def gemm_line(tq, M, N, d, steps, warmup):
@@ -499,7 +599,7 @@ def hist_line(tq, codes, d, steps, warmup):
             "frac_hbm_peak": round(gbs / HBM_PEAK_GBS, 4)}
 
 
-def decode_line(tq, synth, M, N, d):
+def decode_line(tq, synth, M, N, d, single_launch=True):
     """torq_linear (rotate + quantise + GEMM) on M activation rows: microseconds per call and the rate at
     which the packed weights stream through.  Six weight copies rotate so that the Infinity Cache cannot
     hold them."""
@@ -543,7 +643,7 @@ def decode_line(tq, synth, M, N, d):
 
     us = replayed(tq.torq_linear)
     # the one-launch form of the same layer, where it applies (G = 128, at most 64 rows)
-    us_single = round(replayed(tq.torq_linear_single_launch), 2) if (G == 128 and M <= 64) else None
+    us_single = round(replayed(tq.torq_linear_single_launch), 2) if (single_launch and G == 128 and M <= 64) else None
     wbytes = N * d * 0.53125
     rot.close()
     streaming, tile_m, tile_n, pieces = tq.mxfp4_gemm_plan(M, N, d, tq.mxfp4_gemm_workspace_bytes(M, N, d))

@@ -376,6 +376,29 @@ int torq_calibrate_intra(const float *X_host, int64_t n, int max_iter, int k_top
 #define TORQ_DIAG_FLOP_PER_ITER_BF16 (1024.0 * 4 * 16 * 2 * 32 * 32 * 16)
 int torq_diag_mfma_burn(int kind, const void *operands, size_t n_bytes, int iters, float *sink,
                         void *stream);
+/* The two headline kernels with parts of their work left out, to measure on the machine at hand what
+ * each part costs (the kernels run at the board's power limit, so a part's cost is the time by which
+ * the launch shortens without it, not its instruction count).  Operands, shapes and launch shape are
+ * those of mxfp4_gemm's 256 x 256-tile kernel (d a multiple of 512, all five pointers 16-byte aligned)
+ * and of torq_rotate_quantize at G = 128 (dense R_inter).  skip = 0 is the product kernel; with any
+ * other value the OUTPUT IS MEANINGLESS (every access stays within the same buffers).
+ *   torq_diag_gemm_ablation    skip: 1 no buffer loads in the k loop (it multiplies what the prologue
+ *                              staged); 3 also no LDS stores; 7 also no fragment reads (MFMAs and the
+ *                              barrier only); 15 also no barrier; 4 no fragment reads only
+ *   torq_diag_rotate_ablation  skip bits: 1 no low-part pass over R_inter; 2 no hi/lo split of Y on the
+ *                              vector ALU; 4 no amax / conversion in step 4; 8 one R_intra pass instead
+ *                              of three; supported: 0, 1, 2, 4, 6, 8, 9, 15
+ * Any other skip, shape or handle: TORQ_EINVAL. */
+int torq_diag_gemm_ablation(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                            void *out_bf16, int64_t M, int64_t N, int d, int skip, void *stream);
+int torq_diag_rotate_ablation(const torq_rotation_t *r, const void *x_bf16, int64_t M, uint8_t *codes,
+                              uint8_t *scales, int skip, void *stream);
+/* A plain device-to-device copy of n_bytes (a multiple of 16; src and dst 16-byte aligned, not
+ * overlapping) by a kernel of this library, `torq::diag_copy_kernel`: it reads n_bytes and writes
+ * n_bytes, nothing else, which makes it the yardstick for memory-traffic counters (run it in the same
+ * counter collection as the kernel under study and scale by what the counter reads for it).
+ * Errors: TORQ_EINVAL, TORQ_EALIGN, TORQ_EHIP. */
+int torq_diag_copy(const void *src, void *dst, size_t n_bytes, void *stream);
 
 #ifdef __cplusplus
 }

@@ -21,7 +21,7 @@ EXPORTS = [
     "torq_linear_workspace_bytes_n", "torq_block_gram_workspace_bytes", "torq_block_gram", "torq_block_gram_positions",
     "torq_equalize_inter", "torq_code_histogram_workspace_bytes", "torq_code_histogram", "torq_intra_pair_scores",
     "torq_intra_best_angle", "torq_calibrate_intra", "torq_diag_mfma_burn", "torq_linear_static",
-    "torq_linear_single_launch_reset", "torq_linear_single_launch_gave_up", "torq_linear_single_launch_probe",
+    "torq_diag_copy", "torq_diag_gemm_ablation", "torq_diag_rotate_ablation", "torq_linear_single_launch_reset", "torq_linear_single_launch_gave_up", "torq_linear_single_launch_probe",
 ]
 
 TORQ_OK, TORQ_EINVAL, TORQ_EALIGN, TORQ_EWORKSPACE, TORQ_EHIP, TORQ_ENODEVICE, TORQ_ECONVERGE = 0, -1, -2, -3, -4, -5, -6
@@ -118,6 +118,12 @@ def lib():
         L.torq_calibrate_intra.argtypes = [vp, i64, i32, i32, i32, C.c_double, C.c_double, vp, vp, C.POINTER(i32)]
         L.torq_diag_mfma_burn.restype = i32
         L.torq_diag_mfma_burn.argtypes = [i32, vp, sz, i32, vp, vp]
+        L.torq_diag_gemm_ablation.restype = i32
+        L.torq_diag_gemm_ablation.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp]
+        L.torq_diag_rotate_ablation.restype = i32
+        L.torq_diag_rotate_ablation.argtypes = [vp, vp, i64, vp, vp, i32, vp]
+        L.torq_diag_copy.restype = i32
+        L.torq_diag_copy.argtypes = [vp, vp, sz, vp]
         _lib = L
     return _lib
 
@@ -398,6 +404,32 @@ def torq_diag_mfma_burn(kind: int, operands: torch.Tensor, iters: int, sink=None
                                      iters, _dev(sink, torch.float32, "sink"), _stream(stream)),
            "torq_diag_mfma_burn")
     return TORQ_DIAG_FLOP_PER_ITER[kind] * iters
+
+
+def torq_diag_gemm_ablation(A_q, A_s, W_q, W_s, out, skip: int, stream=None):
+    """mxfp4_gemm's 256 x 256-tile kernel with parts of its k loop left out (see include/torq.h); `out` is garbage."""
+    M, N, d = A_q.shape[0], W_q.shape[0], A_q.shape[1] * 2
+    _check(lib().torq_diag_gemm_ablation(_dev(A_q, torch.uint8, "A_q"), _dev(A_s, torch.uint8, "A_s"),
+                                         _dev(W_q, torch.uint8, "W_q"), _dev(W_s, torch.uint8, "W_s"),
+                                         _dev(out, torch.bfloat16, "out"), M, N, d, int(skip), _stream(stream)),
+           "torq_diag_gemm_ablation")
+
+
+def torq_diag_rotate_ablation(rot, x_bf16, codes, scales, skip: int, stream=None):
+    """torq_rotate_quantize's G = 128 kernel with work left out (see include/torq.h); codes / scales are garbage."""
+    _check(lib().torq_diag_rotate_ablation(rot.handle, _dev(x_bf16, torch.bfloat16, "x"), x_bf16.shape[0],
+                                           _dev(codes, torch.uint8, "codes"), _dev(scales, torch.uint8, "scales"),
+                                           int(skip), _stream(stream)), "torq_diag_rotate_ablation")
+
+
+def torq_diag_copy(src: torch.Tensor, dst: torch.Tensor, stream=None):
+    """dst <- src by the library's own copy kernel (known traffic: the counters' yardstick)."""
+    n = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == n and src.is_cuda and dst.is_cuda
+    assert src.is_contiguous() and dst.is_contiguous()
+    _check(lib().torq_diag_copy(C.c_void_p(src.data_ptr()), C.c_void_p(dst.data_ptr()), n, _stream(stream)),
+           "torq_diag_copy")
+    return dst
 
 
 def torq_block_gram_workspace_bytes(G: int) -> int:

@@ -690,6 +690,34 @@ int torq_diag_mfma_burn(int kind, const void *operands, size_t n_bytes, int iter
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 
+int torq_diag_gemm_ablation(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                            void *out_bf16, int64_t M, int64_t N, int d, int skip, void *stream) {
+  if (M <= 0 || N <= 0 || d <= 0 || d % 512 != 0 || skip < 0) return TORQ_EINVAL;
+  if (!A_q || !A_s || !W_q || !W_s || !out_bf16) return TORQ_EINVAL;
+  if (misaligned(A_q) || misaligned(W_q) || misaligned(out_bf16) || misaligned(A_s) || misaligned(W_s)) return TORQ_EALIGN;
+  hipError_t e = torq::launch_mxfp4_gemm_ablated(A_q, A_s, W_q, W_s, out_bf16, M, N, d, skip, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return TORQ_EINVAL;
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+int torq_diag_rotate_ablation(const torq_rotation_t *r, const void *x_bf16, int64_t M, uint8_t *codes,
+                              uint8_t *scales, int skip, void *stream) {
+  if (!r || M < 0 || skip < 0) return TORQ_EINVAL;
+  if (M == 0) return TORQ_OK;
+  if (!x_bf16 || !codes || !scales) return TORQ_EINVAL;
+  if (misaligned(x_bf16) || misaligned(codes) || misaligned(scales)) return TORQ_EALIGN;
+  hipError_t e = torq::launch_rotate_ablated(r, x_bf16, M, codes, scales, skip, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return TORQ_EINVAL;
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
+int torq_diag_copy(const void *src, void *dst, size_t n_bytes, void *stream) {
+  if (!src || !dst || n_bytes % 16 != 0) return TORQ_EINVAL;
+  if (misaligned(src) || misaligned(dst)) return TORQ_EALIGN;
+  hipError_t e = torq::launch_diag_copy(src, dst, n_bytes, (hipStream_t)stream);
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
 // The host routines above behind a guard: an allocation failure comes back as TORQ_ENOMEM.
 int torq_rotation_create(torq_rotation_t **out, int d, int G, const float *R_inter_host, const float *R_intra_host) {
   return guarded([&] { return torq_rotation_create_impl(out, d, G, R_inter_host, R_intra_host); });

@@ -66,4 +66,20 @@ hipError_t launch_mfma_burn(int kind, const uint32_t *words, uint32_t n_words, i
   return hipGetLastError();
 }
 
+// torq_diag_copy: a plain copy of a known number of bytes (16 per lane and step, grid-stride), so that a
+// counter run of any program of this library carries its own scale for the memory-traffic counters.
+__global__ void __launch_bounds__(256) diag_copy_kernel(const uint4 *__restrict__ src, uint4 *__restrict__ dst, size_t n16) {
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
+}
+
+hipError_t launch_diag_copy(const void *src, void *dst, size_t bytes, hipStream_t stream) {
+  const size_t n16 = bytes / 16;
+  if (n16 == 0) return hipSuccess;
+  const size_t want = (n16 + 255) / 256;
+  const unsigned grid = (unsigned)(want < 256 * 16 ? want : 256 * 16);
+  hipLaunchKernelGGL(diag_copy_kernel, dim3(grid), dim3(256), 0, stream, static_cast<const uint4 *>(src),
+                     static_cast<uint4 *>(dst), n16);
+  return hipGetLastError();
+}
+
 }  // namespace torq

@@ -43,7 +43,12 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint3
 // SPLIT: blockIdx.y = which of gridDim.y equal pieces of the k range this workgroup multiplies
 // (each a whole, even number of iterations); the tile's fp32 sums go to partial[blockIdx.y][M][N]
 // and mxfp4_gemm_splitk_reduce_kernel adds the pieces.  Needs FULLK.
-template <int WM, int WN, bool FULLK, bool SPLIT, bool DEEP = false>
+// SKIP (diagnostic builds only, torq_diag_gemm_ablation): parts of the k loop left out to measure what
+// each costs -- 1: the buffer loads, 2: the LDS stores (only with 1: their data would be dead), 4: the
+// fragment and scale reads, 8: the barrier.
+// What is left out is never replaced by anything else: the loop then multiplies the operands that the
+// prologue staged, again and again, and the output is meaningless.  SKIP = 0 is the product.
+template <int WM, int WN, bool FULLK, bool SPLIT, bool DEEP = false, int SKIP = 0>
 __global__ void __launch_bounds__(256)
 mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A_s,
                   const uint8_t *__restrict__ W_q, const uint8_t *__restrict__ W_s,
@@ -222,6 +227,7 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
   __syncthreads();
   SC_LOAD(0, 0);
   F_LOAD(0, 0, 0);
+  if constexpr ((SKIP & 4) != 0) { F_LOAD(1, 0, 1); SC_LOAD(1, 0); }   // every register set holds staged operands
 
   // One k iteration is two scheduling regions, split by the workgroup barrier.  Each region ends
   // with a sched_group_barrier pipeline that tells the machine scheduler how to interleave MFMAs
@@ -239,19 +245,19 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
 #define ITER(P, KT_)                                                                              \
   {                                                                                               \
     const int kt_i = (KT_);                                                                       \
-    F_LOAD(1, P, 1);                                                                              \
+    if constexpr (!(SKIP & 4)) F_LOAD(1, P, 1);                                                                              \
     MFMA_HALF(0, P, 0, 0, WN);                                                                    \
-    F_LOAD(0, P, 2);                                                                              \
-    L_STORE((P) ^ 1, 0);                                                                          \
-    G_LOAD_Q((P) ^ 1, kt_i + AHEAD, 0);                                                           \
+    if constexpr (!(SKIP & 4)) F_LOAD(0, P, 2);                                                                              \
+    if constexpr (!(SKIP & 2)) L_STORE((P) ^ 1, 0);                                                                          \
+    if constexpr (!(SKIP & 1)) G_LOAD_Q((P) ^ 1, kt_i + AHEAD, 0);                                                           \
     MFMA_HALF(1, P, 1, 0, WN);                                                                    \
-    F_LOAD(1, P, 3);                                                                              \
-    L_STORE((P) ^ 1, 1);                                                                          \
-    G_LOAD_Q((P) ^ 1, kt_i + AHEAD, 1);                                                           \
+    if constexpr (!(SKIP & 4)) F_LOAD(1, P, 3);                                                                              \
+    if constexpr (!(SKIP & 2)) L_STORE((P) ^ 1, 1);                                                                          \
+    if constexpr (!(SKIP & 1)) G_LOAD_Q((P) ^ 1, kt_i + AHEAD, 1);                                                           \
     MFMA_HALF(0, P, 2, 0, WN);                                                                    \
-    L_STORE((P) ^ 1, 2);                                                                          \
-    L_STORE((P) ^ 1, 3);                                                                          \
-    if ((P) == 1) S_STORE(((kt_i + 1) >> 1) & 1);                                                 \
+    if constexpr (!(SKIP & 2)) L_STORE((P) ^ 1, 2);                                                                          \
+    if constexpr (!(SKIP & 2)) L_STORE((P) ^ 1, 3);                                                                          \
+    if constexpr (!(SKIP & 2)) if ((P) == 1) S_STORE(((kt_i + 1) >> 1) & 1);                                                 \
     MFMA_HALF(1, P, 3, 0, WN / 2);                                                                \
     /* k-step 0: its MFMAs hide the fragment reads of k-step 1 */                                 \
     _Pragma("unroll") for (int n_ = 0; n_ < WM + WN; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 1) }   \
@@ -267,12 +273,12 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
     }                                                                                             \
     /* first half of k-step 3: the rest of the LDS stores */                                      \
     _Pragma("unroll") for (int n_ = 0; n_ < WM * WN / 2; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_WR, 2) } \
-    __syncthreads();                                                                              \
-    SC_LOAD((P) ^ 1, kt_i + 1);                                                                   \
-    F_LOAD(0, (P) ^ 1, 0);                                                                        \
-    G_LOAD_Q((P) ^ 1, kt_i + AHEAD, 2);                                                           \
-    G_LOAD_Q((P) ^ 1, kt_i + AHEAD, 3);                                                           \
-    if ((P) == 0) S_LOAD(PHYS_KT(kt_i + 2) >> 1);                                                 \
+    if constexpr (!(SKIP & 8)) __syncthreads();                                                                              \
+    if constexpr (!(SKIP & 4)) SC_LOAD((P) ^ 1, kt_i + 1);                                                                   \
+    if constexpr (!(SKIP & 4)) F_LOAD(0, (P) ^ 1, 0);                                                                        \
+    if constexpr (!(SKIP & 1)) G_LOAD_Q((P) ^ 1, kt_i + AHEAD, 2);                                                           \
+    if constexpr (!(SKIP & 1)) G_LOAD_Q((P) ^ 1, kt_i + AHEAD, 3);                                                           \
+    if constexpr (!(SKIP & 1)) if ((P) == 0) S_LOAD(PHYS_KT(kt_i + 2) >> 1);                                                 \
     MFMA_HALF(1, P, 3, WN / 2, WN);                                                               \
     /* second half of k-step 3: fragment and scale reads of the next iteration first, then      \
        the remaining buffer loads */                                                              \
@@ -378,7 +384,7 @@ mxfp4_gemm_splitk_reduce_kernel(const float *__restrict__ partial, int splits, i
   *reinterpret_cast<u64x2 *>(out + e0) = u64x2{__builtin_bit_cast(uint64_t, a), __builtin_bit_cast(uint64_t, b)};
 }
 
-template <int WM, int WN, bool FULLK, bool SPLIT, bool DEEP = false>
+template <int WM, int WN, bool FULLK, bool SPLIT, bool DEEP = false, int SKIP = 0>
 static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                               const uint8_t *W_s, void *out, float *partial, int splits, int64_t M, int64_t N,
                               int d, hipStream_t stream) {
@@ -386,7 +392,7 @@ static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint
   const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   if (tiles_m * tiles_n > 0x7FFFFFFF) return hipErrorInvalidValue;
   const size_t lds_bytes = 2 * (size_t)(BM + BN) * 128 + 2 * (size_t)((BM + BN + 255) / 256 * 256) * 16;
-  auto kern = mxfp4_gemm_kernel<WM, WN, FULLK, SPLIT, DEEP>;
+  auto kern = mxfp4_gemm_kernel<WM, WN, FULLK, SPLIT, DEEP, SKIP>;
   if (lds_bytes > 64 * 1024) {
     // raise the dynamic LDS limit once per process and kernel variant (the call is slow)
     static bool raised = false;
@@ -526,6 +532,20 @@ hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8
   if (plan.cfg == 1) { TORQ_GEMM_LAUNCH(4, 2) }
   TORQ_GEMM_LAUNCH(2, 2)
 #undef TORQ_GEMM_LAUNCH
+}
+
+// torq_diag_gemm_ablation: the 256 x 256-tile kernel with parts of its k loop left out (see SKIP above).
+hipError_t launch_mxfp4_gemm_ablated(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                                     void *out_bf16, int64_t M, int64_t N, int d, int skip, hipStream_t stream) {
+  if ((int64_t)d * 128 >= 0x7FFFFFFF || d % 512 != 0) return hipErrorInvalidValue;
+  if ((reinterpret_cast<uintptr_t>(A_s) & 15u) || (reinterpret_cast<uintptr_t>(W_s) & 15u)) return hipErrorInvalidValue;
+  switch (skip) {
+#define TORQ_ABLATE(S_) \
+  case S_: return launch_tile<4, 4, true, false, false, S_>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream);
+    TORQ_ABLATE(0) TORQ_ABLATE(1) TORQ_ABLATE(3) TORQ_ABLATE(4) TORQ_ABLATE(7) TORQ_ABLATE(15)
+#undef TORQ_ABLATE
+    default: return hipErrorInvalidValue;
+  }
 }
 
 }  // namespace torq

@@ -71,7 +71,11 @@ rotate_kernel(const uint4 *__restrict__ x, int64_t TG, int G,
 // waves per SIMD from G = 64 up as it is).
 // TB: token-groups per batch, processed together (2: every MFMA has an independent neighbour; 1 for a
 // handful of token-groups, where the shortest path through one token-group counts).
-template <int KS16, int TB, int FMT>
+// SKIP (diagnostic builds only, torq_diag_rotate_ablation): work left out to measure what it costs --
+// 1: the R_inter low-part pass, 2: the hi/lo split of Y on the vector ALU (raw register pairs are fed
+// instead), 4: the amax and the conversion of step 4 (bit patterns are stored instead), 8: two of the
+// three R_intra passes.  The output is then meaningless.  SKIP = 0 is the product.
+template <int KS16, int TB, int FMT, int SKIP = 0>
 __global__ void __launch_bounds__(64 * ((KS16 + 1) / 2), (KS16 >= 4 && KS16 <= 8) ? 3 : 2)   // waves per SIMD
 rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
                 const uint16_t *__restrict__ inter_hi, const uint16_t *__restrict__ inter_lo,
@@ -209,7 +213,7 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
         acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[j], Bh[ks], acc[j], 0, 0, 0);
 #pragma unroll
       for (int j = 0; j < TB; ++j)
-        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[j], Bl[ks], acc[j], 0, 0, 0);
+        if constexpr (!(SKIP & 1)) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[j], Bl[ks], acc[j], 0, 0, 0);
     }
 
     if constexpr (DMA) {
@@ -231,8 +235,13 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
 #pragma unroll
         for (int p = 0; p < 4; ++p) {
           const float y0 = acc[j][8 * t + 2 * p], y1 = acc[j][8 * t + 2 * p + 1];
-          hi[p] = pack_bf16_rne(y0, y1);
-          lo[p] = pack_bf16_rne(y0 - __uint_as_float(hi[p] << 16), y1 - __uint_as_float(hi[p] & 0xFFFF0000u));
+          if constexpr ((SKIP & 2) != 0) {
+            hi[p] = __float_as_uint(y0);
+            lo[p] = __float_as_uint(y1);
+          } else {
+            hi[p] = pack_bf16_rne(y0, y1);
+            lo[p] = pack_bf16_rne(y0 - __uint_as_float(hi[p] << 16), y1 - __uint_as_float(hi[p] & 0xFFFF0000u));
+          }
         }
         yh[j][t] = __builtin_bit_cast(bf16x8, i32x4{(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]});
         yl[j][t] = __builtin_bit_cast(bf16x8, i32x4{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]});
@@ -243,11 +252,13 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
 #pragma unroll
     for (int t = 0; t < 2; ++t) {
 #pragma unroll
-      for (int j = 0; j < TB; ++j) zacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Al[t], yh[j][t], zacc[j], 0, 0, 0);
+      for (int j = 0; j < TB; ++j)
+        if constexpr (!(SKIP & 8)) zacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Al[t], yh[j][t], zacc[j], 0, 0, 0);
 #pragma unroll
       for (int j = 0; j < TB; ++j) zacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[t], yl[j][t], zacc[j], 0, 0, 0);
 #pragma unroll
-      for (int j = 0; j < TB; ++j) zacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[t], yh[j][t], zacc[j], 0, 0, 0);
+      for (int j = 0; j < TB; ++j)
+        if constexpr (!(SKIP & 8)) zacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[t], yh[j][t], zacc[j], 0, 0, 0);
     }
 
 #pragma unroll
@@ -268,6 +279,15 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
             codes[blkidx * 2 + h] = make_uint2(pack8_nvfp4(zz, S), pack8_nvfp4(zz + 8, S));
             scales[blkidx * 2 + h] = (uint8_t)sc;
           }
+        } else if constexpr ((SKIP & 4) != 0) {
+          uint32_t c0 = 0, c1 = 0;
+#pragma unroll
+          for (int r = 0; r < 8; ++r) {
+            c0 ^= __float_as_uint(zz[r]);
+            c1 ^= __float_as_uint(zz[8 + r]);
+          }
+          if (live) codes[blkidx * 2 + h] = make_uint2(c0, c1);
+          if (h == 0 && live) scales[blkidx] = (uint8_t)(c0 >> 23);
         } else if constexpr (FMT != FMT_NONE) {
           float amax = fmaxf(amax8(zz), amax8(zz + 8));
           // max with the other half-wave (lane ^ 32): swap the upper half of one copy with the
@@ -401,6 +421,30 @@ hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, 
 #undef TORQ_CASE
   }
   return hipErrorInvalidValue;
+}
+
+// torq_diag_rotate_ablation: rotate_kernel32<8, 2, MXFP4> (G = 128) with work left out (see SKIP above),
+// in the launch shape of the product (three workgroups per CU).
+hipError_t launch_rotate_ablated(const torq_rotation *r, const void *x, int64_t M, uint8_t *codes, uint8_t *scales,
+                                 int skip, hipStream_t stream) {
+  if (r->G != 128 || r->butterfly) return hipErrorInvalidValue;
+  const int64_t TG = M * (int64_t)(r->d / 32 / 128);
+  if (TG == 0) return hipSuccess;
+  const int64_t nbatch = (TG + 1) / 2;
+  const unsigned grid = (unsigned)(nbatch < 768 ? nbatch : 768);
+  const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi), *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
+  switch (skip) {
+#define TORQ_ABLATE(S_)                                                                                             \
+  case S_:                                                                                                          \
+    hipLaunchKernelGGL((rotate_kernel32<8, 2, FMT_MXFP4, S_>), dim3(grid), dim3(256), 32768, stream,                 \
+                       reinterpret_cast<const uint4 *>(x), TG, 128, r->inter_hi, r->inter_lo, ih, il,                \
+                       reinterpret_cast<uint2 *>(codes), scales, (float *)nullptr, 1.0f);                            \
+    break;
+    TORQ_ABLATE(0) TORQ_ABLATE(1) TORQ_ABLATE(2) TORQ_ABLATE(4) TORQ_ABLATE(6) TORQ_ABLATE(8) TORQ_ABLATE(9) TORQ_ABLATE(15)
+#undef TORQ_ABLATE
+    default: return hipErrorInvalidValue;
+  }
+  return hipGetLastError();
 }
 
 }  // namespace torq

@@ -93,4 +93,13 @@ void intra_rotation(const float *X, int64_t n, int max_iter, int k_top, int P, d
 hipError_t launch_mfma_burn(int kind, const uint32_t *words, uint32_t n_words, int iters, float *sink,
                             hipStream_t stream);
 
+// The two headline kernels with parts of their work left out (SKIP bits documented at the kernels):
+// what each part costs in time on this machine.  Outputs are meaningless by design.
+hipError_t launch_mxfp4_gemm_ablated(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                                     void *out_bf16, int64_t M, int64_t N, int d, int skip, hipStream_t stream);
+hipError_t launch_rotate_ablated(const torq_rotation *r, const void *x, int64_t M, uint8_t *codes, uint8_t *scales,
+                                 int skip, hipStream_t stream);
+// plain copy of `bytes` (a multiple of 16) device bytes, the traffic counters' yardstick (diag.hip)
+hipError_t launch_diag_copy(const void *src, void *dst, size_t bytes, hipStream_t stream);
+
 }  // namespace torq

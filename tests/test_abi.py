@@ -76,6 +76,13 @@ def test_compute_calls_reject_bad_arguments_without_launching():
     assert L.torq_diag_mfma_burn(0, good, 64, 4, good, None) == binding.TORQ_EINVAL            # too few operand bytes
     assert L.torq_diag_mfma_burn(1, good, 4096, 0, good, None) == binding.TORQ_EINVAL
     assert L.torq_diag_mfma_burn(1, odd2, 4096, 4, good, None) == binding.TORQ_EALIGN
+    assert L.torq_diag_copy(good, good, 100, None) == binding.TORQ_EINVAL                      # not a multiple of 16
+    assert L.torq_diag_copy(None, good, 160, None) == binding.TORQ_EINVAL
+    assert L.torq_diag_copy(odd, good, 160, None) == binding.TORQ_EALIGN
+    assert L.torq_diag_gemm_ablation(good, good, good, good, good, 256, 256, 768, 0, None) == binding.TORQ_EINVAL   # d % 512
+    assert L.torq_diag_gemm_ablation(good, good, good, good, good, 256, 256, 1024, 2, None) == binding.TORQ_EINVAL  # unknown skip
+    assert L.torq_diag_gemm_ablation(good, odd, good, good, good, 256, 256, 1024, 0, None) == binding.TORQ_EALIGN
+    assert L.torq_diag_rotate_ablation(None, good, 4, good, good, 0, None) == binding.TORQ_EINVAL
 
 
 def test_workspace_size():
