@@ -20,9 +20,20 @@ FLAGS = ["-O3", "-std=c++17", "-fPIC", "--offload-arch=gfx950",
 
 # The rotate kernel post-processes its MFMA results with vector ALU code, so its accumulators are
 # kept in ordinary VGPRs (no v_accvgpr_read traffic); the GEMM needs the AGPR half for its tile.
-EXTRA = {"rotate_quant.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+# rotate_quant.hip writes m0 in inline assembly (the LDS address of a buffer load into LDS) and says so in the
+# clobber list; the compiler warns about every such statement, since it reserves m0 for itself -- nothing
+# else in that kernel uses it.
+EXTRA = {"rotate_quant.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-Wno-inline-asm"],
          "rotate_butterfly.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
          "mxfp4_gemm_skinny.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]}
+
+
+def device_asm(source: str, out_path: str) -> str:
+    """Compile one source to gfx950 assembly text with the flags of the build (for the build test that
+    counts the memory instructions of a hand-scheduled loop)."""
+    cmd = [HIPCC, *FLAGS, *EXTRA.get(source, []), "--cuda-device-only", "-S", os.path.join(CSRC, source), "-o", out_path]
+    subprocess.run(cmd, check=True, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
+    return out_path
 
 
 def build(verbose: bool = False) -> str:

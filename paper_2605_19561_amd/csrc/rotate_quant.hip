@@ -27,6 +27,8 @@
 // LDS (double-buffered, one barrier per batch) and each wave fetches its A
 // operands with ds_read_b64_tr_b16, which performs the (k, b') transpose that
 // the row-major input needs.
+#include <utility>
+
 #include "rotate16_body.h"
 #include "torq_device.h"
 #include "torq_internal.h"
@@ -71,11 +73,7 @@ rotate_kernel(const uint4 *__restrict__ x, int64_t TG, int G,
 // waves per SIMD from G = 64 up as it is).
 // TB: token-groups per batch, processed together (2: every MFMA has an independent neighbour; 1 for a
 // handful of token-groups, where the shortest path through one token-group counts).
-// SKIP (diagnostic builds only, torq_diag_rotate_ablation): work left out to measure what it costs --
-// 1: the R_inter low-part pass, 2: the hi/lo split of Y on the vector ALU (raw register pairs are fed
-// instead), 4: the amax and the conversion of step 4 (bit patterns are stored instead), 8: two of the
-// three R_intra passes.  The output is then meaningless.  SKIP = 0 is the product.
-template <int KS16, int TB, int FMT, int SKIP = 0>
+template <int KS16, int TB, int FMT>
 __global__ void __launch_bounds__(64 * ((KS16 + 1) / 2), (KS16 >= 4 && KS16 <= 8) ? 3 : 2)   // waves per SIMD
 rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
                 const uint16_t *__restrict__ inter_hi, const uint16_t *__restrict__ inter_lo,
@@ -213,7 +211,7 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
         acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[j], Bh[ks], acc[j], 0, 0, 0);
 #pragma unroll
       for (int j = 0; j < TB; ++j)
-        if constexpr (!(SKIP & 1)) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[j], Bl[ks], acc[j], 0, 0, 0);
+        acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[j], Bl[ks], acc[j], 0, 0, 0);
     }
 
     if constexpr (DMA) {
@@ -225,6 +223,239 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
     }
 
     // ---- step 3: Z^T = R_intra^T Y^T with Y split into bf16 hi + lo; then step 4
+    f32x16 zacc[TB];
+    bf16x8 yh[TB][2], yl[TB][2];
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int p = 0; p < 4; ++p) {
+          const float y0 = acc[j][8 * t + 2 * p], y1 = acc[j][8 * t + 2 * p + 1];
+          hi[p] = pack_bf16_rne(y0, y1);
+          lo[p] = pack_bf16_rne(y0 - __uint_as_float(hi[p] << 16), y1 - __uint_as_float(hi[p] & 0xFFFF0000u));
+        }
+        yh[j][t] = __builtin_bit_cast(bf16x8, i32x4{(int)hi[0], (int)hi[1], (int)hi[2], (int)hi[3]});
+        yl[j][t] = __builtin_bit_cast(bf16x8, i32x4{(int)lo[0], (int)lo[1], (int)lo[2], (int)lo[3]});
+      }
+#pragma unroll
+      for (int r = 0; r < 16; ++r) zacc[j][r] = 0.f;
+    }
+#pragma unroll
+    for (int t = 0; t < 2; ++t) {
+#pragma unroll
+      for (int j = 0; j < TB; ++j) zacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Al[t], yh[j][t], zacc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TB; ++j) zacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[t], yl[j][t], zacc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TB; ++j) zacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[t], yh[j][t], zacc[j], 0, 0, 0);
+    }
+
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+      const int64_t tg = batch * TB + j;
+      if (tg < TG) {                                            // uniform over the workgroup
+        const int64_t blkidx = tg * G + 32 * wave + col;        // global block index
+        const bool live = !ODD || 32 * wave + col < 16 * KS16;  // a block row that exists
+        float zz[16];
+#pragma unroll
+        for (int r = 0; r < 16; ++r) zz[r] = zacc[j][r];
+        if constexpr (FMT == FMT_NVFP4) {
+          // the lane's sixteen values are one 16-element block: no cross-lane step
+          const float amax = fmaxf(amax8(zz), amax8(zz + 8));
+          const uint32_t sc = e4m3_from_f32(__fdiv_rn(amax, 6.0f * global_scale));
+          const float S = e4m3_to_f32(sc) * global_scale;
+          if (live) {
+            codes[blkidx * 2 + h] = make_uint2(pack8_nvfp4(zz, S), pack8_nvfp4(zz + 8, S));
+            scales[blkidx * 2 + h] = (uint8_t)sc;
+          }
+        } else if constexpr (FMT != FMT_NONE) {
+          float amax = fmaxf(amax8(zz), amax8(zz + 8));
+          // max with the other half-wave (lane ^ 32): swap the upper half of one copy with the
+          // lower half of the other, then every lane holds both partners' values
+          const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(amax), __float_as_uint(amax), false, false);
+          amax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+          const uint32_t byte = e8m0_from_amax(amax);
+          if constexpr (FMT == FMT_MXINT4) {
+            const float inv = e8m0_inverse_f32(byte);
+            if (live) codes[blkidx * 2 + h] = make_uint2(pack8_int4(zz, inv), pack8_int4(zz + 8, inv));
+          } else {
+            const float sc = e8m0_to_f32(byte);
+            if (live) codes[blkidx * 2 + h] = make_uint2(pack8_e2m1(zz, sc), pack8_e2m1(zz + 8, sc));
+          }
+          if (h == 0 && live) scales[blkidx] = (uint8_t)byte;
+        } else {
+          float4 *o = reinterpret_cast<float4 *>(z_out + blkidx * 32 + 16 * h);
+          if (live) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) o[q] = make_float4(zz[4 * q], zz[4 * q + 1], zz[4 * q + 2], zz[4 * q + 3]);
+          }
+        }
+      }
+    }
+
+    if constexpr (!DMA) {
+      if (have_next) store_batch(buf ^ 1);
+      __syncthreads();
+    }
+  }
+}
+
+// ---------------------------------------------------------------------------
+// The same kernel for G = 96, 112, 128 with THREE LDS buffers, filled two batches ahead (quantising
+// formats only; the fp32 output of torq_rotate stays with rotate_kernel32).  With two buffers the next
+// batch can only be requested once every wave has read the current one, which leaves the request about a
+// third of an iteration to land; with three it is requested a whole iteration earlier, at the top of the
+// iteration before.  Measured against the two-buffer form, same machine: 3 - 5 % (51.5 -> 49.0 us at
+// X [8192, 8192], 311 -> 301 us at [16384, 28672]) -- the kernel runs at the board's power limit, so
+// removing stalls buys little; it is kept because it costs nothing else.
+//
+// Two things are issued from assembly because of how the compiler orders LDS traffic: it places every LDS
+// read it recognises behind ALL outstanding loads into LDS (vmcnt(0)), which would undo the ring.  So
+// the loads into LDS (dma16) and the transposing reads (lds_tr_read) are invisible to it, and the waits
+// are written by hand:
+//   * LDS reads: lds_wait4 (lgkmcnt(0)) in front of the MFMAs that consume them; the next k-step's four
+//     reads are issued right after it and have the MFMAs of this k-step to land.
+//   * loads into LDS: every wave issues exactly PER_ITER_LD = TB * CH of them at the top of an iteration
+//     and exactly PER_ITER_ST = 2 * TB buffer stores at its end, whatever the batch (a token-group past
+//     the end gets empty descriptors: its loads return zeros, its stores are dropped; lanes without a
+//     block store to an out-of-range offset).  Vector-memory operations of a wave complete in order, so
+//     "at most PER_ITER_LD + 2 * PER_ITER_ST operations outstanding" means the batch requested two
+//     iterations ago has landed.  No other vector-memory instruction may appear in the loop: the build
+//     test tests/test_kernel_isa.py counts them in the compiled code.
+// SKIP (diagnostic builds only, torq_diag_rotate_ablation): work left out to measure what it costs --
+// 1: the R_inter low-part pass, 2: the hi/lo split of Y on the vector ALU (raw register pairs are fed
+// instead), 4: the amax and the conversion of step 4 (bit patterns are stored instead), 8: two of the
+// three R_intra passes.  The output is then meaningless.  SKIP = 0 is the product.
+template <class F, int... I>
+__device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, I...>) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+  static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+template <int OFF>
+__device__ __forceinline__ i16x4 lds_tr_read(uint32_t addr) {
+  i16x4 v;
+  asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFF) : "memory");
+  return v;
+}
+__device__ __forceinline__ void lds_wait4(i16x4 &a, i16x4 &b, i16x4 &c, i16x4 &d) {
+  asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(a), "+v"(b), "+v"(c), "+v"(d));
+}
+// 16 bytes per lane from a buffer straight into LDS at lds_addr + 16 * lane (lds_addr wave-uniform)
+__device__ __forceinline__ void dma16(i32x4 rsrc, uint32_t lds_addr, uint32_t voff, uint32_t soff) {
+  asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+               :: "s"(lds_addr), "v"(voff), "s"(rsrc), "s"(soff) : "memory", "m0");
+}
+typedef __attribute__((__vector_size__(2 * sizeof(unsigned)))) unsigned u32x2;
+
+template <int KS16, int FMT, int SKIP = 0>
+__global__ void __launch_bounds__(64 * ((KS16 + 1) / 2), 3)
+rotate_ring_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
+                     const uint16_t *__restrict__ inter_hi, const uint16_t *__restrict__ inter_lo,
+                     const uint4 *__restrict__ intra_hi_frag, const uint4 *__restrict__ intra_lo_frag,
+                     uint8_t *__restrict__ codes, uint8_t *__restrict__ scales, float global_scale) {
+  static_assert(FMT != FMT_NONE, "quantising formats only");
+  constexpr int TB = 2;
+  constexpr int NW = (KS16 + 1) / 2;
+  constexpr bool ODD = (KS16 & 1) != 0;
+  constexpr int TG_BYTES = KS16 * 16 * 64;
+  constexpr int NTHR = 64 * NW;
+  constexpr int CHUNKS = TG_BYTES / 16;
+  constexpr int CH = (CHUNKS + NTHR - 1) / NTHR;
+  constexpr int TG_STRIDE = CH * NTHR * 16;          // a token-group's place in LDS (= TG_BYTES unless KS16 is odd)
+  constexpr int STAGE_BYTES = TB * TG_STRIDE;
+  constexpr int OOB = 0x7FFFFFF0;                    // beyond every descriptor: loads give zero, stores are dropped
+  // three separate arrays: the stages are distinct objects
+  __shared__ __attribute__((aligned(16))) char stage0[STAGE_BYTES];
+  __shared__ __attribute__((aligned(16))) char stage1[STAGE_BYTES];
+  __shared__ __attribute__((aligned(16))) char stage2[STAGE_BYTES];
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63, wave = tid >> 6;
+  const int col = lane & 31, h = lane >> 5;
+  const int b = 32 * wave + col;                     // this lane's block row inside a token-group
+  const bool live = !ODD || b < 16 * KS16;
+
+  bf16x8 Bh[KS16], Bl[KS16];
+#pragma unroll
+  for (int ks = 0; ks < KS16; ++ks) {
+    const size_t off = (size_t)(live ? b : 0) * (32 * NW) + 16 * ks + 8 * h;
+    Bh[ks] = *reinterpret_cast<const bf16x8 *>(inter_hi + off);
+    Bl[ks] = *reinterpret_cast<const bf16x8 *>(inter_lo + off);
+    if (ODD && !live) Bh[ks] = Bl[ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+  }
+  bf16x8 Ah[2], Al[2];
+#pragma unroll
+  for (int t = 0; t < 2; ++t) {
+    Ah[t] = __builtin_bit_cast(bf16x8, intra_hi_frag[t * 64 + lane]);
+    Al[t] = __builtin_bit_cast(bf16x8, intra_lo_frag[t * 64 + lane]);
+  }
+  const int blk = lane >> 4, s16 = lane & 15;
+  const int tr_off = ((8 * (blk >> 1) + (s16 >> 2)) * 32 + 16 * (blk & 1) + 4 * (s16 & 3)) * 2;
+  const int64_t nbatch = (TG + TB - 1) / TB;
+  const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+  // bytes of scales per token-group, and where this lane's scale byte goes in them
+  constexpr int SC_PER_BLK = FMT == FMT_NVFP4 ? 2 : 1;
+  const int sc_off = FMT == FMT_NVFP4 ? (live ? b * 2 + h : OOB) : ((live && h == 0) ? b : OOB);
+  const int cd_off = live ? (b * 2 + h) * 8 : OOB;
+
+  auto dma = [&](int64_t b_, char *dst) {
+#pragma unroll
+    for (int j = 0; j < TB; ++j) {
+      const int64_t tg = b_ * TB + j;
+      const bool ok = b_ < nbatch && tg < TG;
+      const uint64_t base = reinterpret_cast<uint64_t>(x) + (uint64_t)((ok ? tg : 0) * (int64_t)TG_BYTES);
+      const i32x4 rs = i32x4{(int)(uint32_t)base, (int)((uint32_t)(base >> 32) & 0xFFFFu), ok ? TG_BYTES : 0, 0x00020000};
+      const uint32_t la = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) char *)(dst) + j * TG_STRIDE + wave_u * 64 * 16;
+#pragma unroll
+      for (int i = 0; i < CH; ++i) dma16(rs, la + i * NTHR * 16, tid * 16, i * NTHR * 16);
+    }
+  };
+
+  auto compute = [&](int64_t batch, const char *stage_base) {
+    // ---- step 2
+    f32x16 acc[TB];
+#pragma unroll
+    for (int j = 0; j < TB; ++j)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[j][r] = 0.f;
+    const uint32_t sa = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) const char *)(stage_base) + tr_off;
+    i16x4 q[2][4];
+    q[0][0] = lds_tr_read<0>(sa);
+    q[0][1] = lds_tr_read<256>(sa);
+    q[0][2] = lds_tr_read<TG_STRIDE>(sa);
+    q[0][3] = lds_tr_read<TG_STRIDE + 256>(sa);
+    static_for<KS16>([&](auto ks_c) {
+      constexpr int ks = decltype(ks_c)::value;
+      constexpr int cur = ks & 1, nxt = cur ^ 1;
+      lds_wait4(q[cur][0], q[cur][1], q[cur][2], q[cur][3]);
+      if constexpr (ks + 1 < KS16) {
+        q[nxt][0] = lds_tr_read<(ks + 1) * 1024>(sa);
+        q[nxt][1] = lds_tr_read<(ks + 1) * 1024 + 256>(sa);
+        q[nxt][2] = lds_tr_read<TG_STRIDE + (ks + 1) * 1024>(sa);
+        q[nxt][3] = lds_tr_read<TG_STRIDE + (ks + 1) * 1024 + 256>(sa);
+      }
+      bf16x8 xa[TB];
+#pragma unroll
+      for (int j = 0; j < TB; ++j) {
+        union { bf16x8 v; i16x4 h2[2]; } u;
+        u.h2[0] = q[cur][2 * j];
+        u.h2[1] = q[cur][2 * j + 1];
+        xa[j] = u.v;
+      }
+#pragma unroll
+      for (int j = 0; j < TB; ++j) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[j], Bh[ks], acc[j], 0, 0, 0);
+#pragma unroll
+      for (int j = 0; j < TB; ++j)
+        if constexpr (!(SKIP & 1)) acc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(xa[j], Bl[ks], acc[j], 0, 0, 0);
+    });
+
+    // ---- step 3
     f32x16 zacc[TB];
     bf16x8 yh[TB][2], yl[TB][2];
 #pragma unroll
@@ -261,63 +492,84 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
         if constexpr (!(SKIP & 8)) zacc[j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(Ah[t], yh[j][t], zacc[j], 0, 0, 0);
     }
 
+    // ---- step 4 and the two stores of each token-group
 #pragma unroll
     for (int j = 0; j < TB; ++j) {
       const int64_t tg = batch * TB + j;
-      if (tg < TG) {                                            // uniform over the workgroup
-        const int64_t blkidx = tg * G + 32 * wave + col;        // global block index
-        const bool live = !ODD || 32 * wave + col < 16 * KS16;  // a block row that exists
-        float zz[16];
+      const bool ok = tg < TG;
+      float zz[16];
 #pragma unroll
-        for (int r = 0; r < 16; ++r) zz[r] = zacc[j][r];
-        if constexpr (FMT == FMT_NVFP4) {
-          // the lane's sixteen values are one 16-element block: no cross-lane step
-          const float amax = fmaxf(amax8(zz), amax8(zz + 8));
-          const uint32_t sc = e4m3_from_f32(__fdiv_rn(amax, 6.0f * global_scale));
-          const float S = e4m3_to_f32(sc) * global_scale;
-          if (live) {
-            codes[blkidx * 2 + h] = make_uint2(pack8_nvfp4(zz, S), pack8_nvfp4(zz + 8, S));
-            scales[blkidx * 2 + h] = (uint8_t)sc;
-          }
-        } else if constexpr ((SKIP & 4) != 0) {
-          uint32_t c0 = 0, c1 = 0;
+      for (int r = 0; r < 16; ++r) zz[r] = zacc[j][r];
+      u32x2 c;
+      uint32_t byte;
+      if constexpr ((SKIP & 4) != 0) {
+        uint32_t c0 = 0, c1 = 0;
 #pragma unroll
-          for (int r = 0; r < 8; ++r) {
-            c0 ^= __float_as_uint(zz[r]);
-            c1 ^= __float_as_uint(zz[8 + r]);
-          }
-          if (live) codes[blkidx * 2 + h] = make_uint2(c0, c1);
-          if (h == 0 && live) scales[blkidx] = (uint8_t)(c0 >> 23);
-        } else if constexpr (FMT != FMT_NONE) {
-          float amax = fmaxf(amax8(zz), amax8(zz + 8));
-          // max with the other half-wave (lane ^ 32): swap the upper half of one copy with the
-          // lower half of the other, then every lane holds both partners' values
-          const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(amax), __float_as_uint(amax), false, false);
-          amax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-          const uint32_t byte = e8m0_from_amax(amax);
-          if constexpr (FMT == FMT_MXINT4) {
-            const float inv = e8m0_inverse_f32(byte);
-            if (live) codes[blkidx * 2 + h] = make_uint2(pack8_int4(zz, inv), pack8_int4(zz + 8, inv));
-          } else {
-            const float sc = e8m0_to_f32(byte);
-            if (live) codes[blkidx * 2 + h] = make_uint2(pack8_e2m1(zz, sc), pack8_e2m1(zz + 8, sc));
-          }
-          if (h == 0 && live) scales[blkidx] = (uint8_t)byte;
+        for (int r = 0; r < 8; ++r) {
+          c0 ^= __float_as_uint(zz[r]);
+          c1 ^= __float_as_uint(zz[8 + r]);
+        }
+        c = u32x2{c0, c1};
+        byte = c0 >> 23;
+      } else if constexpr (FMT == FMT_NVFP4) {
+        const float amax = fmaxf(amax8(zz), amax8(zz + 8));
+        byte = e4m3_from_f32(__fdiv_rn(amax, 6.0f * global_scale));
+        const float S = e4m3_to_f32(byte) * global_scale;
+        c = u32x2{pack8_nvfp4(zz, S), pack8_nvfp4(zz + 8, S)};
+      } else {
+        float amax = fmaxf(amax8(zz), amax8(zz + 8));
+        const auto sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(amax), __float_as_uint(amax), false, false);
+        amax = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+        byte = e8m0_from_amax(amax);
+        if constexpr (FMT == FMT_MXINT4) {
+          const float inv = e8m0_inverse_f32(byte);
+          c = u32x2{pack8_int4(zz, inv), pack8_int4(zz + 8, inv)};
         } else {
-          float4 *o = reinterpret_cast<float4 *>(z_out + blkidx * 32 + 16 * h);
-          if (live) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) o[q] = make_float4(zz[4 * q], zz[4 * q + 1], zz[4 * q + 2], zz[4 * q + 3]);
-          }
+          const float sc = e8m0_to_f32(byte);
+          c = u32x2{pack8_e2m1(zz, sc), pack8_e2m1(zz + 8, sc)};
         }
       }
+      const __amdgpu_buffer_rsrc_t crs = __builtin_amdgcn_make_buffer_rsrc(
+          codes + (ok ? tg : 0) * (int64_t)(G * 16), 0, ok ? G * 16 : 0, 0x00020000);
+      const __amdgpu_buffer_rsrc_t srs = __builtin_amdgcn_make_buffer_rsrc(
+          scales + (ok ? tg : 0) * (int64_t)(G * SC_PER_BLK), 0, ok ? G * SC_PER_BLK : 0, 0x00020000);
+      __builtin_amdgcn_raw_buffer_store_b64(c, crs, cd_off, 0, 0);
+      __builtin_amdgcn_raw_buffer_store_b8((unsigned char)byte, srs, sc_off, 0, 0);
     }
+  };
 
-    if constexpr (!DMA) {
-      if (have_next) store_batch(buf ^ 1);
-      __syncthreads();
-    }
+  const int64_t stride = gridDim.x;
+  int64_t batch = blockIdx.x;
+  if (batch >= nbatch) return;                       // uniform over the workgroup; before any barrier
+  dma(batch, stage0);
+  dma(batch + stride, stage1);
+  // The resident operands above are ordinary loads; waiting for them here, once, leaves the compiler
+  // nothing to wait for inside the loop (its own wait would come out as vmcnt(0): it does not see the
+  // requests above, which are younger).  The first two batches land with them.
+  __builtin_amdgcn_s_waitcnt(0x0F70);
+  constexpr int PER_ITER_LD = TB * CH, PER_ITER_ST = 2 * TB;
+  static_assert(PER_ITER_LD + 2 * PER_ITER_ST <= 15, "the wait below encodes its count in four bits");
+  int it = 0;
+  // s_waitcnt with vmcnt = N (low four bits), no wait on the other counters
+#define TORQ_RING_ITER(CUR_, FREE_)                                                                 \
+  {                                                                                                 \
+    if (it == 0) __builtin_amdgcn_s_waitcnt(0x0F70 | PER_ITER_LD);                                  \
+    else if (it == 1) __builtin_amdgcn_s_waitcnt(0x0F70 | (PER_ITER_LD + PER_ITER_ST));             \
+    else __builtin_amdgcn_s_waitcnt(0x0F70 | (PER_ITER_LD + 2 * PER_ITER_ST));                      \
+    __syncthreads();           /* everybody's part of this batch has landed; FREE_ has been read */ \
+    dma(batch + 2 * stride, FREE_);                                                                 \
+    compute(batch, CUR_);                                                                           \
+    batch += stride;                                                                                \
+    ++it;                                                                                           \
+    if (batch >= nbatch) break;                                                                     \
   }
+  for (;;) {
+    TORQ_RING_ITER(stage0, stage2)
+    TORQ_RING_ITER(stage1, stage0)
+    TORQ_RING_ITER(stage2, stage1)
+  }
+#undef TORQ_RING_ITER
+  __builtin_amdgcn_s_waitcnt(0x0F70);                // nothing of this wave's is in flight when it ends
 }
 
 // launch KERNEL_<..., FMT> for the runtime format (FMT_NONE when the fp32 output is asked for)
@@ -347,6 +599,15 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
   }                                                                                                             \
   return hipGetLastError();
 
+// Persistent workgroups: `per_cu` of them on each of the 256 CUs; with fewer than a few rounds of
+// batches the grid is cut to ceil(nbatch / rounds) so that every workgroup gets the same number.
+static int64_t balanced_grid(int64_t nbatch, int per_cu) {
+  const int64_t slots = (int64_t)per_cu * 256;
+  if (nbatch <= slots) return nbatch;
+  const int64_t rounds = (nbatch + slots - 1) / slots;
+  return (nbatch + rounds - 1) / rounds;
+}
+
 template <int KS16, int TB = 2>
 static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG, int format, float global_scale,
                                uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
@@ -361,11 +622,31 @@ static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG
   int per_cu = (int)((160 * 1024) / lds_bytes);
   if (per_cu * nw > waves_per_cu) per_cu = waves_per_cu / nw;
   if (per_cu < 1) per_cu = 1;
-  int64_t grid = (int64_t)per_cu * 256;
-  if (grid > nbatch) grid = nbatch;
+  const int64_t grid = balanced_grid(nbatch, per_cu);
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
   TORQ_LAUNCH_FMT(rotate_kernel32, uint2, KS16, TB)
+}
+
+template <int KS16>
+static hipError_t launch_ring32(const torq_rotation *r, const void *x, int64_t TG, int format, float global_scale,
+                                uint8_t *codes, uint8_t *scales, hipStream_t stream) {
+  const int nw = (KS16 + 1) / 2;
+  const int64_t nbatch = (TG + 1) / 2;
+  const int64_t grid = balanced_grid(nbatch, 3);     // 3 x <= 48 KiB of LDS, 12 waves of <= 160 registers
+  const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
+  const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
+#define TORQ_RING_LAUNCH(FMT_, GS_)                                                                                  \
+  hipLaunchKernelGGL((rotate_ring_kernel32<KS16, FMT_>), dim3((unsigned)grid), dim3(64 * nw), 0, stream,               \
+                     reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il, codes, scales, GS_)
+  switch (format) {
+    case FMT_MXFP4: TORQ_RING_LAUNCH(FMT_MXFP4, 1.0f); break;
+    case FMT_MXINT4: TORQ_RING_LAUNCH(FMT_MXINT4, 1.0f); break;
+    case FMT_NVFP4: TORQ_RING_LAUNCH(FMT_NVFP4, global_scale); break;
+    default: return hipErrorInvalidValue;
+  }
+#undef TORQ_RING_LAUNCH
+  return hipGetLastError();
 }
 
 template <int KS, int NT>
@@ -400,6 +681,12 @@ hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, 
   // a handful of token-groups at G = 128 or 112 (decode): one per workgroup
   if (r->G == 128 && TG <= 128) return launch_cfg32<8, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
   if (r->G == 112 && TG <= 128) return launch_cfg32<7, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
+  // quantising, G = 96, 112, 128: the three-buffer form of the 32x32x16 kernel
+  if (!z_out) {
+    if (r->G == 128) return launch_ring32<8>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
+    if (r->G == 112) return launch_ring32<7>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
+    if (r->G == 96) return launch_ring32<6>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
+  }
   // G a multiple of 32, or 16 * odd from 80 up: the 32x32x16 kernel (with a half-empty last tile).
   // Measured on X [16384, d] against the 16x16x32 kernel: G = 112 gains 7 - 9 %, G = 80 3 - 7 % (at
   // three waves per SIMD; at two it lost 3 - 4 %).
@@ -423,22 +710,21 @@ hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, 
   return hipErrorInvalidValue;
 }
 
-// torq_diag_rotate_ablation: rotate_kernel32<8, 2, MXFP4> (G = 128) with work left out (see SKIP above),
-// in the launch shape of the product (three workgroups per CU).
+// torq_diag_rotate_ablation: rotate_ring_kernel32<8, MXFP4> (G = 128) with work left out (see SKIP there),
+// in the launch shape of the product.
 hipError_t launch_rotate_ablated(const torq_rotation *r, const void *x, int64_t M, uint8_t *codes, uint8_t *scales,
                                  int skip, hipStream_t stream) {
   if (r->G != 128 || r->butterfly) return hipErrorInvalidValue;
   const int64_t TG = M * (int64_t)(r->d / 32 / 128);
   if (TG == 0) return hipSuccess;
-  const int64_t nbatch = (TG + 1) / 2;
-  const unsigned grid = (unsigned)(nbatch < 768 ? nbatch : 768);
+  const int64_t grid = balanced_grid((TG + 1) / 2, 3);
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi), *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
   switch (skip) {
 #define TORQ_ABLATE(S_)                                                                                             \
   case S_:                                                                                                          \
-    hipLaunchKernelGGL((rotate_kernel32<8, 2, FMT_MXFP4, S_>), dim3(grid), dim3(256), 32768, stream,                 \
-                       reinterpret_cast<const uint4 *>(x), TG, 128, r->inter_hi, r->inter_lo, ih, il,                \
-                       reinterpret_cast<uint2 *>(codes), scales, (float *)nullptr, 1.0f);                            \
+    hipLaunchKernelGGL((rotate_ring_kernel32<8, FMT_MXFP4, S_>), dim3((unsigned)grid), dim3(256), 0, stream,         \
+                       reinterpret_cast<const uint4 *>(x), TG, 128, r->inter_hi, r->inter_lo, ih, il, codes, scales, \
+                       1.0f);                                                                                       \
     break;
     TORQ_ABLATE(0) TORQ_ABLATE(1) TORQ_ABLATE(2) TORQ_ABLATE(4) TORQ_ABLATE(6) TORQ_ABLATE(8) TORQ_ABLATE(9) TORQ_ABLATE(15)
 #undef TORQ_ABLATE

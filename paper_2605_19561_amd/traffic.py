@@ -32,7 +32,7 @@ COPY_BYTES = 1 << 30
 KERNELS = {
     "mxfp4_gemm/llama3_70b_up": ("torq::mxfp4_gemm_kernel<4,4,true,false,false,0>", 32 * 112 * 256,
                                  ["mxfp4_gemm.hip", "torq_device.h"]),
-    "torq_rotate_quantize/llama3_70b_up": ("torq::rotate_kernel32<8,2,0,0>", 768 * 256,
+    "torq_rotate_quantize/llama3_70b_up": ("torq::rotate_ring_kernel32<8,0,0>", 745 * 256,
                                            ["rotate_quant.hip", "rotate16_body.h", "torq_device.h"]),
 }
 COPY_KERNEL = "torq::diag_copy_kernel"
