@@ -54,12 +54,12 @@ struct DecodeArgs {
 
 // The end of both kernels: add the waves' partial tiles through LDS and store.
 template <int MT, int NS>
-__device__ __forceinline__ void skinny_reduce_store(f32x4 (&acc)[NS][MT], unsigned char *smem, uint16_t *__restrict__ out,
+__device__ __forceinline__ void skinny_reduce_store(f32x4 (&acc)[NS][MT], unsigned char *red_mem, uint16_t *__restrict__ out,
                                                     int M, int64_t N, int64_t n0, int wave, int lane) {
   const int r16 = lane & 15, q = lane >> 4;
   // ---- add the waves' partial tiles in a fixed order (wave 0 + 1 + ... + 7), round, store
   __syncthreads();                                 // everybody is done with the scales
-  float *red = reinterpret_cast<float *>(smem);    // [WAVES - 1][NS][MT][4][64]
+  float *red = reinterpret_cast<float *>(red_mem); // [WAVES - 1][NS][MT][4][64]
   if (wave > 0) {
 #pragma unroll
     for (int n = 0; n < NS; ++n)
@@ -101,8 +101,14 @@ __device__ __forceinline__ void skinny_reduce_store(f32x4 (&acc)[NS][MT], unsign
 }
 
 // MT = number of 16-row activation tiles (M <= 16 MT); NS = 16-row weight strips per workgroup
-// (1 or 2; they share the activation loads); PT = line pairs per wave and trip
-template <int MT, int NS, int PT>
+// (1 or 2; they share the activation loads); PT = line pairs per wave and trip.
+// PERSIST: a workgroup takes the strip groups blockIdx.x, blockIdx.x + gridDim.x, ... and loads the
+// activations' codes (and scale bytes) ONCE, keeping the codes in registers across its groups; only
+// when one trip covers the k range (d / 256 <= PT * WAVES line pairs), where those registers are the
+// trip's own.  Every workgroup otherwise re-reads all activation rows from the L2, which at 8 - 16 rows
+// is half as many bytes again as the weights it streams.  Same arithmetic in the same order: the
+// outputs are bit-identical.
+template <int MT, int NS, int PT, bool PERSIST = false>
 __global__ void __launch_bounds__(64 * WAVES)
 mxfp4_gemm_skinny_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A_s,
                          const uint8_t *__restrict__ W_q, const uint8_t *__restrict__ W_s,
@@ -117,12 +123,6 @@ mxfp4_gemm_skinny_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restr
   const int row_bytes = d / 2, srow_bytes = d / 32;
   const int KS = d / 128;                          // k-steps of one MFMA (128 elements, 4 blocks)
   const int KP = (KS + 1) / 2;                     // pairs of k-steps = whole 128-byte lines of a row
-  const int64_t n0 = (int64_t)blockIdx.x * 16 * NS;
-  const int rows_w = (N - n0 < 16 * NS) ? (int)(N - n0) : 16 * NS;
-
-  // rows past N or M are outside the buffers: their loads deliver zeros
-  const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(W_q + n0 * row_bytes, (uint32_t)rows_w * row_bytes);
-  const __amdgpu_buffer_rsrc_t ws_rsrc = make_rsrc(W_s + n0 * srow_bytes, (uint32_t)rows_w * srow_bytes);
   const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(A_q, (uint32_t)M * row_bytes);
   const __amdgpu_buffer_rsrc_t as_rsrc = make_rsrc(A_s, (uint32_t)M * srow_bytes);
   const int c_voff = r16 * row_bytes + q * 16;     // codes: + 64 per k-step
@@ -135,69 +135,103 @@ mxfp4_gemm_skinny_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restr
   const int pd = sdw + 1;                          // padded
   const int w_ins = (16 * NS * pd + 63) / 64;      // instructions (256 bytes each) for the weight strips
   const int a_ins = (16 * MT * pd + 63) / 64;      // ... and for the activation rows
-  for (int i = wave; i < w_ins + a_ins; i += WAVES) {
-    const bool is_w = i < w_ins;
-    const int j = (is_w ? i : i - w_ins) * 64 + lane;
-    const int row = j / pd, col = j - row * pd;
-    const bool ok = col < sdw && row < (is_w ? 16 * NS : 16 * MT);
-    __builtin_amdgcn_raw_ptr_buffer_load_lds(is_w ? ws_rsrc : as_rsrc, LDSP(smem + i * 256), 4,
-                                             ok ? row * srow_bytes + col * 4 : OOB_VOFF, 0, 0, 0);
-  }
   const int ws_off = r16 * pd * 4 + q;             // this lane's scale byte: + 4 per k-step
   const int as_off = w_ins * 256 + r16 * pd * 4 + q;
+  // the partial tiles of waves 1.. : over the scales (one group per workgroup), behind them (PERSIST:
+  // the activations' scale bytes stay)
+  unsigned char *const red_mem = PERSIST ? smem + (w_ins + a_ins) * 256 : smem;
 
-  f32x4 acc[NS][MT];
-#pragma unroll
-  for (int n = 0; n < NS; ++n)
-#pragma unroll
-    for (int t = 0; t < MT; ++t) acc[n][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+  auto load_scales = [&](int i0, int i1, const __amdgpu_buffer_rsrc_t ws_rs) {
+    for (int i = i0 + wave; i < i1; i += WAVES) {
+      const bool is_w = i < w_ins;
+      const int j = (is_w ? i : i - w_ins) * 64 + lane;
+      const int row = j / pd, col = j - row * pd;
+      const bool ok = col < sdw && row < (is_w ? 16 * NS : 16 * MT);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(is_w ? ws_rs : as_rsrc, LDSP(smem + i * 256), 4,
+                                               ok ? row * srow_bytes + col * 4 : OOB_VOFF, 0, 0, 0);
+    }
+  };
+  // the activation codes of the k-steps of the trip that starts at line pair p0_
+#define TORQ_LOAD_A(DST_, P0_)                                                                    \
+  _Pragma("unroll") for (int u = 0; u < 2 * PT; ++u) {                                            \
+    const int ks = 2 * ((P0_) + (u >> 1) * WAVES) + (u & 1);                                      \
+    const bool in = ks < KS;                                                                      \
+    _Pragma("unroll") for (int t = 0; t < MT; ++t)                                                \
+        DST_[u][t] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, in ? c_voff : OOB_VOFF,        \
+                                                           in ? ks * 64 + t * 16 * row_bytes : 0, 0); \
+  }
+  u32x4 aq_keep[PERSIST ? 2 * PT : 1][MT];
+  if constexpr (PERSIST) {
+    load_scales(w_ins, w_ins + a_ins, as_rsrc);
+    TORQ_LOAD_A(aq_keep, wave)
+  }
 
-  // Wave w takes the line pairs w, w + WAVES, ...; PT pairs (2 PT k-steps) per trip, all of their
-  // loads issued before the first MFMA.  Pairs past the end (and the second k-step of the last
-  // pair when KS is odd) load zeros through the range check instead of branching.
-  bool first = true;
-  for (int p0 = wave; p0 < KP; p0 += PT * WAVES) {
-    u32x4 wq[2 * PT][NS], aq[2 * PT][MT];
+  const int64_t groups = (N + 16 * NS - 1) / (16 * NS);
+  for (int64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {   // one group unless PERSIST
+    const int64_t n0 = grp * 16 * NS;
+    const int rows_w = (N - n0 < 16 * NS) ? (int)(N - n0) : 16 * NS;
+    // rows past N or M are outside the buffers: their loads deliver zeros
+    const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(W_q + n0 * row_bytes, (uint32_t)rows_w * row_bytes);
+    const __amdgpu_buffer_rsrc_t ws_rsrc = make_rsrc(W_s + n0 * srow_bytes, (uint32_t)rows_w * srow_bytes);
+    load_scales(0, PERSIST ? w_ins : w_ins + a_ins, ws_rsrc);
+
+    f32x4 acc[NS][MT];
 #pragma unroll
-    for (int u = 0; u < 2 * PT; ++u) {
-      const int ks = 2 * (p0 + (u >> 1) * WAVES) + (u & 1);
-      const bool in = ks < KS;
-      const int cv = in ? c_voff : OOB_VOFF;
-      const int co = in ? ks * 64 : 0;
+    for (int n = 0; n < NS; ++n)
 #pragma unroll
-      for (int n = 0; n < NS; ++n)
-        wq[u][n] = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, cv, co + (in ? n * 16 * row_bytes : 0), 0);
+      for (int t = 0; t < MT; ++t) acc[n][t] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    // Wave w takes the line pairs w, w + WAVES, ...; PT pairs (2 PT k-steps) per trip, all of their
+    // loads issued before the first MFMA.  Pairs past the end (and the second k-step of the last
+    // pair when KS is odd) load zeros through the range check instead of branching.
+    bool first = true;
+    for (int p0 = wave; p0 < KP; p0 += PT * WAVES) {
+      u32x4 wq[2 * PT][NS], aq_trip[PERSIST ? 1 : 2 * PT][MT];
 #pragma unroll
-      for (int t = 0; t < MT; ++t)
-        aq[u][t] = __builtin_amdgcn_raw_buffer_load_b128(a_rsrc, cv, co + (in ? t * 16 * row_bytes : 0), 0);
-    }
-    __builtin_amdgcn_sched_barrier(0);             // every load of the trip is in flight before the first wait
-    if (first) {
-      __syncthreads();                             // the scales are in LDS
-      first = false;
-    }
+      for (int u = 0; u < 2 * PT; ++u) {
+        const int ks = 2 * (p0 + (u >> 1) * WAVES) + (u & 1);
+        const bool in = ks < KS;
+        const int cv = in ? c_voff : OOB_VOFF;
+        const int co = in ? ks * 64 : 0;
 #pragma unroll
-    for (int u = 0; u < 2 * PT; ++u) {
-      const int ks = 2 * (p0 + (u >> 1) * WAVES) + (u & 1);
-      const int sb = (ks < KS ? ks : 0) * 4;
-      int asc[MT];
+        for (int n = 0; n < NS; ++n)
+          wq[u][n] = __builtin_amdgcn_raw_buffer_load_b128(w_rsrc, cv, co + (in ? n * 16 * row_bytes : 0), 0);
+      }
+      if constexpr (!PERSIST) { TORQ_LOAD_A(aq_trip, p0) }
+      __builtin_amdgcn_sched_barrier(0);           // every load of the trip is in flight before the first wait
+      if (first) {
+        __syncthreads();                           // the scales are in LDS
+        first = false;
+      }
 #pragma unroll
-      for (int t = 0; t < MT; ++t) asc[t] = smem[as_off + t * 16 * pd * 4 + sb];
+      for (int u = 0; u < 2 * PT; ++u) {
+        const int ks = 2 * (p0 + (u >> 1) * WAVES) + (u & 1);
+        const int sb = (ks < KS ? ks : 0) * 4;
+        int asc[MT];
 #pragma unroll
-      for (int n = 0; n < NS; ++n) {
-        const int wsc = smem[ws_off + n * 16 * pd * 4 + sb];
+        for (int t = 0; t < MT; ++t) asc[t] = smem[as_off + t * 16 * pd * 4 + sb];
 #pragma unroll
-        for (int t = 0; t < MT; ++t)
-          acc[n][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
-              i32x8{(int)wq[u][n][0], (int)wq[u][n][1], (int)wq[u][n][2], (int)wq[u][n][3], 0, 0, 0, 0},
-              i32x8{(int)aq[u][t][0], (int)aq[u][t][1], (int)aq[u][t][2], (int)aq[u][t][3], 0, 0, 0, 0},
-              acc[n][t], 4, 4, 0, wsc, 0, asc[t]);
+        for (int n = 0; n < NS; ++n) {
+          const int wsc = smem[ws_off + n * 16 * pd * 4 + sb];
+#pragma unroll
+          for (int t = 0; t < MT; ++t) {
+            const u32x4 av = PERSIST ? aq_keep[PERSIST ? u : 0][t] : aq_trip[PERSIST ? 0 : u][t];
+            acc[n][t] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+                i32x8{(int)wq[u][n][0], (int)wq[u][n][1], (int)wq[u][n][2], (int)wq[u][n][3], 0, 0, 0, 0},
+                i32x8{(int)av[0], (int)av[1], (int)av[2], (int)av[3], 0, 0, 0, 0},
+                acc[n][t], 4, 4, 0, wsc, 0, asc[t]);
+          }
+        }
       }
     }
-  }
-  if (first) __syncthreads();                      // a wave without any pair still meets the others
+    if (first) __syncthreads();                    // a wave without any pair still meets the others
 
-  skinny_reduce_store<MT, NS>(acc, smem, out, M, N, n0, wave, lane);
+    skinny_reduce_store<MT, NS>(acc, red_mem, out, M, N, n0, wave, lane);
+    // PERSIST: the next group's scale bytes replace this group's, which every wave has read (first
+    // barrier of the reduction); its partial tiles replace these once wave 0, the only reader, has
+    // arrived at the next group's barrier
+  }
+#undef TORQ_LOAD_A
 }
 
 // One lane of a consumer workgroup that is done with ctr[0] (see torq_linear_decode_kernel).
@@ -415,6 +449,25 @@ static hipError_t launch_cfg(const uint8_t *A_q, const uint8_t *A_s, const uint8
                        fused->intra_lo_frag, fused->A_q, fused->A_s, W_q, W_s, reinterpret_cast<uint16_t *>(out), (int)M,
                        N, d, fused->P, (int)groups, fused->ctr, fused->spin_limit, fused->raise_ready);
     return hipGetLastError();
+  }
+  // The persistent form (activation codes loaded once per workgroup and kept in registers): 8 - 16 rows,
+  // one trip over the k range, and weights enough for the re-reads to cost more than the parallelism
+  // given up (measured: [16, 8192] x 28672 34.2 -> 28.4 us, [8, 8192] x 28672 32.2 -> 27.4,
+  // [16, 8192] x 8192 10.7 -> 9.7, [16, 4096] x 14336 9.2 -> 9.0; below 24 MB of weights it loses).  Each
+  // workgroup takes `per` groups, the smallest power of two that leaves at most 256 workgroups (one per CU,
+  // evenly loaded: 3 or 7 groups per workgroup measured 15 - 20 % slower than 4, and half as many
+  // workgroups as CUs 30 % slower than one each).
+  const int KP = (d / 128 + 1) / 2;
+  const size_t p_bytes = scale_bytes + red_bytes;
+  if (MT == 1 && M >= 8 && KP <= PT * WAVES && (double)N * (double)d * 0.53125 >= 24e6 && p_bytes <= 64 * 1024) {
+    int64_t per = 1;
+    while ((groups + per - 1) / per > 256) per *= 2;
+    if (per > 1) {
+      const int64_t grid = (groups + per - 1) / per;
+      hipLaunchKernelGGL((mxfp4_gemm_skinny_kernel<MT, NS, PT, true>), dim3((unsigned)grid), dim3(64 * WAVES), p_bytes,
+                         stream, A_q, A_s, W_q, W_s, reinterpret_cast<uint16_t *>(out), (int)M, N, d);
+      return hipGetLastError();
+    }
   }
   if (lds_bytes > SKINNY_MAX_LDS) return hipErrorInvalidValue;
   if (lds_bytes > 64 * 1024) {

@@ -113,6 +113,9 @@ GEMM_FULL = [
     (4096, 25600, 5120),      # Qwen3-32B MLP up / gate
     (4096, 1024, 5120),       # Qwen3-32B k/v projection
     (4096, 8192, 5120),       # Qwen3-32B q projection
+    (16, 28672, 8192),        # LLaMA3-70B MLP up at decode size: workgroups that keep the activations across four strip groups
+    (12, 28000, 8192),        # ... with ragged rows and a ragged last group
+    (8, 8192, 8192),          # ... one strip per group, two groups per workgroup
 ]
 
 
