@@ -82,7 +82,6 @@ void torq_o_quantize(const float *z, int64_t M, int d,
 void torq_o_dequantize(const uint8_t *codes, const uint8_t *scales,
                        int64_t M, int d, float *zhat);
 
-/* steps 1-4 in one call (rotate in double, round to fp32, quantise) */
 /* Other 4-bit block formats behind the same rotations (Section 6, Table 5); the paper defines
  * neither, the definitions state the readings.  MXINT4: 32-element blocks, E8M0 scale as above,
  * integer elements in [-7, 7] as two's-complement nibbles.  NVFP4: 16-element blocks, an FP8 E4M3
@@ -97,6 +96,7 @@ void torq_o_quantize_nvfp4(const float *z, int64_t M, int d, float global_scale,
 void torq_o_dequantize_nvfp4(const uint8_t *codes, const uint8_t *scales_e4m3, int64_t M, int d,
                              float global_scale, float *zhat);
 
+/* steps 1-4 in one call (rotate in double, round to fp32, quantise) */
 void torq_o_rotate_quantize(const uint16_t *x_bf16, int64_t M, int d, int G,
                             const float *R_inter, const float *R_intra,
                             uint8_t *codes, uint8_t *scales);
