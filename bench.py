@@ -643,7 +643,8 @@ def decode_line(tq, synth, M, N, d, single_launch=True):
 
     us = replayed(tq.torq_linear)
     # the one-launch form of the same layer, where it applies (G = 128, at most 64 rows)
-    us_single = round(replayed(tq.torq_linear_single_launch), 2) if (single_launch and G == 128 and M <= 64) else None
+    local = G in (112, 128) and M * (d // 32 // G) <= 4
+    us_single = round(replayed(tq.torq_linear_single_launch), 2) if (single_launch and ((G == 128 and M <= 64) or local)) else None
     wbytes = N * d * 0.53125
     rot.close()
     streaming, tile_m, tile_n, pieces = tq.mxfp4_gemm_plan(M, N, d, tq.mxfp4_gemm_workspace_bytes(M, N, d))

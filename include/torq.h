@@ -166,7 +166,10 @@ int mxfp4_gemm_ws(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, co
  * into `workspace`, then mxfp4_gemm, on one stream.  workspace is device
  * memory of at least torq_linear_workspace_bytes(M, d) bytes, 256-byte aligned
  * sizes; its contents afterwards are the packed activations (codes, then
- * scales at offset M*d/2 rounded up to 256). */
+ * scales at offset M*d/2 rounded up to 256).  For a row or two of a decode step
+ * (at most four token-groups, G = 112 or 128, packed weights up to 48 MB) both
+ * steps run in ONE launch whose workgroups each rotate the rows themselves (form
+ * (1) of torq_linear_single_launch): same codes, same outputs, bit for bit. */
 size_t torq_linear_workspace_bytes(int64_t M, int d);
 /* The same plus the scratch that lets the GEMM inside cut its k range (see mxfp4_gemm_ws);
  * torq_linear uses whatever it is given beyond torq_linear_workspace_bytes(M, d) for that. */
@@ -194,26 +197,38 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16,
 int torq_linear_static(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q, const uint8_t *W_s,
                        void *out_bf16, int64_t M, int64_t N, void *stream);
 
-/* torq_linear for decode sizes in ONE kernel launch (Algorithm 3, steps 1-4 and "Return"): the first
- * workgroups rotate and quantise one token-group each while the others, one per strip of weight rows,
- * already have their weight scales and codes on the way and wait for the activations at a counter
- * in device memory.  Same arguments and workspace as torq_linear, with these limits:
- *   the handle's G is 128 and its R_inter a dense matrix (torq_rotation_create); 0 <= M <= 64;
- *   d a multiple of 128 whose scale rows fit the LDS (every d up to 28672 does).
- * Anything else is TORQ_EINVAL.  The packed activations are left in the workspace as by torq_linear; they
+/* torq_linear for decode sizes in ONE kernel launch (Algorithm 3, steps 1-4 and "Return").  Same
+ * arguments and workspace as torq_linear.  Two forms, chosen by the size:
+ *
+ * (1) Up to four token-groups in all (M * d / (32 G) <= 4: e.g. four rows of d = 4096, one of d = 14336
+ *     or 16384), G = 112 or 128, a dense R_inter: EVERY workgroup of the weight-streaming GEMM rotates and
+ *     quantises all rows itself into its LDS, behind its own weight reads; nothing is handed over between
+ *     workgroups, the packed activations never leave the chip (workgroup 0 stores a copy to the workspace
+ *     for the caller to inspect, which the launch does not read), and the handle's counters are neither
+ *     read nor written.  The codes are torq_rotate_quantize's, bit for bit, and the product is mxfp4_gemm
+ *     of them.  torq_linear itself takes this launch where it is measured faster than its two launches
+ *     (packed weights up to 48 MB: [1, 4096] -> 14336 10.1 against 12.0 us, -> 4096 5.5 against 8.3 us).
+ *
+ * (2) Otherwise, up to 64 rows, G = 128, a dense R_inter: the first workgroups rotate and quantise one
+ *     token-group each while the others, one per strip of weight rows, already have their weight scales
+ *     and codes on the way and wait for the activations at a counter in device memory.
+ *     The packed activations are left in the workspace as by torq_linear; they
  * come from the 16-block rotation kernel, so a value that sits within the rotation's error bar of a
  * rounding boundary may get the neighbouring code of torq_rotate_quantize's; the product is exactly
  * mxfp4_gemm of those codes.  Every workgroup exits: the wait is bounded.  A workgroup whose wait runs
  * out writes NaN to its outputs and raises an error word among the handle's counters that no launch
- * clears: from then on every torq_linear_single_launch on that handle writes NaN to all of `out`
+ * clears: from then on every launch of form (2) on that handle writes NaN to all of `out`
  * (the counters of the failed launch cannot be trusted any more) until
  * torq_linear_single_launch_reset has run; the calls themselves keep returning TORQ_OK, as they only
  * enqueue.  Calls on one
  * handle must not overlap in time (they share the handle's counters; stream order is enough).  On
  * this part the hand-off between workgroups costs what the second launch costs: measured against
- * torq_linear 14.4 against 11.7 us at [1, 4096] -> 14336, 13.1 against 13.5 us at [16, 4096] -> 14336,
+ * torq_linear 13.1 against 13.5 us at [16, 4096] -> 14336,
  * 36.5 against 34.3 us at [16, 8192] -> 28672 and 85 against 37 us at [64, 8192] -> 28672 (where
- * torq_linear takes a tiled GEMM kernel), which is why torq_linear does not use it. */
+ * torq_linear takes a tiled GEMM kernel), which is why torq_linear does not use form (2).
+ *
+ * Limits of both: d a multiple of 128 whose scale rows fit the LDS (every d up to 28672 does);
+ * 0 <= M <= 64.  Anything else is TORQ_EINVAL. */
 int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q, const uint8_t *W_s,
                               void *out_bf16, int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
                               void *stream);
@@ -221,8 +236,8 @@ int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, cons
  *   (one small kernel on `stream`; allowed under stream capture).
  * torq_linear_single_launch_gave_up: *gave_up = 1 if a launch on this handle has given up since the last
  *   reset, else 0.  Copies one word from the device with a blocking copy: not a hot call.
- * torq_linear_single_launch_probe: torq_linear_single_launch with its two internal constants exposed,
- *   for tests of the give-up path that let every workgroup exit normally: spin_limit = how often a
+ * torq_linear_single_launch_probe: form (2) of torq_linear_single_launch (at any size it covers) with its
+ *   two internal constants exposed, for tests of the give-up path that let every workgroup exit normally: spin_limit = how often a
  *   waiting workgroup polls before it gives up (1 .. 2^18; torq_linear_single_launch uses 2^18),
  *   withhold_ready != 0 = the rotating workgroups do their work but never hand over, so every
  *   multiplying workgroup gives up after spin_limit polls. */

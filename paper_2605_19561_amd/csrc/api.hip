@@ -175,6 +175,24 @@ static int torq_rotation_create_impl(torq_rotation_t **out, int d, int G, const 
       }
     }
 
+  // R_inter as the B operand of v_mfma_f32_32x32x16_bf16 in lane order (96 < G <= 128): tile w, k-step
+  // ks, lane (col = l%32, h = l/32), slot j holds R_inter[32 w + col][16 ks + 8 h + j], zero past G
+  std::vector<uint16_t> fh, fl;
+  if (G > 96 && G <= 128) {
+    fh.assign(4 * 8 * 64 * 8, 0);
+    fl.assign(4 * 8 * 64 * 8, 0);
+    for (int w = 0; w < 4; ++w)
+      for (int ks = 0; ks < 8; ++ks)
+        for (int l = 0; l < 64; ++l)
+          for (int j = 0; j < 8; ++j) {
+            const int b = 32 * w + l % 32, bp = 16 * ks + 8 * (l / 32) + j;
+            if (b < G && bp < G) {
+              const size_t at = (((size_t)w * 8 + ks) * 64 + l) * 8 + j;
+              split_bf16(R_inter_host[(size_t)b * G + bp], &fh[at], &fl[at]);
+            }
+          }
+  }
+
   const std::vector<unsigned> zero_ctr(DECODE_CTR_WORDS, 0u);
 
   // every host table exists: from here on nothing throws
@@ -185,6 +203,7 @@ static int torq_rotation_create_impl(torq_rotation_t **out, int d, int G, const 
   r->KS = KS;
   r->device = dev;
   r->inter_hi = r->inter_lo = r->intra_hi = r->intra_lo = r->intra32_hi = r->intra32_lo = nullptr;
+  r->inter32f_hi = r->inter32f_lo = nullptr;
   r->butterfly = nullptr;
   r->decode_ctr = nullptr;
 
@@ -194,6 +213,8 @@ static int torq_rotation_create_impl(torq_rotation_t **out, int d, int G, const 
   if (e == hipSuccess) e = upload(&r->intra_lo, al);
   if (e == hipSuccess) e = upload(&r->intra32_hi, a32h);
   if (e == hipSuccess) e = upload(&r->intra32_lo, a32l);
+  if (e == hipSuccess && !fh.empty()) e = upload(&r->inter32f_hi, fh);
+  if (e == hipSuccess && !fl.empty()) e = upload(&r->inter32f_lo, fl);
   if (e == hipSuccess) e = upload(&r->decode_ctr, zero_ctr);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {
@@ -212,6 +233,8 @@ void torq_rotation_destroy(torq_rotation_t *r) {
   if (r->intra_lo) (void)hipFree(r->intra_lo);
   if (r->intra32_hi) (void)hipFree(r->intra32_hi);
   if (r->intra32_lo) (void)hipFree(r->intra32_lo);
+  if (r->inter32f_hi) (void)hipFree(r->inter32f_hi);
+  if (r->inter32f_lo) (void)hipFree(r->inter32f_lo);
   if (r->butterfly) (void)hipFree(r->butterfly);
   if (r->decode_ctr) (void)hipFree(r->decode_ctr);
   delete r;
@@ -465,6 +488,11 @@ int torq_linear(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q
   if (workspace_bytes < torq_linear_workspace_bytes(M, r->d)) return TORQ_EWORKSPACE;
   uint8_t *codes = static_cast<uint8_t *>(workspace);
   uint8_t *scales = codes + (((size_t)M * (size_t)(r->d / 2) + 255) & ~(size_t)255);
+  // a row or two of a decode step: one launch, every workgroup rotates the rows itself (same bits out)
+  if (torq::torq_linear_local_pays(r, M, N) && (int64_t)r->d * 128 < 0x7FFFFFFF) {
+    hipError_t el = torq::launch_torq_linear_local(r, x_bf16, codes, scales, W_q, W_s, out_bf16, M, N, (hipStream_t)stream);
+    return el == hipSuccess ? TORQ_OK : hip_fail(el);
+  }
   hipError_t e = rotate_any(r, x_bf16, M, TORQ_FMT_MXFP4, 1.0f, codes, scales, nullptr, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
   // whatever the caller gave beyond the packed activations serves the GEMM's split-k pieces
@@ -490,6 +518,10 @@ int torq_linear_static(const torq_rotation_t *r, const void *x_bf16, const uint8
   if (e != hipSuccess) return hip_fail(e);
   uint8_t *codes = ws;
   uint8_t *scales = codes + (((size_t)M * (size_t)(r->d / 2) + 255) & ~(size_t)255);
+  if (torq::torq_linear_local_pays(r, M, N) && (int64_t)r->d * 128 < 0x7FFFFFFF) {      // as torq_linear
+    e = torq::launch_torq_linear_local(r, x_bf16, codes, scales, W_q, W_s, out_bf16, M, N, (hipStream_t)stream);
+    return e == hipSuccess ? TORQ_OK : hip_fail(e);
+  }
   e = rotate_any(r, x_bf16, M, TORQ_FMT_MXFP4, 1.0f, codes, scales, nullptr, (hipStream_t)stream);
   if (e != hipSuccess) return hip_fail(e);
   e = torq::launch_mxfp4_gemm(codes, scales, W_q, W_s, out_bf16, M, N, r->d, nullptr, 0, (hipStream_t)stream);
@@ -517,6 +549,18 @@ int torq_linear_single_launch_probe(const torq_rotation_t *r, const void *x_bf16
 int torq_linear_single_launch(const torq_rotation_t *r, const void *x_bf16, const uint8_t *W_q, const uint8_t *W_s,
                               void *out_bf16, int64_t M, int64_t N, void *workspace, size_t workspace_bytes,
                               void *stream) {
+  // a few token-groups: every workgroup rotates them itself, nothing is handed over between workgroups
+  // (and the handle's counters, the give-up word included, are neither read nor written)
+  if (r && M >= 1 && N >= 1 && torq::torq_linear_local_fits(r, M) && (int64_t)r->d * 128 < 0x7FFFFFFF) {
+    if (!x_bf16 || !W_q || !W_s || !out_bf16 || !workspace) return TORQ_EINVAL;
+    if (misaligned(x_bf16) || misaligned(W_q) || misaligned(out_bf16) || misaligned(workspace)) return TORQ_EALIGN;
+    if (reinterpret_cast<uintptr_t>(W_s) & 3u) return TORQ_EALIGN;
+    if (workspace_bytes < torq_linear_workspace_bytes(M, r->d)) return TORQ_EWORKSPACE;
+    uint8_t *codes = static_cast<uint8_t *>(workspace);
+    uint8_t *scales = codes + (((size_t)M * (size_t)(r->d / 2) + 255) & ~(size_t)255);
+    hipError_t e = torq::launch_torq_linear_local(r, x_bf16, codes, scales, W_q, W_s, out_bf16, M, N, (hipStream_t)stream);
+    return e == hipSuccess ? TORQ_OK : hip_fail(e);
+  }
   return torq_linear_single_launch_probe(r, x_bf16, W_q, W_s, out_bf16, M, N, workspace, workspace_bytes, 1 << 18, 0,
                                          stream);
 }

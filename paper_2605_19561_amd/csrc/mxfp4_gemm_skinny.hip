@@ -16,6 +16,7 @@
 // The first MFMA operand is the weight strip and the second the activations, so an accumulator
 // lane holds out[m = l % 16][n = n0 + 4 (l / 16) + 0..3]: four consecutive outputs of one row.
 #include "rotate16_body.h"
+#include "rotate32_resident.h"
 #include "torq_device.h"
 #include "torq_internal.h"
 
@@ -32,6 +33,7 @@ typedef __attribute__((__vector_size__(4 * sizeof(unsigned)))) unsigned u32x4;
 
 constexpr int WAVES = 8;              // waves per workgroup = ways the k range is split
 constexpr size_t SKINNY_MAX_LDS = 160 * 1024;
+constexpr int LOCAL_MAX_TG = 4;       // token-groups that torq_linear_local_kernel rotates in every workgroup
 constexpr int SKINNY_MIN_GROUPS = 384; // fewer workgroups than this leave CUs without work (256 CUs)
 
 // a voffset that the range check of any buffer used here rejects (the load then delivers zeros)
@@ -420,6 +422,215 @@ torq_linear_decode_kernel(const uint4 *__restrict__ x, int64_t TG, const uint16_
   if (tid == 0) decode_consumer_done(ctr, (int)blockIdx.x - P, groups);
 }
 
+// ---------------------------------------------------------------------------------------------
+// torq_linear for a few token-groups (one to four rows of a decode step) with the packed activations
+// never leaving the chip: Algorithm 3, steps 1-4 and "Return", in one launch and without any hand-off
+// between workgroups.  Every workgroup rotates and quantises ALL token-groups itself (rotate32_resident
+// on its 8 waves, G = 112 or 128: 2.9 MFLOP per token-group, well under a microsecond) into its own LDS while the
+// scale bytes and the first trip of weight codes of its first strips are on the way, and then
+// streams its share of the weight strips as mxfp4_gemm_skinny_kernel<1, NS, PT, true> does, with the
+// activation operand read from LDS instead of from memory.  Workgroups are persistent (the rotation is
+// paid once per workgroup, not once per strip).  Workgroup 0 also stores the codes and scale bytes to
+// A_q / A_s (the caller's workspace, same layout as torq_rotate_quantize), which nothing in the launch
+// reads: they are what was multiplied, for the caller to inspect.
+//
+// One trip of a wave holds 2 PT k-steps of NS strips in registers (32 PT NS bytes per lane); the launcher
+// picks NS and PT so that, where 128 registers allow, one trip is the workgroup's whole share: then every
+// weight byte of the launch is requested before the rotation starts, and the rotation's latency (two
+// dependent reads from memory and a chain of 22 MFMAs) hides behind the stream.
+//
+// LDS: [weight-strip scales | activation scales (16 rows, zero beyond M) | codes, M rows of d / 2 + 16
+// bytes (the pad spreads the rows over the banks) | the token-groups' bf16 values (8 KiB each), later
+// the partial tiles of the reduction (8 NS KiB)].
+namespace {
+struct LocalSink {
+  unsigned char *a_c, *s_a;
+  int a_stride, s_stride, bpr;        // bytes per code row / scale row in LDS; blocks per activation row
+  uint2 *codes_g;                     // workgroup 0: the copy in device memory, else nullptr
+  uint8_t *scales_g;
+  __device__ __forceinline__ void operator()(int64_t blk, int h, uint2 packed, uint32_t byte) const {
+    const int b = (int)blk, row = b / bpr, bk = b - row * bpr;
+    *reinterpret_cast<uint2 *>(a_c + row * a_stride + bk * 16 + h * 8) = packed;
+    if (h == 0) s_a[row * s_stride + bk] = (unsigned char)byte;
+    if (codes_g) {
+      codes_g[blk * 2 + h] = packed;
+      if (h == 0) scales_g[blk] = (uint8_t)byte;
+    }
+  }
+};
+}  // namespace
+
+// The end of torq_linear_local_kernel: as skinny_reduce_store for one activation tile, but with wave n
+// adding strip n (every wave's partial tile goes through LDS, red_mem = 8 NS KiB): with up to four
+// strips per workgroup one wave would add 112 values per lane while seven wait.  Same order of additions
+// (wave 0 + 1 + ... + 7): the same bits.
+template <int NS>
+__device__ __forceinline__ void local_reduce_store(f32x4 (&acc)[NS][1], unsigned char *red_mem, uint16_t *__restrict__ out,
+                                                   int M, int64_t N, int64_t n0, int wave, int lane) {
+  const int r16 = lane & 15, q = lane >> 4;
+  __syncthreads();                                 // everybody is done with the scales and the codes
+  float *red = reinterpret_cast<float *>(red_mem); // [WAVES][NS][4][64]
+#pragma unroll
+  for (int n = 0; n < NS; ++n)
+#pragma unroll
+    for (int r = 0; r < 4; ++r) red[((wave * NS + n) * 4 + r) * 64 + lane] = acc[n][0][r];
+  __syncthreads();
+  if (wave < NS) {
+    const int n = wave;
+    const int64_t nn = n0 + n * 16 + 4 * q;
+    bf16x4 v;
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      float sum = red[(n * 4 + r) * 64 + lane];
+#pragma unroll
+      for (int w = 1; w < WAVES; ++w) sum += red[((w * NS + n) * 4 + r) * 64 + lane];
+      v[r] = (__bf16)sum;
+    }
+    if (r16 < M) {
+      uint16_t *dst = out + (int64_t)r16 * N + nn;
+      if ((N & 3) == 0 && nn + 4 <= N) {
+        *reinterpret_cast<bf16x4 *>(dst) = v;
+      } else {
+        const uint64_t bits = __builtin_bit_cast(uint64_t, v);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+          if (nn + r < N) dst[r] = (uint16_t)(bits >> (16 * r));
+      }
+    }
+  }
+}
+
+// EXACT: d / 256 == PT * WAVES, one trip is the k range with no k-step past the end: its loads then need
+// no range predicate, compile to straight-line code, and the compiler's count of them is exact.
+template <int NS, int PT, bool EXACT>
+__global__ void __launch_bounds__(64 * WAVES, 2)
+torq_linear_local_kernel(const uint4 *__restrict__ x, int TG, int G, const uint4 *__restrict__ inter_hi,
+                         const uint4 *__restrict__ inter_lo, const uint4 *__restrict__ intra_hi_frag,
+                         const uint4 *__restrict__ intra_lo_frag, uint8_t *__restrict__ A_q,
+                         uint8_t *__restrict__ A_s, const uint8_t *__restrict__ W_q,
+                         const uint8_t *__restrict__ W_s, uint16_t *__restrict__ out, int M, int64_t N, int d) {
+  extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int r16 = lane & 15, q = lane >> 4;
+  const int row_bytes = d / 2, srow_bytes = d / 32;
+  const int KS = d / 128;
+  const int KP = (KS + 1) / 2;
+  const int c_voff = r16 * row_bytes + q * 16;
+  const int sdw = srow_bytes / 4, pd = sdw + 1;
+  const int w_ins = (16 * NS * pd + 63) / 64, a_ins = (16 * pd + 63) / 64;
+  const int ws_off = r16 * pd * 4 + q;
+  const int as_off = w_ins * 256 + r16 * pd * 4 + q;
+  const int a_stride = row_bytes + 16;
+  unsigned char *const s_a = smem + w_ins * 256;
+  unsigned char *const a_c = smem + (w_ins + a_ins) * 256;
+  unsigned char *const xs = a_c + (M * a_stride + 255) / 256 * 256;     // TG token-groups, then partial tiles
+
+  const int64_t groups = (N + 16 * NS - 1) / (16 * NS);
+  auto load_w_scales = [&](const __amdgpu_buffer_rsrc_t ws_rs) {
+    for (int i = wave; i < w_ins; i += WAVES) {
+      const int j = i * 64 + lane;
+      const int row = j / pd, col = j - row * pd;
+      const bool ok = col < sdw && row < 16 * NS;
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(ws_rs, LDSP(smem + i * 256), 4, ok ? row * srow_bytes + col * 4 : OOB_VOFF, 0, 0, 0);
+    }
+  };
+  u32x4 wq[2 * PT][NS];
+#define TORQ_LOAD_W(RSRC_, P0_)                                                                   \
+  _Pragma("unroll") for (int u = 0; u < 2 * PT; ++u) {                                            \
+    const int ks = 2 * ((P0_) + (u >> 1) * WAVES) + (u & 1);                                      \
+    const bool in = EXACT || ks < KS;                                                             \
+    _Pragma("unroll") for (int n = 0; n < NS; ++n)                                                \
+        wq[u][n] = __builtin_amdgcn_raw_buffer_load_b128(RSRC_, in ? c_voff : OOB_VOFF,           \
+                                                         in ? ks * 64 + n * 16 * row_bytes : 0, 0); \
+  }
+
+  // ---- steps 1-4 into LDS.  The rotation's own reads from memory are requested first and the first
+  // trip's weight codes right behind them (reads return in order: the rotation must not queue behind
+  // the weights); the scale bytes of the rows past M are zeros
+  for (int i = tid; i < a_ins * 64; i += 64 * WAVES) reinterpret_cast<uint32_t *>(s_a)[i] = 0u;
+  {
+    LocalSink sink;
+    sink.a_c = a_c;
+    sink.s_a = s_a;
+    sink.a_stride = a_stride;
+    sink.s_stride = pd * 4;
+    sink.bpr = srow_bytes;
+    sink.codes_g = blockIdx.x == 0 ? reinterpret_cast<uint2 *>(A_q) : nullptr;
+    sink.scales_g = A_s;
+    const int64_t n0 = (int64_t)blockIdx.x * 16 * NS;
+    const int rows_w = (N - n0 < 16 * NS) ? (int)(N - n0) : 16 * NS;
+    load_w_scales(make_rsrc(W_s + n0 * srow_bytes, (uint32_t)rows_w * srow_bytes));   // few bytes, ahead of everything
+    const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(W_q + n0 * row_bytes, (uint32_t)rows_w * row_bytes);
+    auto weights_first_trip = [&]() {
+      // The waves meet (nothing is waited for) so that every wave's rotation reads are in the CU's
+      // memory pipeline before any wave's weight reads: the pipeline takes requests in order, and a
+      // later wave's 5 KB for the rotation would otherwise queue behind 16 KB of weights per earlier wave.
+      __builtin_amdgcn_sched_barrier(0);
+      __builtin_amdgcn_s_barrier();
+      __builtin_amdgcn_sched_barrier(0);
+      if (EXACT || wave < KP) { TORQ_LOAD_W(w_rsrc, wave) }
+      __builtin_amdgcn_sched_barrier(0);
+    };
+    // (two barriers inside: the first also orders the clearing above before any scale byte, the second
+    // makes the results visible)
+    rotate32_resident(x, TG, G, inter_hi, inter_lo, intra_hi_frag, intra_lo_frag, reinterpret_cast<char *>(xs), sink,
+                      weights_first_trip);
+  }
+
+  // ---- the strip groups of this workgroup
+  bool preloaded = true;
+  for (int64_t grp = blockIdx.x; grp < groups; grp += gridDim.x) {
+    const int64_t n0 = grp * 16 * NS;
+    const int rows_w = (N - n0 < 16 * NS) ? (int)(N - n0) : 16 * NS;
+    const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(W_q + n0 * row_bytes, (uint32_t)rows_w * row_bytes);
+    if (!preloaded) load_w_scales(make_rsrc(W_s + n0 * srow_bytes, (uint32_t)rows_w * srow_bytes));
+
+    f32x4 acc[NS][1];
+#pragma unroll
+    for (int n = 0; n < NS; ++n) acc[n][0] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    bool first = true;
+    for (int p0 = wave; p0 < KP; p0 += PT * WAVES) {
+      if (!(preloaded && first)) { TORQ_LOAD_W(w_rsrc, p0) }
+      u32x4 aq[2 * PT];
+#pragma unroll
+      for (int u = 0; u < 2 * PT; ++u) {
+        const int ks = 2 * (p0 + (u >> 1) * WAVES) + (u & 1);
+        aq[u] = ((EXACT || ks < KS) && r16 < M) ? *reinterpret_cast<const u32x4 *>(a_c + r16 * a_stride + ks * 64 + q * 16)
+                                     : u32x4{0u, 0u, 0u, 0u};
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      if (first) {
+        __syncthreads();                           // the strip's scale bytes are in LDS
+        first = false;
+      }
+#pragma unroll
+      for (int u = 0; u < 2 * PT; ++u) {
+        const int ks = 2 * (p0 + (u >> 1) * WAVES) + (u & 1);
+        const int sb = ((EXACT || ks < KS) ? ks : 0) * 4;
+        const int asc = smem[as_off + sb];
+#pragma unroll
+        for (int n = 0; n < NS; ++n) {
+          const int wsc = smem[ws_off + n * 16 * pd * 4 + sb];
+          acc[n][0] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(
+              i32x8{(int)wq[u][n][0], (int)wq[u][n][1], (int)wq[u][n][2], (int)wq[u][n][3], 0, 0, 0, 0},
+              i32x8{(int)aq[u][0], (int)aq[u][1], (int)aq[u][2], (int)aq[u][3], 0, 0, 0, 0},
+              acc[n][0], 4, 4, 0, wsc, 0, asc);
+        }
+      }
+    }
+    if (first) __syncthreads();                    // a wave without any pair still meets the others
+    preloaded = false;
+
+    // the partial tiles go where the rotation staged its input; the next group's scale bytes replace
+    // this group's once every wave has read them (first barrier of the reduction), and its partial tiles
+    // these once the adding waves have arrived at the next group's barrier
+    local_reduce_store<NS>(acc, xs, out, M, N, n0, wave, lane);
+  }
+#undef TORQ_LOAD_W
+}
+
 template <int MT, int NS, int PT>
 static hipError_t launch_cfg(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
                              void *out, int64_t M, int64_t N, int d, hipStream_t stream, const DecodeArgs *fused) {
@@ -554,6 +765,77 @@ hipError_t launch_torq_linear_decode(const torq_rotation *r, const void *x_bf16,
   fz.spin_limit = spin_limit;
   fz.raise_ready = raise_ready;
   return launch_by_rows(A_q, A_s, W_q, W_s, out, M, N, r->d, stream, &fz);
+}
+
+// torq_linear with the activations rotated and quantised inside every workgroup (torq_linear_local_kernel).
+// Preconditions (torq_linear_local_fits): dense R_inter with 96 < G <= 128, at most LOCAL_MAX_TG
+// token-groups in all, d a multiple of 128, and LDS for one strip per workgroup.
+static size_t local_lds_bytes(int64_t M, int d, int NS) {
+  const int pd = d / 128 + 1;
+  const size_t red = (size_t)WAVES * NS * 4 * 64 * sizeof(float), rot = LOCAL_MAX_TG * (size_t)RotCfg<4>::TG_LDS_BYTES;
+  return (size_t)((16 * NS * pd + 63) / 64 + (16 * pd + 63) / 64) * 256 + ((size_t)M * (d / 2 + 16) + 255) / 256 * 256 +
+         (red > rot ? red : rot);
+}
+
+bool torq_linear_local_fits(const torq_rotation *r, int64_t M) {
+  if (r->butterfly || !r->inter32f_hi || r->G <= 96 || r->G > 128 || r->G % 16 != 0 || r->d % 128 != 0) return false;
+  if (M < 1 || M > 16) return false;
+  if (M * (int64_t)(r->d / 32 / r->G) > LOCAL_MAX_TG) return false;
+  return (r->d / 128 + 1) / 2 <= 8 * WAVES * 4 && local_lds_bytes(M, r->d, 1) <= 64 * 1024;
+}
+
+// Where the one-launch form is the faster way through torq_linear (measured against rotate + quantise
+// followed by the GEMM, HIP-graph replays over rotating weight copies): weights that one or two trips per
+// workgroup cover.  [1, 4096] x 14336: 12.0 -> 10.1 us, x 4096: 8.3 -> 5.5, x 1024: 7.5 -> 5.1,
+// [4, 4096] x 14336: 13.0 -> 11.4, [1, 14336] x 4096 (G = 112): 12.3 -> 11.1, [1, 8192] x 8192: 12.5 ->
+// 10.9, [1, 16384] x 5120: 18.1 -> 15.7; but [1, 8192] x 28672 (125 MB, four trips): 28.7 -> 30.1.
+bool torq_linear_local_pays(const torq_rotation *r, int64_t M, int64_t N) {
+  if (!torq_linear_local_fits(r, M) || N <= 0) return false;
+  return (double)N * (double)r->d * 0.53125 <= 48e6;
+}
+
+template <int NS, int PT>
+static hipError_t launch_local_cfg(const torq_rotation *r, const void *x_bf16, uint8_t *A_q, uint8_t *A_s,
+                                   const uint8_t *W_q, const uint8_t *W_s, void *out, int64_t M, int64_t N,
+                                   hipStream_t stream) {
+  const int d = r->d;
+  const int64_t groups = (N + 16 * NS - 1) / (16 * NS);
+  // as for the persistent GEMM: the smallest power of two of groups per workgroup that leaves at most
+  // 256 workgroups, so that every workgroup has the same share
+  int64_t per = 1;
+  while ((groups + per - 1) / per > 256) per *= 2;
+  const int64_t grid = (groups + per - 1) / per;
+  const bool exact = d % 256 == 0 && d / 256 == PT * WAVES;
+  auto kernel = exact ? torq_linear_local_kernel<NS, PT, true> : torq_linear_local_kernel<NS, PT, false>;
+  hipLaunchKernelGGL(kernel, dim3((unsigned)grid), dim3(64 * WAVES), local_lds_bytes(M, d, NS), stream,
+                     reinterpret_cast<const uint4 *>(x_bf16), (int)(M * (int64_t)(d / 32 / r->G)), r->G,
+                     reinterpret_cast<const uint4 *>(r->inter32f_hi), reinterpret_cast<const uint4 *>(r->inter32f_lo),
+                     reinterpret_cast<const uint4 *>(r->intra32_hi),
+                     reinterpret_cast<const uint4 *>(r->intra32_lo), A_q, A_s, W_q, W_s,
+                     reinterpret_cast<uint16_t *>(out), (int)M, N, d);
+  return hipGetLastError();
+}
+
+hipError_t launch_torq_linear_local(const torq_rotation *r, const void *x_bf16, uint8_t *A_q, uint8_t *A_s,
+                                    const uint8_t *W_q, const uint8_t *W_s, void *out, int64_t M, int64_t N,
+                                    hipStream_t stream) {
+  if (!torq_linear_local_fits(r, M) || N <= 0) return hipErrorInvalidValue;
+  // PT: the line pairs of a wave, so that one trip covers the k range (at most 8); NS: as many strips per
+  // workgroup as leave every CU a workgroup, within the registers (NS PT <= 8: 128 for the weight codes
+  // of a trip) and the LDS
+  const int pairs_per_wave = ((r->d / 128 + 1) / 2 + WAVES - 1) / WAVES;
+  const int PT = pairs_per_wave <= 8 ? pairs_per_wave : 8;
+  const int64_t strips = (N + 15) / 16;
+  int NS = 1;
+  while (NS < 4 && strips > 256 * NS && 2 * NS * PT <= 8 && local_lds_bytes(M, r->d, 2 * NS) <= 64 * 1024) NS *= 2;
+#define TORQ_LOCAL_CASE(NS_, PT_) \
+  if (NS == NS_ && PT == PT_) return launch_local_cfg<NS_, PT_>(r, x_bf16, A_q, A_s, W_q, W_s, out, M, N, stream);
+  TORQ_LOCAL_CASE(1, 1) TORQ_LOCAL_CASE(1, 2) TORQ_LOCAL_CASE(1, 3) TORQ_LOCAL_CASE(1, 4)
+  TORQ_LOCAL_CASE(1, 5) TORQ_LOCAL_CASE(1, 6) TORQ_LOCAL_CASE(1, 7) TORQ_LOCAL_CASE(1, 8)
+  TORQ_LOCAL_CASE(2, 1) TORQ_LOCAL_CASE(2, 2) TORQ_LOCAL_CASE(2, 3) TORQ_LOCAL_CASE(2, 4)
+  TORQ_LOCAL_CASE(4, 1) TORQ_LOCAL_CASE(4, 2)
+#undef TORQ_LOCAL_CASE
+  return hipErrorInvalidValue;
 }
 
 // every counter of a handle back to zero, the error word included (a fill kernel rather than a

@@ -13,6 +13,10 @@ struct torq_rotation {
   int device;        // device the tables live on
   // R_inter as bf16 hi and lo parts, [G][KS*32] row-major, zero-padded columns
   uint16_t *inter_hi, *inter_lo;
+  // 96 < G <= 128 only (else nullptr): the same values in the order in which the lanes of
+  // v_mfma_f32_32x32x16_bf16 take them as B operand, [tile 4][k-step 8][lane 64][8], zero past G, so that
+  // a wave's load of one operand is 1 KiB of consecutive bytes (rotate32_resident.h)
+  uint16_t *inter32f_hi, *inter32f_lo;
   // R_intra^T rows permuted for the accumulator layout, bf16 hi and lo, [32][32]
   uint16_t *intra_hi, *intra_lo;
   // the same matrix as the A operand of v_mfma_f32_32x32x16_bf16 (two k-steps), bf16 hi and lo
@@ -69,6 +73,15 @@ hipError_t launch_mxfp4_gemm_skinny(const uint8_t *A_q, const uint8_t *A_s, cons
 hipError_t launch_torq_linear_decode(const torq_rotation *r, const void *x_bf16, uint8_t *A_q, uint8_t *A_s,
                                      const uint8_t *W_q, const uint8_t *W_s, void *out, int64_t M, int64_t N,
                                      int spin_limit, int raise_ready, hipStream_t stream);
+// torq_linear for a few token-groups with rotate + quantise inside every workgroup of the GEMM's launch
+// (no hand-off between workgroups, the packed activations stay in LDS; workgroup 0 leaves a copy in
+// A_q / A_s).  torq_linear_local_fits: dense R_inter, G = 112 or 128, at most four token-groups.
+bool torq_linear_local_fits(const torq_rotation *r, int64_t M);
+// ... and is measured faster than the two launches (what torq_linear itself then does)
+bool torq_linear_local_pays(const torq_rotation *r, int64_t M, int64_t N);
+hipError_t launch_torq_linear_local(const torq_rotation *r, const void *x_bf16, uint8_t *A_q, uint8_t *A_s,
+                                    const uint8_t *W_q, const uint8_t *W_s, void *out, int64_t M, int64_t N,
+                                    hipStream_t stream);
 // all of the handle's counters back to zero, the sticky error word included
 hipError_t launch_decode_ctr_reset(const torq_rotation *r, hipStream_t stream);
 

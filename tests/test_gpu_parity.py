@@ -860,11 +860,18 @@ DECODE_CASES = [(1, 1024, 4096), (5, 4100, 4096), (16, 14336, 4096), (17, 1032, 
                 (64, 1040, 8192), (2, 520, 12288)]
 
 
-@pytest.mark.parametrize("M,N,d", DECODE_CASES)
+# Up to four token-groups (a row or two of a decode step) torq_linear_single_launch has no hand-off: every
+# workgroup rotates them itself into its LDS; up to three, torq_linear takes that launch too.  (d = 14336:
+# G = 112, four token-groups per row; d = 16384: four of G = 128.)
+LOCAL_CASES = [(1, 14336, 4096), (4, 4100, 4096), (3, 520, 4096), (2, 1032, 8192), (1, 4096, 14336),
+               (1, 1040, 16384), (1, 24, 4096), (1, 2048, 8192), (2, 4096, 4096)]
+
+
+@pytest.mark.parametrize("M,N,d", DECODE_CASES + LOCAL_CASES)
 def test_linear_decode_form_is_rotate_quantize_then_gemm(tq, oracle, M, N, d):
     # at most 64 rows: bit for bit the two-call chain, also on repeated and interleaved calls with
-    # one workspace
-    G = 128
+    # one workspace -- whichever kernels torq_linear takes for the shape
+    G = 128 if (d // 32) % 128 == 0 else 112
     x = synth.activations(M, d, nu=3.0, outliers=max(2, d // 200), outlier_scale=50.0, seed=1200 + M)
     Ri, Ra = synth.rotations(G, seed=5 + M)
     rot = tq.Rotation(d, G, Ri, Ra)
@@ -1001,9 +1008,9 @@ def test_rotate_random_shapes(tq, oracle, M, d, G):
 
 # ------------------------------------ torq_linear_single_launch (rotate + quantise inside the GEMM's launch) ----
 
-@pytest.mark.parametrize("M,N,d", DECODE_CASES)
+@pytest.mark.parametrize("M,N,d", DECODE_CASES + LOCAL_CASES)
 def test_linear_single_launch_against_chain_and_oracle(tq, oracle, M, N, d):
-    G = 128
+    G = 128 if (d // 32) % 128 == 0 else 112
     x = synth.activations(M, d, nu=3.0, outliers=max(2, d // 200), outlier_scale=50.0, seed=1400 + M)
     Ri, Ra = synth.rotations(G, seed=9 + M)
     rot = tq.Rotation(d, G, Ri, Ra)
@@ -1099,7 +1106,8 @@ def test_linear_single_launch_replays_from_a_hip_graph_and_rejects_what_it_canno
 def test_linear_single_launch_give_up_is_sticky_until_reset(tq):
     # The bounded wait, driven from the host: the rotating workgroups do their work but withhold the
     # hand-off, the multiplying workgroups poll 4 times and give up.  Every workgroup exits normally.
-    M, d, N, G = 3, 4096, 2048, 128
+    # (Six token-groups: with four or fewer the launch has no hand-off and no wait.)
+    M, d, N, G = 6, 4096, 2048, 128
     Ri, Ra = synth.rotations(G)
     rot = tq.Rotation(d, G, Ri, Ra)
     gen = torch.Generator(device=DEV)
