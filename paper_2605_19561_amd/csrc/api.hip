@@ -175,23 +175,21 @@ static int torq_rotation_create_impl(torq_rotation_t **out, int d, int G, const 
       }
     }
 
-  // R_inter as the B operand of v_mfma_f32_32x32x16_bf16 in lane order (96 < G <= 128): tile w, k-step
-  // ks, lane (col = l%32, h = l/32), slot j holds R_inter[32 w + col][16 ks + 8 h + j], zero past G
-  std::vector<uint16_t> fh, fl;
-  if (G > 96 && G <= 128) {
-    fh.assign(4 * 8 * 64 * 8, 0);
-    fl.assign(4 * 8 * 64 * 8, 0);
-    for (int w = 0; w < 4; ++w)
-      for (int ks = 0; ks < 8; ++ks)
-        for (int l = 0; l < 64; ++l)
-          for (int j = 0; j < 8; ++j) {
-            const int b = 32 * w + l % 32, bp = 16 * ks + 8 * (l / 32) + j;
-            if (b < G && bp < G) {
-              const size_t at = (((size_t)w * 8 + ks) * 64 + l) * 8 + j;
-              split_bf16(R_inter_host[(size_t)b * G + bp], &fh[at], &fl[at]);
-            }
+  // R_inter as the B operand of v_mfma_f32_32x32x16_bf16 in lane order: tile w < NW = ceil(G / 32),
+  // k-step ks < 2 NW, lane (col = l%32, h = l/32), slot j holds R_inter[32 w + col][16 ks + 8 h + j],
+  // zero past G
+  const int NW = KS;
+  std::vector<uint16_t> fh((size_t)NW * 2 * NW * 64 * 8, 0), fl((size_t)NW * 2 * NW * 64 * 8, 0);
+  for (int w = 0; w < NW; ++w)
+    for (int ks = 0; ks < 2 * NW; ++ks)
+      for (int l = 0; l < 64; ++l)
+        for (int j = 0; j < 8; ++j) {
+          const int b = 32 * w + l % 32, bp = 16 * ks + 8 * (l / 32) + j;
+          if (b < G && bp < G) {
+            const size_t at = (((size_t)w * 2 * NW + ks) * 64 + l) * 8 + j;
+            split_bf16(R_inter_host[(size_t)b * G + bp], &fh[at], &fl[at]);
           }
-  }
+        }
 
   const std::vector<unsigned> zero_ctr(DECODE_CTR_WORDS, 0u);
 
@@ -213,8 +211,8 @@ static int torq_rotation_create_impl(torq_rotation_t **out, int d, int G, const 
   if (e == hipSuccess) e = upload(&r->intra_lo, al);
   if (e == hipSuccess) e = upload(&r->intra32_hi, a32h);
   if (e == hipSuccess) e = upload(&r->intra32_lo, a32l);
-  if (e == hipSuccess && !fh.empty()) e = upload(&r->inter32f_hi, fh);
-  if (e == hipSuccess && !fl.empty()) e = upload(&r->inter32f_lo, fl);
+  if (e == hipSuccess) e = upload(&r->inter32f_hi, fh);
+  if (e == hipSuccess) e = upload(&r->inter32f_lo, fl);
   if (e == hipSuccess) e = upload(&r->decode_ctr, zero_ctr);
   if (e == hipSuccess) e = hipDeviceSynchronize();
   if (e != hipSuccess) {

@@ -778,7 +778,7 @@ static size_t local_lds_bytes(int64_t M, int d, int NS) {
 }
 
 bool torq_linear_local_fits(const torq_rotation *r, int64_t M) {
-  if (r->butterfly || !r->inter32f_hi || r->G <= 96 || r->G > 128 || r->G % 16 != 0 || r->d % 128 != 0) return false;
+  if (r->butterfly || r->G <= 96 || r->G > 128 || r->G % 16 != 0 || r->d % 128 != 0) return false;
   if (M < 1 || M > 16) return false;
   if (M * (int64_t)(r->d / 32 / r->G) > LOCAL_MAX_TG) return false;
   return (r->d / 128 + 1) / 2 <= 8 * WAVES * 4 && local_lds_bytes(M, r->d, 1) <= 64 * 1024;

@@ -99,17 +99,15 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
   const int lane = tid & 63, wave = tid >> 6;
   const int col = lane & 31, h = lane >> 5;
 
-  // ---- resident operands
+  // ---- resident operands: R_inter from the handle's table in lane order ([tile][k-step 2 NW][lane][8],
+  // zeros for the block rows and columns past G), one load of a wave = 1 KiB of consecutive bytes
   bf16x8 Bh[KS16], Bl[KS16];
   {
-    const int b = 32 * wave + col;
-    const bool row = !ODD || b < 16 * KS16;          // the table has G rows of 32 NW entries (zero padded)
+    const uint4 *fh = reinterpret_cast<const uint4 *>(inter_hi), *fl = reinterpret_cast<const uint4 *>(inter_lo);
 #pragma unroll
     for (int ks = 0; ks < KS16; ++ks) {
-      const size_t off = (size_t)(row ? b : 0) * (32 * NW) + 16 * ks + 8 * h;
-      Bh[ks] = *reinterpret_cast<const bf16x8 *>(inter_hi + off);
-      Bl[ks] = *reinterpret_cast<const bf16x8 *>(inter_lo + off);
-      if (ODD && !row) Bh[ks] = Bl[ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+      Bh[ks] = __builtin_bit_cast(bf16x8, fh[(wave * 2 * NW + ks) * 64 + lane]);
+      Bl[ks] = __builtin_bit_cast(bf16x8, fl[(wave * 2 * NW + ks) * 64 + lane]);
     }
   }
   bf16x8 Ah[2], Al[2];
@@ -381,13 +379,15 @@ rotate_ring_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
   const int b = 32 * wave + col;                     // this lane's block row inside a token-group
   const bool live = !ODD || b < 16 * KS16;
 
+  // R_inter from the handle's table in lane order (zeros for the block rows past G)
   bf16x8 Bh[KS16], Bl[KS16];
+  {
+    const uint4 *fh = reinterpret_cast<const uint4 *>(inter_hi), *fl = reinterpret_cast<const uint4 *>(inter_lo);
 #pragma unroll
-  for (int ks = 0; ks < KS16; ++ks) {
-    const size_t off = (size_t)(live ? b : 0) * (32 * NW) + 16 * ks + 8 * h;
-    Bh[ks] = *reinterpret_cast<const bf16x8 *>(inter_hi + off);
-    Bl[ks] = *reinterpret_cast<const bf16x8 *>(inter_lo + off);
-    if (ODD && !live) Bh[ks] = Bl[ks] = bf16x8{0, 0, 0, 0, 0, 0, 0, 0};
+    for (int ks = 0; ks < KS16; ++ks) {
+      Bh[ks] = __builtin_bit_cast(bf16x8, fh[(wave * 2 * NW + ks) * 64 + lane]);
+      Bl[ks] = __builtin_bit_cast(bf16x8, fl[(wave * 2 * NW + ks) * 64 + lane]);
+    }
   }
   bf16x8 Ah[2], Al[2];
 #pragma unroll
@@ -577,22 +577,22 @@ rotate_ring_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
   switch (z_out ? FMT_NONE : format) {                                                                          \
     case FMT_NONE:                                                                                              \
       hipLaunchKernelGGL((KERNEL_<__VA_ARGS__, FMT_NONE>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream, \
-                         reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,        \
+                         reinterpret_cast<const uint4 *>(x), TG, r->G, ri_hi, ri_lo, ih, il,                    \
                          (CODES_T_ *)nullptr, (uint8_t *)nullptr, z_out, 1.0f);                                 \
       break;                                                                                                    \
     case FMT_MXFP4:                                                                                             \
       hipLaunchKernelGGL((KERNEL_<__VA_ARGS__, FMT_MXFP4>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream, \
-                         reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,        \
+                         reinterpret_cast<const uint4 *>(x), TG, r->G, ri_hi, ri_lo, ih, il,                    \
                          reinterpret_cast<CODES_T_ *>(codes), scales, (float *)nullptr, 1.0f);                  \
       break;                                                                                                    \
     case FMT_MXINT4:                                                                                            \
       hipLaunchKernelGGL((KERNEL_<__VA_ARGS__, FMT_MXINT4>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream, \
-                         reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,        \
+                         reinterpret_cast<const uint4 *>(x), TG, r->G, ri_hi, ri_lo, ih, il,                    \
                          reinterpret_cast<CODES_T_ *>(codes), scales, (float *)nullptr, 1.0f);                  \
       break;                                                                                                    \
     case FMT_NVFP4:                                                                                             \
       hipLaunchKernelGGL((KERNEL_<__VA_ARGS__, FMT_NVFP4>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream, \
-                         reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il,        \
+                         reinterpret_cast<const uint4 *>(x), TG, r->G, ri_hi, ri_lo, ih, il,                    \
                          reinterpret_cast<CODES_T_ *>(codes), scales, (float *)nullptr, global_scale);          \
       break;                                                                                                    \
     default: return hipErrorInvalidValue;                                                                       \
@@ -625,6 +625,7 @@ static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG
   const int64_t grid = balanced_grid(nbatch, per_cu);
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
+  const uint16_t *ri_hi = r->inter32f_hi, *ri_lo = r->inter32f_lo;      // the table in lane order
   TORQ_LAUNCH_FMT(rotate_kernel32, uint2, KS16, TB)
 }
 
@@ -638,7 +639,7 @@ static hipError_t launch_ring32(const torq_rotation *r, const void *x, int64_t T
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
 #define TORQ_RING_LAUNCH(FMT_, GS_)                                                                                  \
   hipLaunchKernelGGL((rotate_ring_kernel32<KS16, FMT_>), dim3((unsigned)grid), dim3(64 * nw), 0, stream,               \
-                     reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter_hi, r->inter_lo, ih, il, codes, scales, GS_)
+                     reinterpret_cast<const uint4 *>(x), TG, r->G, r->inter32f_hi, r->inter32f_lo, ih, il, codes, scales, GS_)
   switch (format) {
     case FMT_MXFP4: TORQ_RING_LAUNCH(FMT_MXFP4, 1.0f); break;
     case FMT_MXINT4: TORQ_RING_LAUNCH(FMT_MXINT4, 1.0f); break;
@@ -669,6 +670,7 @@ static hipError_t launch_cfg(const torq_rotation *r, const void *x, int64_t TG, 
   if (grid > nbatch) grid = nbatch;
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra_lo);
+  const uint16_t *ri_hi = r->inter_hi, *ri_lo = r->inter_lo;            // the row-major table
   TORQ_LAUNCH_FMT(rotate_kernel, uint32_t, KS, NT)
 }
 #undef TORQ_LAUNCH_FMT
@@ -723,7 +725,7 @@ hipError_t launch_rotate_ablated(const torq_rotation *r, const void *x, int64_t 
 #define TORQ_ABLATE(S_)                                                                                             \
   case S_:                                                                                                          \
     hipLaunchKernelGGL((rotate_ring_kernel32<8, FMT_MXFP4, S_>), dim3((unsigned)grid), dim3(256), 0, stream,         \
-                       reinterpret_cast<const uint4 *>(x), TG, 128, r->inter_hi, r->inter_lo, ih, il, codes, scales, \
+                       reinterpret_cast<const uint4 *>(x), TG, 128, r->inter32f_hi, r->inter32f_lo, ih, il, codes, scales, \
                        1.0f);                                                                                       \
     break;
     TORQ_ABLATE(0) TORQ_ABLATE(1) TORQ_ABLATE(2) TORQ_ABLATE(4) TORQ_ABLATE(6) TORQ_ABLATE(8) TORQ_ABLATE(9) TORQ_ABLATE(15)

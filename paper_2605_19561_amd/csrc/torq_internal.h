@@ -13,9 +13,9 @@ struct torq_rotation {
   int device;        // device the tables live on
   // R_inter as bf16 hi and lo parts, [G][KS*32] row-major, zero-padded columns
   uint16_t *inter_hi, *inter_lo;
-  // 96 < G <= 128 only (else nullptr): the same values in the order in which the lanes of
-  // v_mfma_f32_32x32x16_bf16 take them as B operand, [tile 4][k-step 8][lane 64][8], zero past G, so that
-  // a wave's load of one operand is 1 KiB of consecutive bytes (rotate32_resident.h)
+  // the same values in the order in which the lanes of v_mfma_f32_32x32x16_bf16 take them as B operand,
+  // [tile NW = ceil(G/32)][k-step 2 NW][lane 64][8], zero past G, so that a wave's load of one operand is
+  // 1 KiB of consecutive bytes (from the row-major table it touches 32 cache lines)
   uint16_t *inter32f_hi, *inter32f_lo;
   // R_intra^T rows permuted for the accumulator layout, bf16 hi and lo, [32][32]
   uint16_t *intra_hi, *intra_lo;
