@@ -212,10 +212,8 @@ int torq_linear_static(const torq_rotation_t *r, const void *x_bf16, const uint8
  * (2) Otherwise, up to 64 rows, G = 128, a dense R_inter: the first workgroups rotate and quantise one
  *     token-group each while the others, one per strip of weight rows, already have their weight scales
  *     and codes on the way and wait for the activations at a counter in device memory.
- *     The packed activations are left in the workspace as by torq_linear; they
- * come from the 16-block rotation kernel, so a value that sits within the rotation's error bar of a
- * rounding boundary may get the neighbouring code of torq_rotate_quantize's; the product is exactly
- * mxfp4_gemm of those codes.  Every workgroup exits: the wait is bounded.  A workgroup whose wait runs
+ *     The packed activations are left in the workspace as by torq_linear: torq_rotate_quantize's codes
+ * and scale bytes, bit for bit, and the product is mxfp4_gemm of them.  Every workgroup exits: the wait is bounded.  A workgroup whose wait runs
  * out writes NaN to its outputs and raises an error word among the handle's counters that no launch
  * clears: from then on every launch of form (2) on that handle writes NaN to all of `out`
  * (the counters of the failed launch cannot be trusted any more) until

@@ -43,7 +43,7 @@ constexpr int OOB_VOFF = 0x7FFFFFF0;
 struct DecodeArgs {
   const uint4 *x;
   int64_t TG;
-  const uint16_t *inter_hi, *inter_lo;
+  const uint4 *inter_hi, *inter_lo;            // R_inter in lane order, R_intra as the 32x32x16 operand
   const uint4 *intra_hi_frag, *intra_lo_frag;
   uint8_t *A_q, *A_s;          // written by the first P workgroups, read by the others
   int P;
@@ -255,7 +255,8 @@ __device__ __forceinline__ void decode_consumer_done(unsigned *ctr, int gid, int
 // torq_linear_single_launch: torq_linear for decode sizes in ONE launch (Algorithm 3, steps 1-4 and
 // "Return").  With a few
 // rows, rotate + quantise is a latency of 4-5 us in front of a GEMM of 4-30 us; here it runs in the
-// first P workgroups of the GEMM's own launch (rotate16_body, one batch of token-groups each) while
+// first P workgroups of the GEMM's own launch (rotate32_resident, one token-group each: the codes are
+// torq_rotate_quantize's, bit for bit) while
 // the others, one per weight strip as in mxfp4_gemm_skinny_kernel, already have their scale bytes and
 // the first trip of their weight codes on the way.  The two meet at counters in device memory
 // (DECODE_CTR_WORDS words, one counter per 128-byte line: read-modify-writes of one address from
@@ -283,8 +284,8 @@ __device__ __forceinline__ void decode_consumer_done(unsigned *ctr, int gid, int
 // counters must not overlap.
 template <int MT, int NS, int PT>
 __global__ void __launch_bounds__(64 * WAVES, 4)
-torq_linear_decode_kernel(const uint4 *__restrict__ x, int64_t TG, const uint16_t *__restrict__ inter_hi,
-                          const uint16_t *__restrict__ inter_lo, const uint4 *__restrict__ intra_hi_frag,
+torq_linear_decode_kernel(const uint4 *__restrict__ x, int64_t TG, const uint4 *__restrict__ inter_hi,
+                          const uint4 *__restrict__ inter_lo, const uint4 *__restrict__ intra_hi_frag,
                           const uint4 *__restrict__ intra_lo_frag, uint8_t *__restrict__ A_q,
                           uint8_t *__restrict__ A_s, const uint8_t *__restrict__ W_q,
                           const uint8_t *__restrict__ W_s, uint16_t *__restrict__ out, int M, int64_t N, int d,
@@ -292,9 +293,23 @@ torq_linear_decode_kernel(const uint4 *__restrict__ x, int64_t TG, const uint16_
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   if ((int)blockIdx.x < P) {
-    rotate16_body<4, 1, FMT_MXFP4, 1, true>(x, TG, 128, inter_hi, inter_lo, intra_hi_frag, intra_lo_frag,
-                                            reinterpret_cast<uint32_t *>(A_q), A_s, nullptr, 1.0f,
-                                            reinterpret_cast<char *>(smem), blockIdx.x, P);
+    {
+      // codes and scale bytes are stored through to device-coherent memory (what an atomic store of device
+      // scope does), for the readers in the other workgroups of this launch
+      struct CoherentSink {
+        unsigned long long *codes;
+        uint8_t *scales;
+        int64_t first_block;
+        __device__ __forceinline__ void operator()(int64_t blk, int h, uint2 packed, uint32_t byte) const {
+          const int64_t b = first_block + blk;
+          __hip_atomic_store(&codes[b * 2 + h], ((unsigned long long)packed.y << 32) | packed.x, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+          if (h == 0) __hip_atomic_store(&scales[b], (uint8_t)byte, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      } sink{reinterpret_cast<unsigned long long *>(A_q), A_s, (int64_t)blockIdx.x * 128};
+      rotate32_resident(x + (int64_t)blockIdx.x * 512, 1, 128, inter_hi, inter_lo, intra_hi_frag, intra_lo_frag,
+                        reinterpret_cast<char *>(smem), sink, []() {});
+    }
     __builtin_amdgcn_s_waitcnt(0);                 // this lane's stores have been acknowledged
     __syncthreads();
     if (tid == 0) {
@@ -641,9 +656,9 @@ static hipError_t launch_cfg(const uint8_t *A_q, const uint8_t *A_s, const uint8
   const size_t red_bytes = (size_t)(WAVES - 1) * NS * MT * 4 * 64 * sizeof(float);
   size_t lds_bytes = scale_bytes > red_bytes ? scale_bytes : red_bytes;
   if (fused) {
-    // + the "ready" word behind the scales; at least the rotation's two staging buffers
+    // + the "ready" word behind the scales; at least the rotation's four token-group places
     lds_bytes = lds_bytes > scale_bytes + 16 ? lds_bytes : scale_bytes + 16;
-    const size_t rot_bytes = 2 * (size_t)RotCfg<4>::TG_LDS_BYTES;
+    const size_t rot_bytes = 4 * (size_t)RotCfg<4>::TG_LDS_BYTES;
     lds_bytes = lds_bytes > rot_bytes ? lds_bytes : rot_bytes;
     if (lds_bytes > SKINNY_MAX_LDS) return hipErrorInvalidValue;
     if (lds_bytes > 64 * 1024) {
@@ -754,10 +769,10 @@ hipError_t launch_torq_linear_decode(const torq_rotation *r, const void *x_bf16,
   DecodeArgs fz;
   fz.x = reinterpret_cast<const uint4 *>(x_bf16);
   fz.TG = M * (int64_t)(r->d / 32 / r->G);
-  fz.inter_hi = r->inter_hi;
-  fz.inter_lo = r->inter_lo;
-  fz.intra_hi_frag = reinterpret_cast<const uint4 *>(r->intra_hi);
-  fz.intra_lo_frag = reinterpret_cast<const uint4 *>(r->intra_lo);
+  fz.inter_hi = reinterpret_cast<const uint4 *>(r->inter32f_hi);
+  fz.inter_lo = reinterpret_cast<const uint4 *>(r->inter32f_lo);
+  fz.intra_hi_frag = reinterpret_cast<const uint4 *>(r->intra32_hi);
+  fz.intra_lo_frag = reinterpret_cast<const uint4 *>(r->intra32_lo);
   fz.A_q = A_q;
   fz.A_s = A_s;
   fz.P = (int)fz.TG;                               // one token-group per rotating workgroup

@@ -1034,6 +1034,9 @@ def test_linear_single_launch_against_chain_and_oracle(tq, oracle, M, N, d):
             outs.append((out.clone(), A_q, A_s))
     assert all(torch.equal(outs[0][k], outs[i][k]) for i in (2, 4) for k in range(3))      # deterministic
     out, A_q, A_s = outs[0]
+    # the codes and scale bytes are the rotate + quantise kernel's own, bit for bit
+    want_q, want_sc = tq.torq_rotate_quantize(rot, xd)
+    assert torch.equal(A_q, want_q) and torch.equal(A_s, want_sc)
     # (2) the codes against the oracle's rotate + quantise: differences only within the rotation's error
     # bar of a rounding boundary (codes) or of a power of two (scales)
     z = oracle.rotate(synth.bf16_bits(x), G, Ri, Ra)
