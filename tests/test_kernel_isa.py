@@ -70,3 +70,65 @@ def test_ring_loop_holds_exactly_the_counted_memory_instructions(ring_kernels):
         waits = [int(re.search(r"vmcnt\((\d+)\)", c).group(1)) for i, c in enumerate(code)
                  if "vmcnt(" in c and i > lds_loads[7]]
         assert waits[0] == 0 and sorted(waits[1:]) == [0, 4, 8, 12, 12, 12], (name, waits)
+
+
+# ---- torq_linear_local_kernel (mxfp4_gemm_skinny.hip): not correctness but the point of the kernel.  The
+# rotation's reads are issued ahead of the workgroup's weight reads and its LDS stores must wait for them
+# alone -- s_waitcnt vmcnt(N) with N >= the number of weight loads behind them.  A load that the compiler
+# moves under a condition, or a predicate on the weight loads, turns that into vmcnt(0): the rotation then
+# waits for the whole weight stream.  Checked on the full-trip (EXACT) instantiations.
+
+@pytest.fixture(scope="module")
+def local_kernels():
+    with tempfile.TemporaryDirectory() as tmp:
+        path = build.device_asm("mxfp4_gemm_skinny.hip", os.path.join(tmp, "skinny.s"))
+        text = open(path).read()
+    kernels, cur = {}, None
+    for line in text.splitlines():
+        m = re.match(r"^(_ZN4torq24torq_linear_local_kernel\w+):", line)
+        if m:
+            cur = m.group(1)
+            kernels[cur] = []
+            continue
+        if cur is None:
+            continue
+        code = line.split(";")[0].strip()
+        if code.startswith(".Lfunc_end"):
+            cur = None
+        elif code and not code.startswith("."):
+            kernels[cur].append(code)
+    meta = {}
+    for m in re.finditer(r"\.name:\s+(_ZN4torq24torq_linear_local_kernel\w+)\n(?:.*\n)*?\s+\.private_segment_fixed_size:\s+(\d+)", text):
+        meta[m.group(1)] = int(m.group(2))
+    return kernels, meta
+
+
+def test_local_kernel_rotation_waits_for_its_own_reads_only(local_kernels):
+    kernels, meta = local_kernels
+    seen = 0
+    for name, code in kernels.items():
+        assert meta.get(name, 0) == 0, f"{name}: spills to scratch memory"
+        m = re.search(r"ILi(\d+)ELi(\d+)ELb(\d)E", name)
+        ns, pt, exact = int(m.group(1)), int(m.group(2)), int(m.group(3))
+        if not exact:
+            continue
+        seen += 1
+        weight_loads = 2 * pt * ns
+        first_barrier = next(i for i, c in enumerate(code) if c.startswith("s_barrier"))
+        second_barrier = next(i for i, c in enumerate(code) if c.startswith("s_barrier") and i > first_barrier)
+        # between the waves' rendezvous and the barrier behind the LDS stores: the weight loads, all of them,
+        # in straight-line code, then the four stores of the token-groups, each behind a wait that leaves
+        # the weight loads in flight
+        span = code[first_barrier + 1:second_barrier]
+        assert not any(c.startswith("s_cbranch") for c in span), name
+        assert sum(c.startswith("buffer_load_dwordx4") for c in span) == weight_loads, name
+        stores = [i for i, c in enumerate(span) if c.startswith("ds_write_b128")]
+        assert len(stores) == 4, (name, len(stores))
+        waits = [int(re.search(r"vmcnt\((\d+)\)", c).group(1)) for c in span[:stores[-1]] if "vmcnt(" in c]
+        assert waits and min(waits) >= weight_loads, (name, waits, weight_loads)
+        # and ahead of the rendezvous: every read of the rotation (16 + 4 operand loads, 4 token-group loads)
+        head = code[:first_barrier]
+        assert sum(c.startswith("global_load_dwordx4") for c in head) == 20, name
+        assert sum(c.startswith("buffer_load_dwordx4") for c in head) == 4, name
+        assert not any("vmcnt(" in c for c in head[next(i for i, c in enumerate(head) if c.startswith("global_load_dwordx4")):]), name
+    assert seen >= 10
