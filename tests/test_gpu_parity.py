@@ -863,8 +863,10 @@ DECODE_CASES = [(1, 1024, 4096), (5, 4100, 4096), (16, 14336, 4096), (17, 1032, 
 # Up to four token-groups (a row or two of a decode step) torq_linear_single_launch has no hand-off: every
 # workgroup rotates them itself into its LDS; up to three, torq_linear takes that launch too.  (d = 14336:
 # G = 112, four token-groups per row; d = 16384: four of G = 128.)
+# d = 3584 and 7168 (G = 112) are not whole trips of the eight waves: the kernel's predicated form.
 LOCAL_CASES = [(1, 14336, 4096), (4, 4100, 4096), (3, 520, 4096), (2, 1032, 8192), (1, 4096, 14336),
-               (1, 1040, 16384), (1, 24, 4096), (1, 2048, 8192), (2, 4096, 4096)]
+               (1, 1040, 16384), (1, 24, 4096), (1, 2048, 8192), (2, 4096, 4096), (2, 1031, 4096),
+               (2, 600, 3584), (1, 2048, 7168), (1, 520, 12288)]
 
 
 @pytest.mark.parametrize("M,N,d", DECODE_CASES + LOCAL_CASES)
