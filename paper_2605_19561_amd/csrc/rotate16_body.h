@@ -1,12 +1,12 @@
 // Steps 1-4 of Algorithm 3 on v_mfma_f32_16x16x32_bf16 for one workgroup of 4 G / NT lanes: the body
-// of rotate_kernel (rotate_quant.hip), as a device function so that the single-launch form of
-// torq_linear (mxfp4_gemm_skinny.hip) can run it in its first workgroups.  The workgroup takes the
+// of rotate_kernel (rotate_quant.hip, G = 16 and 48), as a device function.  The workgroup takes the
 // batches first_batch, first_batch + batch_stride, ... of TB token-groups; `lds` is
 // 2 * TB * RotCfg<KS>::TG_LDS_BYTES bytes of dynamic LDS, 16-byte aligned; every lane of the workgroup
 // must call it (barriers inside).
 // TB: token-groups per batch (RotCfg<KS>::TB for throughput, 1 for the shortest path through one
-// token-group).  COHERENT: codes and scales are stored through to device-coherent memory (what an
-// atomic store of device scope does), for readers in other workgroups of the same launch.
+// token-group).
+// The two helpers at the top (the LDS pointer type of the transposing read, pack_bf16_rne) also serve
+// rotate32_resident.h.
 #pragma once
 #include "torq_device.h"
 
@@ -44,7 +44,7 @@ __device__ __forceinline__ uint32_t pack_bf16_rne(float a, float b) {
 }
 
 // FMT: FMT_NONE writes the rotated fp32 values, else the 4-bit format of step 4 (torq_device.h)
-template <int KS, int NT, int FMT, int TB = RotCfg<KS>::TB, bool COHERENT = false>
+template <int KS, int NT, int FMT, int TB = RotCfg<KS>::TB>
 __device__ __forceinline__ void rotate16_body(const uint4 *__restrict__ x, int64_t TG, int G,
                                               const uint16_t *__restrict__ inter_hi, const uint16_t *__restrict__ inter_lo,
                                               const uint4 *__restrict__ intra_hi_frag, const uint4 *__restrict__ intra_lo_frag,
@@ -191,13 +191,8 @@ __device__ __forceinline__ void rotate16_body(const uint4 *__restrict__ x, int64
           amax = fmaxf(amax, __shfl_xor(amax, 32));
           const uint32_t byte = e8m0_from_amax(amax);
           const uint32_t packed = (FMT == FMT_MXINT4) ? pack8_int4(zz, e8m0_inverse_f32(byte)) : pack8_e2m1(zz, e8m0_to_f32(byte));
-          if constexpr (COHERENT) {
-            __hip_atomic_store(&codes[blk * 4 + q], packed, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            if (q == 0) __hip_atomic_store(&scales[blk], (uint8_t)byte, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          } else {
-            codes[blk * 4 + q] = packed;
-            if (q == 0) scales[blk] = (uint8_t)byte;
-          }
+          codes[blk * 4 + q] = packed;
+          if (q == 0) scales[blk] = (uint8_t)byte;
         } else {
           float4 *o = reinterpret_cast<float4 *>(z_out + blk * 32 + 8 * q);
           o[0] = make_float4(zz[0], zz[1], zz[2], zz[3]);

@@ -174,14 +174,26 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- inter-block rotation: the butterfly over b = 32 j + b0 (all indices are literals after
-    // unrolling)
+    // unrolling).  Round k's NJ coefficients are c[k % 2]; those of round k + 1 are fetched (from LDS when
+    // G >= 128) BEFORE round k's arithmetic and nothing moves across the fences, so the read's latency
+    // passes behind 16 NJ multiply-adds instead of in front of every 16.
+#define TORQ_CF_FETCH(ROUND_)                                                                       \
+  _Pragma("unroll") for (int j = 0; j < NJ; ++j) c[(ROUND_) & 1][j] = cf((ROUND_) * NJ + j);         \
+  __builtin_amdgcn_sched_barrier(0);
+    // (MXINT4 and NVFP4 at G = 128 have no four registers to spare at 128 per lane: they fetch a round's
+    // coefficients where the round starts)
+    constexpr bool AHEAD = !(NJ == 4 && (FMT == FMT_MXINT4 || FMT == FMT_NVFP4));
+#define TORQ_CF_ROUND(K_) if constexpr (AHEAD) { TORQ_CF_FETCH((K_) + 1) } else { TORQ_CF_FETCH(K_) }
+    float c[2][NJ];
+    if constexpr (AHEAD) { TORQ_CF_FETCH(0) }
 #pragma unroll
     for (int m = 0; m < LJ; ++m) {                             // strides 32 hj: pairs of tiles
       const int hj = NJ >> (m + 1);
+      TORQ_CF_ROUND(m)
 #pragma unroll
       for (int j = 0; j < NJ; ++j)
         if ((j & hj) == 0) {
-          const float tp = cf(m * NJ + j), tq = cf(m * NJ + j + hj);
+          const float tp = c[m & 1][j], tq = c[m & 1][j + hj];
 #pragma unroll
           for (int r = 0; r < 16; ++r) {
             const float p = v[j][r], q = v[j + hj][r];
@@ -189,26 +201,39 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
             v[j + hj][r] = fmaf(tq, p, q);
           }
         }
+      __builtin_amdgcn_sched_barrier(0);
     }
+    TORQ_CF_ROUND(LJ)
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {                             // stride 16: lane n ^ 16
-      const float t = cf(LJ * NJ + j);
+      const float t = c[LJ & 1][j];
 #pragma unroll
       for (int r = 0; r < 16; ++r) v[j][r] = fmaf(t, swizzle_f32<0x401F>(v[j][r]), v[j][r]);
     }
+    __builtin_amdgcn_sched_barrier(0);
+    TORQ_CF_ROUND(LJ + 1)
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf((LJ + 1) * NJ + j), "row_mirror");            // stride 8
+    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], c[(LJ + 1) & 1][j], "row_mirror");               // stride 8
+    __builtin_amdgcn_sched_barrier(0);
+    TORQ_CF_ROUND(LJ + 2)
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf((LJ + 2) * NJ + j), "row_half_mirror");       // stride 4
+    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], c[(LJ + 2) & 1][j], "row_half_mirror");          // stride 4
+    __builtin_amdgcn_sched_barrier(0);
+    TORQ_CF_ROUND(LJ + 3)
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf((LJ + 3) * NJ + j), "quad_perm:[2,3,0,1]");   // stride 2
+    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], c[(LJ + 3) & 1][j], "quad_perm:[2,3,0,1]");      // stride 2
+    __builtin_amdgcn_sched_barrier(0);
+    TORQ_CF_ROUND(LJ + 4)
 #pragma unroll
-    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], cf((LJ + 4) * NJ + j), "quad_perm:[1,0,3,2]");   // stride 1
+    for (int j = 0; j < NJ; ++j) TORQ_FMAC16_DPP(v[j], c[(LJ + 4) & 1][j], "quad_perm:[1,0,3,2]");      // stride 1
+    __builtin_amdgcn_sched_barrier(0);
+#undef TORQ_CF_ROUND
+#undef TORQ_CF_FETCH
 
     // ---- the rows' sigma, then step 4
 #pragma unroll
     for (int j = 0; j < NJ; ++j) {
-      const float rs = cf((LJ + 5) * NJ + j);
+      const float rs = AHEAD ? c[(LJ + 5) & 1][j] : cf((LJ + 5) * NJ + j);
       float zz[16];
 #pragma unroll
       for (int r = 0; r < 16; ++r) zz[r] = v[j][r] * rs;
