@@ -406,6 +406,16 @@ int torq_diag_gemm_ablation(const uint8_t *A_q, const uint8_t *A_s, const uint8_
                             void *out_bf16, int64_t M, int64_t N, int d, int skip, void *stream);
 int torq_diag_rotate_ablation(const torq_rotation_t *r, const void *x_bf16, int64_t M, uint8_t *codes,
                               uint8_t *scales, int skip, void *stream);
+/* mxfp4_gemm's tiled kernel in its persistent form -- a workgroup takes several output tiles in turn and its
+ * k loop runs through the tile boundaries (the last two iterations of a tile request the first two of the
+ * workgroup's next one) -- on `workgroups` workgroups, whatever the shape.  mxfp4_gemm takes this form only
+ * from four tiles per compute unit on; this entry point exists so that tests can walk it over several tiles per
+ * workgroup on shapes small enough to check every output.  The result is mxfp4_gemm's, bit for bit.
+ *   tile        0: 256 x 256 output tile, 1: 256 x 128
+ *   d           a multiple of 1024; all five pointers 16-byte aligned; 1 <= workgroups <= 65536
+ * Anything else: TORQ_EINVAL / TORQ_EALIGN. */
+int torq_diag_gemm_persistent(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                              void *out_bf16, int64_t M, int64_t N, int d, int tile, int workgroups, void *stream);
 /* A plain device-to-device copy of n_bytes (a multiple of 16; src and dst 16-byte aligned, not
  * overlapping) by a kernel of this library, `torq::diag_copy_kernel`: it reads n_bytes and writes
  * n_bytes, nothing else, which makes it the yardstick for memory-traffic counters (run it in the same

@@ -21,7 +21,7 @@ EXPORTS = [
     "torq_linear_workspace_bytes_n", "torq_block_gram_workspace_bytes", "torq_block_gram", "torq_block_gram_positions",
     "torq_equalize_inter", "torq_code_histogram_workspace_bytes", "torq_code_histogram", "torq_intra_pair_scores",
     "torq_intra_best_angle", "torq_calibrate_intra", "torq_diag_mfma_burn", "torq_linear_static",
-    "torq_diag_copy", "torq_diag_gemm_ablation", "torq_diag_rotate_ablation", "torq_linear_single_launch_reset", "torq_linear_single_launch_gave_up", "torq_linear_single_launch_probe",
+    "torq_diag_copy", "torq_diag_gemm_ablation", "torq_diag_gemm_persistent", "torq_diag_rotate_ablation", "torq_linear_single_launch_reset", "torq_linear_single_launch_gave_up", "torq_linear_single_launch_probe",
 ]
 
 TORQ_OK, TORQ_EINVAL, TORQ_EALIGN, TORQ_EWORKSPACE, TORQ_EHIP, TORQ_ENODEVICE, TORQ_ECONVERGE = 0, -1, -2, -3, -4, -5, -6
@@ -120,6 +120,8 @@ def lib():
         L.torq_diag_mfma_burn.argtypes = [i32, vp, sz, i32, vp, vp]
         L.torq_diag_gemm_ablation.restype = i32
         L.torq_diag_gemm_ablation.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp]
+        L.torq_diag_gemm_persistent.restype = i32
+        L.torq_diag_gemm_persistent.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, i32, vp]
         L.torq_diag_rotate_ablation.restype = i32
         L.torq_diag_rotate_ablation.argtypes = [vp, vp, i64, vp, vp, i32, vp]
         L.torq_diag_copy.restype = i32
@@ -413,6 +415,18 @@ def torq_diag_gemm_ablation(A_q, A_s, W_q, W_s, out, skip: int, stream=None):
                                          _dev(W_q, torch.uint8, "W_q"), _dev(W_s, torch.uint8, "W_s"),
                                          _dev(out, torch.bfloat16, "out"), M, N, d, int(skip), _stream(stream)),
            "torq_diag_gemm_ablation")
+
+
+def torq_diag_gemm_persistent(A_q, A_s, W_q, W_s, tile: int, workgroups: int, out=None, stream=None):
+    """mxfp4_gemm on the persistent form of its tiled kernel with `workgroups` workgroups (see include/torq.h)."""
+    M, N, d = A_q.shape[0], W_q.shape[0], A_q.shape[1] * 2
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=A_q.device)
+    _check(lib().torq_diag_gemm_persistent(_dev(A_q, torch.uint8, "A_q"), _dev(A_s, torch.uint8, "A_s"),
+                                           _dev(W_q, torch.uint8, "W_q"), _dev(W_s, torch.uint8, "W_s"),
+                                           _dev(out, torch.bfloat16, "out"), M, N, d, int(tile), int(workgroups),
+                                           _stream(stream)), "torq_diag_gemm_persistent")
+    return out
 
 
 def torq_diag_rotate_ablation(rot, x_bf16, codes, scales, skip: int, stream=None):

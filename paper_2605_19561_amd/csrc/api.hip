@@ -742,6 +742,18 @@ int torq_diag_gemm_ablation(const uint8_t *A_q, const uint8_t *A_s, const uint8_
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 
+int torq_diag_gemm_persistent(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                              void *out_bf16, int64_t M, int64_t N, int d, int tile, int workgroups, void *stream) {
+  if (M <= 0 || N <= 0 || d <= 0 || d % 1024 != 0 || (tile != 0 && tile != 1) || workgroups < 1 || workgroups > 65536)
+    return TORQ_EINVAL;
+  if (!A_q || !A_s || !W_q || !W_s || !out_bf16) return TORQ_EINVAL;
+  if (misaligned(A_q) || misaligned(W_q) || misaligned(out_bf16) || misaligned(A_s) || misaligned(W_s)) return TORQ_EALIGN;
+  hipError_t e = torq::launch_mxfp4_gemm_persistent(A_q, A_s, W_q, W_s, out_bf16, M, N, d, tile, workgroups,
+                                                    (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return TORQ_EINVAL;
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
 int torq_diag_rotate_ablation(const torq_rotation_t *r, const void *x_bf16, int64_t M, uint8_t *codes,
                               uint8_t *scales, int skip, void *stream) {
   if (!r || M < 0 || skip < 0) return TORQ_EINVAL;

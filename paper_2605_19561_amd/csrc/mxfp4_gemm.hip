@@ -48,7 +48,15 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void *p, uint3
 // fragment and scale reads, 8: the barrier.
 // What is left out is never replaced by anything else: the loop then multiplies the operands that the
 // prologue staged, again and again, and the output is meaningless.  SKIP = 0 is the product.
-template <int WM, int WN, bool FULLK, bool SPLIT, bool DEEP = false, int SKIP = 0>
+// PERSIST (needs FULLK, no SPLIT, no DEEP, a k range of a multiple of four iterations): the workgroup takes
+// the tiles blockIdx.x, blockIdx.x + gridDim.x, ... and the k loop runs THROUGH the tile boundary.  The loop
+// requests operands two iterations ahead anyway (its last two iterations used to load data nobody reads);
+// here those requests go to the first two iterations of the workgroup's NEXT tile, so that after the
+// epilogue the next tile starts in the state the loop expects -- stage 0 and its scale bytes in LDS, the
+// second iteration in the staging registers, the first fragments read -- with no prologue and no wait for
+// memory.  The epilogue then may only use the LDS of stage 1 (a quarter of the tile at a time), and the
+// accumulators are cleared where it has read them.
+template <int WM, int WN, bool FULLK, bool SPLIT, bool DEEP = false, int SKIP = 0, bool PERSIST = false>
 __global__ void __launch_bounds__(256)
 mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A_s,
                   const uint8_t *__restrict__ W_q, const uint8_t *__restrict__ W_s,
@@ -66,19 +74,27 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
   constexpr int SSTAGE = ROWS * 16;
   extern __shared__ __attribute__((aligned(16))) char lds[];
 
-  // ---- which output tile: contiguous runs of tiles per XCD, groups of GEMM_GROUP_M tile rows
+  static_assert(!PERSIST || (FULLK && !SPLIT && !DEEP && SKIP == 0), "the persistent form is the plain full-k kernel");
+  // ---- which output tile: contiguous runs of tiles per XCD, groups of GEMM_GROUP_M tile rows.  seq: the
+  // position in launch order (the block index; PERSIST: + a multiple of the grid, itself a multiple of 8)
   const int total = tiles_m * tiles_n;
-  int lid = blockIdx.x;
-  if (total % 8 == 0) lid = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
-  const int width = GEMM_GROUP_M * tiles_n;
-  const int group = lid / width;
-  const int first_m = group * GEMM_GROUP_M;
-  const int gsz = (tiles_m - first_m < GEMM_GROUP_M) ? tiles_m - first_m : GEMM_GROUP_M;
-  const int tm = first_m + (lid % width) % gsz;
-  const int tn = (lid % width) / gsz;
-  const int64_t m0 = (int64_t)tm * BM, n0 = (int64_t)tn * BN;
-  const int rows_a = (M - m0 < BM) ? (int)(M - m0) : BM;
-  const int rows_w = (N - n0 < BN) ? (int)(N - n0) : BN;
+  int64_t m0, n0;
+  int rows_a, rows_w;
+  auto tile_at = [&](int seq, int64_t &tm0, int64_t &tn0, int &ra, int &rw) {
+    int lid = seq;
+    if (total % 8 == 0) lid = (seq % 8) * (total / 8) + seq / 8;
+    const int width = GEMM_GROUP_M * tiles_n;
+    const int group = lid / width;
+    const int first_m = group * GEMM_GROUP_M;
+    const int gsz = (tiles_m - first_m < GEMM_GROUP_M) ? tiles_m - first_m : GEMM_GROUP_M;
+    const int tm = first_m + (lid % width) % gsz;
+    const int tn = (lid % width) / gsz;
+    tm0 = (int64_t)tm * BM;
+    tn0 = (int64_t)tn * BN;
+    ra = (M - tm0 < BM) ? (int)(M - tm0) : BM;
+    rw = (N - tn0 < BN) ? (int)(N - tn0) : BN;
+  };
+  tile_at(blockIdx.x, m0, n0, rows_a, rows_w);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wy = wave >> 1, wx = wave & 1;
@@ -88,13 +104,15 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
   // Iterations past the end (the pipeline always loads two ahead) wrap around to a valid k.
   const int kt_count = SPLIT ? KT / (int)gridDim.y : ((KT + 1) & ~1);   // even; odd KT only without FULLK
   const int kt0 = SPLIT ? (int)blockIdx.y * kt_count : 0;
-#define PHYS_KT(KT_) (FULLK ? (((KT_) + kt0) % KT) : (KT_))
+#define PHYS_KT(KT_) (PERSIST ? ((KT_) + l_kt_off) : FULLK ? (((KT_) + kt0) % KT) : (KT_))
 
-  // ---- global side: buffer resources over this tile's rows; reads past them return 0
-  const __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(A_q + m0 * row_bytes, (uint32_t)rows_a * row_bytes);
-  const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(W_q + n0 * row_bytes, (uint32_t)rows_w * row_bytes);
-  const __amdgpu_buffer_rsrc_t as_rsrc = make_rsrc(A_s + m0 * srow_bytes, (uint32_t)rows_a * srow_bytes);
-  const __amdgpu_buffer_rsrc_t ws_rsrc = make_rsrc(W_s + n0 * srow_bytes, (uint32_t)rows_w * srow_bytes);
+  // ---- global side: buffer resources over the rows of the tile that is being LOADED (PERSIST: the next
+  // tile's during the last two iterations of a tile); reads past them return 0
+  __amdgpu_buffer_rsrc_t a_rsrc = make_rsrc(A_q + m0 * row_bytes, (uint32_t)rows_a * row_bytes);
+  __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(W_q + n0 * row_bytes, (uint32_t)rows_w * row_bytes);
+  __amdgpu_buffer_rsrc_t as_rsrc = make_rsrc(A_s + m0 * srow_bytes, (uint32_t)rows_a * srow_bytes);
+  __amdgpu_buffer_rsrc_t ws_rsrc = make_rsrc(W_s + n0 * srow_bytes, (uint32_t)rows_w * srow_bytes);
+  int l_kt_off = 0;                                // PERSIST: - kt_count while the next tile is loaded
   // code chunk id = tid + 256 i: row = tid/8 + 32 i, chunk = tid%8
   const int c_chunk = tid & 7, c_row = tid >> 3;
   const int c_voff = c_row * row_bytes + c_chunk * 16;   // + 32 i rows + 128 kt via the scalar offset
@@ -285,10 +303,90 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
     _Pragma("unroll") for (int n_ = 0; n_ < WM * WN / 2; ++n_) { SGB(SG_MFMA, 1) SGB(SG_DS_RD, 2) SGB(SG_VMEM_RD, 2) } \
     __builtin_amdgcn_sched_barrier(0);                                                            \
   }
-  // an odd KT (only without FULLK) gets one all-zero iteration
-  for (int kt = 0; kt < kt_count; kt += 2) {
-    ITER(0, kt);
-    ITER(1, kt + 1);
+  if constexpr (!PERSIST) {
+    // an odd KT (only without FULLK) gets one all-zero iteration
+    for (int kt = 0; kt < kt_count; kt += 2) {
+      ITER(0, kt);
+      ITER(1, kt + 1);
+    }
+  }
+  if constexpr (PERSIST) {
+    // ---- the workgroup's tiles, one after the other, the k loop running through the boundaries
+    constexpr int ROW_E = 64 * WN;               // bytes of one output row of a wave's piece
+    constexpr int PITCH_E = ROW_E + 16;
+    constexpr int CH_ROW = ROW_E / 16;           // 16-byte chunks per row
+    static_assert(2 * 32 * PITCH_E <= A_STAGE && 2 * 32 * PITCH_E <= W_STAGE, "two waves' quarter pieces per stage-1 buffer");
+    // stage 1 of the codes is dead once the last barrier of a tile's k loop has been passed (the loop's
+    // tail reads stage 0, which already holds the next tile): waves 0, 1 transpose through A's, 2, 3 through W's
+    const bool vec_ok = (N & 7) == 0;
+    for (int seq = blockIdx.x; seq < total; seq += gridDim.x) {
+      // the tile whose first two iterations this tile's last two request: the next one, or this one
+      // again (requests nobody reads, as in the plain kernel)
+      int64_t nm0 = m0, nn0 = n0;
+      int nra = rows_a, nrw = rows_w;
+      if (seq + (int)gridDim.x < total) tile_at(seq + gridDim.x, nm0, nn0, nra, nrw);
+      for (int kt = 0; kt < kt_count; kt += 2) {
+        if (kt == kt_count - 2) {                  // from here on the requests are the next tile's
+          a_rsrc = make_rsrc(A_q + nm0 * row_bytes, (uint32_t)nra * row_bytes);
+          w_rsrc = make_rsrc(W_q + nn0 * row_bytes, (uint32_t)nrw * row_bytes);
+          as_rsrc = make_rsrc(A_s + nm0 * srow_bytes, (uint32_t)nra * srow_bytes);
+          ws_rsrc = make_rsrc(W_s + nn0 * srow_bytes, (uint32_t)nrw * srow_bytes);
+          l_kt_off = -kt_count;
+        }
+        ITER(0, kt);
+        ITER(1, kt + 1);
+      }
+      l_kt_off = 0;
+
+      // ---- epilogue of the tile at (m0, n0), a quarter (32 rows per wave) at a time; see the plain
+      // kernel's for the layout.  The accumulators are cleared as they are read.
+      // (Its addresses are derived here from copies of the lane's coordinates that the compiler cannot see
+      // through: computed ahead of the tile loop they would stay live through the k loop, which has no
+      // register to spare.)
+      int lrow_e = lrow, g_e = g, lane_e = lane, wave_e = __builtin_amdgcn_readfirstlane(wave);
+      asm volatile("" : "+v"(lrow_e), "+v"(g_e), "+v"(lane_e), "+s"(wave_e));
+      const int wy_e = wave_e >> 1, wx_e = wave_e & 1;
+      char *const ep = lds + (wave_e < 2 ? A_STAGE : W_BASE + W_STAGE) + (wave_e & 1) * 32 * PITCH_E;
+#pragma unroll
+      for (int i = 0; i < WM; ++i) {
+#pragma unroll
+        for (int j = 0; j < WN; ++j)
+#pragma unroll
+          for (int rr = 0; rr < 4; ++rr) {
+            bf16x4 v;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              v[e] = (__bf16)acc[j][i][4 * rr + e];
+              acc[j][i][4 * rr + e] = 0.f;
+            }
+            *reinterpret_cast<bf16x4 *>(ep + lrow_e * PITCH_E + (32 * j + 8 * rr + 4 * g_e) * 2) = v;
+          }
+#pragma unroll
+        for (int t = 0; t < 32 * CH_ROW / 64; ++t) {
+          const int idx = t * 64 + lane_e;
+          const int row = idx / CH_ROW, ch = idx % CH_ROW;
+          const u32x4 v = *reinterpret_cast<const u32x4 *>(ep + row * PITCH_E + ch * 16);
+          const int64_t m = m0 + (wy_e * WM + i) * 32 + row;
+          const int64_t n = n0 + wx_e * WN * 32 + ch * 8;
+          if (m < M) {
+            uint16_t *dst = out + m * N + n;
+            if (vec_ok && n + 8 <= N) {
+              *reinterpret_cast<u32x4 *>(dst) = v;
+            } else {
+#pragma unroll
+              for (int e = 0; e < 8; ++e)
+                if (n + e < N) dst[e] = (uint16_t)(v[e >> 1] >> (16 * (e & 1)));
+            }
+          }
+        }
+      }
+      // every wave is done with stage 1 before the next tile's first iteration stores into it
+      __syncthreads();
+      m0 = nm0;
+      n0 = nn0;
+      rows_a = nra;
+      rows_w = nrw;
+    }
   }
 #undef ITER
 #undef SGB
@@ -298,7 +396,9 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
   // line of the output arrive in 16 separate partial writes, so the wave first transposes its
   // piece through LDS (free after the last barrier of the k loop; each wave uses a private
   // region) and then stores 16 bytes per lane with 8 adjacent lanes covering one full line.
-  if (SPLIT) {
+  if constexpr (PERSIST) {
+    // (stored tile by tile above)
+  } else if (SPLIT) {
     // fp32 sums of this k piece: 16 bytes per lane and register quad, straight from the accumulators
     float *const dstp = partial + (size_t)blockIdx.y * (size_t)M * (size_t)N;
 #pragma unroll
@@ -384,15 +484,44 @@ mxfp4_gemm_splitk_reduce_kernel(const float *__restrict__ partial, int splits, i
   *reinterpret_cast<u64x2 *>(out + e0) = u64x2{__builtin_bit_cast(uint64_t, a), __builtin_bit_cast(uint64_t, b)};
 }
 
-template <int WM, int WN, bool FULLK, bool SPLIT, bool DEEP = false, int SKIP = 0>
+// compute units of the current device (256 on this part), asked once
+static int compute_units() {
+  static int cus = 0;
+  if (cus == 0) {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && n > 0)
+      cus = n;
+    else
+      cus = 256;
+  }
+  return cus;
+}
+
+// Whether the persistent form (PERSIST above) takes the launch: more tiles than CUs, so that some
+// workgroup has a second tile to run into, and a k range of a multiple of four iterations.
+// Measured on the same machine against the plain form: [8192, 28672, 8192] (14 tiles per CU) 925 -> 909 us,
+// [4096, 25600, 5120] (6 per CU) 288.4 -> 283.5, [8192, 8192, 28672] (4 per CU) 868 -> 865; with two tiles
+// per CU or fewer nothing or a loss of 1 %.
+static bool persistent_pays(int64_t tiles, int d) { return tiles >= 4 * (int64_t)compute_units() && d % 1024 == 0; }
+
+template <int WM, int WN, bool FULLK, bool SPLIT, bool DEEP = false, int SKIP = 0, bool PERSIST = false>
 static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                               const uint8_t *W_s, void *out, float *partial, int splits, int64_t M, int64_t N,
-                              int d, hipStream_t stream) {
+                              int d, hipStream_t stream, int persist_grid = 0) {
   constexpr int BM = 64 * WM, BN = 64 * WN;
   const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
   if (tiles_m * tiles_n > 0x7FFFFFFF) return hipErrorInvalidValue;
   const size_t lds_bytes = 2 * (size_t)(BM + BN) * 128 + 2 * (size_t)((BM + BN + 255) / 256 * 256) * 16;
-  auto kern = mxfp4_gemm_kernel<WM, WN, FULLK, SPLIT, DEEP, SKIP>;
+  auto kern = mxfp4_gemm_kernel<WM, WN, FULLK, SPLIT, DEEP, SKIP, PERSIST>;
+  // PERSIST: one workgroup per CU, or persist_grid of them (a multiple of 8 where the tile count is one,
+  // so that a workgroup's tiles stay on its XCD's run)
+  int64_t grid = tiles_m * tiles_n;
+  if (PERSIST) {
+    const int64_t want = persist_grid > 0 ? persist_grid : compute_units();
+    grid = grid < want ? grid : want;
+    if ((tiles_m * tiles_n) % 8 == 0 && grid >= 8) grid -= grid % 8;
+  }
   if (lds_bytes > 64 * 1024) {
     // raise the dynamic LDS limit once per process and kernel variant (the call is slow)
     static bool raised = false;
@@ -403,7 +532,7 @@ static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint
       raised = true;
     }
   }
-  hipLaunchKernelGGL(kern, dim3((unsigned)(tiles_m * tiles_n), SPLIT ? splits : 1), dim3(256), lds_bytes, stream, A_q,
+  hipLaunchKernelGGL(kern, dim3((unsigned)grid, SPLIT ? splits : 1), dim3(256), lds_bytes, stream, A_q,
                      A_s, W_q, W_s, reinterpret_cast<uint16_t *>(out), partial, M, N, d, (int)tiles_m, (int)tiles_n);
   hipError_t e = hipGetLastError();
   if (!SPLIT || e != hipSuccess) return e;
@@ -525,12 +654,17 @@ hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8
   if (plan.deep && fullk && splits == 1)
     return launch_tile<2, 2, true, false, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream);
 #define TORQ_GEMM_LAUNCH(WM_, WN_)                                                                             \
+  if (splits == 1 && fullk && persistent_pays(((M + 64 * WM_ - 1) / (64 * WM_)) * ((N + 64 * WN_ - 1) / (64 * WN_)), d)) \
+    return launch_tile<WM_, WN_, true, false, false, 0, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream); \
   return splits > 1 ? launch_tile<WM_, WN_, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream) \
          : fullk    ? launch_tile<WM_, WN_, true, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream)     \
                     : launch_tile<WM_, WN_, false, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream);
   if (plan.cfg == 0) { TORQ_GEMM_LAUNCH(4, 4) }
   if (plan.cfg == 1) { TORQ_GEMM_LAUNCH(4, 2) }
-  TORQ_GEMM_LAUNCH(2, 2)
+  // (two workgroups of the 128 x 128 tile share a CU: the persistent form, one per CU, measured slower)
+  return splits > 1 ? launch_tile<2, 2, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream)
+         : fullk    ? launch_tile<2, 2, true, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream)
+                    : launch_tile<2, 2, false, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream);
 #undef TORQ_GEMM_LAUNCH
 }
 
@@ -546,6 +680,21 @@ hipError_t launch_mxfp4_gemm_ablated(const uint8_t *A_q, const uint8_t *A_s, con
 #undef TORQ_ABLATE
     default: return hipErrorInvalidValue;
   }
+}
+
+// torq_diag_gemm_persistent: the persistent form of the tiled kernel on `workgroups` workgroups, whatever
+// the shape (mxfp4_gemm only takes it from four tiles per CU on), so that its walk over several tiles per
+// workgroup can be checked output by output on small shapes.
+hipError_t launch_mxfp4_gemm_persistent(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                                        void *out_bf16, int64_t M, int64_t N, int d, int tile, int workgroups,
+                                        hipStream_t stream) {
+  if ((int64_t)d * 128 >= 0x7FFFFFFF || d % 1024 != 0 || workgroups < 1) return hipErrorInvalidValue;
+  if ((reinterpret_cast<uintptr_t>(A_s) & 15u) || (reinterpret_cast<uintptr_t>(W_s) & 15u)) return hipErrorInvalidValue;
+  if (tile == 0)
+    return launch_tile<4, 4, true, false, false, 0, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, workgroups);
+  if (tile == 1)
+    return launch_tile<4, 2, true, false, false, 0, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, workgroups);
+  return hipErrorInvalidValue;
 }
 
 }  // namespace torq

@@ -110,6 +110,10 @@ hipError_t launch_mfma_burn(int kind, const uint32_t *words, uint32_t n_words, i
 // what each part costs in time on this machine.  Outputs are meaningless by design.
 hipError_t launch_mxfp4_gemm_ablated(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
                                      void *out_bf16, int64_t M, int64_t N, int d, int skip, hipStream_t stream);
+// the persistent form of the tiled GEMM (tile 0: 256 x 256, 1: 256 x 128) on `workgroups` workgroups
+hipError_t launch_mxfp4_gemm_persistent(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                                        void *out_bf16, int64_t M, int64_t N, int d, int tile, int workgroups,
+                                        hipStream_t stream);
 hipError_t launch_rotate_ablated(const torq_rotation *r, const void *x, int64_t M, uint8_t *codes, uint8_t *scales,
                                  int skip, hipStream_t stream);
 // plain copy of `bytes` (a multiple of 16) device bytes, the traffic counters' yardstick (diag.hip)

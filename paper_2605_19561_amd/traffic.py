@@ -30,7 +30,7 @@ COPY_BYTES = 1 << 30
 
 # what bench.py's headline step launches: key -> (kernel name without spaces, grid size in work-items, sources)
 KERNELS = {
-    "mxfp4_gemm/llama3_70b_up": ("torq::mxfp4_gemm_kernel<4,4,true,false,false,0>", 32 * 112 * 256,
+    "mxfp4_gemm/llama3_70b_up": ("torq::mxfp4_gemm_kernel<4,4,true,false,false,0,true>", 256 * 256,
                                  ["mxfp4_gemm.hip", "torq_device.h"]),
     "torq_rotate_quantize/llama3_70b_up": ("torq::rotate_ring_kernel32<8,0,0>", 745 * 256,
                                            ["rotate_quant.hip", "rotate16_body.h", "torq_device.h"]),

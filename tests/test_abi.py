@@ -82,6 +82,11 @@ def test_compute_calls_reject_bad_arguments_without_launching():
     assert L.torq_diag_gemm_ablation(good, good, good, good, good, 256, 256, 768, 0, None) == binding.TORQ_EINVAL   # d % 512
     assert L.torq_diag_gemm_ablation(good, good, good, good, good, 256, 256, 1024, 2, None) == binding.TORQ_EINVAL  # unknown skip
     assert L.torq_diag_gemm_ablation(good, odd, good, good, good, 256, 256, 1024, 0, None) == binding.TORQ_EALIGN
+    assert L.torq_diag_gemm_persistent(good, good, good, good, good, 256, 256, 1536, 0, 8, None) == binding.TORQ_EINVAL   # d % 1024
+    assert L.torq_diag_gemm_persistent(good, good, good, good, good, 256, 256, 1024, 2, 8, None) == binding.TORQ_EINVAL   # unknown tile
+    assert L.torq_diag_gemm_persistent(good, good, good, good, good, 256, 256, 1024, 0, 0, None) == binding.TORQ_EINVAL   # no workgroups
+    assert L.torq_diag_gemm_persistent(good, good, good, good, None, 256, 256, 1024, 0, 8, None) == binding.TORQ_EINVAL
+    assert L.torq_diag_gemm_persistent(good, good, good, odd, good, 256, 256, 1024, 0, 8, None) == binding.TORQ_EALIGN
     assert L.torq_diag_rotate_ablation(None, good, 4, good, good, 0, None) == binding.TORQ_EINVAL
 
 

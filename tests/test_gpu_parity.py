@@ -264,6 +264,38 @@ def test_gemm_random_codes(tq, oracle, M, N, d):
     _assert_every_output_within_one_ulp(_bits(got), want)
 
 
+# The persistent form of the tiled kernel (a workgroup walks several output tiles, its k loop running through
+# the tile boundaries) on few workgroups, so that small shapes exercise what mxfp4_gemm only does from four
+# tiles per CU on: two to seven tiles per workgroup, uneven shares, ragged last tile rows and columns, a
+# tile count that is not a multiple of 8 (no XCD mapping), one tile per workgroup, more workgroups than
+# tiles, the shortest k range.  Every output against the oracle, and the bits of mxfp4_gemm.
+GEMM_PERSISTENT = [  # (M, N, d, tile, workgroups)
+    (1024, 1024, 1024, 0, 8), (1024, 1024, 1024, 0, 16), (1000, 1300, 1024, 0, 8), (1000, 1300, 2048, 0, 5),
+    (700, 2000, 1024, 0, 3), (512, 768, 3072, 0, 1), (1024, 1024, 1024, 1, 8), (900, 1100, 2048, 1, 16),
+    (300, 1030, 1024, 1, 7), (256, 256, 1024, 0, 64)]
+
+
+@pytest.mark.parametrize("M,N,d,tile,wgs", GEMM_PERSISTENT)
+def test_gemm_persistent_form_walks_tiles(tq, oracle, M, N, d, tile, wgs):
+    rng = np.random.default_rng(M + 3 * N + d + wgs)
+    A_q = rng.integers(0, 256, size=(M, d // 2), dtype=np.uint8)
+    W_q = rng.integers(0, 256, size=(N, d // 2), dtype=np.uint8)
+    A_s = rng.integers(118, 136, size=(M, d // 32), dtype=np.uint8)
+    W_s = rng.integers(110, 126, size=(N, d // 32), dtype=np.uint8)
+    want = oracle.gemm(A_q, A_s, W_q, W_s)
+    ops = [torch.from_numpy(a).to(DEV) for a in (A_q, A_s, W_q, W_s)]
+    out = torch.full((M, N), float("nan"), dtype=torch.bfloat16, device=DEV)      # every output must be written
+    tq.torq_diag_gemm_persistent(*ops, tile, wgs, out=out)
+    torch.cuda.synchronize()
+    assert _rel_fro(_bits(out), want) <= 1e-3
+    _assert_every_output_within_one_ulp(_bits(out), want)
+    assert torch.equal(out, tq.mxfp4_gemm(*ops))
+    # again into the same buffer (the accumulators are cleared by the epilogue: nothing may carry over)
+    tq.torq_diag_gemm_persistent(*ops, tile, wgs, out=out)
+    torch.cuda.synchronize()
+    assert torch.equal(out, tq.mxfp4_gemm(*ops))
+
+
 # Few activation rows (M <= 64) take the weight-streaming kernel: one MFMA k-step only, an odd
 # number of k-steps, more k than one trip of a wave covers, every count of 16-row activation tiles
 # with a ragged last one, N not a multiple of 16 or of 4, and enough weight rows (with M >= 8) for
