@@ -393,7 +393,8 @@ int torq_diag_mfma_burn(int kind, const void *operands, size_t n_bytes, int iter
  * each part costs (the kernels run at the board's power limit, so a part's cost is the time by which
  * the launch shortens without it, not its instruction count).  Operands, shapes and launch shape are
  * those of mxfp4_gemm's 256 x 256-tile kernel (d a multiple of 512, all five pointers 16-byte aligned)
- * and of torq_rotate_quantize at G = 128 (dense R_inter).  skip = 0 is the product kernel; with any
+ * and of torq_rotate_quantize at G = 128 (dense R_inter).  skip = 0 is the product kernel (the GEMM's in
+ * its plain form, one workgroup per tile, which mxfp4_gemm runs below four tiles per compute unit); with any
  * other value the OUTPUT IS MEANINGLESS (every access stays within the same buffers).
  *   torq_diag_gemm_ablation    skip: 1 no buffer loads in the k loop (it multiplies what the prologue
  *                              staged); 3 also no LDS stores; 7 also no fragment reads (MFMAs and the
