@@ -181,7 +181,6 @@ def main():
                      "traffic": gemm_traffic, "traffic_stale": gemm_stale,
                      "avg_kernel_ms": round(gemm_ms, 4),
                      "sustained_mfma_only": round(sustained[tq.TORQ_DIAG_FP4], 1),
-                     "frac_of_sustained": round(gemm_tflops / sustained[tq.TORQ_DIAG_FP4], 4),
                      "board": gemm_env},
         "roofline_rotate_quant": {"kernel": "torq_rotate_quantize", "bound": "hbm", "achieved": round(rq_gbs, 1),
                                   "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(rq_gbs / HBM_PEAK_GBS, 4),
