@@ -47,6 +47,13 @@ def test_static_scratch_entry_point_matches_torq_linear(tq):
         m_max -= 1
     got3, want3 = _case(tq, rot, W_q, W_s, m_max, d, N, seed=33)
     assert torch.equal(got3.view(torch.int16), want3.view(torch.int16))
+    # two rows of a decode step: both entry points take ONE launch there (every workgroup rotates the rows itself);
+    # checked against torq_linear and against the two separate calls
+    got4, want4 = _case(tq, rot, W_q, W_s, 2, d, N, seed=34)
+    assert torch.equal(got4.view(torch.int16), want4.view(torch.int16))
+    x4 = synth.activations(2, d, nu=3.0, outliers=8, outlier_scale=50.0, seed=34).to(DEV)
+    chain = tq.mxfp4_gemm(*tq.torq_rotate_quantize(rot, x4), W_q, W_s)
+    assert torch.equal(got4.view(torch.int16), chain.view(torch.int16))
     x = torch.zeros((m_max + 1, d), dtype=torch.bfloat16, device=DEV)
     out = torch.zeros((m_max + 1, N), dtype=torch.bfloat16, device=DEV)
     with pytest.raises(tq.TorqError) as err:
