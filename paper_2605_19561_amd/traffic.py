@@ -4,11 +4,11 @@ Two counter runs of one program of this library (bench.py --headline-only --cali
 `--pmc FETCH_SIZE` and one with `--pmc WRITE_SIZE` (KiB per dispatch), each also holding launches of
 the library's plain copy kernel (torq_diag_copy) of a known size:
 
-    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d gpurun_out/prof/fetch -o p -- \
+    rocprofv3 --pmc FETCH_SIZE --kernel-trace --output-format csv -d prof/fetch -o p -- \
         python3 bench.py --headline-only --calibrate-copy --no-cpu-baseline --no-board-sample --steps 5 --warmup 2
-    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d gpurun_out/prof/write -o p -- \
+    rocprofv3 --pmc WRITE_SIZE --kernel-trace --output-format csv -d prof/write -o p -- \
         python3 bench.py --headline-only --calibrate-copy --no-cpu-baseline --no-board-sample --steps 5 --warmup 2
-    python3 -m paper_2605_19561_amd.traffic --fetch gpurun_out/prof/fetch --write gpurun_out/prof/write
+    python3 -m paper_2605_19561_amd.traffic --fetch prof/fetch --write prof/write
 
 The copy kernel reads COPY_BYTES and writes COPY_BYTES; bytes = counter * 1024 * (COPY_BYTES / (1024 *
 the counter's value for the copy)).  bench.py reads the file and calls its figures stale when the kernel
