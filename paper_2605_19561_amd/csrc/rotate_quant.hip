@@ -301,7 +301,7 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
 }
 
 // ---------------------------------------------------------------------------
-// The same kernel for G = 96, 112, 128 with THREE LDS buffers, filled two batches ahead (quantising
+// The same kernel for G = 80, 96, 112, 128 with THREE LDS buffers, filled two batches ahead (quantising
 // formats only; the fp32 output of torq_rotate stays with rotate_kernel32).  With two buffers the next
 // batch can only be requested once every wave has read the current one, which leaves the request about a
 // third of an iteration to land; with three it is requested a whole iteration earlier, at the top of the
@@ -634,7 +634,8 @@ static hipError_t launch_ring32(const torq_rotation *r, const void *x, int64_t T
                                 uint8_t *codes, uint8_t *scales, hipStream_t stream) {
   const int nw = (KS16 + 1) / 2;
   const int64_t nbatch = (TG + 1) / 2;
-  const int64_t grid = balanced_grid(nbatch, 3);     // 3 x <= 48 KiB of LDS, 12 waves of <= 160 registers
+  // 3 x <= 48 KiB of LDS, 12 waves of <= 160 registers (G = 80: 4 x 36 KiB, 12 waves of three per workgroup)
+  const int64_t grid = balanced_grid(nbatch, KS16 == 5 ? 4 : 3);
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
 #define TORQ_RING_LAUNCH(FMT_, GS_)                                                                                  \
@@ -683,11 +684,15 @@ hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, 
   // a handful of token-groups at G = 128 or 112 (decode): one per workgroup
   if (r->G == 128 && TG <= 128) return launch_cfg32<8, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
   if (r->G == 112 && TG <= 128) return launch_cfg32<7, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
-  // quantising, G = 96, 112, 128: the three-buffer form of the 32x32x16 kernel
+  // quantising, G = 80 ... 128: the three-buffer form of the 32x32x16 kernel
   if (!z_out) {
     if (r->G == 128) return launch_ring32<8>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
     if (r->G == 112) return launch_ring32<7>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
     if (r->G == 96) return launch_ring32<6>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
+    // G = 80 from eight batches per workgroup on (X [4096, 25600]: 72 -> 69 us, [16384, 5120]: 57.5 -> 55.6;
+    // with four, X [4096, 5120], the two batches requested ahead of the loop cost more than the ring saves)
+    if (r->G == 80 && TG >= 2 * 8 * 4 * 256)
+      return launch_ring32<5>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
   }
   // G a multiple of 32, or 16 * odd from 80 up: the 32x32x16 kernel (with a half-empty last tile).
   // Measured on X [16384, d] against the 16x16x32 kernel: G = 112 gains 7 - 9 %, G = 80 3 - 7 % (at
