@@ -685,14 +685,15 @@ hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, 
   if (r->G == 128 && TG <= 128) return launch_cfg32<8, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
   if (r->G == 112 && TG <= 128) return launch_cfg32<7, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
   // quantising, G = 80 ... 128: the three-buffer form of the 32x32x16 kernel
-  if (!z_out) {
+  // ... from eight batches per workgroup on: below, the two batches requested ahead of the loop cost more
+  // than the ring saves (same machine, ring against two buffers: X [4096, 4096] 18.7 against 17.3 us,
+  // [1024, 4096] 8.8 against 8.2, [2048, 14336] 27.1 against 25.5, [4096, 5120] 18.2 against 17.3; equal at
+  // [8192, 4096]; from [16384, 4096] on the ring wins, 45.7 against 49.6 us there)
+  if (!z_out && TG >= 2 * 8 * 3 * 256) {
     if (r->G == 128) return launch_ring32<8>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
     if (r->G == 112) return launch_ring32<7>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
     if (r->G == 96) return launch_ring32<6>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
-    // G = 80 from eight batches per workgroup on (X [4096, 25600]: 72 -> 69 us, [16384, 5120]: 57.5 -> 55.6;
-    // with four, X [4096, 5120], the two batches requested ahead of the loop cost more than the ring saves)
-    if (r->G == 80 && TG >= 2 * 8 * 4 * 256)
-      return launch_ring32<5>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
+    if (r->G == 80) return launch_ring32<5>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
   }
   // G a multiple of 32, or 16 * odd from 80 up: the 32x32x16 kernel (with a half-empty last tile).
   // Measured on X [16384, d] against the 16x16x32 kernel: G = 112 gains 7 - 9 %, G = 80 3 - 7 % (at
