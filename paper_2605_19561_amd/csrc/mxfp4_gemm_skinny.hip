@@ -54,48 +54,47 @@ struct DecodeArgs {
 
 }  // namespace
 
-// The end of both kernels: add the waves' partial tiles through LDS and store.
+// The end of both kernels: add the waves' partial tiles through LDS and store.  Every wave's partial
+// tiles go through LDS (red_mem: WAVES NS MT KiB) and the NS MT output tiles are shared out over the
+// waves (tile k to wave k % WAVES), each added in the same fixed order, wave 0 + 1 + ... + 7: the same
+// bits whichever wave does it (one wave adding up to eight tiles took a microsecond while seven waited).
 template <int MT, int NS>
 __device__ __forceinline__ void skinny_reduce_store(f32x4 (&acc)[NS][MT], unsigned char *red_mem, uint16_t *__restrict__ out,
                                                     int M, int64_t N, int64_t n0, int wave, int lane) {
   const int r16 = lane & 15, q = lane >> 4;
-  // ---- add the waves' partial tiles in a fixed order (wave 0 + 1 + ... + 7), round, store
   __syncthreads();                                 // everybody is done with the scales
-  float *red = reinterpret_cast<float *>(red_mem); // [WAVES - 1][NS][MT][4][64]
-  if (wave > 0) {
+  float *red = reinterpret_cast<float *>(red_mem); // [WAVES][NS][MT][4][64]
 #pragma unroll
-    for (int n = 0; n < NS; ++n)
+  for (int n = 0; n < NS; ++n)
 #pragma unroll
-      for (int t = 0; t < MT; ++t)
+    for (int t = 0; t < MT; ++t)
 #pragma unroll
-        for (int r = 0; r < 4; ++r) red[((((wave - 1) * NS + n) * MT + t) * 4 + r) * 64 + lane] = acc[n][t][r];
-  }
+      for (int r = 0; r < 4; ++r) red[(((wave * NS + n) * MT + t) * 4 + r) * 64 + lane] = acc[n][t][r];
   __syncthreads();
-  if (wave == 0) {
 #pragma unroll
-    for (int n = 0; n < NS; ++n) {
-      const int64_t nn = n0 + n * 16 + 4 * q;
+  for (int n = 0; n < NS; ++n) {
+    const int64_t nn = n0 + n * 16 + 4 * q;
 #pragma unroll
-      for (int t = 0; t < MT; ++t) {
-        bf16x4 v;
+    for (int t = 0; t < MT; ++t) {
+      if ((n * MT + t) % WAVES != wave) continue;  // uniform over the wave
+      bf16x4 v;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          float sum = acc[n][t][r];
+      for (int r = 0; r < 4; ++r) {
+        float sum = red[((n * MT + t) * 4 + r) * 64 + lane];
 #pragma unroll
-          for (int w = 0; w < WAVES - 1; ++w) sum += red[(((w * NS + n) * MT + t) * 4 + r) * 64 + lane];
-          v[r] = (__bf16)sum;
-        }
-        const int m = t * 16 + r16;
-        if (m < M) {
-          uint16_t *dst = out + (int64_t)m * N + nn;
-          if ((N & 3) == 0 && nn + 4 <= N) {
-            *reinterpret_cast<bf16x4 *>(dst) = v;
-          } else {
-            const uint64_t bits = __builtin_bit_cast(uint64_t, v);
+        for (int w = 1; w < WAVES; ++w) sum += red[(((w * NS + n) * MT + t) * 4 + r) * 64 + lane];
+        v[r] = (__bf16)sum;
+      }
+      const int m = t * 16 + r16;
+      if (m < M) {
+        uint16_t *dst = out + (int64_t)m * N + nn;
+        if ((N & 3) == 0 && nn + 4 <= N) {
+          *reinterpret_cast<bf16x4 *>(dst) = v;
+        } else {
+          const uint64_t bits = __builtin_bit_cast(uint64_t, v);
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-              if (nn + r < N) dst[r] = (uint16_t)(bits >> (16 * r));
-          }
+          for (int r = 0; r < 4; ++r)
+            if (nn + r < N) dst[r] = (uint16_t)(bits >> (16 * r));
         }
       }
     }
@@ -117,7 +116,7 @@ mxfp4_gemm_skinny_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restr
                          uint16_t *__restrict__ out, int M, int64_t N, int d) {
   // dynamic LDS: scale bytes of the weight strips (16 NS rows) and of the activation rows (16 MT),
   // d / 32 bytes each, every row padded by 4 bytes (the lanes of a k-step read one byte of 16
-  // different rows); the partial tiles of waves 1.. are overlaid on it after the k loop
+  // different rows); the waves' partial tiles are overlaid on it after the k loop
   extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -139,7 +138,7 @@ mxfp4_gemm_skinny_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restr
   const int a_ins = (16 * MT * pd + 63) / 64;      // ... and for the activation rows
   const int ws_off = r16 * pd * 4 + q;             // this lane's scale byte: + 4 per k-step
   const int as_off = w_ins * 256 + r16 * pd * 4 + q;
-  // the partial tiles of waves 1.. : over the scales (one group per workgroup), behind them (PERSIST:
+  // the waves' partial tiles: over the scales (one group per workgroup), behind them (PERSIST:
   // the activations' scale bytes stay)
   unsigned char *const red_mem = PERSIST ? smem + (w_ins + a_ins) * 256 : smem;
 
@@ -230,7 +229,7 @@ mxfp4_gemm_skinny_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restr
 
     skinny_reduce_store<MT, NS>(acc, red_mem, out, M, N, n0, wave, lane);
     // PERSIST: the next group's scale bytes replace this group's, which every wave has read (first
-    // barrier of the reduction); its partial tiles replace these once wave 0, the only reader, has
+    // barrier of the reduction); its partial tiles replace these once the adding waves have
     // arrived at the next group's barrier
   }
 #undef TORQ_LOAD_A
@@ -653,7 +652,7 @@ static hipError_t launch_cfg(const uint8_t *A_q, const uint8_t *A_s, const uint8
   if (groups > 0x7FFFFFF0) return hipErrorInvalidValue;
   const int pd = d / 128 + 1;                      // padded dwords per scale row
   const size_t scale_bytes = (size_t)((16 * NS * pd + 63) / 64 + (16 * MT * pd + 63) / 64) * 256;
-  const size_t red_bytes = (size_t)(WAVES - 1) * NS * MT * 4 * 64 * sizeof(float);
+  const size_t red_bytes = (size_t)WAVES * NS * MT * 4 * 64 * sizeof(float);
   size_t lds_bytes = scale_bytes > red_bytes ? scale_bytes : red_bytes;
   if (fused) {
     // + the "ready" word behind the scales; at least the rotation's four token-group places
