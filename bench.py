@@ -367,6 +367,23 @@ def settle(torch, call, warmup, seconds=0.04):
         torch.cuda.synchronize()
 
 
+def timed_median(torch, call, steps, groups=5):
+    """Milliseconds per call: `groups` timed groups of `steps` calls each, the median group.  The lines
+    that use it time windows of 0.2 to 20 ms, and one interruption of the queue inside a window that short
+    (seen in about one default run of three, on a different line each time, gone on the next run) would
+    otherwise decide the line."""
+    per_call = []
+    for _ in range(groups):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(steps):
+            call()
+        e1.record()
+        torch.cuda.synchronize()
+        per_call.append(e0.elapsed_time(e1) / steps)
+    return sorted(per_call)[groups // 2]
+
+
 def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0, butterfly=False, M=16384, recipe=None):
     """rotate+quantise alone on X [M, d] (the memory-bound sweep); fmt 1 / 2: MXINT4 / NVFP4 output;
     butterfly: R_inter as log2 G rounds of plane rotations instead of a dense G x G matrix.  The launches
@@ -400,13 +417,7 @@ def sweep_line(tq, synth, d, steps, warmup, G=None, fmt=0, butterfly=False, M=16
         else:
             tq.torq_rotate_quantize_fmt(rot, xi, fmt, gs, codes=codes, scales=scales)
     settle(torch, call, warmup)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(steps):
-        call()
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / steps
+    ms = timed_median(torch, call, steps)
     bytes_per_element = 2.0 + 0.5 + (1.0 / 16 if fmt == 2 else 1.0 / 32)
     gbs = M * d * bytes_per_element / (ms * 1e-3) / 1e9
     rot.close()
@@ -531,13 +542,7 @@ def gemm_line(tq, M, N, d, steps, warmup):
     out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
     ws = torch.empty((max(tq.mxfp4_gemm_workspace_bytes(M, N, d), 16),), dtype=torch.uint8, device=dev)
     settle(torch, lambda: tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=out, workspace=ws), warmup)
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    e0.record()
-    for _ in range(steps):
-        tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=out, workspace=ws)
-    e1.record()
-    torch.cuda.synchronize()
-    ms = e0.elapsed_time(e1) / steps
+    ms = timed_median(torch, lambda: tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=out, workspace=ws), steps)
     tf = 2.0 * M * N * d / (ms * 1e-3) / 1e12
     streaming, tile_m, tile_n, pieces = tq.mxfp4_gemm_plan(M, N, d, ws.numel())
     kernel = "weight-streaming" if streaming else f"tiled {tile_m}x{tile_n}" + (f", k cut in {pieces}" if pieces > 1 else "")
@@ -631,14 +636,7 @@ def decode_line(tq, synth, M, N, d, single_launch=True):
             for i in range(calls):
                 fn(rot, x, W_q[i % n_copies], W_s[i % n_copies], out=out, workspace=ws)
         settle(torch, graph.replay, 1)
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 10
-        e0.record()
-        for _ in range(reps):
-            graph.replay()
-        e1.record()
-        torch.cuda.synchronize()
-        return e0.elapsed_time(e1) * 1e3 / (reps * calls)
+        return timed_median(torch, graph.replay, 4) * 1e3 / calls
 
     us = replayed(tq.torq_linear)
     # the one-launch form of the same layer, where it applies (G = 128, at most 64 rows)
