@@ -681,19 +681,32 @@ hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, 
                          uint8_t *codes, uint8_t *scales, float *z_out, hipStream_t stream) {
   const int64_t TG = M * (int64_t)(r->d / 32 / r->G);
   if (TG == 0) return hipSuccess;
-  // a handful of token-groups at G = 128 or 112 (decode): one per workgroup
-  if (r->G == 128 && TG <= 128) return launch_cfg32<8, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
-  if (r->G == 112 && TG <= 128) return launch_cfg32<7, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
-  // quantising, G = 80 ... 128: the three-buffer form of the 32x32x16 kernel
-  // ... from eight batches per workgroup on: below, the two batches requested ahead of the loop cost more
-  // than the ring saves (same machine, ring against two buffers: X [4096, 4096] 18.7 against 17.3 us,
+  constexpr int64_t RING_MIN_TG = 2 * 8 * 3 * 256;       // eight batches for each of the ring's 768 workgroups
+  // quantising, G = 80 ... 128, large inputs: the three-buffer form of the 32x32x16 kernel.  Below eight
+  // batches per workgroup the two batches requested ahead of the loop cost more than the ring saves (same
+  // machine, ring against two buffers of two token-groups: X [4096, 4096] 18.7 against 17.3 us,
   // [1024, 4096] 8.8 against 8.2, [2048, 14336] 27.1 against 25.5, [4096, 5120] 18.2 against 17.3; equal at
   // [8192, 4096]; from [16384, 4096] on the ring wins, 45.7 against 49.6 us there)
-  if (!z_out && TG >= 2 * 8 * 3 * 256) {
+  if (!z_out && TG >= RING_MIN_TG) {
     if (r->G == 128) return launch_ring32<8>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
     if (r->G == 112) return launch_ring32<7>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
     if (r->G == 96) return launch_ring32<6>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
     if (r->G == 80) return launch_ring32<5>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
+  }
+  // Below that, batches of ONE token-group for G = 128, 112, 80 (and G = 64 up to 16384 token-groups): twice
+  // as many, half as large, so the workgroups' shares are more even and a workgroup's first results leave
+  // sooner.  Against batches of two on the same machine: X [256 .. 1024, 4096] 9.0 -> 8.0 us,
+  // [4096, 4096] 18.2 -> 17.0, [8192, 4096] 28.0 -> 27.2, [2048, 14336] 27.0 -> 25.4, [2048, 8192] 18.2 -> 16.9,
+  // [4096, 5120] G = 80 19.9 -> 18.5, [8192, 4096] G = 64 25.5 -> 24.6; nothing at [2048, 4096]; G = 96 and
+  // G = 32 lose 0 - 5 % and keep two (as does everything that writes fp32 rotated values at these G but
+  // G = 128 and 112 with a handful of token-groups, the decode case)
+  if (!z_out || TG <= 128) {
+    if (r->G == 128) return launch_cfg32<8, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
+    if (r->G == 112) return launch_cfg32<7, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
+  }
+  if (!z_out) {
+    if (r->G == 80) return launch_cfg32<5, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
+    if (r->G == 64 && TG <= 16384) return launch_cfg32<4, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
   }
   // G a multiple of 32, or 16 * odd from 80 up: the 32x32x16 kernel (with a half-empty last tile).
   // Measured on X [16384, d] against the 16x16x32 kernel: G = 112 gains 7 - 9 %, G = 80 3 - 7 % (at

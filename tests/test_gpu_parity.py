@@ -709,7 +709,7 @@ def test_quantize_fmt_mxfp4_is_the_plain_entry_point(tq):
     assert torch.equal(c0, c1) and torch.equal(s0, s1)
 
 
-@pytest.mark.parametrize("d,G", [(4096, 128), (5120, 80), (1024, 32), (512, 16)])
+@pytest.mark.parametrize("d,G", [(4096, 128), (14336, 112), (5120, 80), (2048, 64), (1024, 32), (512, 16)])
 @pytest.mark.parametrize("fmt", [1, 2])
 def test_rotate_quantize_fmt_is_rotate_then_quantize(tq, oracle, d, G, fmt):
     # the fused kernel's step 4 in the other formats = the stand-alone quantiser on the fused
