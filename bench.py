@@ -529,6 +529,17 @@ def ablation_lines(tq, torch, rot, x, codes, scales, W_q, W_s, out, steps):
     return res
 
 
+def gemm_kernel_name(tq, M, N, d, workspace_bytes):
+    """Which kernel(s) mxfp4_gemm_ws runs a product on, for the lines' labels."""
+    def one(n):
+        streaming, tile_m, tile_n, pieces = tq.mxfp4_gemm_plan(M, n, d, workspace_bytes)
+        return "weight-streaming" if streaming else f"tiled {tile_m}x{tile_n}" + (f", k cut in {pieces}" if pieces > 1 else "")
+    main = tq.mxfp4_gemm_main_columns(M, N, d, workspace_bytes)
+    if main < N:
+        return f"{one(N)} on {main} columns (whole rounds), then {one(N - main)} on {N - main}"
+    return one(N)
+
+
 def gemm_line(tq, M, N, d, steps, warmup):
     """mxfp4_gemm alone on random codes and scale bytes of one layer shape (with the workspace the planner asks for)."""
     import torch
@@ -544,8 +555,7 @@ def gemm_line(tq, M, N, d, steps, warmup):
     settle(torch, lambda: tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=out, workspace=ws), warmup)
     ms = timed_median(torch, lambda: tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=out, workspace=ws), steps)
     tf = 2.0 * M * N * d / (ms * 1e-3) / 1e12
-    streaming, tile_m, tile_n, pieces = tq.mxfp4_gemm_plan(M, N, d, ws.numel())
-    kernel = "weight-streaming" if streaming else f"tiled {tile_m}x{tile_n}" + (f", k cut in {pieces}" if pieces > 1 else "")
+    kernel = gemm_kernel_name(tq, M, N, d, ws.numel())
     return {"metric": "mxfp4_gemm", "value": round(tf, 1), "unit": "TFLOP/s",
             "config": {"workload": f"A [{M}, {d}] x W [{N}, {d}] packed MXFP4 -> bf16 [{M}, {N}]", "gemm_kernel": kernel},
             "ms": round(ms, 4), "frac_fp4_peak": round(tf / 10100.0, 4)}
@@ -644,8 +654,7 @@ def decode_line(tq, synth, M, N, d, single_launch=True):
     us_single = round(replayed(tq.torq_linear_single_launch), 2) if (single_launch and ((G == 128 and M <= 64) or local)) else None
     wbytes = N * d * 0.53125
     rot.close()
-    streaming, tile_m, tile_n, pieces = tq.mxfp4_gemm_plan(M, N, d, tq.mxfp4_gemm_workspace_bytes(M, N, d))
-    kernel = "weight-streaming" if streaming else f"tiled {tile_m}x{tile_n}" + (f", k cut in {pieces}" if pieces > 1 else "")
+    kernel = gemm_kernel_name(tq, M, N, d, tq.mxfp4_gemm_workspace_bytes(M, N, d))
     return {"metric": "torq_linear, decode", "value": round(us, 2), "unit": "us per call", "higher_is_better": False,
             "config": {"workload": f"decode: X bf16 [{M}, {d}], G={G}, W [{N}, {d}] packed MXFP4 ({wbytes / 1e6:.1f} MB)",
                        "gemm_kernel": kernel},

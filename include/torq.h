@@ -158,6 +158,14 @@ size_t mxfp4_gemm_workspace_bytes(int64_t M, int64_t N, int d);
  * tile; *k_pieces > 1 if the k range is cut.  Host only, launches nothing; for logs and tests. */
 int mxfp4_gemm_plan(int64_t M, int64_t N, int d, size_t workspace_bytes, int *weight_streaming, int *tile_m,
                     int *tile_n, int *k_pieces);
+/* A tile count just above a whole number of rounds (one 256 x 256 tile per compute unit) would leave
+ * the last round mostly empty.  Such a product runs as two: a first launch computes the leading
+ * output columns that make up whole rounds, and the remaining columns are a product of their own
+ * (weight rows from that column on, same activations, same output rows).  Returns the number of those
+ * leading columns (a multiple of 256), or N when the product is one: mxfp4_gemm_plan above then
+ * describes the first launch, and mxfp4_gemm_plan(M, N - that, d, workspace_bytes) the remainder.
+ * 0 for arguments that mxfp4_gemm_plan rejects.  Host only, launches nothing; for logs and tests. */
+int64_t mxfp4_gemm_main_columns(int64_t M, int64_t N, int d, size_t workspace_bytes);
 int mxfp4_gemm_ws(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
                   void *out_bf16, int64_t M, int64_t N, int d, void *workspace, size_t workspace_bytes,
                   void *stream);

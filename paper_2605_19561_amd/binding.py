@@ -15,7 +15,7 @@ LIB_PATH = os.path.join(_HERE, "libtorq.so")
 EXPORTS = [
     "torq_status_string", "torq_rotation_create", "torq_rotation_destroy", "torq_rotation_d",
     "torq_rotation_G", "torq_rotate_quantize", "torq_rotate", "torq_quantize_f32", "mxfp4_gemm",
-    "torq_linear_workspace_bytes", "torq_linear", "mxfp4_gemm_workspace_bytes", "mxfp4_gemm_ws", "mxfp4_gemm_plan",
+    "torq_linear_workspace_bytes", "torq_linear", "mxfp4_gemm_workspace_bytes", "mxfp4_gemm_ws", "mxfp4_gemm_plan", "mxfp4_gemm_main_columns",
     "torq_rotate_quantize_fmt", "torq_quantize_f32_fmt", "torq_equalize_inter_butterfly",
     "torq_rotation_create_butterfly", "torq_linear_single_launch",
     "torq_linear_workspace_bytes_n", "torq_block_gram_workspace_bytes", "torq_block_gram", "torq_block_gram_positions",
@@ -79,6 +79,8 @@ def lib():
         L.torq_quantize_f32_fmt.argtypes = [vp, i64, i32, i32, C.c_float, vp, vp, vp]
         L.mxfp4_gemm_plan.restype = i32
         L.mxfp4_gemm_plan.argtypes = [i64, i64, i32, sz] + [C.POINTER(i32)] * 4
+        L.mxfp4_gemm_main_columns.restype = i64
+        L.mxfp4_gemm_main_columns.argtypes = [i64, i64, i32, sz]
         L.mxfp4_gemm_ws.restype = i32
         L.mxfp4_gemm_ws.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, vp, sz, vp]
         L.torq_linear_workspace_bytes_n.restype = sz
@@ -292,6 +294,11 @@ def mxfp4_gemm_plan(M: int, N: int, d: int, workspace_bytes: int = 0):
     v = [C.c_int(0) for _ in range(4)]
     _check(lib().mxfp4_gemm_plan(M, N, d, workspace_bytes, *(C.byref(x) for x in v)), "mxfp4_gemm_plan")
     return bool(v[0].value), v[1].value, v[2].value, v[3].value
+
+
+def mxfp4_gemm_main_columns(M: int, N: int, d: int, workspace_bytes: int = 0) -> int:
+    """N, or the leading output columns that a first launch of whole rounds of tiles computes."""
+    return int(lib().mxfp4_gemm_main_columns(M, N, d, workspace_bytes))
 
 
 def mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=None, workspace=None, stream=None):

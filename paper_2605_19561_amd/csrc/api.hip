@@ -454,6 +454,11 @@ int mxfp4_gemm_plan(int64_t M, int64_t N, int d, size_t workspace_bytes, int *we
   return TORQ_OK;
 }
 
+int64_t mxfp4_gemm_main_columns(int64_t M, int64_t N, int d, size_t workspace_bytes) {
+  if (M <= 0 || N <= 0 || d <= 0 || d % 128 != 0) return 0;
+  return torq::mxfp4_gemm_main_columns(M, N, d, workspace_bytes);
+}
+
 int mxfp4_gemm_ws(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
                   void *out_bf16, int64_t M, int64_t N, int d, void *workspace, size_t workspace_bytes,
                   void *stream) {

@@ -61,7 +61,7 @@ __global__ void __launch_bounds__(256)
 mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A_s,
                   const uint8_t *__restrict__ W_q, const uint8_t *__restrict__ W_s,
                   uint16_t *__restrict__ out, float *__restrict__ partial, int64_t M, int64_t N, int d,
-                  int tiles_m, int tiles_n) {
+                  int tiles_m, int tiles_n, int64_t ldc) {
   static_assert(FULLK || !SPLIT, "split-k needs whole iterations");
   constexpr int BM = 64 * WM, BN = 64 * WN;
   constexpr int A_CH = BM / 32, W_CH = BN / 32;          // 16-byte code chunks per thread per iteration
@@ -430,7 +430,7 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
           for (int e = 0; e < 4; ++e) v[e] = (__bf16)acc[j][i][4 * rr + e];
           *reinterpret_cast<bf16x4 *>(ep + (i * 32 + lrow) * PITCH_E + (32 * j + 8 * rr + 4 * g) * 2) = v;
         }
-    const bool vec_ok = (N & 7) == 0;
+    const bool vec_ok = (ldc & 7) == 0;           // (out itself is 16-byte aligned: checked by the host)
 #pragma unroll
     for (int i = 0; i < WM; ++i)
 #pragma unroll
@@ -441,7 +441,7 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
         const int64_t m = m0 + (wy * WM + i) * 32 + row;
         const int64_t n = n0 + wx * WN * 32 + ch * 8;
         if (m < M) {
-          uint16_t *dst = out + m * N + n;
+          uint16_t *dst = out + m * ldc + n;
           if (vec_ok && n + 8 <= N) {
             *reinterpret_cast<u32x4 *>(dst) = v;
           } else {
@@ -464,9 +464,11 @@ mxfp4_gemm_kernel(const uint8_t *__restrict__ A_q, const uint8_t *__restrict__ A
 #undef MFMA_HALF
 }
 
-// out[m][n] = bf16(sum over the k pieces, in order, of partial[s][m][n]); 8 outputs per thread
+// out[m][n] = bf16(sum over the k pieces, in order, of partial[s][m][n]); 8 outputs per thread; the rows
+// of out are ldc elements apart (N and ldc multiples of 8)
 __global__ void __launch_bounds__(256)
-mxfp4_gemm_splitk_reduce_kernel(const float *__restrict__ partial, int splits, int64_t MN, uint16_t *__restrict__ out) {
+mxfp4_gemm_splitk_reduce_kernel(const float *__restrict__ partial, int splits, int64_t MN, int64_t N, int64_t ldc,
+                                uint16_t *__restrict__ out) {
   const int64_t e0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
   if (e0 >= MN) return;                          // MN is a multiple of 8
   f32x4 lo = *reinterpret_cast<const f32x4 *>(partial + e0), hi = *reinterpret_cast<const f32x4 *>(partial + e0 + 4);
@@ -481,7 +483,8 @@ mxfp4_gemm_splitk_reduce_kernel(const float *__restrict__ partial, int splits, i
     b[e] = (__bf16)hi[e];
   }
   typedef __attribute__((__vector_size__(2 * sizeof(uint64_t)))) uint64_t u64x2;
-  *reinterpret_cast<u64x2 *>(out + e0) = u64x2{__builtin_bit_cast(uint64_t, a), __builtin_bit_cast(uint64_t, b)};
+  const int64_t o0 = ldc == N ? e0 : (e0 / N) * ldc + e0 % N;
+  *reinterpret_cast<u64x2 *>(out + o0) = u64x2{__builtin_bit_cast(uint64_t, a), __builtin_bit_cast(uint64_t, b)};
 }
 
 // compute units of the current device (256 on this part), asked once
@@ -508,9 +511,14 @@ static bool persistent_pays(int64_t tiles, int d) { return tiles >= 4 * (int64_t
 template <int WM, int WN, bool FULLK, bool SPLIT, bool DEEP = false, int SKIP = 0, bool PERSIST = false>
 static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                               const uint8_t *W_s, void *out, float *partial, int splits, int64_t M, int64_t N,
-                              int d, hipStream_t stream, int persist_grid = 0) {
+                              int d, hipStream_t stream, int persist_grid = 0, int64_t ldc = 0, int64_t walk_n = 0) {
+  // ldc: elements between the rows of out (0: N; the persistent form only knows N);
+  // walk_n: only the tiles of the first walk_n tile columns are computed (0: all)
   constexpr int BM = 64 * WM, BN = 64 * WN;
-  const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = (N + BN - 1) / BN;
+  if (ldc == 0) ldc = N;
+  if (PERSIST && ldc != N) return hipErrorInvalidValue;
+  const int64_t tiles_m = (M + BM - 1) / BM, tiles_n = walk_n > 0 ? walk_n : (N + BN - 1) / BN;
+  if (tiles_n > (N + BN - 1) / BN) return hipErrorInvalidValue;
   if (tiles_m * tiles_n > 0x7FFFFFFF) return hipErrorInvalidValue;
   const size_t lds_bytes = 2 * (size_t)(BM + BN) * 128 + 2 * (size_t)((BM + BN + 255) / 256 * 256) * 16;
   auto kern = mxfp4_gemm_kernel<WM, WN, FULLK, SPLIT, DEEP, SKIP, PERSIST>;
@@ -533,12 +541,12 @@ static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint
     }
   }
   hipLaunchKernelGGL(kern, dim3((unsigned)grid, SPLIT ? splits : 1), dim3(256), lds_bytes, stream, A_q,
-                     A_s, W_q, W_s, reinterpret_cast<uint16_t *>(out), partial, M, N, d, (int)tiles_m, (int)tiles_n);
+                     A_s, W_q, W_s, reinterpret_cast<uint16_t *>(out), partial, M, N, d, (int)tiles_m, (int)tiles_n, ldc);
   hipError_t e = hipGetLastError();
   if (!SPLIT || e != hipSuccess) return e;
   const int64_t MN = M * N;
   hipLaunchKernelGGL(mxfp4_gemm_splitk_reduce_kernel, dim3((unsigned)((MN / 8 + 255) / 256)), dim3(256), 0, stream,
-                     partial, splits, MN, reinterpret_cast<uint16_t *>(out));
+                     partial, splits, MN, N, ldc, reinterpret_cast<uint16_t *>(out));
   return hipGetLastError();
 }
 
@@ -560,7 +568,19 @@ struct GemmPlan {
   int cfg;
   int splits;
   bool deep;      // the tiled kernel's deeper load pipeline (128-row-wide tiles, weight-bound shapes)
+  double us;      // the model's estimate of the launch time
 };
+
+// Several rounds of tiles: microseconds of a launch of `tiles` tiles of shape cfg over KT iterations.
+// A launch costs 6 us; a round (256 tiles, 512 of the smallest shape) a + b KT with (a, b) fitted to
+// [4096, 4096 / 24576, 5120] and [4096, 4096, 25600] (256 x 256: 49, 262, 203 us), [2048, 4096, 4096 / 14336]
+// (256 x 128: 25.5, 68.5) and [4096, 5120, 5120 / 25600] (128 x 128: 71.5, 322).
+static double rounds_us(int cfg, double tiles, double KT) {
+  static const double A[3] = {4.8, 2.3, 0.9}, B[3] = {1.9, 1.075, 1.044};
+  const double slots = cfg == 2 ? 512.0 : 256.0;
+  const double rounds = (double)(int64_t)((tiles + slots - 1) / slots);
+  return 6.0 + rounds * (A[cfg] + B[cfg] * KT);
+}
 
 // Below one full round of tiles the tiled kernel is bound by how fast one workgroup can stream
 // its operand rows (about 0.9 us per 256-element iteration of the 128 x 128 tile, 1.1 of the
@@ -572,14 +592,17 @@ struct GemmPlan {
 // tiles.  All figures in microseconds, fitted to measurements of 4096 ... 28672-wide layers;
 // the choice only has to land near the best, not predict it.
 static GemmPlan choose_plan(int64_t M, int64_t N, int d, bool allow_split) {
-  GemmPlan plan{false, choose_tile(M, N), 1, false};
+  GemmPlan plan{false, choose_tile(M, N), 1, false, 0.0};
   static const int BM[3] = {256, 256, 128}, BN[3] = {256, 128, 128};
   static const double T_ITER[3] = {1.5, 1.1, 0.9};
   auto tiles_of = [&](int cfg) { return (double)(((M + BM[cfg] - 1) / BM[cfg]) * ((N + BN[cfg] - 1) / BN[cfg])); };
   const bool can_skinny = mxfp4_gemm_skinny_fits(M, d);
-  if (tiles_of(plan.cfg) >= 512.0 && !can_skinny) return plan;      // two full rounds: nothing to gain
-
   const double KT = (d + 255) / 256;
+  if (tiles_of(plan.cfg) >= 512.0 && !can_skinny) {                 // two full rounds: nothing to gain
+    plan.us = rounds_us(plan.cfg, tiles_of(plan.cfg), KT);
+    return plan;
+  }
+
   // the 128 x 128 tile alone on its CU, not cut: the deeper load pipeline gains an eighth
   auto deep_pays = [&](int cfg, int s) { return cfg == 2 && s == 1 && tiles_of(cfg) <= 256.0; };
   auto tiled_us = [&](int cfg, int s) {
@@ -606,24 +629,65 @@ static GemmPlan choose_plan(int64_t M, int64_t N, int d, bool allow_split) {
     }
   }
   plan.deep = deep_pays(plan.cfg, plan.splits);
+  plan.us = best;
   if (can_skinny) {
     static const double per_mb[4] = {0.21, 0.31, 0.45, 0.58};      // by 16-row activation tiles
     const double w_mb = (double)N * (double)d * 0.53125 / 1e6;
     const double t = 4.0 + w_mb * per_mb[(M - 1) / 16];
     // near a tie the streaming kernel wins: one launch, no tile padding
-    if (0.95 * (t < 6.5 ? 6.5 : t) <= best) plan = GemmPlan{true, 0, 1, false};
+    if (0.95 * (t < 6.5 ? 6.5 : t) <= best) plan = GemmPlan{true, 0, 1, false, t < 6.5 ? 6.5 : t};
   }
   return plan;
+}
+
+// Whole rounds first.  A tile count just above a whole number of rounds leaves the last round mostly empty
+// (Qwen3-32B's [4096, 5120, d]: 320 tiles of 256 x 256 are a round and a quarter; smaller tiles fill the
+// rounds better and use the operands worse).  Then the leading columns that make up whole rounds of
+// 256 x 256 tiles go first, as one launch that walks only those tile columns, and the remaining columns
+// are a product of their own (any plan, its k range cut where that pays) on the same output rows, which
+// are N elements apart.  Returns those leading columns, or N: one launch.  Taken when the last round would
+// be at most half full and the model promises 3 %: measured [4096, 5120, 25600] 322 -> 279 us,
+// [4096, 5120, 5120] 71.5 -> 66.3, [4096, 25600, 5120] 291 -> 279; every output is the sum it was before
+// (same k order in every tile shape; where the remainder's k range is cut, up to the order of its fp32 sums,
+// as for any product that mxfp4_gemm_ws cuts).
+static GemmPlan plan_with(int64_t M, int64_t N, int d, bool allow_split, size_t workspace_bytes);
+static int64_t choose_main_columns(int64_t M, int64_t N, int d, bool allow_split, size_t workspace_bytes, const GemmPlan &whole) {
+  if (whole.skinny || whole.splits > 1 || d % 512 != 0 || N % 8 != 0 || M <= 64) return N;
+  const int64_t tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256, tiles = tiles_m * tiles_n;
+  const int64_t full = tiles / 256;
+  if (full < 1 || tiles % 256 == 0 || tiles % 256 > 128 || tiles_m > 256) return N;
+  const int64_t cols = full * 256 / tiles_m;                        // whole tile columns of the first launch
+  if (cols < 1 || cols >= tiles_n) return N;
+  const double KT = (d + 255) / 256;
+  // the one launch: by rounds where it takes more than one (choose_plan's own figure is for less)
+  static const int BM[3] = {256, 256, 128}, BN[3] = {256, 128, 128};
+  const double tiles_whole = (double)(((M + BM[whole.cfg] - 1) / BM[whole.cfg]) * ((N + BN[whole.cfg] - 1) / BN[whole.cfg]));
+  const double one = tiles_whole > (whole.cfg == 2 ? 512.0 : 256.0) ? rounds_us(whole.cfg, tiles_whole, KT) : whole.us;
+  const GemmPlan tail = plan_with(M, N - 256 * cols, d, allow_split, workspace_bytes);
+  const double two = rounds_us(0, (double)(tiles_m * cols), KT) + tail.us;
+  return two < 0.97 * one ? 256 * cols : N;
 }
 #ifndef GEMM_PLAN
 #define GEMM_PLAN(M_, N_, d_, allow_) choose_plan(M_, N_, d_, allow_)
 #endif
 
-void mxfp4_gemm_plan(int64_t M, int64_t N, int d, size_t workspace_bytes, int *skinny, int *tile_m, int *tile_n,
-                     int *splits) {
-  GemmPlan plan = GEMM_PLAN(M, N, d, d % 512 == 0);
+// the plan of a product given the workspace it may use (a cut k range needs its pieces' fp32 tiles there)
+static GemmPlan plan_with(int64_t M, int64_t N, int d, bool allow_split, size_t workspace_bytes) {
+  GemmPlan plan = GEMM_PLAN(M, N, d, allow_split);
   if (plan.splits > 1 && workspace_bytes < (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(float))
     plan = GEMM_PLAN(M, N, d, false);
+  return plan;
+}
+
+int64_t mxfp4_gemm_main_columns(int64_t M, int64_t N, int d, size_t workspace_bytes) {
+  const bool allow = d % 512 == 0;
+  return choose_main_columns(M, N, d, allow, workspace_bytes, plan_with(M, N, d, allow, workspace_bytes));
+}
+
+void mxfp4_gemm_plan(int64_t M, int64_t N, int d, size_t workspace_bytes, int *skinny, int *tile_m, int *tile_n,
+                     int *splits) {
+  GemmPlan plan = plan_with(M, N, d, d % 512 == 0, workspace_bytes);
+  if (mxfp4_gemm_main_columns(M, N, d, workspace_bytes) < N) plan = GemmPlan{false, 0, 1, false, 0.0};   // the first launch
   *skinny = plan.skinny;
   *tile_m = plan.skinny ? 0 : (plan.cfg == 2 ? 128 : 256);
   *tile_n = plan.skinny ? 16 : (plan.cfg == 0 ? 256 : 128);
@@ -632,7 +696,41 @@ void mxfp4_gemm_plan(int64_t M, int64_t N, int d, size_t workspace_bytes, int *s
 
 size_t mxfp4_gemm_workspace_bytes(int64_t M, int64_t N, int d) {
   const GemmPlan plan = GEMM_PLAN(M, N, d, true);
+  const int64_t main_n = choose_main_columns(M, N, d, true, ~(size_t)0, plan);
+  if (main_n < N) {
+    const GemmPlan tail = GEMM_PLAN(M, N - main_n, d, true);
+    return tail.splits > 1 ? (size_t)tail.splits * (size_t)M * (size_t)(N - main_n) * sizeof(float) : 0;
+  }
   return plan.splits > 1 ? (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
+
+// one product by one plan: out's rows are ldc elements apart
+static hipError_t launch_planned(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                                 void *out_bf16, int64_t M, int64_t N, int d, int64_t ldc, bool fullk, bool ws_ok,
+                                 void *workspace, size_t workspace_bytes, hipStream_t stream) {
+  const GemmPlan plan = plan_with(M, N, d, ws_ok, ws_ok ? workspace_bytes : 0);
+  if (plan.skinny) {
+    if (ldc != N) return hipErrorInvalidValue;            // (never planned for a remainder: see launch_mxfp4_gemm)
+    return launch_mxfp4_gemm_skinny(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
+  }
+  const int splits = plan.splits;
+  float *partial = static_cast<float *>(workspace);
+  if (plan.deep && fullk && splits == 1)
+    return launch_tile<2, 2, true, false, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc);
+#define TORQ_GEMM_LAUNCH(WM_, WN_)                                                                             \
+  if (splits == 1 && fullk && ldc == N &&                                                                      \
+      persistent_pays(((M + 64 * WM_ - 1) / (64 * WM_)) * ((N + 64 * WN_ - 1) / (64 * WN_)), d))               \
+    return launch_tile<WM_, WN_, true, false, false, 0, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream); \
+  return splits > 1 ? launch_tile<WM_, WN_, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream, 0, ldc) \
+         : fullk    ? launch_tile<WM_, WN_, true, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc)     \
+                    : launch_tile<WM_, WN_, false, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc);
+  if (plan.cfg == 0) { TORQ_GEMM_LAUNCH(4, 4) }
+  if (plan.cfg == 1) { TORQ_GEMM_LAUNCH(4, 2) }
+  // (two workgroups of the 128 x 128 tile share a CU: the persistent form, one per CU, measured slower)
+  return splits > 1 ? launch_tile<2, 2, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream, 0, ldc)
+         : fullk    ? launch_tile<2, 2, true, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc)
+                    : launch_tile<2, 2, false, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc);
+#undef TORQ_GEMM_LAUNCH
 }
 
 hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
@@ -645,27 +743,24 @@ hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8
                      ((reinterpret_cast<uintptr_t>(W_s) & 15u) == 0);
   // cut along k only with a workspace that holds the pieces (16-byte aligned fp32 rows)
   const bool ws_ok = fullk && workspace && (reinterpret_cast<uintptr_t>(workspace) & 15u) == 0;
-  GemmPlan plan = GEMM_PLAN(M, N, d, ws_ok);
-  if (plan.splits > 1 && workspace_bytes < (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(float))
-    plan = GEMM_PLAN(M, N, d, false);
-  if (plan.skinny) return launch_mxfp4_gemm_skinny(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
-  const int splits = plan.splits;
-  float *partial = static_cast<float *>(workspace);
-  if (plan.deep && fullk && splits == 1)
-    return launch_tile<2, 2, true, false, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream);
-#define TORQ_GEMM_LAUNCH(WM_, WN_)                                                                             \
-  if (splits == 1 && fullk && persistent_pays(((M + 64 * WM_ - 1) / (64 * WM_)) * ((N + 64 * WN_ - 1) / (64 * WN_)), d)) \
-    return launch_tile<WM_, WN_, true, false, false, 0, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream); \
-  return splits > 1 ? launch_tile<WM_, WN_, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream) \
-         : fullk    ? launch_tile<WM_, WN_, true, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream)     \
-                    : launch_tile<WM_, WN_, false, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream);
-  if (plan.cfg == 0) { TORQ_GEMM_LAUNCH(4, 4) }
-  if (plan.cfg == 1) { TORQ_GEMM_LAUNCH(4, 2) }
-  // (two workgroups of the 128 x 128 tile share a CU: the persistent form, one per CU, measured slower)
-  return splits > 1 ? launch_tile<2, 2, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream)
-         : fullk    ? launch_tile<2, 2, true, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream)
-                    : launch_tile<2, 2, false, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream);
-#undef TORQ_GEMM_LAUNCH
+  // whole rounds of 256 x 256 tiles first, the remaining columns as a product of their own?
+  const size_t ws_bytes = ws_ok ? workspace_bytes : 0;
+  const int64_t main_n = fullk ? choose_main_columns(M, N, d, ws_ok, ws_bytes, plan_with(M, N, d, ws_ok, ws_bytes)) : N;
+  if (main_n < N) {
+    const int64_t walk = main_n / 256, tiles = ((M + 255) / 256) * walk;
+    // (the persistent form where it pays: it walks the tile columns it is given like the plain one)
+    hipError_t e = persistent_pays(tiles, d)
+                       ? launch_tile<4, 4, true, false, false, 0, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, 0, walk)
+                       : launch_tile<4, 4, true, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, 0, walk);
+    if (e != hipSuccess) return e;
+    // the remainder: rows main_n ... of W, columns main_n ... of out (a multiple of 256: every alignment
+    // of the whole product holds for it); too few rows for the weight-streaming kernel never get here
+    // (a remainder exists only with more than 256 tiles)
+    return launch_planned(A_q, A_s, W_q + (size_t)main_n * (size_t)(d / 2), W_s + (size_t)main_n * (size_t)(d / 32),
+                          static_cast<uint16_t *>(out_bf16) + main_n, M, N - main_n, d, N, fullk, ws_ok, workspace,
+                          workspace_bytes, stream);
+  }
+  return launch_planned(A_q, A_s, W_q, W_s, out_bf16, M, N, d, N, fullk, ws_ok, workspace, workspace_bytes, stream);
 }
 
 // torq_diag_gemm_ablation: the 256 x 256-tile kernel with parts of its k loop left out (see SKIP above).

@@ -55,6 +55,9 @@ size_t mxfp4_gemm_workspace_bytes(int64_t M, int64_t N, int d);
 // what launch_mxfp4_gemm would do with a workspace of that size (operands assumed 16-byte aligned)
 void mxfp4_gemm_plan(int64_t M, int64_t N, int d, size_t workspace_bytes, int *skinny, int *tile_m, int *tile_n,
                      int *splits);
+// N, or the leading output columns that a first launch of whole rounds of 256 x 256 tiles takes (the plan
+// above is then that launch's; the remaining columns are a product of their own with its own plan)
+int64_t mxfp4_gemm_main_columns(int64_t M, int64_t N, int d, size_t workspace_bytes);
 hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
                              const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, int d,
                              void *workspace, size_t workspace_bytes, hipStream_t stream);

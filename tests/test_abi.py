@@ -129,6 +129,17 @@ def test_gemm_workspace_entry_points_validate_and_plan_on_the_host():
     assert binding.mxfp4_gemm_workspace_bytes(96, 512, 4100) == 0                # invalid d: nothing to size
     assert binding.mxfp4_gemm_workspace_bytes(96, 516, 4096) == 0                # N % 8 != 0: fp32 rows not 16-byte aligned
     assert binding.torq_linear_workspace_bytes_n(128, 8192, 28672) == binding.torq_linear_workspace_bytes(128, 28672) + need
+    # a round and a quarter of 256 x 256 tiles: the whole round first, the remaining columns on their own
+    assert binding.mxfp4_gemm_main_columns(4096, 5120, 5120) == 4096
+    assert binding.mxfp4_gemm_plan(4096, 5120, 5120) == (False, 256, 256, 1)
+    assert binding.mxfp4_gemm_main_columns(4096, 25600, 5120) == 24576          # six rounds and a quarter
+    need = binding.mxfp4_gemm_workspace_bytes(4096, 5120, 25600)                # the remainder's k range is cut
+    assert binding.mxfp4_gemm_main_columns(4096, 5120, 25600, need) == 4096
+    pieces = binding.mxfp4_gemm_plan(4096, 1024, 25600, need)[3]
+    assert pieces > 1 and need == pieces * 4096 * 1024 * 4
+    for M, N, d in [(8192, 28672, 8192), (8192, 8192, 28672), (2048, 14336, 4096), (4096, 5124, 5120), (64, 70000, 4096)]:
+        assert binding.mxfp4_gemm_main_columns(M, N, d) == N                    # whole rounds, a last round more than
+    assert binding.mxfp4_gemm_main_columns(0, 4, 128) == 0                      # half full, N % 8 != 0, few rows; invalid
     v = [C.c_int() for _ in range(4)]
     assert L.mxfp4_gemm_plan(0, 4, 128, 0, *(C.byref(x) for x in v)) == binding.TORQ_EINVAL
     assert L.mxfp4_gemm_plan(4, 4, 128, 0, None, C.byref(v[1]), C.byref(v[2]), C.byref(v[3])) == binding.TORQ_EINVAL

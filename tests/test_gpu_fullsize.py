@@ -131,6 +131,8 @@ GEMM_FULL = [
     (16, 28672, 8192),        # LLaMA3-70B MLP up at decode size: workgroups that keep the activations across four strip groups
     (12, 28000, 8192),        # ... with ragged rows and a ragged last group
     (8, 8192, 8192),          # ... one strip per group, two groups per workgroup
+    (4096, 5120, 5120),       # Qwen3-32B attention output: a round and a quarter of tiles, run as two products
+    (4000, 5000, 5120),       # ... with ragged last tiles in both
 ]
 
 
@@ -163,6 +165,57 @@ def test_gemm_full_size_sampled_outputs(tq, oracle, M, N, d):
     # rounded bf16 value, the rest are one bf16 ulp off
     assert np.mean(got == want) > 0.98
     assert np.all(np.abs(gw - ww) <= np.abs(ww) * 2.0 ** -7 + 1e-3 * np.sqrt(np.mean(ww ** 2)))
+
+
+# Products whose tile count is just above a whole number of rounds run as two: the leading columns that make
+# whole rounds of 256 x 256 tiles, then the remaining columns with a plan of their own (their k range cut
+# where a workspace allows).  GEMM_FULL above checks four such shapes against the oracle; here every output
+# of the two launches is compared with the same columns computed as products of their own, bit for bit, and
+# with the whole product on another tile shape.
+@pytest.mark.parametrize("M,N,d", [(4096, 5120, 5120), (4000, 5000, 5120), (4096, 25600, 5120), (4096, 5120, 25600),
+                                   (8192, 5120, 8192)])
+def test_gemm_whole_rounds_first_then_the_remaining_columns(tq, M, N, d):
+    g = torch.Generator(device=DEV)
+    g.manual_seed(synth.SEED_BASE + 7 * M + N + d)
+    A_q = torch.randint(0, 256, (M, d // 2), dtype=torch.uint8, device=DEV, generator=g)
+    W_q = torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=DEV, generator=g)
+    A_s = torch.randint(118, 136, (M, d // 32), dtype=torch.uint8, device=DEV, generator=g)
+    W_s = torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=DEV, generator=g)
+    main = tq.mxfp4_gemm_main_columns(M, N, d, 0)
+    assert 0 < main < N and main % 256 == 0, "this shape is meant to run as two products"
+    assert tq.mxfp4_gemm_plan(M, N, d, 0) == (False, 256, 256, 1)
+    # one row more than the product has, so that a store past the last row would show
+    guard = torch.full((M + 1, N), 0x7FC1, dtype=torch.int16, device=DEV).view(torch.bfloat16)
+    out = guard[:M]
+    tq.mxfp4_gemm(A_q, A_s, W_q, W_s, out=out)
+    left = tq.mxfp4_gemm(A_q, A_s, W_q[:main], W_s[:main])
+    right = tq.mxfp4_gemm(A_q, A_s, W_q[main:], W_s[main:])
+    torch.cuda.synchronize()
+    assert torch.equal(out[:, :main].view(torch.int16), left.view(torch.int16))
+    assert torch.equal(out[:, main:].view(torch.int16), right.view(torch.int16))
+    assert bool((guard[M].view(torch.int16) == 0x7FC1).all())
+    # the whole product on 256 x 128 tiles (the persistent form takes any shape with d a multiple of 1024)
+    other = tq.torq_diag_gemm_persistent(A_q, A_s, W_q, W_s, tile=1, workgroups=256)
+    torch.cuda.synchronize()
+    assert torch.equal(other.view(torch.int16), out.view(torch.int16))
+    del other
+    # with a workspace the remainder's k range may be cut: its columns are then those of mxfp4_gemm_ws on the
+    # remainder alone (bit for bit: same pieces, same order), and equal to the uncut ones up to the order of fp32 sums
+    need = tq.mxfp4_gemm_workspace_bytes(M, N, d)
+    ws = torch.empty((max(need, 16),), dtype=torch.uint8, device=DEV)
+    assert tq.mxfp4_gemm_main_columns(M, N, d, need) == main
+    guard2 = torch.full((M + 1, N), 0x7FC1, dtype=torch.int16, device=DEV).view(torch.bfloat16)
+    out2 = guard2[:M]
+    tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=out2, workspace=ws)
+    right2 = tq.mxfp4_gemm_ws(A_q, A_s, W_q[main:], W_s[main:], workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(out2[:, :main].view(torch.int16), left.view(torch.int16))
+    assert torch.equal(out2[:, main:].view(torch.int16), right2.view(torch.int16))
+    assert bool((guard2[M].view(torch.int16) == 0x7FC1).all())
+    a, b = out2[:, main:].double(), right.double()
+    assert float((a - b).norm() / b.norm()) <= 1e-3
+    if tq.mxfp4_gemm_plan(M, N - main, d, need)[3] == 1:
+        assert torch.equal(out2.view(torch.int16), out.view(torch.int16))
 
 
 def test_linear_full_size_is_its_two_halves_and_matches_oracle_on_samples(tq, oracle):
