@@ -626,7 +626,17 @@ static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
   const uint16_t *ri_hi = r->inter32f_hi, *ri_lo = r->inter32f_lo;      // the table in lane order
-  TORQ_LAUNCH_FMT(rotate_kernel32, uint2, KS16, TB)
+  if constexpr (TB == 2 && (KS16 == 5 || KS16 == 7 || KS16 == 8)) {
+    // G = 80, 112, 128 quantise in batches of one or on three buffers (launch_rotate): batches of two only
+    // write rotated fp32 values there, and only that kernel is built
+    if (!z_out) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((rotate_kernel32<KS16, TB, FMT_NONE>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream,
+                       reinterpret_cast<const uint4 *>(x), TG, r->G, ri_hi, ri_lo, ih, il, (uint2 *)nullptr,
+                       (uint8_t *)nullptr, z_out, 1.0f);
+    return hipGetLastError();
+  } else {
+    TORQ_LAUNCH_FMT(rotate_kernel32, uint2, KS16, TB)
+  }
 }
 
 template <int KS16>
