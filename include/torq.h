@@ -116,7 +116,9 @@ int torq_quantize_f32(const float *z_f32, int64_t M, int d,
  * on the block-scaled fp4 matrix cores, fp32 accumulation, one rounding to
  * bf16 (nearest even).  A_q [M][d/2], A_s [M][d/32], W_q [N][d/2],
  * W_s [N][d/32] in the layout torq_rotate_quantize writes; out [M][N] bf16
- * row-major.  d must be a multiple of 128.  Weights are prepared offline by
+ * row-major.  d must be a multiple of 128.  One or two kernel launches on
+ * `stream` (mxfp4_gemm_main_columns below says which); every output is the sum
+ * over k in the same order either way.  Weights are prepared offline by
  * running torq_rotate_quantize over the rows of W (the map x -> z is
  * orthogonal, so rotating W's rows is the weight fusion W' of Section 5). */
 int mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s,
