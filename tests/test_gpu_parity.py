@@ -98,7 +98,20 @@ ROT_CASES = [
 ]
 
 
-@pytest.mark.parametrize("M,d,G,nu,outl,oscale", ROT_CASES)
+def _random_rot_cases(seed):
+    # shapes nobody chose: every G = 16, 32, ... 256 once, one to four token-groups per row, 1 <= M < 200
+    rng = np.random.default_rng(seed)
+    out = []
+    for G in range(16, 257, 16):
+        d = 32 * G * int(rng.integers(1, 5))
+        out.append((int(rng.integers(1, 200)), d, G, 3.0, max(2, d // 200), 50.0))
+    return out
+
+
+ROT_RANDOM = _random_rot_cases(20260519)
+
+
+@pytest.mark.parametrize("M,d,G,nu,outl,oscale", ROT_CASES + ROT_RANDOM)
 def test_rotate_within_1e3_of_row_rms(tq, oracle, M, d, G, nu, outl, oscale):
     x = synth.activations(M, d, nu=nu, outliers=outl, outlier_scale=oscale, seed=1000 + G + M)
     Ri, Ra = synth.rotations(G, seed=77 + G)
@@ -121,7 +134,7 @@ def _boundary_slack(z, scales, tol):
     return np.abs(a[..., None] - bounds).min(axis=-1), s
 
 
-@pytest.mark.parametrize("M,d,G,nu,outl,oscale", ROT_CASES[:1] + ROT_CASES[5:6] + ROT_CASES[8:9] + ROT_CASES[12:])
+@pytest.mark.parametrize("M,d,G,nu,outl,oscale", ROT_CASES[:1] + ROT_CASES[5:6] + ROT_CASES[8:9] + ROT_CASES[12:] + ROT_RANDOM)
 def test_rotate_quantize_against_oracle(tq, oracle, M, d, G, nu, outl, oscale):
     x = synth.activations(M, d, nu=nu, outliers=outl, outlier_scale=oscale, seed=2000 + G + M)
     Ri, Ra = synth.rotations(G, seed=78 + G)
@@ -262,6 +275,31 @@ def test_gemm_random_codes(tq, oracle, M, N, d):
     torch.cuda.synchronize()
     assert _rel_fro(_bits(got), want) <= 1e-3
     _assert_every_output_within_one_ulp(_bits(got), want)
+
+
+def _random_gemm_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    return [(int(rng.integers(1, 700)), int(rng.integers(1, 900)), 128 * int(rng.integers(1, 17))) for _ in range(n)]
+
+
+# Shapes nobody chose: sixteen drawn from a seeded generator (1 <= M < 700, 1 <= N < 900, d = 128 ... 2048 in
+# steps of 128: every kernel family, ragged edges almost always, whole and broken 512-element pieces), each
+# through mxfp4_gemm and through mxfp4_gemm_ws with the workspace the planner asks for; every output.
+@pytest.mark.parametrize("M,N,d", _random_gemm_shapes(16, 20260519))
+def test_gemm_random_shapes(tq, oracle, M, N, d):
+    rng = np.random.default_rng(M * 11 + N * 5 + d)
+    A_q = rng.integers(0, 256, size=(M, d // 2), dtype=np.uint8)
+    W_q = rng.integers(0, 256, size=(N, d // 2), dtype=np.uint8)
+    A_s = rng.integers(118, 136, size=(M, d // 32), dtype=np.uint8)
+    W_s = rng.integers(110, 126, size=(N, d // 32), dtype=np.uint8)
+    want = oracle.gemm(A_q, A_s, W_q, W_s)
+    dev = [torch.from_numpy(a).to(DEV) for a in (A_q, A_s, W_q, W_s)]
+    got = tq.mxfp4_gemm(*dev)
+    got_ws = tq.mxfp4_gemm_ws(*dev)
+    torch.cuda.synchronize()
+    for g in (got, got_ws):
+        assert _rel_fro(_bits(g), want) <= 1e-3
+        _assert_every_output_within_one_ulp(_bits(g), want)
 
 
 # The persistent form of the tiled kernel (a workgroup walks several output tiles, its k loop running through
