@@ -626,17 +626,7 @@ static hipError_t launch_cfg32(const torq_rotation *r, const void *x, int64_t TG
   const uint4 *ih = reinterpret_cast<const uint4 *>(r->intra32_hi);
   const uint4 *il = reinterpret_cast<const uint4 *>(r->intra32_lo);
   const uint16_t *ri_hi = r->inter32f_hi, *ri_lo = r->inter32f_lo;      // the table in lane order
-  if constexpr (TB == 2 && (KS16 == 5 || KS16 == 7 || KS16 == 8)) {
-    // G = 80, 112, 128 quantise in batches of one or on three buffers (launch_rotate): batches of two only
-    // write rotated fp32 values there, and only that kernel is built
-    if (!z_out) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((rotate_kernel32<KS16, TB, FMT_NONE>), dim3((unsigned)grid), dim3(64 * nw), lds_bytes, stream,
-                       reinterpret_cast<const uint4 *>(x), TG, r->G, ri_hi, ri_lo, ih, il, (uint2 *)nullptr,
-                       (uint8_t *)nullptr, z_out, 1.0f);
-    return hipGetLastError();
-  } else {
-    TORQ_LAUNCH_FMT(rotate_kernel32, uint2, KS16, TB)
-  }
+  TORQ_LAUNCH_FMT(rotate_kernel32, uint2, KS16, TB)
 }
 
 template <int KS16>
@@ -703,20 +693,23 @@ hipError_t launch_rotate(const torq_rotation *r, const void *x_bf16, int64_t M, 
     if (r->G == 96) return launch_ring32<6>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
     if (r->G == 80) return launch_ring32<5>(r, x_bf16, TG, format, global_scale, codes, scales, stream);
   }
-  // Below that, batches of ONE token-group for G = 128, 112, 80 (and G = 64 up to 16384 token-groups): twice
-  // as many, half as large, so the workgroups' shares are more even and a workgroup's first results leave
-  // sooner.  Against batches of two on the same machine: X [256 .. 1024, 4096] 9.0 -> 8.0 us,
-  // [4096, 4096] 18.2 -> 17.0, [8192, 4096] 28.0 -> 27.2, [2048, 14336] 27.0 -> 25.4, [2048, 8192] 18.2 -> 16.9,
-  // [4096, 5120] G = 80 19.9 -> 18.5, [8192, 4096] G = 64 25.5 -> 24.6; nothing at [2048, 4096]; G = 96 and
-  // G = 32 lose 0 - 5 % and keep two (as does everything that writes fp32 rotated values at these G but
-  // G = 128 and 112 with a handful of token-groups, the decode case)
-  if (!z_out || TG <= 128) {
+  // Below that, batches of ONE token-group instead of two for G = 128, 112 and 80 (a) up to 256 token-groups
+  // (they spread over twice as many workgroups) and (b) from 3072 on (three or more batches of two per
+  // workgroup: as batches of one the same share leaves in smaller steps).  Between, two per batch, on fewer
+  // workgroups: each loads its slice of R_inter, 64 KB, first.  HIP-graph replays over rotating input copies,
+  // one per batch against two, same machine: X [256, 4096] 3.7 against 4.3 us, [512, 4096] 4.7 / 4.6,
+  // [1536, 4096] 8.25 / 7.97, [2048, 4096] 10.4 / 9.9, [1024, 8192] 10.3 / 9.9, [3072, 4096] 12.8 / 12.9,
+  // [4096, 4096] 15.7 / 16.2, [4096, 5120] (G = 80) 17.8 / 19.7; plain launch loops agree from [4096, 4096] on
+  // ([8192, 4096] 27.2 / 28.0, [2048, 8192] 16.9 / 18.2) and are bound by the host below.  G = 64 gains 3 % from
+  // 3072 to 16384 token-groups; G = 96 and G = 32 lose 0 - 5 % and keep two.  (The fp32 output keeps batches of
+  // two but for a handful of token-groups at G = 128 and 112, the decode case.)
+  const bool one_per_batch = !z_out ? (TG <= 256 || TG >= 3072) : TG <= 128;
+  if (one_per_batch) {
     if (r->G == 128) return launch_cfg32<8, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
     if (r->G == 112) return launch_cfg32<7, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
-  }
-  if (!z_out) {
-    if (r->G == 80) return launch_cfg32<5, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
-    if (r->G == 64 && TG <= 16384) return launch_cfg32<4, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
+    if (r->G == 80 && !z_out) return launch_cfg32<5, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
+    if (r->G == 64 && !z_out && TG >= 3072 && TG <= 16384)
+      return launch_cfg32<4, 1>(r, x_bf16, TG, format, global_scale, codes, scales, z_out, stream);
   }
   // G a multiple of 32, or 16 * odd from 80 up: the 32x32x16 kernel (with a half-empty last tile).
   // Measured on X [16384, d] against the 16x16x32 kernel: G = 112 gains 7 - 9 %, G = 80 3 - 7 % (at

@@ -57,13 +57,16 @@ def test_rotate_quantize_full_size_sampled_rows(tq, oracle, name, M):
     _rotate_quantize_checks(tq, oracle, synth.workload_activations(name, device=DEV, M=M))
 
 
-# The three-buffer kernel takes G = 80 ... 128 from 12288 token-groups on; below that G = 128, 112 and 80 (and
-# G = 64 up to 16384 token-groups) quantise in batches of one token-group, everything else in batches of two.
-# The benchmark shapes above cover the three-buffer kernel at G = 128 and 80 and batches of one at G = 128, 112
-# and 80 (the fp32 values they are compared with come from batches of two every time): here G = 112 and 96
-# above the threshold, G = 128 one token-group above and one below it (a last batch of one token-group either
-# way), and G = 64 (d = 2048) on its last size with batches of one and its first with batches of two.
-@pytest.mark.parametrize("M,d", [(4096, 14336), (4096, 9216), (12289, 4096), (12287, 4096), (16384, 2048), (16385, 2048)])
+# The three-buffer kernel takes G = 80 ... 128 from 12288 token-groups on; below that G = 128, 112 and 80 quantise
+# in batches of one token-group up to 256 token-groups and from 3072 on, in batches of two between (G = 64: batches
+# of one from 3072 to 16384 token-groups).  The benchmark shapes above cover the three-buffer kernel at G = 128 and
+# 80, batches of one at G = 128, 112 and 80 and batches of two at G = 128 (the fp32 values they are compared with
+# come from batches of two every time): here G = 112 and 96 above the three-buffer threshold, G = 128 one
+# token-group above and one below it (a last batch of one token-group either way), both sides of 256 and of 3072
+# token-groups at G = 128, batches of two at G = 80 and 112, and G = 64 (d = 2048) on its last size with batches
+# of one and its first with batches of two again.
+@pytest.mark.parametrize("M,d", [(4096, 14336), (4096, 9216), (12289, 4096), (12287, 4096), (16384, 2048), (16385, 2048),
+                                 (256, 4096), (257, 4096), (3071, 4096), (3072, 4096), (1000, 5120), (300, 14336)])
 def test_rotate_quantize_around_the_three_buffer_threshold(tq, oracle, M, d):
     x = synth.activations(M, d, nu=3.0, outliers=round(0.005 * d), outlier_scale=50.0, seed=4242 + d, device=DEV)
     _rotate_quantize_checks(tq, oracle, x)
