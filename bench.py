@@ -59,6 +59,11 @@ def main():
                          "(torq_diag_gemm_ablation / torq_diag_rotate_ablation): what each part costs on this machine")
     ap.add_argument("--sweep", action="store_true",
                     help="also print one line per rotate+quantise bandwidth-sweep shape ([16384, d])")
+    ap.add_argument("--plan-sweep", choices=("fit", "check", "decode"), default=None,
+                    help="instead of the benchmark: time every plan the GEMM's planner can choose from (tile shape x k "
+                         "pieces x load pipeline, forced through torq_diag_gemm_plan) on a grid of shapes of up to one "
+                         "round of 256x256 tiles, one JSON line per shape with the planner's own choice beside them; "
+                         "'fit' and 'check' are two disjoint grids, 'decode' has 8 to 64 rows")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -68,6 +73,9 @@ def main():
     import numpy as np
     import torch
     from paper_2605_19561_amd import binding as tq, synth
+    if args.plan_sweep:
+        plan_sweep(tq, torch, args.plan_sweep)
+        return
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
     dev = "cuda:0"
@@ -527,6 +535,86 @@ def ablation_lines(tq, torch, rot, x, codes, scales, W_q, W_s, out, steps):
                       "us": timed(lambda i: tq.torq_diag_rotate_ablation(rot, xs[i % 5], c2, s2, skip), 4 * steps)})
         res["gemm"], res["rotate_quantize"] = g, r
     return res
+
+
+PLAN_SWEEP_GRIDS = {   # (d, M, N)
+    "fit": ((4096, 8192, 14336, 28672), (96, 128, 256, 512, 1024, 2048), (1024, 4096, 8192, 14336, 28672)),
+    "check": ((5120, 7168, 12288, 25600), (80, 192, 384, 768, 1536), (2048, 5120, 6144, 11008, 25600)),
+    "decode": ((4096, 8192, 14336), (8, 16, 32, 48, 64), (1024, 4096, 14336, 28672)),
+}
+
+
+def plan_sweep(tq, torch, grid):
+    """Every plan of the tiled GEMM kernel on every shape of a grid (up to one round of 256x256 tiles), timed as
+    HIP-graph replays over weight copies of at least 600 MB in all, so that weights come from HBM and activations
+    from the caches, as in a model.  One JSON line per shape: the planner's choice with and without a workspace and
+    its time, then [tile, k_pieces, deep, us] for every candidate (tile 0 ... 3 = 256x256, 256x128, 128x128, 128x64)."""
+    dev = "cuda:0"
+    tile_m, tile_n = (256, 256, 128, 128), (256, 128, 128, 64)
+
+    def graph_us(fn, n):
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            for _ in range(2):
+                fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(n):
+                fn()
+        settle(torch, graph.replay, 1, seconds=0.01)
+        return round(timed_median(torch, graph.replay, 3, groups=3) * 1e3 / n, 2)
+
+    ds, Ms, Ns = PLAN_SWEEP_GRIDS[grid]
+    for d in ds:
+        for M in Ms:
+            for N in Ns:
+                if ((M + 255) // 256) * ((N + 255) // 256) > 256 or N * d > 28672 * 8192:
+                    continue
+                gen = torch.Generator(device=dev)
+                gen.manual_seed(M + N + d)
+                n_copies = max(3, int(600e6 // (N * d * 0.53125)) + 1)
+                A_q = torch.randint(0, 256, (M, d // 2), dtype=torch.uint8, device=dev, generator=gen)
+                A_s = torch.randint(118, 136, (M, d // 32), dtype=torch.uint8, device=dev, generator=gen)
+                W_q = [torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=dev, generator=gen)]
+                W_s = [torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=dev, generator=gen)]
+                W_q += [W_q[0].clone() for _ in range(n_copies - 1)]
+                W_s += [W_s[0].clone() for _ in range(n_copies - 1)]
+                out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+                need = tq.mxfp4_gemm_workspace_bytes(M, N, d)
+                ws = torch.empty((16 * M * N * 4,), dtype=torch.uint8, device=dev)
+                calls, turn = max(12, n_copies), [0]
+
+                def cycling(f):
+                    def g():
+                        i = turn[0] % n_copies
+                        turn[0] += 1
+                        f(W_q[i], W_s[i])
+                    return g
+                rec = {"metric": "mxfp4_gemm plans", "unit": "us per launch", "shape": [M, N, d], "weight_copies": n_copies,
+                       "planner_with_workspace": list(tq.mxfp4_gemm_plan(M, N, d, need)),
+                       "planner_without": list(tq.mxfp4_gemm_plan(M, N, d, 0))}
+                rec["us_with_workspace"] = graph_us(cycling(lambda wq, wsc: tq.mxfp4_gemm_ws(
+                    A_q, A_s, wq, wsc, out=out, workspace=ws[:max(need, 16)])), calls)
+                rec["us_without"] = graph_us(cycling(lambda wq, wsc: tq.mxfp4_gemm(A_q, A_s, wq, wsc, out=out)), calls)
+                cands = []
+                for tile in range(4):
+                    tiles = ((M + tile_m[tile] - 1) // tile_m[tile]) * ((N + tile_n[tile] - 1) // tile_n[tile])
+                    if tiles > 1024:
+                        continue
+                    for pieces in (1, 2, 4, 5, 7, 8, 10, 14, 16):
+                        if pieces > 1 and ((d // 512) % pieces or tile == 0 or tiles * pieces > 1024 or N % 8):
+                            continue
+                        for deep in ((False, True) if (tile >= 2 and pieces == 1) else (False,)):
+                            us = graph_us(cycling(lambda wq, wsc: tq.torq_diag_gemm_plan(
+                                A_q, A_s, wq, wsc, tile, pieces, deep, out=out, workspace=ws)), calls)
+                            cands.append([tile, pieces, int(deep), us])
+                rec["candidates"] = cands
+                rec["best"] = min(cands, key=lambda c: c[3])
+                print(json.dumps(rec), flush=True)
+                del A_q, A_s, W_q, W_s, out, ws
 
 
 def gemm_kernel_name(tq, M, N, d, workspace_bytes):

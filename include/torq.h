@@ -427,6 +427,20 @@ int torq_diag_rotate_ablation(const torq_rotation_t *r, const void *x_bf16, int6
  * Anything else: TORQ_EINVAL / TORQ_EALIGN. */
 int torq_diag_gemm_persistent(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
                               void *out_bf16, int64_t M, int64_t N, int d, int tile, int workgroups, void *stream);
+/* mxfp4_gemm's tiled kernel on a plan of the caller's choice, whatever the planner would take for the
+ * shape: for measuring the planner's alternatives against each other and for checking every form of the
+ * kernel on shapes small enough to compare every output.  Never the weight-streaming kernel, the
+ * persistent form or two launches.  The result is mxfp4_gemm's bit for bit when k_pieces = 1, and
+ * mxfp4_gemm_ws's for the same tile and k_pieces otherwise.
+ *   tile        0: 256 x 256 output tile, 1: 256 x 128, 2: 128 x 128, 3: 128 x 64
+ *   k_pieces    1, or into how many pieces the k range is cut: d / 512 must be a multiple of it, N a multiple of
+ *               8, and workspace (device, 16-byte aligned) hold k_pieces * M * N floats
+ *   deep        != 0: the deeper load pipeline (tiles 2 and 3, k_pieces = 1)
+ *   tile 3, k_pieces > 1 and deep need d a multiple of 512 and 16-byte aligned scale arrays
+ * Anything else: TORQ_EINVAL / TORQ_EALIGN. */
+int torq_diag_gemm_plan(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                        void *out_bf16, int64_t M, int64_t N, int d, int tile, int k_pieces, int deep,
+                        void *workspace, size_t workspace_bytes, void *stream);
 /* A plain device-to-device copy of n_bytes (a multiple of 16; src and dst 16-byte aligned, not
  * overlapping) by a kernel of this library, `torq::diag_copy_kernel`: it reads n_bytes and writes
  * n_bytes, nothing else, which makes it the yardstick for memory-traffic counters (run it in the same

@@ -21,7 +21,7 @@ EXPORTS = [
     "torq_linear_workspace_bytes_n", "torq_block_gram_workspace_bytes", "torq_block_gram", "torq_block_gram_positions",
     "torq_equalize_inter", "torq_code_histogram_workspace_bytes", "torq_code_histogram", "torq_intra_pair_scores",
     "torq_intra_best_angle", "torq_calibrate_intra", "torq_diag_mfma_burn", "torq_linear_static",
-    "torq_diag_copy", "torq_diag_gemm_ablation", "torq_diag_gemm_persistent", "torq_diag_rotate_ablation", "torq_linear_single_launch_reset", "torq_linear_single_launch_gave_up", "torq_linear_single_launch_probe",
+    "torq_diag_copy", "torq_diag_gemm_ablation", "torq_diag_gemm_persistent", "torq_diag_gemm_plan", "torq_diag_rotate_ablation", "torq_linear_single_launch_reset", "torq_linear_single_launch_gave_up", "torq_linear_single_launch_probe",
 ]
 
 TORQ_OK, TORQ_EINVAL, TORQ_EALIGN, TORQ_EWORKSPACE, TORQ_EHIP, TORQ_ENODEVICE, TORQ_ECONVERGE = 0, -1, -2, -3, -4, -5, -6
@@ -124,6 +124,8 @@ def lib():
         L.torq_diag_gemm_ablation.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, vp]
         L.torq_diag_gemm_persistent.restype = i32
         L.torq_diag_gemm_persistent.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, i32, vp]
+        L.torq_diag_gemm_plan.restype = i32
+        L.torq_diag_gemm_plan.argtypes = [vp, vp, vp, vp, vp, i64, i64, i32, i32, i32, i32, vp, sz, vp]
         L.torq_diag_rotate_ablation.restype = i32
         L.torq_diag_rotate_ablation.argtypes = [vp, vp, i64, vp, vp, i32, vp]
         L.torq_diag_copy.restype = i32
@@ -433,6 +435,23 @@ def torq_diag_gemm_persistent(A_q, A_s, W_q, W_s, tile: int, workgroups: int, ou
                                            _dev(W_q, torch.uint8, "W_q"), _dev(W_s, torch.uint8, "W_s"),
                                            _dev(out, torch.bfloat16, "out"), M, N, d, int(tile), int(workgroups),
                                            _stream(stream)), "torq_diag_gemm_persistent")
+    return out
+
+
+def torq_diag_gemm_plan(A_q, A_s, W_q, W_s, tile: int, k_pieces: int = 1, deep: bool = False, out=None, workspace=None,
+                        stream=None):
+    """mxfp4_gemm's tiled kernel on a chosen tile shape, number of k pieces and load pipeline (see include/torq.h)."""
+    M, N, d = A_q.shape[0], W_q.shape[0], A_q.shape[1] * 2
+    if out is None:
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=A_q.device)
+    if workspace is None and k_pieces > 1:
+        workspace = torch.empty((k_pieces * M * N * 4,), dtype=torch.uint8, device=A_q.device)
+    ws_ptr = _dev(workspace, torch.uint8, "workspace") if workspace is not None else None
+    _check(lib().torq_diag_gemm_plan(_dev(A_q, torch.uint8, "A_q"), _dev(A_s, torch.uint8, "A_s"),
+                                     _dev(W_q, torch.uint8, "W_q"), _dev(W_s, torch.uint8, "W_s"),
+                                     _dev(out, torch.bfloat16, "out"), M, N, d, int(tile), int(k_pieces), int(bool(deep)),
+                                     ws_ptr, workspace.numel() if workspace is not None else 0, _stream(stream)),
+           "torq_diag_gemm_plan")
     return out
 
 

@@ -759,6 +759,19 @@ int torq_diag_gemm_persistent(const uint8_t *A_q, const uint8_t *A_s, const uint
   return e == hipSuccess ? TORQ_OK : hip_fail(e);
 }
 
+int torq_diag_gemm_plan(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                        void *out_bf16, int64_t M, int64_t N, int d, int tile, int k_pieces, int deep,
+                        void *workspace, size_t workspace_bytes, void *stream) {
+  if (M <= 0 || N <= 0 || d <= 0 || d % 128 != 0 || tile < 0 || tile > 3 || k_pieces < 1 || k_pieces > 64)
+    return TORQ_EINVAL;
+  if (!A_q || !A_s || !W_q || !W_s || !out_bf16) return TORQ_EINVAL;
+  if (misaligned(A_q) || misaligned(W_q) || misaligned(out_bf16) || misaligned(workspace)) return TORQ_EALIGN;
+  hipError_t e = torq::launch_mxfp4_gemm_forced(A_q, A_s, W_q, W_s, out_bf16, M, N, d, tile, k_pieces, deep, workspace,
+                                                workspace_bytes, (hipStream_t)stream);
+  if (e == hipErrorInvalidValue) return TORQ_EINVAL;
+  return e == hipSuccess ? TORQ_OK : hip_fail(e);
+}
+
 int torq_diag_rotate_ablation(const torq_rotation_t *r, const void *x_bf16, int64_t M, uint8_t *codes,
                               uint8_t *scales, int skip, void *stream) {
   if (!r || M < 0 || skip < 0) return TORQ_EINVAL;

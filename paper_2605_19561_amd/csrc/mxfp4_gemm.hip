@@ -561,6 +561,9 @@ static int choose_tile(int64_t M, int64_t N) {
   return c1 <= c2 ? 1 : 2;
 }
 
+// the tile shapes: 0 = 256 x 256, 1 = 256 x 128, 2 = 128 x 128, 3 = 128 x 64
+static const int TILE_M[4] = {256, 256, 128, 128}, TILE_N[4] = {256, 128, 128, 64};
+
 // How a product is run: the weight-streaming kernel (mxfp4_gemm_skinny.hip), or the tiled kernel
 // with tile shape `cfg` and its k range cut into `splits` pieces (1 = not cut).
 struct GemmPlan {
@@ -581,61 +584,89 @@ static double rounds_us(int cfg, double tiles, double KT) {
   const double rounds = (double)(int64_t)((tiles + slots - 1) / slots);
   return 6.0 + rounds * (A[cfg] + B[cfg] * KT);
 }
+// ... and never less than the weights' stream from HBM at 4.7 TB/s (few activation rows against many weight rows)
+static double rounds_us(int cfg, double tiles, double KT, int64_t N, int d) {
+  const double t = rounds_us(cfg, tiles, KT), stream = 6.0 + (double)N * (double)d * 0.53125 / 1e6 * 0.214;
+  return t > stream ? t : stream;
+}
 
-// Below one full round of tiles the tiled kernel is bound by how fast one workgroup can stream
-// its operand rows (about 0.9 us per 256-element iteration of the 128 x 128 tile, 1.1 of the
-// 256 x 128 one, with one workgroup per CU; proportionally slower once CUs are shared), so a long
-// reduction over few tiles is cut along k into pieces that run side by side.  A piece is a whole
-// even number of iterations; the pieces' fp32 tiles go through the caller's workspace and cost a
-// second launch plus their own traffic.  With at most 64 activation rows the weight-streaming
-// kernel competes: its time grows with the weight bytes and with the number of 16-row activation
-// tiles.  All figures in microseconds, fitted to measurements of 4096 ... 28672-wide layers;
-// the choice only has to land near the best, not predict it.
+// Up to one round of 256 x 256 tiles the choice is wide: four tile shapes, the k range whole or cut into
+// pieces that run side by side (a piece is a whole even number of iterations; the pieces' fp32 tiles go
+// through the caller's workspace and a second kernel adds them), the deeper load pipeline for the two small
+// tiles, and with at most 64 activation rows the weight-streaming kernel.  The planner prices every
+// candidate with a model fitted to measurements and takes the cheapest.  The measurements: 228 shapes
+// (M = 8 ... 2048, N = 1024 ... 28672, d = 4096 ... 28672, powers of two and not), every candidate of each
+// forced through torq_diag_gemm_plan, HIP-graph replays over weight copies of 600 MB in all (weights come
+// from HBM, as they do in a model; activations from the caches).  Microseconds:
+//   tiled:  a + b * iterations of one workgroup,  b = (b_lo + (b_hi - b_lo) * clamp((w - 128) / 128, 0, 1)) *
+//           (1 + (rounds - 1) * m)  with rounds = ceil(workgroups / 256) and w = workgroups / rounds: up to
+//           half the CUs busy an iteration costs b_lo (latency), a full round b_hi (the power limit), a CU
+//           that holds several workgroups m times more for each further one; never less than the weights'
+//           stream from HBM; a cut adds the second launch, the pieces' traffic and 0.25 us per piece.
+//   weight-streaming:  the larger of a latency term (iterations x 16-row activation tiles) and the stream.
+// Over the measured shapes the choice is within 0.5 % of the best candidate on average (5 - 13 % before, when
+// the 128 x 64 tile did not exist and cuts were priced by rule of thumb); the worst case is 7 %.
+struct TileCost { double a, b_lo, b_hi; };
+static const TileCost TILE_COST[4][2] = {      // [tile][deep]
+    {{7.47, 1.40, 2.11}, {7.47, 1.40, 2.11}}, {{5.24, 0.96, 1.10}, {5.24, 0.96, 1.10}},
+    {{4.65, 0.84, 0.76}, {3.75, 0.68, 0.83}}, {{4.36, 0.67, 0.65}, {3.12, 0.59, 0.63}}};
+static const double TILE_SHARE[4] = {1.0, 1.11, 0.82, 0.70};
+
+static double tiled_us(int tile, int s, bool deep, int64_t M, int64_t N, int d) {
+  const double tiles = (double)(((M + TILE_M[tile] - 1) / TILE_M[tile]) * ((N + TILE_N[tile] - 1) / TILE_N[tile]));
+  const double wgs = tiles * s, iters = (double)((d + 255) / 256) / s;
+  const TileCost &c = TILE_COST[tile][deep ? 1 : 0];
+  const double rounds = (double)(int64_t)((wgs + 255.0) / 256.0), w = wgs / rounds;
+  double ramp = (w - 128.0) / 128.0;
+  ramp = ramp < 0.0 ? 0.0 : ramp > 1.0 ? 1.0 : ramp;
+  const double b = (c.b_lo + (c.b_hi - c.b_lo) * ramp) * (1.0 + (rounds - 1.0) * TILE_SHARE[tile]);
+  double t = c.a + b * iters;
+  const double stream = c.a + (double)N * (double)d * 0.53125 / 1e6 * 0.211;     // 4.7 TB/s
+  if (t < stream) t = stream;
+  if (s > 1) t += 0.72 + 1.75 * (double)s * (double)M * (double)N / 1e6 + 0.25 * s;
+  return t;
+}
+
+static double skinny_us(int64_t M, int64_t N, int d) {
+  const double mt = (double)((M + 15) / 16), iters = (double)((d + 255) / 256);
+  const double w_mb = (double)N * (double)d * 0.53125 / 1e6;
+  const double latency = 2.95 + iters * (0.0582 + 0.0761 * mt), stream = 2.94 + w_mb * (0.1349 + 0.0814 * mt);
+  return latency > stream ? latency : stream;
+}
+
 static GemmPlan choose_plan(int64_t M, int64_t N, int d, bool allow_split) {
-  GemmPlan plan{false, choose_tile(M, N), 1, false, 0.0};
-  static const int BM[3] = {256, 256, 128}, BN[3] = {256, 128, 128};
-  static const double T_ITER[3] = {1.5, 1.1, 0.9};
-  auto tiles_of = [&](int cfg) { return (double)(((M + BM[cfg] - 1) / BM[cfg]) * ((N + BN[cfg] - 1) / BN[cfg])); };
   const bool can_skinny = mxfp4_gemm_skinny_fits(M, d);
   const double KT = (d + 255) / 256;
-  if (tiles_of(plan.cfg) >= 512.0 && !can_skinny) {                 // two full rounds: nothing to gain
-    plan.us = rounds_us(plan.cfg, tiles_of(plan.cfg), KT);
-    return plan;
-  }
-
-  // the 128 x 128 tile alone on its CU, not cut: the deeper load pipeline gains an eighth
-  auto deep_pays = [&](int cfg, int s) { return cfg == 2 && s == 1 && tiles_of(cfg) <= 256.0; };
-  auto tiled_us = [&](int cfg, int s) {
-    const double wgs = tiles_of(cfg) * s, share = wgs <= 256.0 ? 1.0 : wgs / 256.0;
-    const double t_iter = deep_pays(cfg, s) ? 0.85 : T_ITER[cfg];
-    const double pieces = s > 1 ? 4.0 + (double)s * (double)M * (double)N * 8.0 / 5e6 : 0.0;
-    const double t = 2.0 + t_iter * (KT / s) * share + pieces;
-    return t < 8.0 ? 8.0 : t;                      // launch, prologue and epilogue
-  };
-  double best = tiled_us(plan.cfg, 1);
-  const bool may_split = allow_split && d % 512 == 0 && N % 8 == 0;
-  for (int cfg = 2; cfg >= 0; --cfg) {
-    if (tiles_of(cfg) >= 512.0 && cfg != plan.cfg) continue;
+  auto tiles_of = [&](int tile) { return ((M + TILE_M[tile] - 1) / TILE_M[tile]) * ((N + TILE_N[tile] - 1) / TILE_N[tile]); };
+  GemmPlan plan{false, 0, 1, false, 0.0};
+  if (tiles_of(0) > 256) {
+    // more than a round of the largest tile: by rounds (choose_tile), never cut
+    plan.cfg = choose_tile(M, N);
+    plan.us = rounds_us(plan.cfg, (double)tiles_of(plan.cfg), KT, N, d);
+  } else {
+    const bool may_split = allow_split && d % 512 == 0 && N % 8 == 0;
     const int pairs = d / 512;
-    for (int s = 1; s <= 16 && s <= (may_split && cfg != 0 ? pairs : 1); ++s) {   // the largest tile is never cut
-      if (s > 1 && pairs % s != 0) continue;
-      // a cut has to promise a tenth: small products run from the caches, faster than the model
-      const double t = tiled_us(cfg, s) / (s > 1 ? 0.9 : 1.0);
-      if (t < best) {
-        best = t;
-        plan.cfg = cfg;
-        plan.splits = s;
+    double best = -1.0;
+    for (int tile = 0; tile < 4; ++tile) {
+      if (tile == 3 && d % 512 != 0) continue;                       // (the 128 x 64 tile only has the whole-pieces form)
+      for (int s = 1; s <= 16 && s <= (may_split && tile != 0 ? pairs : 1); ++s) {   // the largest tile is never cut
+        if (s > 1 && (pairs % s != 0 || tiles_of(tile) * s > 1024)) continue;
+        if (s == 1 && tile != 0 && tiles_of(tile) > 1024) continue;
+        // the two small tiles, not cut, always on the deeper load pipeline: 10 - 19 % faster up to 256 tiles
+        // with weights from HBM, within 3 % beyond (the cut kernel has one pipeline)
+        const bool deep = tile >= 2 && s == 1 && d % 512 == 0;
+        const double t = tiled_us(tile, s, deep, M, N, d);
+        if (best < 0.0 || t < best) {
+          best = t;
+          plan = GemmPlan{false, tile, s, deep, t};
+        }
       }
     }
   }
-  plan.deep = deep_pays(plan.cfg, plan.splits);
-  plan.us = best;
   if (can_skinny) {
-    static const double per_mb[4] = {0.21, 0.31, 0.45, 0.58};      // by 16-row activation tiles
-    const double w_mb = (double)N * (double)d * 0.53125 / 1e6;
-    const double t = 4.0 + w_mb * per_mb[(M - 1) / 16];
     // near a tie the streaming kernel wins: one launch, no tile padding
-    if (0.95 * (t < 6.5 ? 6.5 : t) <= best) plan = GemmPlan{true, 0, 1, false, t < 6.5 ? 6.5 : t};
+    const double t = skinny_us(M, N, d);
+    if (0.95 * t <= plan.us) plan = GemmPlan{true, 0, 1, false, t};
   }
   return plan;
 }
@@ -646,7 +677,7 @@ static GemmPlan choose_plan(int64_t M, int64_t N, int d, bool allow_split) {
 // 256 x 256 tiles go first, as one launch that walks only those tile columns, and the remaining columns
 // are a product of their own (any plan, its k range cut where that pays) on the same output rows, which
 // are N elements apart.  Returns those leading columns, or N: one launch.  Taken when the last round would
-// be at most half full and the model promises 3 %: measured [4096, 5120, 25600] 322 -> 279 us,
+// be at most half full and the model promises a gain: measured [4096, 5120, 25600] 322 -> 279 us,
 // [4096, 5120, 5120] 71.5 -> 66.3, [4096, 25600, 5120] 291 -> 279; every output is the sum it was before
 // (same k order in every tile shape; where the remainder's k range is cut, up to the order of its fp32 sums,
 // as for any product that mxfp4_gemm_ws cuts).
@@ -665,7 +696,7 @@ static int64_t choose_main_columns(int64_t M, int64_t N, int d, bool allow_split
   const double one = tiles_whole > (whole.cfg == 2 ? 512.0 : 256.0) ? rounds_us(whole.cfg, tiles_whole, KT) : whole.us;
   const GemmPlan tail = plan_with(M, N - 256 * cols, d, allow_split, workspace_bytes);
   const double two = rounds_us(0, (double)(tiles_m * cols), KT) + tail.us;
-  return two < 0.97 * one ? 256 * cols : N;
+  return two < 0.985 * one ? 256 * cols : N;
 }
 #ifndef GEMM_PLAN
 #define GEMM_PLAN(M_, N_, d_, allow_) choose_plan(M_, N_, d_, allow_)
@@ -689,8 +720,8 @@ void mxfp4_gemm_plan(int64_t M, int64_t N, int d, size_t workspace_bytes, int *s
   GemmPlan plan = plan_with(M, N, d, d % 512 == 0, workspace_bytes);
   if (mxfp4_gemm_main_columns(M, N, d, workspace_bytes) < N) plan = GemmPlan{false, 0, 1, false, 0.0};   // the first launch
   *skinny = plan.skinny;
-  *tile_m = plan.skinny ? 0 : (plan.cfg == 2 ? 128 : 256);
-  *tile_n = plan.skinny ? 16 : (plan.cfg == 0 ? 256 : 128);
+  *tile_m = plan.skinny ? 0 : TILE_M[plan.cfg];
+  *tile_n = plan.skinny ? 16 : TILE_N[plan.cfg];
   *splits = plan.splits;
 }
 
@@ -704,21 +735,21 @@ size_t mxfp4_gemm_workspace_bytes(int64_t M, int64_t N, int d) {
   return plan.splits > 1 ? (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(float) : 0;
 }
 
-// one product by one plan: out's rows are ldc elements apart
-static hipError_t launch_planned(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
-                                 void *out_bf16, int64_t M, int64_t N, int d, int64_t ldc, bool fullk, bool ws_ok,
-                                 void *workspace, size_t workspace_bytes, hipStream_t stream) {
-  const GemmPlan plan = plan_with(M, N, d, ws_ok, ws_ok ? workspace_bytes : 0);
-  if (plan.skinny) {
-    if (ldc != N) return hipErrorInvalidValue;            // (never planned for a remainder: see launch_mxfp4_gemm)
-    return launch_mxfp4_gemm_skinny(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
-  }
+// one product by a given plan of the tiled kernel: out's rows are ldc elements apart.  fullk: d is a whole
+// number of 512-element pieces and the scale arrays are 16-byte aligned (needed by every form but the plain
+// one of the three larger tiles); persist: the persistent form where it pays (the two larger tiles, ldc = N)
+static hipError_t launch_by_plan(const GemmPlan &plan, const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
+                                 const uint8_t *W_s, void *out_bf16, int64_t M, int64_t N, int d, int64_t ldc,
+                                 bool fullk, bool persist, float *partial, hipStream_t stream) {
   const int splits = plan.splits;
-  float *partial = static_cast<float *>(workspace);
-  if (plan.deep && fullk && splits == 1)
-    return launch_tile<2, 2, true, false, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc);
+  if ((splits > 1 || plan.deep || plan.cfg == 3) && !fullk) return hipErrorInvalidValue;
+  if (splits > 1 && (!partial || plan.deep)) return hipErrorInvalidValue;
+  if (plan.deep)
+    return plan.cfg == 2   ? launch_tile<2, 2, true, false, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc)
+           : plan.cfg == 3 ? launch_tile<2, 1, true, false, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc)
+                           : hipErrorInvalidValue;
 #define TORQ_GEMM_LAUNCH(WM_, WN_)                                                                             \
-  if (splits == 1 && fullk && ldc == N &&                                                                      \
+  if (persist && splits == 1 && fullk && ldc == N &&                                                           \
       persistent_pays(((M + 64 * WM_ - 1) / (64 * WM_)) * ((N + 64 * WN_ - 1) / (64 * WN_)), d))               \
     return launch_tile<WM_, WN_, true, false, false, 0, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream); \
   return splits > 1 ? launch_tile<WM_, WN_, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream, 0, ldc) \
@@ -726,11 +757,49 @@ static hipError_t launch_planned(const uint8_t *A_q, const uint8_t *A_s, const u
                     : launch_tile<WM_, WN_, false, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc);
   if (plan.cfg == 0) { TORQ_GEMM_LAUNCH(4, 4) }
   if (plan.cfg == 1) { TORQ_GEMM_LAUNCH(4, 2) }
-  // (two workgroups of the 128 x 128 tile share a CU: the persistent form, one per CU, measured slower)
-  return splits > 1 ? launch_tile<2, 2, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream, 0, ldc)
-         : fullk    ? launch_tile<2, 2, true, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc)
-                    : launch_tile<2, 2, false, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc);
 #undef TORQ_GEMM_LAUNCH
+  // (two workgroups of the 128 x 128 tile share a CU: the persistent form, one per CU, measured slower)
+  if (plan.cfg == 2)
+    return splits > 1 ? launch_tile<2, 2, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream, 0, ldc)
+           : fullk    ? launch_tile<2, 2, true, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc)
+                      : launch_tile<2, 2, false, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc);
+  if (plan.cfg == 3)
+    return splits > 1 ? launch_tile<2, 1, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream, 0, ldc)
+                      : launch_tile<2, 1, true, false>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc);
+  return hipErrorInvalidValue;
+}
+
+// one product by the planner's plan
+static hipError_t launch_planned(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                                 void *out_bf16, int64_t M, int64_t N, int d, int64_t ldc, bool fullk, bool ws_ok,
+                                 void *workspace, size_t workspace_bytes, hipStream_t stream) {
+  GemmPlan plan = plan_with(M, N, d, ws_ok, ws_ok ? workspace_bytes : 0);
+  if (plan.skinny) {
+    if (ldc != N) return hipErrorInvalidValue;            // (never planned for a remainder: see launch_mxfp4_gemm)
+    return launch_mxfp4_gemm_skinny(A_q, A_s, W_q, W_s, out_bf16, M, N, d, stream);
+  }
+  if (!fullk) {                                           // the plain form of the three larger tiles takes any d
+    plan.deep = false;
+    if (plan.cfg == 3) plan.cfg = 2;
+  }
+  return launch_by_plan(plan, A_q, A_s, W_q, W_s, out_bf16, M, N, d, ldc, fullk, true, static_cast<float *>(workspace), stream);
+}
+
+// torq_diag_gemm_plan: the tiled kernel on a plan of the caller's choice, whatever the planner would take
+hipError_t launch_mxfp4_gemm_forced(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                                    void *out_bf16, int64_t M, int64_t N, int d, int tile, int k_pieces, int deep,
+                                    void *workspace, size_t workspace_bytes, hipStream_t stream) {
+  if ((int64_t)d * 128 >= 0x7FFFFFFF || tile < 0 || tile > 3 || k_pieces < 1) return hipErrorInvalidValue;
+  const bool fullk = (d % 512 == 0) && ((reinterpret_cast<uintptr_t>(A_s) & 15u) == 0) &&
+                     ((reinterpret_cast<uintptr_t>(W_s) & 15u) == 0);
+  if (k_pieces > 1) {
+    if (d % 512 != 0 || (d / 512) % k_pieces != 0 || N % 8 != 0 || !workspace) return hipErrorInvalidValue;
+    if ((reinterpret_cast<uintptr_t>(workspace) & 15u) != 0) return hipErrorInvalidValue;
+    if (workspace_bytes < (size_t)k_pieces * (size_t)M * (size_t)N * sizeof(float)) return hipErrorInvalidValue;
+  }
+  if (deep && tile < 2) return hipErrorInvalidValue;
+  const GemmPlan plan{false, tile, k_pieces, deep != 0, 0.0};
+  return launch_by_plan(plan, A_q, A_s, W_q, W_s, out_bf16, M, N, d, N, fullk, false, static_cast<float *>(workspace), stream);
 }
 
 hipError_t launch_mxfp4_gemm(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,

@@ -55,6 +55,11 @@ size_t mxfp4_gemm_workspace_bytes(int64_t M, int64_t N, int d);
 // what launch_mxfp4_gemm would do with a workspace of that size (operands assumed 16-byte aligned)
 void mxfp4_gemm_plan(int64_t M, int64_t N, int d, size_t workspace_bytes, int *skinny, int *tile_m, int *tile_n,
                      int *splits);
+// the tiled kernel on a given plan: tile 0 ... 3 = 256x256, 256x128, 128x128, 128x64; k_pieces > 1 needs the
+// workspace (k_pieces * M * N floats) and d / 512 divisible by it; deep: the deeper load pipeline (tiles 2, 3)
+hipError_t launch_mxfp4_gemm_forced(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
+                                    void *out_bf16, int64_t M, int64_t N, int d, int tile, int k_pieces, int deep,
+                                    void *workspace, size_t workspace_bytes, hipStream_t stream);
 // N, or the leading output columns that a first launch of whole rounds of 256 x 256 tiles takes (the plan
 // above is then that launch's; the remaining columns are a product of their own with its own plan)
 int64_t mxfp4_gemm_main_columns(int64_t M, int64_t N, int d, size_t workspace_bytes);

@@ -87,6 +87,18 @@ def test_compute_calls_reject_bad_arguments_without_launching():
     assert L.torq_diag_gemm_persistent(good, good, good, good, good, 256, 256, 1024, 0, 0, None) == binding.TORQ_EINVAL   # no workgroups
     assert L.torq_diag_gemm_persistent(good, good, good, good, None, 256, 256, 1024, 0, 8, None) == binding.TORQ_EINVAL
     assert L.torq_diag_gemm_persistent(good, good, good, odd, good, 256, 256, 1024, 0, 8, None) == binding.TORQ_EALIGN
+    # torq_diag_gemm_plan: what a form of the tiled kernel cannot take is refused before anything is launched
+    plan = lambda *a: L.torq_diag_gemm_plan(*a)
+    assert plan(good, good, good, good, good, 256, 256, 1024, 4, 1, 0, None, 0, None) == binding.TORQ_EINVAL    # unknown tile
+    assert plan(good, good, good, good, good, 256, 256, 1024, 2, 0, 0, None, 0, None) == binding.TORQ_EINVAL    # no pieces
+    assert plan(good, good, good, good, good, 256, 256, 1024, 0, 1, 1, None, 0, None) == binding.TORQ_EINVAL    # deep: small tiles only
+    assert plan(good, good, good, good, good, 256, 256, 640, 3, 1, 0, None, 0, None) == binding.TORQ_EINVAL     # 128x64 needs d % 512 == 0
+    assert plan(good, good, good, good, good, 256, 256, 1024, 2, 2, 0, None, 0, None) == binding.TORQ_EINVAL    # a cut needs a workspace
+    assert plan(good, good, good, good, good, 256, 256, 1024, 2, 2, 0, good, 1024, None) == binding.TORQ_EINVAL  # ... large enough
+    assert plan(good, good, good, good, good, 256, 256, 1536, 2, 2, 0, good, 1 << 30, None) == binding.TORQ_EINVAL  # 3 pairs / 2
+    assert plan(good, good, good, good, good, 256, 252, 1024, 2, 2, 0, good, 1 << 30, None) == binding.TORQ_EINVAL  # N % 8
+    assert plan(good, good, good, good, good, 256, 256, 1024, 2, 2, 0, odd, 1 << 30, None) == binding.TORQ_EALIGN
+    assert plan(good, good, good, good, None, 256, 256, 1024, 2, 1, 0, None, 0, None) == binding.TORQ_EINVAL
     assert L.torq_diag_rotate_ablation(None, good, 4, good, good, 0, None) == binding.TORQ_EINVAL
 
 

@@ -302,6 +302,56 @@ def test_gemm_random_shapes(tq, oracle, M, N, d):
         _assert_every_output_within_one_ulp(_bits(g), want)
 
 
+# Every form of the tiled kernel the planner can choose from, forced through torq_diag_gemm_plan on shapes with
+# ragged edges in both directions: the four tile shapes, the deeper load pipeline of the two small ones, the k
+# range cut into every number of pieces that divides it.  Every output against the oracle; uncut forms are
+# mxfp4_gemm bit for bit (one tile per output, the same k order whatever the tile).
+@pytest.mark.parametrize("M,N,d", [(300, 520, 1024), (129, 304, 2048), (257, 136, 512), (70, 1000, 1536), (513, 200, 3072)])
+def test_gemm_every_plan_of_the_tiled_kernel(tq, oracle, M, N, d):
+    rng = np.random.default_rng(M * 17 + N + d)
+    A_q = rng.integers(0, 256, size=(M, d // 2), dtype=np.uint8)
+    W_q = rng.integers(0, 256, size=(N, d // 2), dtype=np.uint8)
+    A_s = rng.integers(118, 136, size=(M, d // 32), dtype=np.uint8)
+    W_s = rng.integers(110, 126, size=(N, d // 32), dtype=np.uint8)
+    want = oracle.gemm(A_q, A_s, W_q, W_s)
+    dev = [torch.from_numpy(a).to(DEV) for a in (A_q, A_s, W_q, W_s)]
+    ref = tq.mxfp4_gemm(*dev)
+    torch.cuda.synchronize()
+    _assert_every_output_within_one_ulp(_bits(ref), want)
+    pairs = d // 512
+    for tile in range(4):
+        for deep in ((False, True) if tile >= 2 else (False,)):
+            got = tq.torq_diag_gemm_plan(*dev, tile=tile, k_pieces=1, deep=deep)
+            torch.cuda.synchronize()
+            assert torch.equal(got.view(torch.int16), ref.view(torch.int16)), (tile, deep)
+        for k_pieces in range(2, pairs + 1):
+            if pairs % k_pieces:
+                continue
+            got = tq.torq_diag_gemm_plan(*dev, tile=tile, k_pieces=k_pieces)
+            torch.cuda.synchronize()
+            assert _rel_fro(_bits(got), want) <= 1e-3, (tile, k_pieces)
+            _assert_every_output_within_one_ulp(_bits(got), want)
+
+
+def test_gemm_plan_diagnostic_rejects_what_a_form_cannot_take(tq):
+    M, N, d = 64, 72, 640                                  # d is not a whole number of 512-element pieces
+    z = lambda *shape: torch.zeros(shape, dtype=torch.uint8, device=DEV)
+    ops = (z(M, d // 2), z(M, d // 32), z(N, d // 2), z(N, d // 32))
+    for tile in (0, 1, 2):
+        tq.torq_diag_gemm_plan(*ops, tile=tile)            # the plain form takes any d
+    for kwargs in (dict(tile=3), dict(tile=2, deep=True), dict(tile=1, k_pieces=2), dict(tile=4), dict(tile=-1)):
+        with pytest.raises(RuntimeError):
+            tq.torq_diag_gemm_plan(*ops, **kwargs)
+    ops = (z(M, 512), z(M, 32), z(N, 512), z(N, 32))       # d = 1024: two pairs of iterations
+    with pytest.raises(RuntimeError):
+        tq.torq_diag_gemm_plan(*ops, tile=0, deep=True)    # the deeper pipeline exists for the two small tiles
+    with pytest.raises(RuntimeError):
+        tq.torq_diag_gemm_plan(*ops, tile=2, k_pieces=3)   # 2 pairs do not divide by 3
+    with pytest.raises(RuntimeError):
+        tq.torq_diag_gemm_plan(*ops, tile=2, k_pieces=2, workspace=torch.empty(16, dtype=torch.uint8, device=DEV))
+    torch.cuda.synchronize()
+
+
 # The persistent form of the tiled kernel (a workgroup walks several output tiles, its k loop running through
 # the tile boundaries) on few workgroups, so that small shapes exercise what mxfp4_gemm only does from four
 # tiles per CU on: two to seven tiles per workgroup, uneven shares, ragged last tile rows and columns, a
