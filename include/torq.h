@@ -435,7 +435,7 @@ int torq_diag_gemm_persistent(const uint8_t *A_q, const uint8_t *A_s, const uint
  *   tile        0: 256 x 256 output tile, 1: 256 x 128, 2: 128 x 128, 3: 128 x 64
  *   k_pieces    1, or into how many pieces the k range is cut: d / 512 must be a multiple of it, N a multiple of
  *               8, and workspace (device, 16-byte aligned) hold k_pieces * M * N floats
- *   deep        != 0: the deeper load pipeline (tiles 2 and 3, k_pieces = 1)
+ *   deep        != 0: the deeper load pipeline (tiles 2 and 3 only)
  *   tile 3, k_pieces > 1 and deep need d a multiple of 512 and 16-byte aligned scale arrays
  * Anything else: TORQ_EINVAL / TORQ_EALIGN. */
 int torq_diag_gemm_plan(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,

@@ -653,9 +653,10 @@ static GemmPlan choose_plan(int64_t M, int64_t N, int d, bool allow_split) {
         if (s > 1 && (pairs % s != 0 || tiles_of(tile) * s > 1024)) continue;
         if (s == 1 && tile != 0 && tiles_of(tile) > 1024) continue;
         // the two small tiles, not cut, always on the deeper load pipeline: 10 - 19 % faster up to 256 tiles
-        // with weights from HBM, within 3 % beyond (the cut kernel has one pipeline)
-        const bool deep = tile >= 2 && s == 1 && d % 512 == 0;
-        const double t = tiled_us(tile, s, deep, M, N, d);
+        // with weights from HBM, within 3 % beyond; cut, up to 256 workgroups (2 - 7 % faster there, 1 - 2 %
+        // slower beyond; priced like the plain pipeline)
+        const bool deep = tile >= 2 && d % 512 == 0 && (s == 1 || tiles_of(tile) * s <= 256);
+        const double t = tiled_us(tile, s, deep && s == 1, M, N, d);
         if (best < 0.0 || t < best) {
           best = t;
           plan = GemmPlan{false, tile, s, deep, t};
@@ -743,7 +744,11 @@ static hipError_t launch_by_plan(const GemmPlan &plan, const uint8_t *A_q, const
                                  bool fullk, bool persist, float *partial, hipStream_t stream) {
   const int splits = plan.splits;
   if ((splits > 1 || plan.deep || plan.cfg == 3) && !fullk) return hipErrorInvalidValue;
-  if (splits > 1 && (!partial || plan.deep)) return hipErrorInvalidValue;
+  if (splits > 1 && !partial) return hipErrorInvalidValue;
+  if (plan.deep && splits > 1)
+    return plan.cfg == 2   ? launch_tile<2, 2, true, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream, 0, ldc)
+           : plan.cfg == 3 ? launch_tile<2, 1, true, true, true>(A_q, A_s, W_q, W_s, out_bf16, partial, splits, M, N, d, stream, 0, ldc)
+                           : hipErrorInvalidValue;
   if (plan.deep)
     return plan.cfg == 2   ? launch_tile<2, 2, true, false, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc)
            : plan.cfg == 3 ? launch_tile<2, 1, true, false, true>(A_q, A_s, W_q, W_s, out_bf16, nullptr, 1, M, N, d, stream, 0, ldc)

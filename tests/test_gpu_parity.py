@@ -331,6 +331,10 @@ def test_gemm_every_plan_of_the_tiled_kernel(tq, oracle, M, N, d):
             torch.cuda.synchronize()
             assert _rel_fro(_bits(got), want) <= 1e-3, (tile, k_pieces)
             _assert_every_output_within_one_ulp(_bits(got), want)
+            if tile >= 2:        # the same pieces through the deeper pipeline: the same sums in the same order
+                deep = tq.torq_diag_gemm_plan(*dev, tile=tile, k_pieces=k_pieces, deep=True)
+                torch.cuda.synchronize()
+                assert torch.equal(deep.view(torch.int16), got.view(torch.int16)), (tile, k_pieces)
 
 
 def test_gemm_plan_diagnostic_rejects_what_a_form_cannot_take(tq):
