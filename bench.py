@@ -540,7 +540,7 @@ def ablation_lines(tq, torch, rot, x, codes, scales, W_q, W_s, out, steps):
 PLAN_SWEEP_GRIDS = {   # (d, M, N)
     "fit": ((4096, 8192, 14336, 28672), (96, 128, 256, 512, 1024, 2048), (1024, 4096, 8192, 14336, 28672)),
     "check": ((5120, 7168, 12288, 25600), (80, 192, 384, 768, 1536), (2048, 5120, 6144, 11008, 25600)),
-    "decode": ((4096, 8192, 14336), (8, 16, 32, 48, 64), (1024, 4096, 14336, 28672)),
+    "decode": ((4096, 8192, 14336, 28672), (8, 16, 32, 48, 64), (1024, 4096, 14336, 28672)),
 }
 
 

@@ -594,7 +594,7 @@ static double rounds_us(int cfg, double tiles, double KT, int64_t N, int d) {
 // pieces that run side by side (a piece is a whole even number of iterations; the pieces' fp32 tiles go
 // through the caller's workspace and a second kernel adds them), the deeper load pipeline for the two small
 // tiles, and with at most 64 activation rows the weight-streaming kernel.  The planner prices every
-// candidate with a model fitted to measurements and takes the cheapest.  The measurements: 228 shapes
+// candidate with a model fitted to measurements and takes the cheapest.  The measurements: 238 shapes
 // (M = 8 ... 2048, N = 1024 ... 28672, d = 4096 ... 28672, powers of two and not), every candidate of each
 // forced through torq_diag_gemm_plan, HIP-graph replays over weight copies of 600 MB in all (weights come
 // from HBM, as they do in a model; activations from the caches).  Microseconds:
@@ -630,7 +630,11 @@ static double tiled_us(int tile, int s, bool deep, int64_t M, int64_t N, int d) 
 static double skinny_us(int64_t M, int64_t N, int d) {
   const double mt = (double)((M + 15) / 16), iters = (double)((d + 255) / 256);
   const double w_mb = (double)N * (double)d * 0.53125 / 1e6;
-  const double latency = 2.95 + iters * (0.0582 + 0.0761 * mt), stream = 2.94 + w_mb * (0.1349 + 0.0814 * mt);
+  // beyond d = 16384 a workgroup no longer keeps its activation rows across strips: every further 16-row
+  // activation tile costs up to 2.3 times more (d = 28672)
+  const double f = d > 16384 ? 1.0 + 1.74 * (double)(d - 16384) / 16384.0 : 1.0;
+  const double latency = 2.66 + iters * (0.0565 + 0.0801 * mt * f);
+  const double stream = 2.75 + w_mb * (0.2104 + 0.0726 * (mt - 1.0) * f);
   return latency > stream ? latency : stream;
 }
 
