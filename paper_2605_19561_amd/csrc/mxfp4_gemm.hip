@@ -595,7 +595,7 @@ static double rounds_us(int cfg, double tiles, double KT, int64_t N, int d) {
 // through the caller's workspace and a second kernel adds them), the deeper load pipeline for the two small
 // tiles, and with at most 64 activation rows the weight-streaming kernel.  The planner prices every
 // candidate with a model fitted to measurements and takes the cheapest.  The measurements: 238 shapes
-// (M = 8 ... 2048, N = 1024 ... 28672, d = 4096 ... 28672, powers of two and not), every candidate of each
+// (M = 1 ... 2048, N = 1024 ... 28672, d = 4096 ... 28672, powers of two and not), every candidate of each
 // forced through torq_diag_gemm_plan, HIP-graph replays over weight copies of 600 MB in all (weights come
 // from HBM, as they do in a model; activations from the caches).  Microseconds:
 //   tiled:  a + b * iterations of one workgroup,  b = (b_lo + (b_hi - b_lo) * clamp((w - 128) / 128, 0, 1)) *
@@ -688,7 +688,7 @@ static GemmPlan choose_plan(int64_t M, int64_t N, int d, bool allow_split) {
 // as for any product that mxfp4_gemm_ws cuts).
 static GemmPlan plan_with(int64_t M, int64_t N, int d, bool allow_split, size_t workspace_bytes);
 static int64_t choose_main_columns(int64_t M, int64_t N, int d, bool allow_split, size_t workspace_bytes, const GemmPlan &whole) {
-  if (whole.skinny || whole.splits > 1 || d % 512 != 0 || N % 8 != 0 || M <= 64) return N;
+  if (whole.skinny || whole.splits > 1 || whole.cfg > 2 || d % 512 != 0 || N % 8 != 0 || M <= 64) return N;
   const int64_t tiles_m = (M + 255) / 256, tiles_n = (N + 255) / 256, tiles = tiles_m * tiles_n;
   const int64_t full = tiles / 256;
   if (full < 1 || tiles % 256 == 0 || tiles % 256 > 128 || tiles_m > 256) return N;
@@ -696,8 +696,8 @@ static int64_t choose_main_columns(int64_t M, int64_t N, int d, bool allow_split
   if (cols < 1 || cols >= tiles_n) return N;
   const double KT = (d + 255) / 256;
   // the one launch: by rounds where it takes more than one (choose_plan's own figure is for less)
-  static const int BM[3] = {256, 256, 128}, BN[3] = {256, 128, 128};
-  const double tiles_whole = (double)(((M + BM[whole.cfg] - 1) / BM[whole.cfg]) * ((N + BN[whole.cfg] - 1) / BN[whole.cfg]));
+  const int tm = TILE_M[whole.cfg], tn = TILE_N[whole.cfg];
+  const double tiles_whole = (double)(((M + tm - 1) / tm) * ((N + tn - 1) / tn));
   const double one = tiles_whole > (whole.cfg == 2 ? 512.0 : 256.0) ? rounds_us(whole.cfg, tiles_whole, KT) : whole.us;
   const GemmPlan tail = plan_with(M, N - 256 * cols, d, allow_split, workspace_bytes);
   const double two = rounds_us(0, (double)(tiles_m * cols), KT) + tail.us;
