@@ -221,10 +221,12 @@ def test_gemm_whole_rounds_first_then_the_remaining_columns(tq, M, N, d):
         assert torch.equal(out2.view(torch.int16), out.view(torch.int16))
 
 
-def test_linear_full_size_is_its_two_halves_and_matches_oracle_on_samples(tq, oracle):
-    name = "llama3_70b_up"
+# (the two Qwen3-32B layers run their product as whole rounds of tiles plus the remaining columns, the second
+# with the remainder's k range cut in the workspace that torq_linear is given)
+@pytest.mark.parametrize("name,N", [("llama3_70b_up", 4096), ("qwen3_32b", 5120), ("qwen3_32b_down", 5120)])
+def test_linear_full_size_is_its_two_halves_and_matches_oracle_on_samples(tq, oracle, name, N):
     wl = synth.WORKLOADS[name]
-    M, d, N = wl["M"], wl["d"], 4096            # N trimmed: the weights are generated and prepared here
+    M, d = wl["M"], wl["d"]                     # N trimmed: the weights are generated and prepared here
     G = synth.default_G(d)
     x = synth.workload_activations(name, device=DEV)
     w = synth.workload_weights(name, device=DEV, N=N)
@@ -233,9 +235,11 @@ def test_linear_full_size_is_its_two_halves_and_matches_oracle_on_samples(tq, or
     W_q, W_s = tq.torq_rotate_quantize(rot, w)
     out = tq.torq_linear(rot, x, W_q, W_s)
     A_q, A_s = tq.torq_rotate_quantize(rot, x)
-    out2 = tq.mxfp4_gemm(A_q, A_s, W_q, W_s)
+    out2 = tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s)
     torch.cuda.synchronize()
     assert torch.equal(out, out2)
+    if name != "llama3_70b_up":
+        assert tq.mxfp4_gemm_main_columns(M, N, d, tq.mxfp4_gemm_workspace_bytes(M, N, d)) < N
     rng = np.random.default_rng(5)
     rm = np.unique(rng.integers(0, M, size=12))
     rn = np.unique(rng.integers(0, N, size=48))
