@@ -703,8 +703,8 @@ def hist_line(tq, codes, d, steps, warmup):
 
 def decode_line(tq, synth, M, N, d, single_launch=True):
     """torq_linear (rotate + quantise + GEMM) on M activation rows: microseconds per call and the rate at
-    which the packed weights stream through.  Six weight copies rotate so that the Infinity Cache cannot
-    hold them."""
+    which the packed weights stream through.  The calls cycle over weight copies of at least 600 MB in all (at
+    least six), so that the 256 MB Infinity Cache holds none of them: weights come from HBM, as in a model."""
     import torch
     dev = "cuda:0"
     G = synth.default_G(d)
@@ -714,12 +714,12 @@ def decode_line(tq, synth, M, N, d, single_launch=True):
     rot = tq.Rotation(d, G, Ri, Ra)
     gen = torch.Generator(device=dev)
     gen.manual_seed(synth.SEED_BASE + N + d)
-    n_copies = 6
+    n_copies = max(6, int(600e6 // (N * d * 0.53125)) + 1)
     W_q = [torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=dev, generator=gen) for _ in range(n_copies)]
     W_s = [torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=dev, generator=gen) for _ in range(n_copies)]
     out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
     ws = torch.empty((tq.torq_linear_workspace_bytes_n(M, N, d),), dtype=torch.uint8, device=dev)
-    calls = 24
+    calls = max(24, n_copies)
 
     def replayed(fn):
         side = torch.cuda.Stream()

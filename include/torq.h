@@ -177,7 +177,7 @@ int mxfp4_gemm_ws(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, co
  * memory of at least torq_linear_workspace_bytes(M, d) bytes, 256-byte aligned
  * sizes; its contents afterwards are the packed activations (codes, then
  * scales at offset M*d/2 rounded up to 256).  For a row or two of a decode step
- * (at most four token-groups, G = 112 or 128, packed weights up to 48 MB) both
+ * (at most four token-groups, G = 112 or 128, packed weights up to 16 - 20 MB) both
  * steps run in ONE launch whose workgroups each rotate the rows themselves (form
  * (1) of torq_linear_single_launch): same codes, same outputs, bit for bit. */
 size_t torq_linear_workspace_bytes(int64_t M, int d);
@@ -217,7 +217,8 @@ int torq_linear_static(const torq_rotation_t *r, const void *x_bf16, const uint8
  *     for the caller to inspect, which the launch does not read), and the handle's counters are neither
  *     read nor written.  The codes are torq_rotate_quantize's, bit for bit, and the product is mxfp4_gemm
  *     of them.  torq_linear itself takes this launch where it is measured faster than its two launches
- *     (packed weights up to 48 MB: [1, 4096] -> 14336 10.1 against 12.0 us, -> 4096 5.5 against 8.3 us).
+ *     with weights that come from HBM (up to 20 MB of packed weights for one or two token-groups, 16 MB for
+ *     three or four: [1, 4096] -> 4096 6.2 against 7.7 us, -> 8192 8.3 against 9.0, -> 14336 11.4 against 11.6).
  *
  * (2) Otherwise, up to 64 rows, G = 128, a dense R_inter: the first workgroups rotate and quantise one
  *     token-group each while the others, one per strip of weight rows, already have their weight scales

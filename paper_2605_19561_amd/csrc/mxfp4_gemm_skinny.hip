@@ -798,14 +798,18 @@ bool torq_linear_local_fits(const torq_rotation *r, int64_t M) {
   return (r->d / 128 + 1) / 2 <= 8 * WAVES * 4 && local_lds_bytes(M, r->d, 1) <= 64 * 1024;
 }
 
-// Where the one-launch form is the faster way through torq_linear (measured against rotate + quantise
-// followed by the GEMM, HIP-graph replays over rotating weight copies): weights that one or two trips per
-// workgroup cover.  [1, 4096] x 14336: 12.0 -> 10.1 us, x 4096: 8.3 -> 5.5, x 1024: 7.5 -> 5.1,
-// [4, 4096] x 14336: 13.0 -> 11.4, [1, 14336] x 4096 (G = 112): 12.3 -> 11.1, [1, 8192] x 8192: 12.5 ->
-// 10.9, [1, 16384] x 5120: 18.1 -> 15.7; but [1, 8192] x 28672 (125 MB, four trips): 28.7 -> 30.1.
+// Where the one-launch form is the faster way through torq_linear, measured against rotate + quantise
+// followed by the GEMM as HIP-graph replays over weight copies of 600 MB in all (weights from HBM, as in a
+// model; with six copies of a 31 MB layer the 256 MB Infinity Cache held them, and the form seemed to pay up
+// to 48 MB): one or two token-groups up to 20 MB of packed weights, three or four up to 16 MB.  One launch
+// against two, us: [1, 4096] x 1024 5.9 / 7.3, x 4096 6.2 / 7.7, x 8192 8.3 / 9.0, x 11008 11.2 / 10.2,
+// x 14336 11.4 / 11.6; [1, 8192] x 4096 8.6 / 9.6, x 8192 12.1 / 12.1; [4, 4096] x 4096 7.9 / 8.0, x 6144
+// 9.1 / 9.3, x 8192 10.0 / 9.4, x 14336 12.8 / 12.2; [2, 8192] x 2048 8.7 / 9.1, x 4096 10.1 / 9.7;
+// [1, 14336] x 2048 (G = 112) 10.7 / 11.9, x 4096 12.4 / 12.6; [1, 8192] x 28672 (125 MB): 30.1 / 28.7.
 bool torq_linear_local_pays(const torq_rotation *r, int64_t M, int64_t N) {
   if (!torq_linear_local_fits(r, M) || N <= 0) return false;
-  return (double)N * (double)r->d * 0.53125 <= 48e6;
+  const int64_t token_groups = M * (int64_t)(r->d / 32 / r->G);
+  return (double)N * (double)r->d * 0.53125 <= (token_groups <= 2 ? 20e6 : 16e6);
 }
 
 template <int NS, int PT>
