@@ -179,7 +179,8 @@ def main():
         "data": "synthetic",
         "timing": "timed steps start after the warm-up steps and 40 ms more of them (clock settled); per-kernel times "
                   "from HIP events around back-to-back launches; HBM-bound kernels cycle over input copies of more than "
-                  "600 MB in all, so the 256 MB Infinity Cache serves none of them",
+                  "600 MB in all, and the GEMM and torq_linear lines of `configs` over weight copies of as much, so the "
+                  "256 MB Infinity Cache serves none of them (weights come from HBM, as a model's do)",
         "config": {"workload": f"{args.workload}: X bf16 [{M}, {d}] Student-t(nu={wl['nu']}) with "
                                f"{wl['outliers']} outlier channels x{wl['outlier_scale']:g}, G={G}, "
                                f"W [{N}, {d}] ~ N(0, {wl['wstd']}^2) rotated+quantised offline, out bf16 [{M}, {N}]",
@@ -455,7 +456,7 @@ def config_lines(tq, synth, torch, steps, warmup, headline):
         r = gemm_line(tq, M, N, d, steps, warmup)
         out.append({"config": cfg, "kernel": "mxfp4_gemm (" + r["config"]["gemm_kernel"] + ")", "shape": f"[{M},{N},{d}]",
                     "us": round(r["ms"] * 1e3, 2), "value": r["value"], "unit": "TFLOP/s", "bound": "mfma",
-                    "frac": r["frac_fp4_peak"]})
+                    "frac": r["frac_fp4_peak"], "weight_copies": r["config"]["weight_copies"]})
 
     def decode(cfg, M, N, d):
         r = decode_line(tq, synth, M, N, d, single_launch=False)
@@ -629,23 +630,35 @@ def gemm_kernel_name(tq, M, N, d, workspace_bytes):
 
 
 def gemm_line(tq, M, N, d, steps, warmup):
-    """mxfp4_gemm alone on random codes and scale bytes of one layer shape (with the workspace the planner asks for)."""
+    """mxfp4_gemm alone on random codes and scale bytes of one layer shape (with the workspace the planner asks
+    for).  The launches cycle over weight copies of at least 600 MB in all (at least three), so that the weights
+    come from HBM, as a model's do; the activations stay where the kernel before left them."""
     import torch
     dev = "cuda:0"
     gen = torch.Generator(device=dev)
     gen.manual_seed(M + N + d)
+    n_copies = max(3, int(600e6 // (N * d * 0.53125)) + 1)
     A_q = torch.randint(0, 256, (M, d // 2), dtype=torch.uint8, device=dev, generator=gen)
-    W_q = torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=dev, generator=gen)
     A_s = torch.randint(118, 136, (M, d // 32), dtype=torch.uint8, device=dev, generator=gen)
-    W_s = torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=dev, generator=gen)
+    W_q = [torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=dev, generator=gen)]
+    W_s = [torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=dev, generator=gen)]
+    W_q += [W_q[0].clone() for _ in range(n_copies - 1)]
+    W_s += [W_s[0].clone() for _ in range(n_copies - 1)]
     out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
     ws = torch.empty((max(tq.mxfp4_gemm_workspace_bytes(M, N, d), 16),), dtype=torch.uint8, device=dev)
-    settle(torch, lambda: tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=out, workspace=ws), warmup)
-    ms = timed_median(torch, lambda: tq.mxfp4_gemm_ws(A_q, A_s, W_q, W_s, out=out, workspace=ws), steps)
+    turn = [0]
+
+    def call():
+        i = turn[0] % n_copies
+        turn[0] += 1
+        tq.mxfp4_gemm_ws(A_q, A_s, W_q[i], W_s[i], out=out, workspace=ws)
+    settle(torch, call, warmup)
+    ms = timed_median(torch, call, steps)
     tf = 2.0 * M * N * d / (ms * 1e-3) / 1e12
     kernel = gemm_kernel_name(tq, M, N, d, ws.numel())
     return {"metric": "mxfp4_gemm", "value": round(tf, 1), "unit": "TFLOP/s",
-            "config": {"workload": f"A [{M}, {d}] x W [{N}, {d}] packed MXFP4 -> bf16 [{M}, {N}]", "gemm_kernel": kernel},
+            "config": {"workload": f"A [{M}, {d}] x W [{N}, {d}] packed MXFP4 -> bf16 [{M}, {N}]", "gemm_kernel": kernel,
+                       "weight_copies": n_copies},
             "ms": round(ms, 4), "frac_fp4_peak": round(tf / 10100.0, 4)}
 
 
