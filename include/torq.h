@@ -421,7 +421,7 @@ int torq_diag_rotate_ablation(const torq_rotation_t *r, const void *x_bf16, int6
 /* mxfp4_gemm's tiled kernel in its persistent form -- a workgroup takes several output tiles in turn and its
  * k loop runs through the tile boundaries (the last two iterations of a tile request the first two of the
  * workgroup's next one) -- on `workgroups` workgroups, whatever the shape.  mxfp4_gemm takes this form only
- * from four tiles per compute unit on; this entry point exists so that tests can walk it over several tiles per
+ * from a round and a half of tiles on; this entry point exists so that tests can walk it over several tiles per
  * workgroup on shapes small enough to check every output.  The result is mxfp4_gemm's, bit for bit.
  *   tile        0: 256 x 256 output tile, 1: 256 x 128
  *   d           a multiple of 1024; all five pointers 16-byte aligned; 1 <= workgroups <= 65536

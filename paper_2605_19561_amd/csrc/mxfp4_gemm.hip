@@ -501,12 +501,14 @@ static int compute_units() {
   return cus;
 }
 
-// Whether the persistent form (PERSIST above) takes the launch: more tiles than CUs, so that some
-// workgroup has a second tile to run into, and a k range of a multiple of four iterations.
+// Whether the persistent form (PERSIST above) takes the launch: more than a round and a half of tiles, so
+// that most workgroups have a second tile to run into, and a k range of a multiple of four iterations.
 // Measured on the same machine against the plain form: [8192, 28672, 8192] (14 tiles per CU) 925 -> 909 us,
-// [4096, 25600, 5120] (6 per CU) 288.4 -> 283.5, [8192, 8192, 28672] (4 per CU) 868 -> 865; with two tiles
-// per CU or fewer nothing or a loss of 1 %.
-static bool persistent_pays(int64_t tiles, int d) { return tiles >= 4 * (int64_t)compute_units() && d % 1024 == 0; }
+// [4096, 25600, 5120] (6 per CU) 288.4 -> 283.5, [8192, 8192, 28672] (4 per CU) 868 -> 865; and with the
+// weights from HBM (launches cycling over weight copies of 600 MB): [4096, 14336, 4096] (3.5 per CU)
+// 154.9 -> 148.7, [8192, 5120, 4096] (2.5) 114.7 -> 110.7, [4096, 8192, 4096] (2) 82.5 -> 81.0,
+// [2048, 14336, 4096] (1.75) 78.9 -> 77.1; equal within 1 % at d = 8192 from 1.75 to 2.7 per CU.
+static bool persistent_pays(int64_t tiles, int d) { return 2 * tiles > 3 * (int64_t)compute_units() && d % 1024 == 0; }
 
 template <int WM, int WN, bool FULLK, bool SPLIT, bool DEEP = false, int SKIP = 0, bool PERSIST = false>
 static hipError_t launch_tile(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q,
@@ -856,7 +858,7 @@ hipError_t launch_mxfp4_gemm_ablated(const uint8_t *A_q, const uint8_t *A_s, con
 }
 
 // torq_diag_gemm_persistent: the persistent form of the tiled kernel on `workgroups` workgroups, whatever
-// the shape (mxfp4_gemm only takes it from four tiles per CU on), so that its walk over several tiles per
+// the shape (mxfp4_gemm only takes it from a round and a half of tiles on), so that its walk over several tiles per
 // workgroup can be checked output by output on small shapes.
 hipError_t launch_mxfp4_gemm_persistent(const uint8_t *A_q, const uint8_t *A_s, const uint8_t *W_q, const uint8_t *W_s,
                                         void *out_bf16, int64_t M, int64_t N, int d, int tile, int workgroups,
