@@ -472,7 +472,33 @@ mxfp4_gemm_splitk_reduce_kernel(const float *__restrict__ partial, int splits, i
   const int64_t e0 = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 8;
   if (e0 >= MN) return;                          // MN is a multiple of 8
   f32x4 lo = *reinterpret_cast<const f32x4 *>(partial + e0), hi = *reinterpret_cast<const f32x4 *>(partial + e0 + 4);
-  for (int s = 1; s < splits; ++s) {
+  // four pieces requested at a time, added in order (the sums are those of one piece after the other)
+  int s = 1;
+  for (; s + 4 <= splits; s += 4) {
+    f32x4 l[4], h[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      l[u] = *reinterpret_cast<const f32x4 *>(partial + (size_t)(s + u) * MN + e0);
+      h[u] = *reinterpret_cast<const f32x4 *>(partial + (size_t)(s + u) * MN + e0 + 4);
+    }
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      lo += l[u];
+      hi += h[u];
+    }
+  }
+  if (s + 2 <= splits) {
+    const f32x4 l0 = *reinterpret_cast<const f32x4 *>(partial + (size_t)s * MN + e0);
+    const f32x4 h0 = *reinterpret_cast<const f32x4 *>(partial + (size_t)s * MN + e0 + 4);
+    const f32x4 l1 = *reinterpret_cast<const f32x4 *>(partial + (size_t)(s + 1) * MN + e0);
+    const f32x4 h1 = *reinterpret_cast<const f32x4 *>(partial + (size_t)(s + 1) * MN + e0 + 4);
+    lo += l0;
+    hi += h0;
+    lo += l1;
+    hi += h1;
+    s += 2;
+  }
+  if (s < splits) {
     lo += *reinterpret_cast<const f32x4 *>(partial + (size_t)s * MN + e0);
     hi += *reinterpret_cast<const f32x4 *>(partial + (size_t)s * MN + e0 + 4);
   }
