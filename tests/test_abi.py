@@ -157,6 +157,34 @@ def test_gemm_workspace_entry_points_validate_and_plan_on_the_host():
     assert L.mxfp4_gemm_plan(4, 4, 128, 0, None, C.byref(v[1]), C.byref(v[2]), C.byref(v[3])) == binding.TORQ_EINVAL
 
 
+def test_gemm_planner_invariants_over_random_shapes():
+    # whatever the cost model prefers, a plan has to be one the kernels can run: pieces that divide the k range
+    # into whole pairs of iterations, fp32 rows that are 16-byte aligned, a workspace that holds them, a first
+    # launch of whole tile columns
+    import numpy as np
+    rng = np.random.default_rng(20260519)
+    shapes = [(int(rng.integers(1, 5000)), int(rng.integers(1, 40000)), 128 * int(rng.integers(1, 225))) for _ in range(400)]
+    shapes += [(M, N, d) for M in (1, 64, 65, 4096) for N in (8, 1000, 5120, 70000) for d in (128, 512, 5120, 28672)]
+    for M, N, d in shapes:
+        need = binding.mxfp4_gemm_workspace_bytes(M, N, d)
+        for ws in (0, need):
+            main = binding.mxfp4_gemm_main_columns(M, N, d, ws)
+            assert main == N or (0 < main < N and main % 256 == 0 and d % 512 == 0 and N % 8 == 0), (M, N, d, main)
+            for n in ((N,) if main == N else (N, N - main)):
+                streaming, tm, tn, pieces = binding.mxfp4_gemm_plan(M, n, d, ws)
+                if streaming:
+                    assert M <= 64 and pieces == 1
+                    continue
+                assert (tm, tn) in ((256, 256), (256, 128), (128, 128), (128, 64)), (M, n, d, tm, tn)
+                if (tm, tn) == (128, 64):
+                    assert d % 512 == 0
+                if pieces > 1:
+                    assert d % 512 == 0 and (d // 512) % pieces == 0 and n % 8 == 0 and (tm, tn) != (256, 256)
+                    assert ws >= pieces * M * n * 4, (M, n, d, pieces, ws)
+            if main < N:
+                assert binding.mxfp4_gemm_plan(M, N, d, ws)[:3] == (False, 256, 256)
+
+
 def test_format_entry_points_reject_unknown_formats_and_bad_scales():
     L = binding.lib()
     good = C.c_void_p(0x1000)
