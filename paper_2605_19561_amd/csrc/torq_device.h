@@ -91,8 +91,25 @@ __device__ __forceinline__ float e4m3_to_f32(uint32_t code) {     // code <= 0x7
 }
 // NVFP4: eight values of a block with effective scale S = e4m3 value * tensor scale.  IEEE
 // division, then the e2m1 rounding of pack8_e2m1; a block whose scale rounded to zero keeps signs.
+// The division is only carried out where it can matter.  With r = 1 / S to one ulp, a = z r is within
+// 2^-22 (relative) of the IEEE quotient q, so a (1 - 2^-20) <= q <= a (1 + 2^-20) in magnitude; the e2m1
+// rounding is monotone, so where both ends of that bracket round to the same code q does as well, and it
+// is the code of a.  Otherwise (a quotient within 2^-20 of a rounding boundary, ties among them: a few
+// values in a million) the lane divides.  S outside [2^-100, 2^100]: always divides.
 __device__ __forceinline__ uint32_t pack8_nvfp4(const float z[8], float S) {
   float a[8];
+  if (S >= 0x1p-100f && S <= 0x1p100f) {
+    const float r = __builtin_amdgcn_rcpf(S);
+    float lo[8], hi[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      a[i] = z[i] * r;
+      lo[i] = a[i] * 0.99999904632568359375f;      // 1 - 2^-20
+      hi[i] = a[i] * 1.00000095367431640625f;      // 1 + 2^-20
+    }
+    const uint32_t c = pack8_e2m1(a, 1.0f);
+    if (pack8_e2m1(lo, 1.0f) == pack8_e2m1(hi, 1.0f)) return c;
+  }
 #pragma unroll
   for (int i = 0; i < 8; ++i) a[i] = (S > 0.0f) ? __fdiv_rn(z[i], S) : copysignf(0.0f, z[i]);
   return pack8_e2m1(a, 1.0f);

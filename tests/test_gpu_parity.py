@@ -794,6 +794,42 @@ def test_quantize_nvfp4_bit_exact(tq, oracle, M, d, gs):
     assert np.array_equal(_np(s), want_s) and np.array_equal(_np(c), want_c)
 
 
+@pytest.mark.parametrize("gs", [1.0, 0.0123, 3.7e-7])
+@pytest.mark.parametrize("top", [6.0, 5.3, 0.011, 7000.0])
+def test_quantize_nvfp4_quotients_next_to_every_rounding_boundary(tq, oracle, gs, top):
+    # The kernel divides only where the quotient z / S comes within 2^-20 of a rounding boundary of the e2m1
+    # codebook and multiplies by 1 / S elsewhere: values whose quotients sit 0, 1, 2, ... 40 ulps on either
+    # side of every boundary (and much further out), both signs, every block on one scale that is not a power
+    # of two.  Bit for bit against the oracle's IEEE division.
+    amax = np.float32(top * gs)                                 # fixes the block's scale byte and S
+    probe = np.zeros((1, 16), np.float32)
+    probe[0, 0] = amax
+    byte = int(oracle.quantize_nvfp4(probe, gs)[1][0, 0])
+    e4m3 = np.float32(np.ldexp(1 + (byte & 7) / 8.0, (byte >> 3) - 7) if (byte >> 3) else (byte & 7) / 512.0)
+    S = np.float32(e4m3 * np.float32(gs))
+    assert S > 0
+    vals = []
+    for b in (0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0):
+        centre = np.float32(np.float32(b) * S)
+        for k in list(range(-40, 41)) + [-3000, 3000, -(1 << 16), 1 << 16]:
+            v = (centre.view(np.int32) + np.int32(k)).view(np.float32)        # k ulps from b S
+            if abs(v) <= amax:
+                vals += [v, -v]
+    vals = np.array(vals, np.float32)
+    blocks = -(-len(vals) // 15)
+    body = np.zeros((blocks * 15,), np.float32)
+    body[:len(vals)] = vals
+    z = np.concatenate([np.full((blocks, 1), amax, np.float32), body.reshape(blocks, 15)], axis=1).reshape(1, blocks * 16)
+    want_c, want_s = oracle.quantize_nvfp4(z, gs)
+    assert np.all(want_s == byte)
+    c, sc = tq.torq_quantize_f32_fmt(torch.from_numpy(z).to(DEV), tq.TORQ_FMT_NVFP4, gs)
+    torch.cuda.synchronize()
+    assert np.array_equal(_np(sc), want_s) and np.array_equal(_np(c), want_c)
+    # the values straddle their boundaries: both neighbouring codes occur
+    codes = np.stack([want_c & 15, want_c >> 4], axis=-1).reshape(-1) & 7
+    assert len(np.unique(codes)) >= 6
+
+
 def test_quantize_fmt_mxfp4_is_the_plain_entry_point(tq):
     z = torch.from_numpy(_format_input(33, 1024, 7)).to(DEV)
     c0, s0 = tq.torq_quantize_f32(z)
