@@ -33,7 +33,7 @@ __global__ void __launch_bounds__(256) quantize_f32_kernel(const float4 *__restr
     if constexpr (FMT == FMT_NVFP4) {
       float amax = amax8(v);
       amax = fmaxf(amax, __int_as_float(__builtin_amdgcn_mov_dpp(__float_as_int(amax), 0xB1, 0xF, 0xF, true)));
-      const uint32_t q = e4m3_from_f32(__fdiv_rn(amax, 6.0f * global_scale));
+      const uint32_t q = nvfp4_scale_code(amax, 6.0f * global_scale);
       codes[i] = pack8_nvfp4(v, e4m3_to_f32(q) * global_scale);
       if ((threadIdx.x & 1) == 0) scales[i >> 1] = (uint8_t)q;
     } else {

@@ -181,7 +181,7 @@ __device__ __forceinline__ void rotate16_body(const uint4 *__restrict__ x, int64
           // ---- step 4 for 16-element blocks: lanes q and q ^ 1 share one, E4M3 scale byte each
           float amax = amax8(zz);
           amax = fmaxf(amax, __shfl_xor(amax, 16));
-          const uint32_t sc = e4m3_from_f32(__fdiv_rn(amax, 6.0f * global_scale));
+          const uint32_t sc = nvfp4_scale_code(amax, 6.0f * global_scale);
           codes[blk * 4 + q] = pack8_nvfp4(zz, e4m3_to_f32(sc) * global_scale);
           if ((q & 1) == 0) scales[blk * 2 + (q >> 1)] = (uint8_t)sc;
         } else if constexpr (FMT != FMT_NONE) {

@@ -240,7 +240,7 @@ rotate_butterfly_kernel(const uint4 *__restrict__ x, int64_t TG, const float *__
       const int64_t blkidx = tg * G + 32 * j + b0;              // global block index
       if constexpr (FMT == FMT_NVFP4) {
         const float amax = fmaxf(amax8(zz), amax8(zz + 8));
-        const uint32_t sc = e4m3_from_f32(__fdiv_rn(amax, 6.0f * global_scale));
+        const uint32_t sc = nvfp4_scale_code(amax, 6.0f * global_scale);
         const float S = e4m3_to_f32(sc) * global_scale;
         codes[blkidx * 2 + h] = make_uint2(pack8_nvfp4(zz, S), pack8_nvfp4(zz + 8, S));
         scales[blkidx * 2 + h] = (uint8_t)sc;

@@ -262,7 +262,7 @@ rotate_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
         if constexpr (FMT == FMT_NVFP4) {
           // the lane's sixteen values are one 16-element block: no cross-lane step
           const float amax = fmaxf(amax8(zz), amax8(zz + 8));
-          const uint32_t sc = e4m3_from_f32(__fdiv_rn(amax, 6.0f * global_scale));
+          const uint32_t sc = nvfp4_scale_code(amax, 6.0f * global_scale);
           const float S = e4m3_to_f32(sc) * global_scale;
           if (live) {
             codes[blkidx * 2 + h] = make_uint2(pack8_nvfp4(zz, S), pack8_nvfp4(zz + 8, S));
@@ -513,7 +513,7 @@ rotate_ring_kernel32(const uint4 *__restrict__ x, int64_t TG, int G,
         byte = c0 >> 23;
       } else if constexpr (FMT == FMT_NVFP4) {
         const float amax = fmaxf(amax8(zz), amax8(zz + 8));
-        byte = e4m3_from_f32(__fdiv_rn(amax, 6.0f * global_scale));
+        byte = nvfp4_scale_code(amax, 6.0f * global_scale);
         const float S = e4m3_to_f32(byte) * global_scale;
         c = u32x2{pack8_nvfp4(zz, S), pack8_nvfp4(zz + 8, S)};
       } else {

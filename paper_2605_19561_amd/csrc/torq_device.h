@@ -89,6 +89,18 @@ __device__ __forceinline__ float e4m3_to_f32(uint32_t code) {     // code <= 0x7
   return (code >> 3) ? __uint_as_float(((code >> 3) + 120u) << 23 | (code & 7u) << 20)
                      : (float)code * 0.001953125f;
 }
+// NVFP4's block scale: the E4M3 code of amax / (6 * tensor scale), an IEEE division by definition.  As in
+// pack8_nvfp4 below the division is carried out only where it can matter: the conversion is monotone, so
+// where both ends of a bracket around the quotient convert to the same code the quotient does too.
+__device__ __forceinline__ uint32_t nvfp4_scale_code(float amax, float six_gs) {
+  if (six_gs >= 0x1p-100f && six_gs <= 0x1p100f) {
+    const float t = amax * __builtin_amdgcn_rcpf(six_gs);
+    const uint32_t lo = e4m3_from_f32(t * 0.99999904632568359375f), hi = e4m3_from_f32(t * 1.00000095367431640625f);
+    if (lo == hi) return lo;
+  }
+  return e4m3_from_f32(__fdiv_rn(amax, six_gs));
+}
+
 // NVFP4: eight values of a block with effective scale S = e4m3 value * tensor scale.  IEEE
 // division, then the e2m1 rounding of pack8_e2m1; a block whose scale rounded to zero keeps signs.
 // The division is only carried out where it can matter.  With r = 1 / S to one ulp, a = z r is within

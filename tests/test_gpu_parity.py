@@ -830,6 +830,33 @@ def test_quantize_nvfp4_quotients_next_to_every_rounding_boundary(tq, oracle, gs
     assert len(np.unique(codes)) >= 6
 
 
+@pytest.mark.parametrize("gs", [1.0, 0.0123, 3.7e-7])
+def test_quantize_nvfp4_scale_quotients_next_to_every_e4m3_boundary(tq, oracle, gs):
+    # the same for the block scale, the E4M3 code of amax / (6 gs): block maxima whose quotients sit 0 ... 40 ulps
+    # on either side of the midpoint between every pair of neighbouring E4M3 values (subnormal ones included, and
+    # the saturation point), one block each
+    def e4m3_value(code):
+        return np.ldexp(1 + (code & 7) / 8.0, (code >> 3) - 7) if (code >> 3) else (code & 7) / 512.0
+    six_gs = np.float32(np.float32(6.0) * np.float32(gs))
+    vals = []
+    for code in range(0, 0x7E):
+        mid = np.float32(0.5 * (e4m3_value(code) + e4m3_value(code + 1)))
+        centre = np.float32(mid * six_gs)
+        for k in list(range(-40, 41)) + [-3000, 3000]:
+            vals.append((centre.view(np.int32) + np.int32(k)).view(np.float32))
+    vals = np.array(vals, np.float32)
+    z = np.zeros((len(vals), 16), np.float32)
+    z[:, 3] = vals
+    z[1::2, 3] *= -1
+    z[:, 9] = 0.3 * vals
+    z = z.reshape(-1, 32 * 83)
+    want_c, want_s = oracle.quantize_nvfp4(z, gs)
+    c, sc = tq.torq_quantize_f32_fmt(torch.from_numpy(z).to(DEV), tq.TORQ_FMT_NVFP4, gs)
+    torch.cuda.synchronize()
+    assert np.array_equal(_np(sc), want_s) and np.array_equal(_np(c), want_c)
+    assert len(np.unique(want_s)) >= 0x7E                       # every code from 0 (or 1) to 0x7E occurs
+
+
 def test_quantize_fmt_mxfp4_is_the_plain_entry_point(tq):
     z = torch.from_numpy(_format_input(33, 1024, 7)).to(DEV)
     c0, s0 = tq.torq_quantize_f32(z)
