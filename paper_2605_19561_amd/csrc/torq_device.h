@@ -63,15 +63,16 @@ constexpr int FMT_NONE = -1, FMT_MXFP4 = 0, FMT_MXINT4 = 1, FMT_NVFP4 = 2;
 __device__ __forceinline__ float e8m0_inverse_f32(uint32_t byte) {   // byte <= 252 for finite input
   return __uint_as_float((254u - byte) << 23);
 }
-// Clamping to [-7, 7] commutes with rounding to the nearest integer (the bounds are integers), and
-// adding 1.5 * 2^23 rounds a value of that range to the nearest integer, ties to even, leaving it in
-// two's complement in the low mantissa bits.
+// Adding 1.5 * 2^23 rounds a small value to the nearest integer, ties to even, leaving it in two's
+// complement in the low mantissa bits; the product with a power of two is exact, so one fused
+// multiply-add rounds exactly what a multiply followed by that add would.  Clamping to [-7, 7] commutes
+// with the rounding (the bounds are integers) and is done on the sum.
 __device__ __forceinline__ uint32_t pack8_int4(const float z[8], float inv_scale) {
   uint32_t r = 0;
 #pragma unroll
   for (int i = 0; i < 8; ++i) {
-    const float a = __builtin_amdgcn_fmed3f(z[i] * inv_scale, -7.0f, 7.0f);
-    r |= (__float_as_uint(a + 12582912.0f) & 15u) << (4 * i);
+    const float t = __builtin_amdgcn_fmed3f(__builtin_fmaf(z[i], inv_scale, 12582912.0f), 12582905.0f, 12582919.0f);
+    r |= (__float_as_uint(t) & 15u) << (4 * i);
   }
   return r;
 }
