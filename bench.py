@@ -59,11 +59,17 @@ def main():
                          "(torq_diag_gemm_ablation / torq_diag_rotate_ablation): what each part costs on this machine")
     ap.add_argument("--sweep", action="store_true",
                     help="also print one line per rotate+quantise bandwidth-sweep shape ([16384, d])")
-    ap.add_argument("--plan-sweep", choices=("fit", "check", "decode"), default=None,
+    ap.add_argument("--decode-forms", action="store_true",
+                    help="instead of the benchmark: torq_linear as the library routes it, as its two launches (rotate + "
+                         "quantise, then the GEMM) and as the one launch whose workgroups rotate the rows themselves, on a "
+                         "grid of decode shapes with one to four token-groups, weights from HBM; one JSON line per shape")
+    ap.add_argument("--plan-sweep", choices=("fit", "check", "decode", "rounds"), default=None,
                     help="instead of the benchmark: time every plan the GEMM's planner can choose from (tile shape x k "
                          "pieces x load pipeline, forced through torq_diag_gemm_plan) on a grid of shapes of up to one "
                          "round of 256x256 tiles, one JSON line per shape with the planner's own choice beside them; "
-                         "'fit' and 'check' are two disjoint grids, 'decode' has 8 to 64 rows")
+                         "'fit' and 'check' are two disjoint grids, 'decode' has 8 to 64 rows; 'rounds' is the regime beyond "
+                         "one round (one to seven rounds of 256x256 tiles): the planner's choice, two launches included, "
+                         "against one launch of each tile shape, plain and persistent")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -73,8 +79,14 @@ def main():
     import numpy as np
     import torch
     from paper_2605_19561_amd import binding as tq, synth
+    if args.plan_sweep == "rounds":
+        rounds_sweep(tq, torch)
+        return
     if args.plan_sweep:
         plan_sweep(tq, torch, args.plan_sweep)
+        return
+    if args.decode_forms:
+        decode_forms(tq, synth, torch)
         return
 
     assert torch.cuda.is_available(), "bench.py needs the MI355X"
@@ -616,6 +628,125 @@ def plan_sweep(tq, torch, grid):
                 rec["best"] = min(cands, key=lambda c: c[3])
                 print(json.dumps(rec), flush=True)
                 del A_q, A_s, W_q, W_s, out, ws
+
+
+def _graph_us(torch, fn, n, groups=5):
+    """Microseconds per call of fn from replays of a HIP graph of n calls (no launch overhead of the host)."""
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(2):
+            fn()
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        for _ in range(n):
+            fn()
+    settle(torch, graph.replay, 1, seconds=0.02)
+    return round(timed_median(torch, graph.replay, 3, groups=groups) * 1e3 / n, 2)
+
+
+def _weight_copies(torch, N, d, seed, dev="cuda:0"):
+    """Copies of one random packed weight matrix, at least 600 MB in all (at least three)."""
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    n_copies = max(3, int(600e6 // (N * d * 0.53125)) + 1)
+    W_q = [torch.randint(0, 256, (N, d // 2), dtype=torch.uint8, device=dev, generator=gen)]
+    W_s = [torch.randint(110, 126, (N, d // 32), dtype=torch.uint8, device=dev, generator=gen)]
+    W_q += [W_q[0].clone() for _ in range(n_copies - 1)]
+    W_s += [W_s[0].clone() for _ in range(n_copies - 1)]
+    return W_q, W_s, n_copies
+
+
+def rounds_sweep(tq, torch):
+    """Beyond one round of 256x256 tiles: mxfp4_gemm_ws as planned (whole rounds first where the planner takes two
+    launches, the persistent form where it pays) against ONE launch of each tile shape, plain (torq_diag_gemm_plan)
+    and persistent (torq_diag_gemm_persistent); launches cycle over weight copies of at least 600 MB in all."""
+    dev = "cuda:0"
+    for d in (4096, 8192):
+        for M in (2048, 4096, 8192):
+            for N in (4096, 5120, 8192, 11008, 14336):
+                tiles = ((M + 255) // 256) * ((N + 255) // 256)
+                if tiles <= 256 or tiles > 2048:
+                    continue
+                gen = torch.Generator(device=dev)
+                gen.manual_seed(M + N + d)
+                A_q = torch.randint(0, 256, (M, d // 2), dtype=torch.uint8, device=dev, generator=gen)
+                A_s = torch.randint(118, 136, (M, d // 32), dtype=torch.uint8, device=dev, generator=gen)
+                W_q, W_s, n_copies = _weight_copies(torch, N, d, M + N + d + 1)
+                out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+                ws = torch.empty((max(tq.mxfp4_gemm_workspace_bytes(M, N, d), 16),), dtype=torch.uint8, device=dev)
+                turn = [0]
+
+                def form(kind, tile=0):
+                    def f():
+                        i = turn[0] % n_copies
+                        turn[0] += 1
+                        if kind == "planned":
+                            tq.mxfp4_gemm_ws(A_q, A_s, W_q[i], W_s[i], out=out, workspace=ws)
+                        elif kind == "plain":
+                            tq.torq_diag_gemm_plan(A_q, A_s, W_q[i], W_s[i], tile, 1, False, out=out)
+                        else:
+                            tq.torq_diag_gemm_persistent(A_q, A_s, W_q[i], W_s[i], tile=tile, workgroups=256, out=out)
+                    return f
+                rec = {"metric": "mxfp4_gemm beyond one round", "unit": "us per launch", "shape": [M, N, d],
+                       "tiles_256x256": tiles, "weight_copies": n_copies,
+                       "planned": gemm_kernel_name(tq, M, N, d, ws.numel())}
+                for name, f in (("us_planned", form("planned")), ("us_256x256", form("plain", 0)),
+                                ("us_256x128", form("plain", 1)), ("us_128x128", form("plain", 2)),
+                                ("us_256x256_persistent", form("persistent", 0)),
+                                ("us_256x128_persistent", form("persistent", 1))):
+                    settle(torch, f, 3)
+                    rec[name] = round(timed_median(torch, f, 20) * 1e3, 1)
+                print(json.dumps(rec), flush=True)
+                del W_q, W_s
+
+
+def decode_forms(tq, synth, torch):
+    """torq_linear with one to four token-groups as the library routes it, as two launches and as the one launch
+    whose workgroups rotate the rows themselves; HIP-graph replays over weight copies of at least 600 MB in all."""
+    dev = "cuda:0"
+    shapes = [(M, N, 4096) for M in (1, 2, 4) for N in (1024, 2048, 4096, 6144, 8192, 11008, 14336)]
+    shapes += [(M, N, 8192) for M in (1, 2) for N in (1024, 2048, 4096, 8192)]
+    shapes += [(1, N, 14336) for N in (1024, 2048, 4096)]
+    for M, N, d in shapes:
+        G = synth.default_G(d)
+        x = synth.activations(M, d, nu=3.0, outliers=round(0.005 * d), outlier_scale=50.0, seed=synth.SEED_BASE + 7,
+                              device=dev)
+        Ri, Ra = synth.rotations(G)
+        rot = tq.Rotation(d, G, Ri, Ra)
+        W_q, W_s, n_copies = _weight_copies(torch, N, d, N + d)
+        out = torch.empty((M, N), dtype=torch.bfloat16, device=dev)
+        ws = torch.empty((tq.torq_linear_workspace_bytes_n(M, N, d),), dtype=torch.uint8, device=dev)
+        codes = torch.empty((M, d // 2), dtype=torch.uint8, device=dev)
+        scales = torch.empty((M, d // 32), dtype=torch.uint8, device=dev)
+        gws = torch.empty((max(tq.mxfp4_gemm_workspace_bytes(M, N, d), 16),), dtype=torch.uint8, device=dev)
+        turn = [0]
+
+        def routed():
+            i = turn[0] % n_copies
+            turn[0] += 1
+            tq.torq_linear(rot, x, W_q[i], W_s[i], out=out, workspace=ws)
+
+        def two():
+            i = turn[0] % n_copies
+            turn[0] += 1
+            tq.torq_rotate_quantize(rot, x, codes=codes, scales=scales)
+            tq.mxfp4_gemm_ws(codes, scales, W_q[i], W_s[i], out=out, workspace=gws)
+
+        def one():
+            i = turn[0] % n_copies
+            turn[0] += 1
+            tq.torq_linear_single_launch(rot, x, W_q[i], W_s[i], out=out, workspace=ws)
+        calls = max(24, n_copies)
+        print(json.dumps({"metric": "torq_linear, decode forms", "unit": "us per call", "shape": [M, N, d], "G": G,
+                          "token_groups": M * (d // 32 // G), "weights_MB": round(N * d * 0.53125 / 1e6, 1),
+                          "weight_copies": n_copies, "us_torq_linear": _graph_us(torch, routed, calls),
+                          "us_two_launches": _graph_us(torch, two, calls),
+                          "us_one_launch": _graph_us(torch, one, calls)}), flush=True)
+        rot.close()
+        del W_q, W_s
 
 
 def gemm_kernel_name(tq, M, N, d, workspace_bytes):
